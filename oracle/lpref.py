@@ -1,0 +1,358 @@
+"""CPU oracle, part 2 of 2: the synchronous local step in float64.  TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, definition-level implementation of what the HIP library computes; it shares no
+code with it.  Pinned by tests/test_oracle_*.py (finite differences, closed forms, the
+invariants of the relaxed problem); nothing here is pinned by a value printed in the paper,
+because the paper prints none for the local step.
+
+Notation (the paper's symbol in brackets): x_k [lambda_k] is the auxiliary variable that module
+k takes as input; lam_k [kappa_{k+1}] the explicit multiplier on the interface that module k
+produces; rho = 2*beta because the paper weights psi = ||.||^2 (no 1/2) by beta.
+
+What follows what:
+  module_forward     - decoupled feature flow of Sec. 4.1: X_{kn} = x_k, X_{m+1} = X_m + F(X_m, W_m)
+  local_loss_grad    - per-interface term of the penalty functional (Sec. 3.2) / augmented Lagrangian
+                       (Sec. 3.3, expanded in App. C) and the terminal condition of the discrete
+                       adjoint (Sec. 4.1, second line of the backward dynamic)
+  ce_loss_grad       - terminal loss phi, mini-batch mean (Sec. 2.1) and its terminal adjoint
+  module_backward    - discrete adjoint recursion P_m = P_{m+1} dX_{m+1}/dX_m and the weight
+                       gradient P_{m+1} dF/dW of Sec. 4.1
+  auxnet_forward     - AuxNet forward map of Sec. 4.2 in its one-block, from-the-image form
+  multiplier_update  - multiplier update rule of Sec. 4.1
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from workloads.configs import ModuleDesc, AuxDesc, NetDesc, Block, block_convs
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "liblpref.so")
+        if not os.path.exists(path):
+            from .build import build
+            build()
+        L = ctypes.CDLL(path)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int64)
+        ints = [ctypes.c_int] * 9
+        L.lpref_conv_fwd.argtypes = [dp, dp, dp] + ints
+        L.lpref_conv_dgrad.argtypes = [dp, dp, dp] + ints
+        L.lpref_conv_wgrad.argtypes = [dp, dp, dp] + ints
+        L.lpref_conv_fwd_at.argtypes = [dp, dp] + ints + [ctypes.c_int] * 4
+        L.lpref_conv_fwd_at.restype = ctypes.c_double
+        L.lpref_im2col_index.argtypes = [ctypes.c_int64, ctypes.c_int64] + [ctypes.c_int] * 7
+        L.lpref_im2col_index.restype = ctypes.c_int64
+        L.lpref_maxpool_fwd.argtypes = [dp, dp, ip] + [ctypes.c_int] * 7
+        L.lpref_maxpool_bwd.argtypes = [dp, ip, dp, ctypes.c_int64, ctypes.c_int64]
+        L.lpref_num_threads.restype = ctypes.c_int
+        _LIB = L
+    return _LIB
+
+
+def num_threads() -> int:
+    return int(_lib().lpref_num_threads())
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _c64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _out_hw(H, W, R, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+
+
+# ----------------------------------------------------------------------------- primitives
+def conv_fwd(x, w, stride, pad):
+    x, w = _c64(x), _c64(w)
+    N, H, W, Cin = x.shape
+    Cout, R, S, Cin2 = w.shape
+    assert Cin == Cin2
+    Ho, Wo = _out_hw(H, W, R, stride, pad)
+    y = np.empty((N, Ho, Wo, Cout))
+    _lib().lpref_conv_fwd(_dp(x), _dp(w), _dp(y), N, H, W, Cin, Cout, R, S, stride, pad)
+    return y
+
+
+def conv_fwd_at(x, w, stride, pad, n, ho, wo, co):
+    """A single output element of conv_fwd (x, w must already be contiguous float64)."""
+    N, H, W, Cin = x.shape
+    Cout, R, S, _ = w.shape
+    return _lib().lpref_conv_fwd_at(_dp(x), _dp(w), N, H, W, Cin, Cout, R, S, stride, pad, n, ho, wo, co)
+
+
+def conv_dgrad(dy, w, x_shape, stride, pad):
+    dy, w = _c64(dy), _c64(w)
+    N, H, W, Cin = x_shape
+    Cout, R, S, _ = w.shape
+    dx = np.empty(x_shape)
+    _lib().lpref_conv_dgrad(_dp(dy), _dp(w), _dp(dx), N, H, W, Cin, Cout, R, S, stride, pad)
+    return dx
+
+
+def conv_wgrad(x, dy, w_shape, stride, pad):
+    x, dy = _c64(x), _c64(dy)
+    N, H, W, Cin = x.shape
+    Cout, R, S, _ = w_shape
+    dw = np.empty(w_shape)
+    _lib().lpref_conv_wgrad(_dp(x), _dp(dy), _dp(dw), N, H, W, Cin, Cout, R, S, stride, pad)
+    return dw
+
+
+def im2col_index(m, q, H, W, Cin, R, S, stride, pad):
+    return int(_lib().lpref_im2col_index(int(m), int(q), H, W, Cin, R, S, stride, pad))
+
+
+def maxpool_fwd(x, R=3, stride=2, pad=1):
+    x = _c64(x)
+    N, H, W, C = x.shape
+    Ho, Wo = _out_hw(H, W, R, stride, pad)
+    y = np.empty((N, Ho, Wo, C))
+    idx = np.empty((N, Ho, Wo, C), dtype=np.int64)
+    _lib().lpref_maxpool_fwd(_dp(x), _dp(y), idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                             N, H, W, C, R, stride, pad)
+    return y, idx
+
+
+def maxpool_bwd(dy, idx, x_shape):
+    dy = _c64(dy)
+    dx = np.empty(x_shape)
+    _lib().lpref_maxpool_bwd(_dp(dy), idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), _dp(dx),
+                             dy.size, dx.size)
+    return dx
+
+
+def bn_fwd(y, gamma, beta, eps):
+    """Training-mode batch norm: per-channel mean and biased variance over N*H*W."""
+    mean = y.mean(axis=(0, 1, 2))
+    var = ((y - mean) ** 2).mean(axis=(0, 1, 2))
+    invstd = 1.0 / np.sqrt(var + eps)
+    yhat = (y - mean) * invstd
+    return gamma * yhat + beta, (yhat, invstd)
+
+
+def bn_bwd(dz, cache, gamma):
+    """Exact gradient through the batch statistics."""
+    yhat, invstd = cache
+    M = dz.shape[0] * dz.shape[1] * dz.shape[2]
+    dbeta = dz.sum(axis=(0, 1, 2))
+    dgamma = (dz * yhat).sum(axis=(0, 1, 2))
+    dy = gamma * invstd * (dz - dbeta / M - yhat * (dgamma / M))
+    return dy, dgamma, dbeta
+
+
+# ----------------------------------------------------------------------------- conv+BN unit
+def _cbr_fwd(x, w, gamma, beta, stride, pad, relu, eps):
+    y = conv_fwd(x, w, stride, pad)
+    z, bc = bn_fwd(y, gamma, beta, eps)
+    a = np.maximum(z, 0.0) if relu else z
+    return a, (x, w, gamma, bc, z if relu else None, stride, pad)
+
+
+def _cbr_bwd(da, cache, need_dx=True):
+    x, w, gamma, bc, z, stride, pad = cache
+    dz = da * (z > 0.0) if z is not None else da          # ReLU gradient is 0 at exactly 0
+    dy, dgamma, dbeta = bn_bwd(dz, bc, gamma)
+    dw = conv_wgrad(x, dy, w.shape, stride, pad)
+    dx = conv_dgrad(dy, w, x.shape, stride, pad) if need_dx else None
+    return dx, [dw, dgamma, dbeta]
+
+
+# ----------------------------------------------------------------------------- residual block
+def block_forward(x, p, b: Block, eps):
+    """X_{m+1} = skip(X_m) + F(X_m, W_m); F = conv-BN-ReLU ... conv-BN (no ReLU after the add)."""
+    convs = block_convs(b)
+    main = [c for c in convs if c[0] != 3]
+    caches, a, i = [], x, 0
+    for j, (_, r, ci, co, st, pad) in enumerate(main):
+        a, c = _cbr_fwd(a, p[i], p[i + 1], p[i + 2], st, pad, relu=(j < len(main) - 1), eps=eps)
+        caches.append(c)
+        i += 3
+    if b.proj:
+        _, r, ci, co, st, pad = convs[-1]
+        s, pc = _cbr_fwd(x, p[i], p[i + 1], p[i + 2], st, pad, relu=False, eps=eps)
+    else:
+        s, pc = x, None
+    return s + a, (caches, pc)
+
+
+def block_backward(dout, cache, need_dx=True):
+    caches, pc = cache
+    grads = []
+    da = dout
+    for j in range(len(caches) - 1, -1, -1):
+        da, g = _cbr_bwd(da, caches[j], need_dx=(need_dx or j > 0))
+        grads = g + grads
+    dx = da
+    if pc is not None:
+        dxp, g = _cbr_bwd(dout, pc, need_dx=need_dx)
+        grads = grads + g
+        if need_dx:
+            dx = dx + dxp
+    elif need_dx:
+        dx = dx + dout
+    return dx, grads
+
+
+# ----------------------------------------------------------------------------- module
+def module_forward(m: ModuleDesc, x, params, eps=1e-5):
+    """Returns (F_k(x_k), logits or None, cache).  params: list in workloads.module_tensor_specs order."""
+    p = [_c64(t) for t in params]
+    a = _c64(x)
+    cache = {"stem": None, "blocks": [], "head": None, "in_shape": a.shape}
+    i = 0
+    if m.stem == 1:
+        a, c = _cbr_fwd(a, p[0], p[1], p[2], 1, 1, True, eps)
+        cache["stem"] = (c, None)
+        i = 3
+    elif m.stem == 2:
+        a, c = _cbr_fwd(a, p[0], p[1], p[2], 2, 3, True, eps)
+        pre_shape = a.shape
+        a, idx = maxpool_fwd(a, 3, 2, 1)
+        cache["stem"] = (c, (idx, pre_shape))
+        i = 3
+    for b in m.blocks:
+        n = 3 * len(block_convs(b))
+        a, c = block_forward(a, p[i:i + n], b, eps)
+        cache["blocks"].append(c)
+        i += n
+    logits = None
+    if m.head:
+        pooled = a.mean(axis=(1, 2))
+        logits = pooled @ p[i].T + p[i + 1]
+        cache["head"] = (pooled, p[i], a.shape)
+    return a, logits, cache
+
+
+def module_backward(m: ModuleDesc, cache, dy=None, dlogits=None, need_dx=True):
+    """Module-local back-propagation from the terminal adjoint: dy (on F_k(x_k)) or dlogits (last module).
+
+    Returns (dparams list in packing order, dx_k or None)."""
+    tail = []
+    if m.head:
+        pooled, wfc, shp = cache["head"]
+        dwfc = dlogits.T @ pooled
+        dbfc = dlogits.sum(axis=0)
+        dpooled = dlogits @ wfc
+        g = np.broadcast_to(dpooled[:, None, None, :] / (shp[1] * shp[2]), shp).copy()
+        tail = [dwfc, dbfc]
+    else:
+        g = _c64(dy)
+    grads = []
+    nb = len(cache["blocks"])
+    for j in range(nb - 1, -1, -1):
+        first = (j == 0 and cache["stem"] is None)
+        g, bg = block_backward(g, cache["blocks"][j], need_dx=(need_dx or not first))
+        grads = bg + grads
+    if cache["stem"] is not None:
+        c, mp = cache["stem"]
+        if mp is not None:
+            g = maxpool_bwd(g, mp[0], mp[1])
+        g, sg = _cbr_bwd(g, c, need_dx=need_dx)
+        grads = sg + grads
+    return grads + tail, (g if need_dx else None)
+
+
+# ----------------------------------------------------------------------------- losses
+def local_loss_grad(y, x_next, lam, rho, scale=1.0):
+    """loss_k = s*(rho/2*sum r^2 + sum lam*r), dy = s*(rho*r + lam), r = F_k(x_k) - x_{k+1}; lam=None: penalty."""
+    r = _c64(y) - _c64(x_next)
+    loss = 0.5 * rho * np.sum(r * r)
+    dy = rho * r
+    if lam is not None:
+        lam = _c64(lam)
+        loss = loss + np.sum(lam * r)
+        dy = dy + lam
+    return scale * loss, scale * dy
+
+
+def ce_loss_grad(logits, labels):
+    """Mini-batch mean of softmax cross-entropy and its gradient w.r.t. the logits."""
+    z = _c64(logits)
+    N = z.shape[0]
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    se = e.sum(axis=1, keepdims=True)
+    lse = np.log(se) + zmax
+    loss = float(np.mean(lse[:, 0] - z[np.arange(N), labels]))
+    dz = e / se
+    dz[np.arange(N), labels] -= 1.0
+    return loss, dz / N
+
+
+def multiplier_update(lam, y, x_next, step):
+    """lam_k <- lam_k + step * (F_k(x_k) - x_{k+1})   (paper: step = eta/(2*beta) = eta/rho)."""
+    return _c64(lam) + step * (_c64(y) - _c64(x_next))
+
+
+def auxnet_forward(a: AuxDesc, image, params, eps=1e-5):
+    """x = [ReLU](BN(conv3x3_stride(image)))."""
+    out, _ = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]),
+                      a.stride, 1, a.relu, eps)
+    return out
+
+
+# ----------------------------------------------------------------------------- whole step / serial net
+def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=False):
+    """One synchronous local step of all K modules.
+
+    xs: [x_0 (image), x_1, ..., x_{K-1}]; lams: K-1 multipliers or None (penalty).
+    Returns dict with y (K-1 interface outputs + last-module features), logits, loss[K], dy, dlogits,
+    dparams[K], dx[K] (dx[0] None unless need_dx0)."""
+    K = net.K
+    out = {"y": [], "loss": [], "dy": [], "dparams": [], "dx": [], "logits": None, "dlogits": None}
+    for k in range(K):
+        m = net.modules[k]
+        y, logits, cache = module_forward(m, xs[k], params[k], net.bn_eps)
+        out["y"].append(y)
+        if k < K - 1:
+            lam = None if lams is None else lams[k]
+            loss, dy = local_loss_grad(y, xs[k + 1], lam, net.rho, scale)
+            out["dy"].append(dy)
+            dp, dx = module_backward(m, cache, dy=dy, need_dx=(k > 0 or need_dx0))
+        else:
+            loss, dz = ce_loss_grad(logits, labels)
+            out["logits"], out["dlogits"] = logits, dz
+            dp, dx = module_backward(m, cache, dlogits=dz, need_dx=(k > 0 or need_dx0))
+        out["loss"].append(loss)
+        out["dparams"].append(dp)
+        out["dx"].append(dx)
+    return out
+
+
+def serial_forward(net: NetDesc, image, params):
+    """Layer-serial forward (K=1 reading): states [x_0, X at every module boundary], logits, caches."""
+    xs, caches, a, logits = [_c64(image)], [], _c64(image), None
+    for k in range(net.K):
+        a, logits, c = module_forward(net.modules[k], a, params[k], net.bn_eps)
+        caches.append(c)
+        if k < net.K - 1:
+            xs.append(a)
+    return xs, logits, caches
+
+
+def serial_backward(net: NetDesc, caches, logits, labels, need_dx0=False):
+    """End-to-end back-propagation of the classification loss: (loss, dparams[K], adjoints at interfaces).
+
+    adjoint[k] = d phi / d X at the input of module k (k >= 1)."""
+    loss, dz = ce_loss_grad(logits, labels)
+    K = net.K
+    dparams, adj = [None] * K, [None] * K
+    g = None
+    for k in range(K - 1, -1, -1):
+        if k == K - 1:
+            dp, g = module_backward(net.modules[k], caches[k], dlogits=dz, need_dx=(k > 0 or need_dx0))
+        else:
+            dp, g = module_backward(net.modules[k], caches[k], dy=g, need_dx=(k > 0 or need_dx0))
+        dparams[k], adj[k] = dp, g
+    return loss, dparams, adj

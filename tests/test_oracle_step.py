@@ -1,0 +1,180 @@
+"""Pins of the oracle's local step: finite differences and the invariants the relaxed problem implies."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lpref
+from tests.helpers import mini_basic, mini_bottleneck, step_inputs, rel_err
+
+
+def _local_loss(net, k, x, params, x_next, lam, labels, scale):
+    m = net.modules[k]
+    y, logits, _ = lpref.module_forward(m, x, params, net.bn_eps)
+    if k < net.K - 1:
+        return lpref.local_loss_grad(y, x_next, lam, net.rho, scale)[0]
+    return lpref.ce_loss_grad(logits, labels)[0]
+
+
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+def test_module_backward_finite_differences(mk):
+    """Every parameter tensor and the module input: directional derivatives, one tensor at a time,
+    plus single coordinates, against central differences of the local loss (float64)."""
+    net = mk()
+    net.rho, net.al = 1.3, True
+    net.lam_sigma = 0.5
+    inp = step_inputs(net, lpref)
+    rng = np.random.default_rng(7)
+    scale = 0.7
+    out = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], scale, need_dx0=True)
+    h = 1e-6
+    for k in range(net.K):
+        x, p = inp["xs"][k], inp["params"][k]
+        xn = inp["xs"][k + 1] if k < net.K - 1 else None
+        lam = inp["lams"][k] if k < net.K - 1 else None
+        f = lambda xx, pp: _local_loss(net, k, xx, pp, xn, lam, inp["labels"], scale)
+        specs = wl.module_tensor_specs(net.modules[k])
+        assert len(specs) == len(p) == len(out["dparams"][k])
+        for i, sp in enumerate(specs):
+            assert out["dparams"][k][i].shape == tuple(sp.shape)
+            d = rng.standard_normal(p[i].shape)
+            pp, pm = list(p), list(p)
+            pp[i], pm[i] = p[i] + h * d, p[i] - h * d
+            fd = (f(x, pp) - f(x, pm)) / (2 * h)
+            an = float(np.sum(out["dparams"][k][i] * d))
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, sp.name, fd, an)
+            j = tuple(rng.integers(0, s) for s in p[i].shape)
+            e = np.zeros_like(p[i]); e[j] = h
+            pp[i], pm[i] = p[i] + e, p[i] - e
+            fd = (f(x, pp) - f(x, pm)) / (2 * h)
+            assert abs(fd - out["dparams"][k][i][j]) <= 2e-6 * max(1.0, abs(fd)), (k, sp.name, j)
+        d = rng.standard_normal(x.shape)
+        fd = (f(x + h * d, p) - f(x - h * d, p)) / (2 * h)
+        an = float(np.sum(out["dx"][k] * d))
+        assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, "dx", fd, an)
+
+
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+def test_vanish_invariant(mk):
+    """x_{k+1} = F_k(x_k) and zero multipliers: every penalty term, its terminal adjoint, every weight
+    gradient and every dx of modules 0..K-2 vanish exactly (the relaxed problem reduces to the original)."""
+    net = mk()
+    inp = step_inputs(net, lpref, consistent=True)
+    states, _, _ = lpref.serial_forward(net, inp["image"], inp["params"])
+    xs = [inp["image"]] + states[1:]
+    out = lpref.local_step(net, xs, inp["params"], inp["labels"], None, 1.0, need_dx0=True)
+    for k in range(net.K - 1):
+        assert out["loss"][k] == 0.0
+        assert not out["dy"][k].any()
+        assert all(not g.any() for g in out["dparams"][k])
+        assert not out["dx"][k].any()
+    assert out["loss"][-1] > 0.0
+
+
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+def test_last_module_equals_end_to_end_and_serial_fd(mk):
+    """With consistent auxiliary variables the last module's local gradients are those of end-to-end
+    back-propagation; the end-to-end gradients themselves are pinned by finite differences of the
+    serial network's loss."""
+    net = mk()
+    inp = step_inputs(net, lpref, consistent=True)
+    states, logits, caches = lpref.serial_forward(net, inp["image"], inp["params"])
+    loss, dps, adj = lpref.serial_backward(net, caches, logits, inp["labels"], need_dx0=True)
+    xs = [inp["image"]] + states[1:]
+    out = lpref.local_step(net, xs, inp["params"], inp["labels"], None, 1.0, need_dx0=True)
+    assert out["loss"][-1] == loss
+    for a, b in zip(out["dparams"][-1], dps[-1]):
+        np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(out["dx"][-1], adj[-1])
+
+    def serial_loss(params, image):
+        _, lg, _ = lpref.serial_forward(net, image, params)
+        return lpref.ce_loss_grad(lg, inp["labels"])[0]
+
+    rng = np.random.default_rng(3)
+    h = 1e-6
+    for k in range(net.K):
+        for i in range(len(inp["params"][k])):
+            d = rng.standard_normal(inp["params"][k][i].shape)
+            pp = [list(p) for p in inp["params"]]; pm = [list(p) for p in inp["params"]]
+            pp[k][i] = pp[k][i] + h * d; pm[k][i] = pm[k][i] - h * d
+            fd = (serial_loss(pp, inp["image"]) - serial_loss(pm, inp["image"])) / (2 * h)
+            an = float(np.sum(dps[k][i] * d))
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, i, fd, an)
+    d = rng.standard_normal(inp["image"].shape)
+    fd = (serial_loss(inp["params"], inp["image"] + h * d) - serial_loss(inp["params"], inp["image"] - h * d)) / (2 * h)
+    assert abs(fd - float(np.sum(adj[0] * d))) <= 2e-6
+
+
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+def test_multiplier_equal_to_adjoint_reproduces_end_to_end(mk):
+    """Consistent auxiliary variables, arbitrary rho, multiplier on each interface := end-to-end adjoint
+    there: every module's weight gradients and dx equal end-to-end back-propagation."""
+    net = mk()
+    net.rho = 3.7
+    inp = step_inputs(net, lpref, consistent=True)
+    states, logits, caches = lpref.serial_forward(net, inp["image"], inp["params"])
+    _, dps, adj = lpref.serial_backward(net, caches, logits, inp["labels"], need_dx0=True)
+    xs = [inp["image"]] + states[1:]
+    lams = [adj[k + 1] for k in range(net.K - 1)]
+    out = lpref.local_step(net, xs, inp["params"], inp["labels"], lams, 1.0, need_dx0=True)
+    for k in range(net.K):
+        for a, b in zip(out["dparams"][k], dps[k]):
+            assert rel_err(a, b) < 1e-12
+        assert rel_err(out["dx"][k], adj[k]) < 1e-12
+    # zero multipliers reproduce the penalty method bit for bit
+    zero = [np.zeros_like(l) for l in lams]
+    noisy = step_inputs(net, lpref)
+    o1 = lpref.local_step(net, noisy["xs"], noisy["params"], noisy["labels"], zero, 1.0)
+    o2 = lpref.local_step(net, noisy["xs"], noisy["params"], noisy["labels"], None, 1.0)
+    for k in range(net.K):
+        assert o1["loss"][k] == o2["loss"][k]
+        for a, b in zip(o1["dparams"][k], o2["dparams"][k]):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_module_zero_has_no_incoming_penalty_and_split_matches_serial():
+    """Module k's forward from the serial state equals the serial network's next state (the split
+    changes nothing when the constraints hold), and the local step never touches a multiplier for the
+    last module."""
+    net = mini_basic()
+    inp = step_inputs(net, lpref, consistent=True)
+    states, logits, _ = lpref.serial_forward(net, inp["image"], inp["params"])
+    for k in range(net.K):
+        y, lg, _ = lpref.module_forward(net.modules[k], states[k], inp["params"][k], net.bn_eps)
+        if k < net.K - 1:
+            np.testing.assert_array_equal(y, states[k + 1])
+        else:
+            np.testing.assert_array_equal(lg, logits)
+
+
+def test_auxnet_forward_definition():
+    net = wl.make_config("resnet56", batch=2)
+    a = net.aux[3]                      # stride 2, 32 channels
+    img = wl.make_image(net)
+    p = wl.make_aux_params(net, 3)
+    x = lpref.auxnet_forward(a, img, p, net.bn_eps)
+    assert x.shape == (2, 16, 16, 32) == (net.modules[4].N, net.modules[4].H, net.modules[4].W, net.modules[4].C)
+    y = lpref.conv_fwd(img, p[0], 2, 1)
+    mu, var = y.mean(axis=(0, 1, 2)), y.var(axis=(0, 1, 2))
+    np.testing.assert_allclose(x, p[1] * (y - mu) / np.sqrt(var + net.bn_eps) + p[2], rtol=1e-12, atol=1e-12)
+    a.relu = True
+    np.testing.assert_array_equal(lpref.auxnet_forward(a, img, p, net.bn_eps), np.maximum(x, 0.0))
+
+
+def test_workload_descriptors():
+    """Shapes of the five workloads (module inputs/outputs, block split, conv FLOPs per sample)."""
+    from workloads import configs as cfg
+    expect = {"tiny": ([1, 1], 0.0012), "resnet20": ([3, 2, 2, 2], 0.0816),
+              "resnet56": ([4, 4, 4, 3, 3, 3, 3, 3], 0.2515), "wrn28_10": ([3, 3, 3, 3], 10.49),
+              "resnet50": ([3, 4, 6, 3], 8.17)}
+    for name, (split, gf) in expect.items():
+        net = wl.make_config(name)
+        assert [len(m.blocks) for m in net.modules] == split
+        assert abs(cfg.conv_flops_forward(net) / net.modules[0].N / 1e9 - gf) < 0.006 * max(gf, 0.1) + 1e-4
+        for k in range(net.K - 1):
+            nx = net.modules[k + 1]
+            assert net.modules[k].out_shape() == (nx.N, nx.H, nx.W, nx.C)
+    w = wl.make_config("wrn28_10")
+    assert [(m.H, m.C) for m in w.modules] == [(32, 3), (32, 160), (16, 320), (8, 640)]
+    r = wl.make_config("resnet50")
+    assert [(m.H, m.C) for m in r.modules] == [(224, 3), (56, 256), (28, 512), (14, 1024)]

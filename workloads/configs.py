@@ -1,0 +1,229 @@
+"""Descriptors of the synthetic workloads (shapes only, no arithmetic).
+
+A network is K modules; module k is a stack of residual blocks with its own
+weights (Sec. 4.1, the feature-flow equation of the decoupled forward pass).
+The input layer S (stem) belongs to module 0 and the output layer T (head) to
+module K-1 (footnote of Sec. 4.2.1).  Auxiliary variable x_k is module k's input.
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+CONFIG_NAMES = ("tiny", "resnet20", "resnet56", "wrn28_10", "resnet50")
+
+
+@dataclass
+class Block:
+    kind: str          # "basic" (3x3,3x3) or "bottleneck" (1x1,3x3,1x1)
+    cin: int
+    cout: int
+    width: int         # bottleneck inner width (basic: == cout)
+    stride: int        # stride of the block (basic: first 3x3; bottleneck: the 3x3)
+    proj: bool         # 1x1 conv(stride)+BN on the skip path
+
+
+@dataclass
+class ModuleDesc:
+    stem: int          # 0 none, 1 conv3x3(3->stem_cout)+BN+ReLU, 2 conv7x7 s2 +BN+ReLU+maxpool3x3 s2
+    stem_cout: int
+    blocks: List[Block]
+    head: bool         # global avgpool + linear(+bias)
+    n_classes: int
+    N: int
+    H: int
+    W: int
+    C: int             # dims of the module input x_k, NHWC
+
+    def out_shape(self) -> Tuple[int, int, int, int]:
+        n, h, w, c = self.N, self.H, self.W, self.C
+        if self.stem == 1:
+            c = self.stem_cout
+        elif self.stem == 2:
+            h, w, c = h // 4, w // 4, self.stem_cout
+        for b in self.blocks:
+            h, w, c = h // b.stride, w // b.stride, b.cout
+        return n, h, w, c
+
+
+@dataclass
+class AuxDesc:
+    cin: int
+    cout: int
+    stride: int
+    relu: bool
+
+
+@dataclass
+class NetDesc:
+    name: str
+    K: int
+    modules: List[ModuleDesc]
+    aux: Optional[List[AuxDesc]]     # K-1 entries (x_1..x_{K-1} from the image) or None
+    dtype: str                       # "f32" or "bf16" (storage type; accumulation is fp32)
+    bn_eps: float = 1e-5
+    al: bool = False                 # augmented Lagrangian (multipliers present) vs penalty
+    rho: float = 1.0
+    lam_sigma: float = 0.0
+    noise_sigma: float = 0.1
+    step: float = 0.1                # multiplier step (learning rate / rho)
+    seed: int = 0
+
+
+@dataclass
+class TensorSpec:
+    name: str
+    kind: str          # "conv" | "bn_gamma" | "bn_beta" | "fc_w" | "fc_b"
+    shape: Tuple[int, ...]
+    fan_in: int = 0
+    block: int = -1    # -1 stem, n_blocks head, else block index
+    slot: int = 0      # conv slot inside the block: 0,1,2 main path; 3 projection
+
+
+def _split(blocks: List[Block], counts: List[int]) -> List[List[Block]]:
+    out, i = [], 0
+    for c in counts:
+        out.append(blocks[i:i + c])
+        i += c
+    assert i == len(blocks)
+    return out
+
+
+def _basic_stages(c0: int, widths: List[int], per_stage: int) -> List[Block]:
+    blocks, cin = [], c0
+    for si, c in enumerate(widths):
+        for bi in range(per_stage):
+            stride = 2 if (si > 0 and bi == 0) else 1
+            blocks.append(Block("basic", cin, c, c, stride, proj=(stride != 1 or cin != c)))
+            cin = c
+    return blocks
+
+
+def _assemble(name, per_module, n, h, w, c_img, stem, stem_cout, n_classes, **kw) -> NetDesc:
+    mods = []
+    K = len(per_module)
+    shape = (n, h, w, c_img)
+    for k, blks in enumerate(per_module):
+        m = ModuleDesc(stem=stem if k == 0 else 0, stem_cout=stem_cout if k == 0 else 0,
+                       blocks=blks, head=(k == K - 1), n_classes=n_classes,
+                       N=shape[0], H=shape[1], W=shape[2], C=shape[3])
+        shape = m.out_shape()
+        mods.append(m)
+    return NetDesc(name=name, K=K, modules=mods, aux=None, dtype="f32", **kw)
+
+
+def make_config(name: str, batch: Optional[int] = None) -> NetDesc:
+    """The five synthetic workloads; `batch` overrides the mini-batch size only."""
+    if name == "tiny":
+        n = batch or 4
+        blk = lambda: Block("basic", 16, 16, 16, 1, False)
+        net = _assemble("tiny", [[blk()], [blk()]], n, 8, 8, 16, 0, 0, 10, seed=0)
+        return net
+    if name == "resnet20":
+        n = batch or 128
+        blocks = _basic_stages(16, [16, 32, 64], 3)
+        net = _assemble("resnet20", _split(blocks, [3, 2, 2, 2]), n, 32, 32, 3, 1, 16, 10, seed=1)
+        return net
+    if name == "resnet56":
+        n = batch or 128
+        blocks = _basic_stages(16, [16, 32, 64], 9)
+        net = _assemble("resnet56", _split(blocks, [4, 4, 4, 3, 3, 3, 3, 3]), n, 32, 32, 3, 1, 16, 100,
+                        seed=2, al=True, lam_sigma=0.01)
+        net.dtype = "bf16"
+        net.aux = []
+        for m in net.modules[1:]:
+            net.aux.append(AuxDesc(cin=3, cout=m.C, stride=32 // m.H, relu=False))
+        return net
+    if name == "wrn28_10":
+        n = batch or 128
+        blocks = _basic_stages(16, [160, 320, 640], 4)
+        net = _assemble("wrn28_10", _split(blocks, [3, 3, 3, 3]), n, 32, 32, 3, 1, 16, 100,
+                        seed=3, al=True, lam_sigma=0.01)
+        net.dtype = "bf16"
+        return net
+    if name == "resnet50":
+        n = batch or 64
+        blocks, cin = [], 64
+        for si, (w, cnt) in enumerate(zip([64, 128, 256, 512], [3, 4, 6, 3])):
+            for bi in range(cnt):
+                stride = 2 if (si > 0 and bi == 0) else 1
+                blocks.append(Block("bottleneck", cin, 4 * w, w, stride, proj=(bi == 0)))
+                cin = 4 * w
+        net = _assemble("resnet50", _split(blocks, [3, 4, 6, 3]), n, 224, 224, 3, 2, 64, 1000, seed=4)
+        net.dtype = "bf16"
+        return net
+    raise ValueError(f"unknown config {name!r}; choose from {CONFIG_NAMES}")
+
+
+def block_convs(b: Block):
+    """(slot, R, cin, cout, stride, pad) of each convolution of a block, main path first."""
+    if b.kind == "basic":
+        convs = [(0, 3, b.cin, b.cout, b.stride, 1), (1, 3, b.cout, b.cout, 1, 1)]
+    else:
+        convs = [(0, 1, b.cin, b.width, 1, 0), (1, 3, b.width, b.width, b.stride, 1),
+                 (2, 1, b.width, b.cout, 1, 0)]
+    if b.proj:
+        convs.append((3, 1, b.cin, b.cout, b.stride, 0))
+    return convs
+
+
+def module_tensor_specs(m: ModuleDesc) -> List[TensorSpec]:
+    """Parameter tensors of one module in packing order.  Filters are KRSC."""
+    t: List[TensorSpec] = []
+    if m.stem:
+        r = 3 if m.stem == 1 else 7
+        t.append(TensorSpec("stem.conv", "conv", (m.stem_cout, r, r, m.C), r * r * m.C, -1, 0))
+        t.append(TensorSpec("stem.bn.gamma", "bn_gamma", (m.stem_cout,), 0, -1, 0))
+        t.append(TensorSpec("stem.bn.beta", "bn_beta", (m.stem_cout,), 0, -1, 0))
+    for i, b in enumerate(m.blocks):
+        for slot, r, ci, co, _, _ in block_convs(b):
+            nm = f"block{i}." + ("proj" if slot == 3 else f"conv{slot + 1}")
+            t.append(TensorSpec(nm, "conv", (co, r, r, ci), r * r * ci, i, slot))
+            t.append(TensorSpec(nm + ".bn.gamma", "bn_gamma", (co,), 0, i, slot))
+            t.append(TensorSpec(nm + ".bn.beta", "bn_beta", (co,), 0, i, slot))
+    if m.head:
+        c = m.out_shape()[3]
+        nb = len(m.blocks)
+        t.append(TensorSpec("head.fc.w", "fc_w", (m.n_classes, c), c, nb, 0))
+        t.append(TensorSpec("head.fc.b", "fc_b", (m.n_classes,), c, nb, 0))
+    return t
+
+
+def aux_tensor_specs(a: AuxDesc) -> List[TensorSpec]:
+    return [TensorSpec("aux.conv", "conv", (a.cout, 3, 3, a.cin), 9 * a.cin, -1, 0),
+            TensorSpec("aux.bn.gamma", "bn_gamma", (a.cout,), 0, -1, 0),
+            TensorSpec("aux.bn.beta", "bn_beta", (a.cout,), 0, -1, 0)]
+
+
+def module_conv_shapes(m: ModuleDesc):
+    """List of (M, Ngemm, Kgemm, needs_dgrad) for every convolution of the module."""
+    out = []
+    n, h, w, c = m.N, m.H, m.W, m.C
+    if m.stem == 1:
+        out.append((n * h * w, m.stem_cout, 9 * c, False))
+        c = m.stem_cout
+    elif m.stem == 2:
+        out.append((n * (h // 2) * (w // 2), m.stem_cout, 49 * c, False))
+        h, w, c = h // 4, w // 4, m.stem_cout
+    for b in m.blocks:
+        hh, ww = h, w
+        for slot, r, ci, co, st, _ in block_convs(b):
+            if slot == 3:
+                out.append((n * (h // b.stride) * (w // b.stride), co, ci, True))
+            else:
+                hh, ww = hh // st, ww // st
+                out.append((n * hh * ww, co, r * r * ci, True))
+        h, w, c = h // b.stride, w // b.stride, b.cout
+    return out
+
+
+def conv_flops_forward(net: NetDesc) -> float:
+    """2*M*Ngemm*Kgemm summed over every convolution of every module (one forward pass)."""
+    return float(sum(2.0 * M * Nn * Kk for m in net.modules for (M, Nn, Kk, _) in module_conv_shapes(m)))
+
+
+def conv_flops_step(net: NetDesc) -> float:
+    """Forward + wgrad for every conv, + dgrad for every conv except an image-facing stem."""
+    tot = 0.0
+    for m in net.modules:
+        for (M, Nn, Kk, dg) in module_conv_shapes(m):
+            tot += 2.0 * M * Nn * Kk * (3.0 if dg else 2.0)
+    return tot
