@@ -1,0 +1,168 @@
+/*
+ * lp.h - C ABI of the module-parallel local step on one MI355X (gfx950).
+ *
+ * One synchronous local step of the auxiliary-variable, module-parallel training of a residual
+ * network: each of K modules (a stack of residual blocks with its own weights) starts from its
+ * auxiliary variable x_k, runs its blocks forward, evaluates its local loss against x_{k+1}
+ * (cross-entropy for the last module) and back-propagates inside the module only.  All K modules
+ * are independent inside the step and are executed together as grouped kernel launches.
+ *
+ * Symbols (paper's letter in brackets):  x_k [lambda_k] auxiliary variable = input of module k,
+ * x_0 = the mini-batch;  F_k(x_k) [X^k_{kn+n}] output of module k;  lam_k [kappa_{k+1}] explicit
+ * multiplier on the interface produced by module k;  rho = 2*beta (the paper weights
+ * psi = ||.||^2, without 1/2, by beta).
+ *
+ * Conventions
+ *  - every tensor pointer is a DEVICE pointer owned by the caller and borrowed until the work
+ *    enqueued on `stream` has completed; `stream` is a hipStream_t passed as void* (NULL = default
+ *    stream); calls only enqueue work and return;
+ *  - activations are NHWC [N,H,W,C], filters KRSC [Cout,R,S,Cin]; tensors in the net's storage type
+ *    (LP_F32 or LP_BF16) are: x_k, F_k(x_k), lam_k, dy, dx, conv filters.  BN affine parameters, the
+ *    linear head, logits, losses and every parameter gradient are fp32.  All accumulation is fp32
+ *    (batch statistics are summed across tiles in fp64);
+ *  - arrays indexed by module have K entries, arrays indexed by interface have K-1 entries and entry
+ *    k belongs to the interface between module k and k+1 (y[k], x_next[k] = x_{k+1}, lam[k], dy[k]);
+ *  - `module_mask` bit k selects module k; entries of unselected modules may be NULL;
+ *  - every entry point returns lp_status and never throws; lp_last_error() gives the text of the
+ *    last failure on the calling thread.  All argument checks run on the host.
+ */
+#ifndef LP_H
+#define LP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LP_OK = 0,
+    LP_ERR_INVALID_ARG = 1,   /* NULL required pointer, K < 1, mask beyond K, misaligned tensor, rho < 0 */
+    LP_ERR_SHAPE = 2,         /* inconsistent block chain, H or W not divisible by a stride           */
+    LP_ERR_DTYPE = 3,
+    LP_ERR_WORKSPACE = 4,     /* workspace missing or too small                                      */
+    LP_ERR_STATE = 5,         /* backward without a matching forward                                  */
+    LP_ERR_HIP = 6            /* a HIP call or kernel launch failed                                   */
+} lp_status;
+
+typedef enum { LP_F32 = 0, LP_BF16 = 1 } lp_dtype;
+typedef enum { LP_BLOCK_BASIC = 0, LP_BLOCK_BOTTLENECK = 1 } lp_block_kind;
+
+/* Residual block X_{m+1} = skip(X_m) + F(X_m, W_m)  (Sec. 2.1 and the feature flow of Sec. 4.1).
+ * basic:      F = conv3x3(stride) - BN - ReLU - conv3x3 - BN
+ * bottleneck: F = conv1x1 - BN - ReLU - conv3x3(stride) - BN - ReLU - conv1x1 - BN   (inner width `width`)
+ * skip = identity, or conv1x1(stride) - BN when `proj` is set.  There is no ReLU after the sum. */
+typedef struct {
+    int kind;      /* lp_block_kind */
+    int cin, cout;
+    int width;     /* bottleneck inner width; ignored for basic blocks */
+    int stride;    /* 1 or 2 */
+    int proj;      /* required when stride != 1 or cin != cout */
+} lp_block_desc;
+
+/* Module k: [input layer S] + blocks + [output layer T]  (S and T belong to the first and last worker,
+ * footnote in Sec. 4.2.1).  stem 0: none; 1: conv3x3(C -> stem_cout) - BN - ReLU;
+ * 2: conv7x7 stride 2 pad 3 - BN - ReLU - maxpool3x3 stride 2 pad 1.  head: global average pool then
+ * linear(+bias) to n_classes.  N,H,W,C: shape of the module input x_k. */
+typedef struct {
+    int stem, stem_cout;
+    int n_blocks;
+    const lp_block_desc* blocks;   /* host pointer, copied by lp_net_create */
+    int head, n_classes;
+    int N, H, W, C;
+} lp_module_desc;
+
+/* One AuxNet block generating x_{j+1} from the mini-batch (Sec. 4.2, forward map of the auxiliary-variable
+ * network, in its one-block form): conv3x3(cin -> cout, stride, pad 1) - BN(batch statistics) [- ReLU]. */
+typedef struct { int cin, cout, stride, relu; } lp_aux_desc;
+
+typedef enum { LP_T_CONV = 0, LP_T_BN_GAMMA = 1, LP_T_BN_BETA = 2, LP_T_FC_W = 3, LP_T_FC_B = 4 } lp_tensor_kind;
+
+/* One parameter tensor inside a module's packed parameter buffer.  The gradient buffer of the module
+ * holds the same tensors in the same order, all fp32, at `grad_offset`. */
+typedef struct {
+    int kind;              /* lp_tensor_kind */
+    int block;             /* -1 stem, 0..n_blocks-1, n_blocks = head */
+    int slot;              /* conv index inside the block: 0,1,2 main path, 3 projection */
+    int dtype;             /* lp_dtype of the parameter itself */
+    int ndim;
+    int dims[4];
+    size_t offset;         /* byte offset in the parameter buffer (256-byte aligned) */
+    size_t grad_offset;    /* byte offset in the fp32 gradient buffer (256-byte aligned) */
+    size_t numel;
+} lp_tensor_info;
+
+struct lp_net;
+
+/* Build the launch plan for K modules (and K-1 AuxNet blocks when aux != NULL).  Host only: no device
+ * memory is touched.  Descriptors are copied.  Errors: LP_ERR_INVALID_ARG, LP_ERR_SHAPE, LP_ERR_DTYPE. */
+lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* aux, int dtype, float bn_eps,
+                        struct lp_net** out);
+lp_status lp_net_destroy(struct lp_net* net);
+
+/* Packed parameter layout of module k (aux = 0) or of AuxNet block k (aux = 1). */
+lp_status lp_net_param_bytes(const struct lp_net* net, int aux, int k, size_t* param_bytes, size_t* grad_bytes);
+lp_status lp_net_num_tensors(const struct lp_net* net, int aux, int k, int* n);
+lp_status lp_net_tensor_info(const struct lp_net* net, int aux, int k, int i, lp_tensor_info* info);
+
+/* Workspace: saved activations, batch statistics, gradient scratch, re-laid-out filters.  The caller
+ * allocates `bytes` of device memory (256-byte aligned) and lends it for the lifetime of the net. */
+lp_status lp_net_workspace_bytes(const struct lp_net* net, size_t* bytes);
+lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes);
+
+/* x_{j+1} = AuxNet_j(image), j = 0..K-2  (Sec. 4.2; first loop of Algorithm 1, from-the-image form).
+ * image: [N,H,W,C] of module 0.  aux_params[j]: packed parameters of AuxNet block j.  x_out[j]: x_{j+1}. */
+lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
+                            const void* const* aux_params, void* const* x_out);
+
+/* Decoupled forward pass of the selected modules (feature-flow equation of Sec. 4.1):
+ * X = x_k; X <- skip(X) + F(X, W) for every block; y[k] = F_k(x_k) for k < K-1; the last module writes
+ * logits [N, n_classes] (fp32).  Saves what the backward pass needs in the workspace. */
+lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_mask,
+                            const void* const* x, const void* const* params,
+                            void* const* y, float* logits);
+
+/* Local losses and terminal adjoints (penalty functional of Sec. 3.2 / augmented Lagrangian of Sec. 3.3;
+ * terminal condition of the discrete adjoint in Sec. 4.1).  For k < K-1, with r = y[k] - x_next[k]:
+ *   loss[k] = loss_scale * (rho/2 * sum r^2 + sum lam[k]*r),   dy[k] = loss_scale * (rho*r + lam[k]);
+ * lam == NULL (or lam[k] == NULL) is the penalty method.  For k = K-1: loss[K-1] = mini-batch mean of the
+ * softmax cross-entropy of logits against labels (int32 [N], values in [0, n_classes)), and
+ * dlogits = (softmax - onehot)/N.  loss: K fp32 device scalars (overwritten). */
+lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_mask,
+                             const void* const* y, const void* const* x_next, const void* const* lam,
+                             float rho, float loss_scale,
+                             const float* logits, const int32_t* labels,
+                             float* loss, void* const* dy, float* dlogits);
+
+/* Module-local back-propagation (discrete adjoint recursion and weight gradient of Sec. 4.1) from the
+ * terminal adjoint dy[k] (k < K-1) or dlogits (k = K-1).  dparams[k]: fp32 gradient buffer of module k
+ * (overwritten).  dx[k]: gradient with respect to x_k, written for k >= 1, and for k = 0 only when module 0
+ * has no stem and dx[0] != NULL.  Requires lp_module_forward of the same modules since the last backward:
+ * otherwise LP_ERR_STATE. */
+lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_mask,
+                             const void* const* dy, const float* dlogits, const void* const* params,
+                             float* const* dparams, void* const* dx);
+
+/* Multiplier update of Sec. 4.1: lam[k] <- lam[k] + step * (y[k] - x_next[k]) for every interface k with
+ * lam[k] != NULL (the paper's step is eta/(2*beta) = eta/rho). */
+lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const* lam,
+                                  const void* const* y, const void* const* x_next, float step);
+
+/* Flat NHWC offset read by element (m, q) of the implicit-GEMM operand of a forward convolution as the
+ * device kernels compute it (m = output pixel index, q = (r*S+s)*Cin+ci), -1 in the padding.  Evaluated on
+ * the device for `count` (m,q) pairs; out: int64 [count] device.  For bit-exact address checks. */
+lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, int S, int stride, int pad,
+                                  const int64_t* m, const int64_t* q, int64_t* out, int count);
+
+/* Read-only view of a saved activation after lp_module_forward (for layer-wise checks): which = 0 output of
+ * the stem, 1 + 8*block + {0,1,2: pre-BN conv output of slot, 3: projection conv output, 4: block output}. */
+lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel);
+
+const char* lp_last_error(void);
+const char* lp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LP_H */

@@ -19,6 +19,14 @@ What follows what:
                        gradient P_{m+1} dF/dW of Sec. 4.1
   auxnet_forward     - AuxNet forward map of Sec. 4.2 in its one-block, from-the-image form
   multiplier_update  - multiplier update rule of Sec. 4.1
+
+Storage rounding.  Every routine that composes layers takes `q`, a callable applied where the
+bf16 mode of the method stores a tensor (conv output before BN, activation after BN+ReLU, block
+output, every stored gradient); q=None (the default) is the plain float64 definition, and that is
+what the pins exercise.  With q = round-to-bf16 the oracle is the same sequence of definitions with
+each stored tensor rounded once, so that decisions taken from stored values (the ReLU mask, the
+pooling argmax) are taken in the precision the bf16 mode defines.  Batch statistics are taken from
+the unrounded convolution result and applied to the stored one, as the bf16 mode specifies.
 """
 import ctypes
 import os
@@ -132,12 +140,17 @@ def maxpool_bwd(dy, idx, x_shape):
     return dx
 
 
-def bn_fwd(y, gamma, beta, eps):
-    """Training-mode batch norm: per-channel mean and biased variance over N*H*W."""
+def _id(a):
+    return a
+
+
+def bn_fwd(y, gamma, beta, eps, q=None):
+    """Training-mode batch norm: per-channel mean and biased variance over N*H*W.
+    With storage rounding q the statistics come from y and are applied to q(y)."""
     mean = y.mean(axis=(0, 1, 2))
     var = ((y - mean) ** 2).mean(axis=(0, 1, 2))
     invstd = 1.0 / np.sqrt(var + eps)
-    yhat = (y - mean) * invstd
+    yhat = ((y if q is None else q(y)) - mean) * invstd
     return gamma * yhat + beta, (yhat, invstd)
 
 
@@ -152,78 +165,92 @@ def bn_bwd(dz, cache, gamma):
 
 
 # ----------------------------------------------------------------------------- conv+BN unit
-def _cbr_fwd(x, w, gamma, beta, stride, pad, relu, eps):
+def _cbr_fwd(x, w, gamma, beta, stride, pad, relu, eps, q=None):
+    """conv -> BN(batch statistics) [-> ReLU].  The result is NOT rounded here (the caller stores it)."""
     y = conv_fwd(x, w, stride, pad)
-    z, bc = bn_fwd(y, gamma, beta, eps)
+    z, bc = bn_fwd(y, gamma, beta, eps, q)
     a = np.maximum(z, 0.0) if relu else z
     return a, (x, w, gamma, bc, z if relu else None, stride, pad)
 
 
-def _cbr_bwd(da, cache, need_dx=True):
+def _cbr_bwd(da, cache, need_dx=True, q=None):
+    """Returns the unrounded data-gradient (the caller stores it) and [dW, dgamma, dbeta]."""
+    q = q or _id
     x, w, gamma, bc, z, stride, pad = cache
     dz = da * (z > 0.0) if z is not None else da          # ReLU gradient is 0 at exactly 0
     dy, dgamma, dbeta = bn_bwd(dz, bc, gamma)
+    dy = q(dy)
     dw = conv_wgrad(x, dy, w.shape, stride, pad)
     dx = conv_dgrad(dy, w, x.shape, stride, pad) if need_dx else None
     return dx, [dw, dgamma, dbeta]
 
 
 # ----------------------------------------------------------------------------- residual block
-def block_forward(x, p, b: Block, eps):
+def block_forward(x, p, b: Block, eps, q=None):
     """X_{m+1} = skip(X_m) + F(X_m, W_m); F = conv-BN-ReLU ... conv-BN (no ReLU after the add)."""
+    qq = q or _id
     convs = block_convs(b)
     main = [c for c in convs if c[0] != 3]
     caches, a, i = [], x, 0
     for j, (_, r, ci, co, st, pad) in enumerate(main):
-        a, c = _cbr_fwd(a, p[i], p[i + 1], p[i + 2], st, pad, relu=(j < len(main) - 1), eps=eps)
+        inner = j < len(main) - 1
+        a, c = _cbr_fwd(a, p[i], p[i + 1], p[i + 2], st, pad, relu=inner, eps=eps, q=q)
+        if inner:
+            a = qq(a)                      # activation between two convolutions is stored
         caches.append(c)
         i += 3
     if b.proj:
         _, r, ci, co, st, pad = convs[-1]
-        s, pc = _cbr_fwd(x, p[i], p[i + 1], p[i + 2], st, pad, relu=False, eps=eps)
+        s, pc = _cbr_fwd(x, p[i], p[i + 1], p[i + 2], st, pad, relu=False, eps=eps, q=q)
     else:
         s, pc = x, None
-    return s + a, (caches, pc)
+    return qq(s + a), (caches, pc)         # the block output is stored
 
 
-def block_backward(dout, cache, need_dx=True):
+def block_backward(dout, cache, need_dx=True, q=None):
+    qq = q or _id
     caches, pc = cache
     grads = []
     da = dout
     for j in range(len(caches) - 1, -1, -1):
-        da, g = _cbr_bwd(da, caches[j], need_dx=(need_dx or j > 0))
+        da, g = _cbr_bwd(da, caches[j], need_dx=(need_dx or j > 0), q=q)
+        if j > 0:
+            da = qq(da)                    # gradient of a stored activation is stored
         grads = g + grads
     dx = da
     if pc is not None:
-        dxp, g = _cbr_bwd(dout, pc, need_dx=need_dx)
+        dxp, g = _cbr_bwd(dout, pc, need_dx=need_dx, q=q)
         grads = grads + g
         if need_dx:
-            dx = dx + dxp
+            dx = qq(dx + qq(dxp))          # the projection's data-gradient is stored, then added
     elif need_dx:
-        dx = dx + dout
+        dx = qq(dx + dout)
     return dx, grads
 
 
 # ----------------------------------------------------------------------------- module
-def module_forward(m: ModuleDesc, x, params, eps=1e-5):
+def module_forward(m: ModuleDesc, x, params, eps=1e-5, q=None):
     """Returns (F_k(x_k), logits or None, cache).  params: list in workloads.module_tensor_specs order."""
+    qq = q or _id
     p = [_c64(t) for t in params]
     a = _c64(x)
     cache = {"stem": None, "blocks": [], "head": None, "in_shape": a.shape}
     i = 0
     if m.stem == 1:
-        a, c = _cbr_fwd(a, p[0], p[1], p[2], 1, 1, True, eps)
+        a, c = _cbr_fwd(a, p[0], p[1], p[2], 1, 1, True, eps, q)
+        a = qq(a)
         cache["stem"] = (c, None)
         i = 3
     elif m.stem == 2:
-        a, c = _cbr_fwd(a, p[0], p[1], p[2], 2, 3, True, eps)
+        a, c = _cbr_fwd(a, p[0], p[1], p[2], 2, 3, True, eps, q)
+        a = qq(a)
         pre_shape = a.shape
         a, idx = maxpool_fwd(a, 3, 2, 1)
         cache["stem"] = (c, (idx, pre_shape))
         i = 3
     for b in m.blocks:
         n = 3 * len(block_convs(b))
-        a, c = block_forward(a, p[i:i + n], b, eps)
+        a, c = block_forward(a, p[i:i + n], b, eps, q)
         cache["blocks"].append(c)
         i += n
     logits = None
@@ -234,17 +261,18 @@ def module_forward(m: ModuleDesc, x, params, eps=1e-5):
     return a, logits, cache
 
 
-def module_backward(m: ModuleDesc, cache, dy=None, dlogits=None, need_dx=True):
+def module_backward(m: ModuleDesc, cache, dy=None, dlogits=None, need_dx=True, q=None):
     """Module-local back-propagation from the terminal adjoint: dy (on F_k(x_k)) or dlogits (last module).
 
     Returns (dparams list in packing order, dx_k or None)."""
+    qq = q or _id
     tail = []
     if m.head:
         pooled, wfc, shp = cache["head"]
         dwfc = dlogits.T @ pooled
         dbfc = dlogits.sum(axis=0)
         dpooled = dlogits @ wfc
-        g = np.broadcast_to(dpooled[:, None, None, :] / (shp[1] * shp[2]), shp).copy()
+        g = qq(np.broadcast_to(dpooled[:, None, None, :] / (shp[1] * shp[2]), shp).copy())
         tail = [dwfc, dbfc]
     else:
         g = _c64(dy)
@@ -252,13 +280,15 @@ def module_backward(m: ModuleDesc, cache, dy=None, dlogits=None, need_dx=True):
     nb = len(cache["blocks"])
     for j in range(nb - 1, -1, -1):
         first = (j == 0 and cache["stem"] is None)
-        g, bg = block_backward(g, cache["blocks"][j], need_dx=(need_dx or not first))
+        g, bg = block_backward(g, cache["blocks"][j], need_dx=(need_dx or not first), q=q)
         grads = bg + grads
     if cache["stem"] is not None:
         c, mp = cache["stem"]
         if mp is not None:
-            g = maxpool_bwd(g, mp[0], mp[1])
-        g, sg = _cbr_bwd(g, c, need_dx=need_dx)
+            g = qq(maxpool_bwd(g, mp[0], mp[1]))
+        g, sg = _cbr_bwd(g, c, need_dx=need_dx, q=q)
+        if g is not None:
+            g = qq(g)
         grads = sg + grads
     return grads + tail, (g if need_dx else None)
 
@@ -295,15 +325,15 @@ def multiplier_update(lam, y, x_next, step):
     return _c64(lam) + step * (_c64(y) - _c64(x_next))
 
 
-def auxnet_forward(a: AuxDesc, image, params, eps=1e-5):
+def auxnet_forward(a: AuxDesc, image, params, eps=1e-5, q=None):
     """x = [ReLU](BN(conv3x3_stride(image)))."""
     out, _ = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]),
-                      a.stride, 1, a.relu, eps)
-    return out
+                      a.stride, 1, a.relu, eps, q)
+    return out if q is None else q(out)
 
 
 # ----------------------------------------------------------------------------- whole step / serial net
-def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=False):
+def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=False, q=None):
     """One synchronous local step of all K modules.
 
     xs: [x_0 (image), x_1, ..., x_{K-1}]; lams: K-1 multipliers or None (penalty).
@@ -313,17 +343,19 @@ def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=
     out = {"y": [], "loss": [], "dy": [], "dparams": [], "dx": [], "logits": None, "dlogits": None}
     for k in range(K):
         m = net.modules[k]
-        y, logits, cache = module_forward(m, xs[k], params[k], net.bn_eps)
+        y, logits, cache = module_forward(m, xs[k], params[k], net.bn_eps, q)
         out["y"].append(y)
         if k < K - 1:
             lam = None if lams is None else lams[k]
             loss, dy = local_loss_grad(y, xs[k + 1], lam, net.rho, scale)
+            if q is not None:
+                dy = q(dy)
             out["dy"].append(dy)
-            dp, dx = module_backward(m, cache, dy=dy, need_dx=(k > 0 or need_dx0))
+            dp, dx = module_backward(m, cache, dy=dy, need_dx=(k > 0 or need_dx0), q=q)
         else:
             loss, dz = ce_loss_grad(logits, labels)
             out["logits"], out["dlogits"] = logits, dz
-            dp, dx = module_backward(m, cache, dlogits=dz, need_dx=(k > 0 or need_dx0))
+            dp, dx = module_backward(m, cache, dlogits=dz, need_dx=(k > 0 or need_dx0), q=q)
         out["loss"].append(loss)
         out["dparams"].append(dp)
         out["dx"].append(dx)

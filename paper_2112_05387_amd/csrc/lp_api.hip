@@ -1,0 +1,1108 @@
+// Host side of the local-step library: descriptor validation, packed parameter layout, workspace layout,
+// the per-module operation lists of the forward and backward passes, and the scheduler that merges the same
+// operation of different modules into one grouped launch (the K local steps of Sec. 4.1 are independent, so
+// they are advanced in lock-step on one GPU).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/lp.h"
+#include "lp_kernels.h"
+
+using namespace lp;
+
+// ----------------------------------------------------------------------------------------------------
+// errors
+// ----------------------------------------------------------------------------------------------------
+static thread_local std::string g_err;
+
+static lp_status fail(lp_status st, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return st;
+}
+
+// ----------------------------------------------------------------------------------------------------
+// plan structures
+// ----------------------------------------------------------------------------------------------------
+namespace {
+
+enum Space { SP_NONE = 0, SP_WS, SP_X, SP_Y, SP_PARAM, SP_DPARAM, SP_DY, SP_DX, SP_LOGITS, SP_DLOGITS,
+             SP_AUXP, SP_XOUT, SP_IMAGE };
+struct Ref { int space = SP_NONE; int idx = 0; size_t off = 0; };
+static Ref mk(int sp, int idx, size_t off) { Ref r; r.space = sp; r.idx = idx; r.off = off; return r; }
+
+struct Bindings {
+    char* ws = nullptr;
+    const void* const* x = nullptr;
+    void* const* y = nullptr;
+    const void* const* params = nullptr;
+    float* const* dparams = nullptr;
+    const void* const* dy = nullptr;
+    void* const* dx = nullptr;
+    float* logits = nullptr;
+    const float* dlogits = nullptr;
+    const void* const* auxp = nullptr;
+    void* const* xout = nullptr;
+    const void* image = nullptr;
+};
+static void* resolve(const Ref& r, const Bindings& b) {
+    switch (r.space) {
+        case SP_WS: return b.ws + r.off;
+        case SP_X: return (char*)b.x[r.idx] + r.off;
+        case SP_Y: return (char*)b.y[r.idx] + r.off;
+        case SP_PARAM: return (char*)b.params[r.idx] + r.off;
+        case SP_DPARAM: return (char*)b.dparams[r.idx] + r.off;
+        case SP_DY: return (char*)b.dy[r.idx] + r.off;
+        case SP_DX: return (char*)b.dx[r.idx] + r.off;
+        case SP_LOGITS: return (char*)b.logits + r.off;
+        case SP_DLOGITS: return (char*)b.dlogits + r.off;
+        case SP_AUXP: return (char*)b.auxp[r.idx] + r.off;
+        case SP_XOUT: return (char*)b.xout[r.idx] + r.off;
+        case SP_IMAGE: return (char*)b.image + r.off;
+        default: return nullptr;
+    }
+}
+
+enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD };
+
+struct Op {
+    int type = 0, cfg = 0;
+    bool vec = true;
+    Ref r[10];
+    size_t fill_bytes = 0;
+    ConvProb conv;
+    WgradProb wg;
+    WtransProb wt;
+    BnApplyProb bna;
+    BnBwdProb bnb;
+    PoolProb pool;
+    HeadProb head;
+    int key() const { return type * 64 + cfg * 2 + (vec ? 1 : 0); }
+};
+typedef std::vector<Op> Step;              // operations of one module that may run concurrently
+typedef std::vector<Step> Program;         // steps run in order
+
+// one conv + batch-norm unit
+struct Unit {
+    int R = 3, cin = 0, cout = 0, stride = 1, pad = 1;
+    int N = 0, H = 0, W = 0, Ho = 0, Wo = 0;
+    bool relu = false, need_dgrad = true;
+    int t_w = -1, t_g = -1, t_b = -1;      // tensor table indices
+    size_t ws_y = 0, ws_stats = 0, ws_red = 0, ws_wt = 0;
+    size_t out_elems() const { return (size_t)N * Ho * Wo * cout; }
+    size_t in_elems() const { return (size_t)N * H * W * cin; }
+};
+struct BlockPlan {
+    std::vector<Unit> main;                // 2 (basic) or 3 (bottleneck)
+    bool has_proj = false;
+    Unit proj;
+    std::vector<size_t> ws_act;            // activations between main convs
+    Ref in, out;                           // block input / output tensors
+    size_t in_elems = 0, out_elems = 0;
+};
+struct ModulePlan {
+    lp_module_desc d;
+    std::vector<lp_block_desc> blocks;
+    std::vector<lp_tensor_info> tensors;
+    size_t param_bytes = 0, grad_bytes = 0;
+    bool has_stem = false;
+    Unit stem;
+    size_t ws_stem_act = 0;                // stem output (after ReLU; before pooling for stem 2)
+    size_t ws_pool_out = 0, ws_pool_arg = 0;
+    int pH = 0, pW = 0;                    // dims after the stem conv (pool input)
+    std::vector<BlockPlan> bp;
+    int oN = 0, oH = 0, oW = 0, oC = 0;    // F_k(x_k) shape
+    size_t ws_feat = 0;                    // last module: F_k(x_k)
+    size_t ws_pooled = 0, ws_dfeat = 0;
+    int t_fcw = -1, t_fcb = -1;
+    size_t ws_stats0 = 0, ws_stats_bytes = 0, ws_red0 = 0, ws_red_bytes = 0;
+    size_t ws_G[2] = {0, 0}, ws_D = 0, ws_Dp = 0, ws_A = 0, ws_P = 0, ws_gpool = 0;
+    Program fwd, bwd, bwd_dx0;             // bwd_dx0: variant that also produces dx for a stem-less module 0
+};
+struct AuxPlan {
+    lp_aux_desc d;
+    Unit u;
+    std::vector<lp_tensor_info> tensors;
+    size_t param_bytes = 0, grad_bytes = 0;
+    Program fwd;
+};
+
+}  // namespace
+
+struct lp_net {
+    int K = 0, dtype = 0;
+    float eps = 1e-5f;
+    size_t esz = 4;
+    std::vector<ModulePlan> mods;
+    std::vector<AuxPlan> aux;
+    size_t ws_bytes = 0;
+    char* ws = nullptr;
+    size_t ws_given = 0;
+    uint32_t fwd_done = 0;
+    std::vector<const void*> saved_x;
+};
+
+namespace {
+
+static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+static int conv_cfg_for(int ncol, bool vec) {
+    int cfg;
+    if (ncol % 160 == 0) cfg = CFG_N160;
+    else if (ncol <= 16) cfg = CFG_N16;
+    else if (ncol <= 32) cfg = CFG_N32;
+    else if (ncol <= 64) cfg = CFG_N64;
+    else cfg = CFG_N128;
+    if (!vec && cfg > CFG_N64) cfg = CFG_N64;
+    return cfg;
+}
+static int wgrad_cfg_for(int cout, int kg, bool vec) {
+    int cfg;
+    if (cout % 160 == 0 && kg % 160 == 0) cfg = CFG_N160;
+    else if (cout <= 16) cfg = CFG_N16;
+    else if (cout <= 32) cfg = CFG_N32;
+    else if (cout <= 64) cfg = CFG_N64;
+    else cfg = CFG_N128;
+    if (!vec && cfg > CFG_N64) cfg = CFG_N64;
+    return cfg;
+}
+
+struct Builder {
+    lp_net* net;
+    int epv() const { return net->dtype == LP_BF16 ? 8 : 4; }
+
+    // ---- op constructors ------------------------------------------------------------------------
+    Op fill(Ref p, size_t bytes) const {
+        Op o; o.type = OP_FILL; o.r[0] = p; o.fill_bytes = bytes; return o;
+    }
+    Op conv_fwd(const Unit& u, Ref in, Ref w, Ref out, Ref stats) const {
+        Op o; o.type = OP_CONV;
+        ConvProb& c = o.conv; memset(&c, 0, sizeof(c));
+        c.M = u.N * u.Ho * u.Wo; c.Ncol = u.cout; c.Cin = u.cin; c.Kg = u.R * u.R * u.cin;
+        c.OA = u.Ho; c.OB = u.Wo; c.IH = u.H; c.IW = u.W; c.imul = u.stride;
+        c.ntr = u.R; c.nts = u.R; c.dh0 = -u.pad; c.dhs = 1; c.dw0 = -u.pad; c.dws = 1;
+        c.r0 = 0; c.rs = 1; c.s0 = 0; c.ss = 1; c.S = u.R; c.ldw = c.Kg;
+        c.OH = u.Ho; c.OW = u.Wo; c.omul = 1; c.ooh = 0; c.oow = 0;
+        o.vec = (u.cin % epv()) == 0;
+        o.cfg = conv_cfg_for(c.Ncol, o.vec);
+        o.r[0] = in; o.r[1] = w; o.r[2] = out; o.r[5] = stats;
+        return o;
+    }
+    // data-gradient of unit u: dX[N,H,W,cin] from dY[N,Ho,Wo,cout] and the re-laid-out filters [cin][R][R][cout]
+    void conv_dgrad(const Unit& u, Ref dy, Ref wt, Ref dx, Ref add0, Ref add1, Step& step) const {
+        const int st = u.stride;
+        for (int ph = 0; ph < st; ++ph)
+            for (int pw = 0; pw < st; ++pw) {
+                Op o; o.type = OP_CONV;
+                ConvProb& c = o.conv; memset(&c, 0, sizeof(c));
+                c.Ncol = u.cin; c.Cin = u.cout; c.S = u.R; c.ldw = u.R * u.R * u.cout;
+                c.IH = u.Ho; c.IW = u.Wo; c.imul = 1;
+                c.OH = u.H; c.OW = u.W; c.omul = st; c.ooh = ph; c.oow = pw;
+                c.OA = u.H / st; c.OB = u.W / st;
+                c.M = u.N * c.OA * c.OB;
+                // taps r with (ph + pad - r) divisible by the stride; source row = a + (ph + pad - r)/stride
+                c.r0 = (ph + u.pad) % st; c.rs = st;
+                c.ntr = c.r0 < u.R ? (u.R - c.r0 + st - 1) / st : 0;
+                c.dh0 = (ph + u.pad - c.r0) / st; c.dhs = -1;
+                c.s0 = (pw + u.pad) % st; c.ss = st;
+                c.nts = c.s0 < u.R ? (u.R - c.s0 + st - 1) / st : 0;
+                c.dw0 = (pw + u.pad - c.s0) / st; c.dws = -1;
+                if (c.ntr == 0 || c.nts == 0) { c.ntr = 0; c.nts = 1; }
+                c.Kg = c.ntr * c.nts * c.Cin;
+                o.vec = (u.cout % epv()) == 0;
+                o.cfg = conv_cfg_for(c.Ncol, o.vec);
+                o.r[0] = dy; o.r[1] = wt; o.r[2] = dx; o.r[3] = add0; o.r[4] = add1;
+                step.push_back(o);
+            }
+    }
+    Op wgrad(const Unit& u, Ref x, Ref dy, Ref dw) const {
+        Op o; o.type = OP_WGRAD;
+        WgradProb& w = o.wg; memset(&w, 0, sizeof(w));
+        w.M = u.N * u.Ho * u.Wo; w.Cout = u.cout; w.Cin = u.cin; w.Kg = u.R * u.R * u.cin;
+        w.Ho = u.Ho; w.Wo = u.Wo; w.IH = u.H; w.IW = u.W; w.stride = u.stride; w.pad = u.pad; w.R = u.R; w.S = u.R;
+        o.vec = (u.cin % epv()) == 0;
+        o.cfg = wgrad_cfg_for(u.cout, w.Kg, o.vec);
+        const CfgInfo ci = wgrad_cfg_info(o.cfg, net->dtype);
+        int ks = (w.M + 4095) / 4096;
+        ks = std::max(1, std::min(ks, 64));
+        int chunk = (w.M + ks - 1) / ks;
+        chunk = (chunk + ci.BK - 1) / ci.BK * ci.BK;
+        ks = (w.M + chunk - 1) / chunk;
+        w.ksplit = ks; w.kchunk = chunk;
+        w.tiles_m = (w.Cout + ci.BM - 1) / ci.BM; w.tiles_n = (w.Kg + ci.BN - 1) / ci.BN;
+        o.r[0] = x; o.r[1] = dy; o.r[2] = dw;
+        return o;
+    }
+    Op wtrans(const Unit& u, Ref w, Ref wt) const {
+        Op o; o.type = OP_WTRANS;
+        memset(&o.wt, 0, sizeof(o.wt));
+        o.wt.Cout = u.cout; o.wt.RS = u.R * u.R; o.wt.Cin = u.cin;
+        o.r[0] = w; o.r[1] = wt;
+        return o;
+    }
+    Op bn_apply(int M, int C, Ref y, Ref out, Ref stats, Ref gamma, Ref beta, bool relu,
+                int skip_mode = 0, Ref skip = Ref(), Ref sstats = Ref(), Ref sgamma = Ref(), Ref sbeta = Ref()) const {
+        Op o; o.type = OP_BN_APPLY;
+        memset(&o.bna, 0, sizeof(o.bna));
+        o.bna.M = M; o.bna.C = C; o.bna.relu = relu; o.bna.skip_mode = skip_mode;
+        o.r[0] = y; o.r[1] = out; o.r[2] = stats; o.r[3] = gamma; o.r[4] = beta;
+        o.r[5] = skip; o.r[6] = sstats; o.r[7] = sgamma; o.r[8] = sbeta;
+        return o;
+    }
+    Op bn_bwd(int type, int M, int C, Ref g, Ref y, Ref dy, Ref stats, Ref gamma, Ref beta, Ref red, Ref dgamma,
+              Ref dbeta, bool relu) const {
+        Op o; o.type = type;
+        memset(&o.bnb, 0, sizeof(o.bnb));
+        o.bnb.M = M; o.bnb.C = C; o.bnb.relu = relu;
+        o.r[0] = g; o.r[1] = y; o.r[2] = dy; o.r[3] = stats; o.r[4] = gamma; o.r[5] = beta; o.r[6] = red;
+        o.r[7] = dgamma; o.r[8] = dbeta;
+        return o;
+    }
+};
+
+static Ref param_ref(const ModulePlan& m, int k, int t) { return mk(SP_PARAM, k, m.tensors[t].offset); }
+static Ref grad_ref(const ModulePlan& m, int k, int t) { return mk(SP_DPARAM, k, m.tensors[t].grad_offset); }
+
+static void add_tensor(std::vector<lp_tensor_info>& v, size_t& poff, size_t& goff, int kind, int block, int slot,
+                       int dtype, std::initializer_list<int> dims) {
+    lp_tensor_info t;
+    memset(&t, 0, sizeof(t));
+    t.kind = kind; t.block = block; t.slot = slot; t.dtype = dtype; t.ndim = (int)dims.size();
+    size_t n = 1; int i = 0;
+    for (int d : dims) { t.dims[i++] = d; n *= (size_t)d; }
+    t.numel = n;
+    t.offset = poff; t.grad_offset = goff;
+    poff = align_up(poff + n * (dtype == LP_BF16 ? 2 : 4));
+    goff = align_up(goff + n * 4);
+    v.push_back(t);
+}
+static void add_unit_tensors(std::vector<lp_tensor_info>& v, size_t& poff, size_t& goff, Unit& u, int block, int slot,
+                             int dtype) {
+    u.t_w = (int)v.size();
+    add_tensor(v, poff, goff, LP_T_CONV, block, slot, dtype, {u.cout, u.R, u.R, u.cin});
+    u.t_g = (int)v.size();
+    add_tensor(v, poff, goff, LP_T_BN_GAMMA, block, slot, LP_F32, {u.cout});
+    u.t_b = (int)v.size();
+    add_tensor(v, poff, goff, LP_T_BN_BETA, block, slot, LP_F32, {u.cout});
+}
+
+static Unit make_unit(int R, int cin, int cout, int stride, int pad, int N, int H, int W, bool relu) {
+    Unit u;
+    u.R = R; u.cin = cin; u.cout = cout; u.stride = stride; u.pad = pad; u.N = N; u.H = H; u.W = W;
+    u.Ho = (H + 2 * pad - R) / stride + 1; u.Wo = (W + 2 * pad - R) / stride + 1;
+    u.relu = relu;
+    return u;
+}
+
+struct WsAlloc {
+    size_t off = 0;
+    size_t take(size_t bytes) { const size_t o = off; off = align_up(off + std::max<size_t>(bytes, 16)); return o; }
+};
+
+// ---- build one module: units, tensors, workspace, programs ------------------------------------------------
+static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
+    ModulePlan& m = net->mods[k];
+    const lp_module_desc& d = m.d;
+    const int dt = net->dtype;
+    const size_t esz = net->esz;
+    const int epv = dt == LP_BF16 ? 8 : 4;
+    const bool last = (k == net->K - 1);
+    size_t poff = 0, goff = 0;
+    int N = d.N, H = d.H, W = d.W, C = d.C;
+
+    auto check_c = [&](int c, const char* what) -> lp_status {
+        if (c <= 0 || c % epv != 0 || c > 2048)
+            return fail(LP_ERR_SHAPE, "module %d: %s = %d must be a positive multiple of %d and at most 2048", k, what, c, epv);
+        return LP_OK;
+    };
+    lp_status st;
+    if (d.stem == 1 || d.stem == 2) {
+        if ((st = check_c(d.stem_cout, "stem_cout")) != LP_OK) return st;
+        m.has_stem = true;
+        if (d.stem == 1) m.stem = make_unit(3, C, d.stem_cout, 1, 1, N, H, W, true);
+        else {
+            if (H % 4 || W % 4) return fail(LP_ERR_SHAPE, "module %d: stem 2 needs H and W divisible by 4", k);
+            m.stem = make_unit(7, C, d.stem_cout, 2, 3, N, H, W, true);
+        }
+        m.stem.need_dgrad = false;
+        add_unit_tensors(m.tensors, poff, goff, m.stem, -1, 0, dt);
+        H = m.stem.Ho; W = m.stem.Wo; C = d.stem_cout;
+        m.pH = H; m.pW = W;
+        if (d.stem == 2) { H = (H + 2 - 3) / 2 + 1; W = (W + 2 - 3) / 2 + 1; }
+    } else if (d.stem != 0) {
+        return fail(LP_ERR_INVALID_ARG, "module %d: stem must be 0, 1 or 2", k);
+    } else if ((st = check_c(C, "input channels C")) != LP_OK) return st;
+
+    for (int i = 0; i < d.n_blocks; ++i) {
+        const lp_block_desc& b = m.blocks[i];
+        if (b.kind != LP_BLOCK_BASIC && b.kind != LP_BLOCK_BOTTLENECK)
+            return fail(LP_ERR_INVALID_ARG, "module %d block %d: unknown kind %d", k, i, b.kind);
+        if (b.cin != C) return fail(LP_ERR_SHAPE, "module %d block %d: cin %d does not match incoming %d channels", k, i, b.cin, C);
+        if (b.stride != 1 && b.stride != 2) return fail(LP_ERR_SHAPE, "module %d block %d: stride %d (1 or 2)", k, i, b.stride);
+        if (H % b.stride || W % b.stride) return fail(LP_ERR_SHAPE, "module %d block %d: %dx%d not divisible by stride", k, i, H, W);
+        if ((b.stride != 1 || b.cin != b.cout) && !b.proj)
+            return fail(LP_ERR_SHAPE, "module %d block %d: shape changes, projection required", k, i);
+        if ((st = check_c(b.cout, "cout")) != LP_OK) return st;
+        BlockPlan bp;
+        if (b.kind == LP_BLOCK_BASIC) {
+            bp.main.push_back(make_unit(3, b.cin, b.cout, b.stride, 1, N, H, W, true));
+            bp.main.push_back(make_unit(3, b.cout, b.cout, 1, 1, N, H / b.stride, W / b.stride, false));
+        } else {
+            if ((st = check_c(b.width, "width")) != LP_OK) return st;
+            bp.main.push_back(make_unit(1, b.cin, b.width, 1, 0, N, H, W, true));
+            bp.main.push_back(make_unit(3, b.width, b.width, b.stride, 1, N, H, W, true));
+            bp.main.push_back(make_unit(1, b.width, b.cout, 1, 0, N, H / b.stride, W / b.stride, false));
+        }
+        for (size_t j = 0; j < bp.main.size(); ++j) add_unit_tensors(m.tensors, poff, goff, bp.main[j], i, (int)j, dt);
+        if (b.proj) {
+            bp.has_proj = true;
+            bp.proj = make_unit(1, b.cin, b.cout, b.stride, 0, N, H, W, false);
+            add_unit_tensors(m.tensors, poff, goff, bp.proj, i, 3, dt);
+        }
+        bp.in_elems = (size_t)N * H * W * C;
+        H /= b.stride; W /= b.stride; C = b.cout;
+        bp.out_elems = (size_t)N * H * W * C;
+        if (bp.in_elems >= (1u << 31) || bp.out_elems >= (1u << 31))
+            return fail(LP_ERR_SHAPE, "module %d block %d: tensor beyond 2^31 elements", k, i);
+        m.bp.push_back(bp);
+    }
+    m.oN = N; m.oH = H; m.oW = W; m.oC = C;
+    if (d.head != (last ? 1 : 0))
+        return fail(LP_ERR_SHAPE, "module %d: head must be set on the last module and only there", k);
+    if (last) {
+        if (d.n_classes < 1) return fail(LP_ERR_INVALID_ARG, "module %d: n_classes %d", k, d.n_classes);
+        m.t_fcw = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_FC_W, d.n_blocks, 0, LP_F32, {d.n_classes, C});
+        m.t_fcb = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_FC_B, d.n_blocks, 0, LP_F32, {d.n_classes});
+    }
+    if (m.tensors.empty()) return fail(LP_ERR_SHAPE, "module %d has no layers", k);
+    m.param_bytes = poff; m.grad_bytes = goff;
+
+    // ---- workspace ------------------------------------------------------------------------------
+    // module 0 without a stem: its first block skips the data-gradient unless dx[0] is requested
+    const bool first_block_dx_optional = (k == 0 && !m.has_stem);
+    std::vector<Unit*> units;
+    if (m.has_stem) units.push_back(&m.stem);
+    for (auto& bp : m.bp) {
+        for (auto& u : bp.main) units.push_back(&u);
+        if (bp.has_proj) units.push_back(&bp.proj);
+    }
+    m.ws_stats0 = ws.off;
+    for (Unit* u : units) u->ws_stats = ws.take(sizeof(double) * 2 * u->cout);
+    m.ws_stats_bytes = ws.off - m.ws_stats0;
+    m.ws_red0 = ws.off;
+    for (Unit* u : units) u->ws_red = ws.take(sizeof(double) * 2 * u->cout);
+    m.ws_red_bytes = ws.off - m.ws_red0;
+    size_t maxD = 0, maxA = 0, maxG = 0, maxP = 0;
+    for (Unit* u : units) {
+        u->ws_y = ws.take(u->out_elems() * esz);
+        if (u->need_dgrad) u->ws_wt = ws.take((size_t)u->cout * u->R * u->R * u->cin * esz);
+        maxD = std::max(maxD, u->out_elems());
+    }
+    if (m.has_stem) {
+        m.ws_stem_act = ws.take(m.stem.out_elems() * esz);
+        maxG = std::max(maxG, m.stem.out_elems());
+        if (d.stem == 2) {
+            const int Hp = (m.pH + 2 - 3) / 2 + 1, Wp = (m.pW + 2 - 3) / 2 + 1;
+            const size_t pn = (size_t)d.N * Hp * Wp * d.stem_cout;
+            m.ws_pool_out = ws.take(pn * esz);
+            m.ws_pool_arg = ws.take(pn);
+            m.ws_gpool = ws.take(m.stem.out_elems() * esz);
+        }
+    }
+    for (size_t i = 0; i < m.bp.size(); ++i) {
+        BlockPlan& bp = m.bp[i];
+        for (size_t j = 0; j + 1 < bp.main.size(); ++j) {
+            bp.ws_act.push_back(ws.take(bp.main[j].out_elems() * esz));
+            maxA = std::max(maxA, bp.main[j].out_elems());
+        }
+        // input
+        if (i == 0) {
+            if (m.has_stem) bp.in = mk(SP_WS, 0, d.stem == 2 ? m.ws_pool_out : m.ws_stem_act);
+            else bp.in = mk(SP_X, k, 0);
+        } else bp.in = m.bp[i - 1].out;
+        // output
+        if (i + 1 == m.bp.size() && !last) bp.out = mk(SP_Y, k, 0);
+        else {
+            const size_t o = ws.take(bp.out_elems * esz);
+            bp.out = mk(SP_WS, 0, o);
+            if (i + 1 == m.bp.size()) m.ws_feat = o;
+        }
+        maxG = std::max(maxG, std::max(bp.in_elems, bp.out_elems));
+        if (bp.has_proj) maxP = std::max(maxP, bp.in_elems);
+    }
+    if (m.bp.empty()) return fail(LP_ERR_SHAPE, "module %d: at least one residual block is required", k);
+    m.ws_G[0] = ws.take(maxG * esz); m.ws_G[1] = ws.take(maxG * esz);
+    m.ws_D = ws.take(maxD * esz); m.ws_Dp = ws.take(maxD * esz);
+    m.ws_A = ws.take(std::max<size_t>(maxA, 1) * esz);
+    m.ws_P = ws.take(std::max<size_t>(maxP, 1) * esz);
+    if (last) {
+        m.ws_pooled = ws.take((size_t)N * C * 4);
+        m.ws_dfeat = ws.take((size_t)N * H * W * C * esz);
+    }
+
+    // ---- forward program ----------------------------------------------------------------------------
+    Builder B{net};
+    auto stats = [&](const Unit& u) { return mk(SP_WS, 0, u.ws_stats); };
+    auto redr = [&](const Unit& u) { return mk(SP_WS, 0, u.ws_red); };
+    auto yref = [&](const Unit& u) { return mk(SP_WS, 0, u.ws_y); };
+    auto wref = [&](const Unit& u) { return param_ref(m, k, u.t_w); };
+    auto gref = [&](const Unit& u) { return param_ref(m, k, u.t_g); };
+    auto bref = [&](const Unit& u) { return param_ref(m, k, u.t_b); };
+    auto Mof = [&](const Unit& u) { return u.N * u.Ho * u.Wo; };
+
+    Program& F = m.fwd;
+    F.push_back(Step{B.fill(mk(SP_WS, 0, m.ws_stats0), m.ws_stats_bytes)});
+    if (m.has_stem) {
+        const Unit& u = m.stem;
+        F.push_back(Step{B.conv_fwd(u, mk(SP_X, k, 0), wref(u), yref(u), stats(u))});
+        F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), mk(SP_WS, 0, m.ws_stem_act), stats(u), gref(u), bref(u), true)});
+        if (d.stem == 2) {
+            Op o; o.type = OP_POOL_FWD;
+            memset(&o.pool, 0, sizeof(o.pool));
+            o.pool.N = d.N; o.pool.H = m.pH; o.pool.W = m.pW; o.pool.C = d.stem_cout;
+            o.pool.Ho = (m.pH + 2 - 3) / 2 + 1; o.pool.Wo = (m.pW + 2 - 3) / 2 + 1;
+            o.pool.R = 3; o.pool.stride = 2; o.pool.pad = 1;
+            o.r[0] = mk(SP_WS, 0, m.ws_stem_act); o.r[1] = mk(SP_WS, 0, m.ws_pool_out); o.r[2] = mk(SP_WS, 0, m.ws_pool_arg);
+            F.push_back(Step{o});
+        }
+    }
+    for (auto& bp : m.bp) {
+        Ref cur = bp.in;
+        for (size_t j = 0; j < bp.main.size(); ++j) {
+            const Unit& u = bp.main[j];
+            Step s{B.conv_fwd(u, cur, wref(u), yref(u), stats(u))};
+            if (j == 0 && bp.has_proj) s.push_back(B.conv_fwd(bp.proj, bp.in, wref(bp.proj), yref(bp.proj), stats(bp.proj)));
+            F.push_back(s);
+            if (j + 1 < bp.main.size()) {
+                Ref a = mk(SP_WS, 0, bp.ws_act[j]);
+                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), a, stats(u), gref(u), bref(u), true)});
+                cur = a;
+            } else if (bp.has_proj) {
+                const Unit& p = bp.proj;
+                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), false, 2, yref(p),
+                                            stats(p), gref(p), bref(p))});
+            } else {
+                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), false, 1, bp.in)});
+            }
+        }
+    }
+    if (last) {
+        Op o; o.type = OP_HEAD_FWD;
+        memset(&o.head, 0, sizeof(o.head));
+        o.head.N = N; o.head.HW = H * W; o.head.C = C; o.head.classes = d.n_classes;
+        o.r[0] = mk(SP_WS, 0, m.ws_feat); o.r[1] = mk(SP_WS, 0, m.ws_pooled);
+        o.r[2] = param_ref(m, k, m.t_fcw); o.r[3] = param_ref(m, k, m.t_fcb); o.r[4] = mk(SP_LOGITS, 0, 0);
+        F.push_back(Step{o});
+    }
+
+    // ---- backward program (two variants when the data-gradient of the first block is optional) ----------
+    for (int variant = 0; variant < (first_block_dx_optional ? 2 : 1); ++variant) {
+        const bool want_dx_first = first_block_dx_optional ? (variant == 1) : true;
+        Program& Bw = variant == 0 ? m.bwd : m.bwd_dx0;
+        {
+            Step s{B.fill(mk(SP_WS, 0, m.ws_red0), m.ws_red_bytes), B.fill(mk(SP_DPARAM, k, 0), m.grad_bytes)};
+            Bw.push_back(s);
+        }
+        {   // filter re-layouts for every data-gradient of this pass
+            Step s;
+            for (size_t i = 0; i < m.bp.size(); ++i) {
+                const bool need_in_grad = (i > 0) || m.has_stem || want_dx_first;
+                BlockPlan& bp = m.bp[i];
+                for (size_t j = 0; j < bp.main.size(); ++j)
+                    if (j > 0 || need_in_grad) s.push_back(B.wtrans(bp.main[j], wref(bp.main[j]), mk(SP_WS, 0, bp.main[j].ws_wt)));
+                if (bp.has_proj && need_in_grad) s.push_back(B.wtrans(bp.proj, wref(bp.proj), mk(SP_WS, 0, bp.proj.ws_wt)));
+            }
+            if (!s.empty()) Bw.push_back(s);
+        }
+        Ref g;                                      // gradient with respect to the current block output
+        if (last) {
+            Op o; o.type = OP_HEAD_BWD;
+            memset(&o.head, 0, sizeof(o.head));
+            o.head.N = N; o.head.HW = H * W; o.head.C = C; o.head.classes = d.n_classes;
+            o.r[1] = mk(SP_WS, 0, m.ws_pooled); o.r[2] = param_ref(m, k, m.t_fcw); o.r[5] = mk(SP_DLOGITS, 0, 0);
+            o.r[6] = grad_ref(m, k, m.t_fcw); o.r[7] = grad_ref(m, k, m.t_fcb); o.r[8] = mk(SP_WS, 0, m.ws_dfeat);
+            Bw.push_back(Step{o});
+            g = mk(SP_WS, 0, m.ws_dfeat);
+        } else g = mk(SP_DY, k, 0);
+        const Ref Dm = mk(SP_WS, 0, m.ws_D), Dp = mk(SP_WS, 0, m.ws_Dp), A = mk(SP_WS, 0, m.ws_A), Pp = mk(SP_WS, 0, m.ws_P);
+        for (int i = (int)m.bp.size() - 1; i >= 0; --i) {
+            BlockPlan& bp = m.bp[i];
+            const bool need_in_grad = (i > 0) || m.has_stem || want_dx_first;
+            Ref gin;                                // where the gradient with respect to the block input goes
+            if (i == 0 && !m.has_stem) gin = mk(SP_DX, k, 0);
+            else gin = mk(SP_WS, 0, m.ws_G[i & 1]);
+            const int nm = (int)bp.main.size();
+            Ref gcur = g;                           // gradient arriving at the BN output of unit j
+            for (int j = nm - 1; j >= 0; --j) {
+                const Unit& u = bp.main[j];
+                const bool lastu = (j == nm - 1);
+                Step s1{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
+                                 grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), u.relu)};
+                Step s2{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
+                                 grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), u.relu)};
+                if (lastu && bp.has_proj) {
+                    const Unit& p = bp.proj;
+                    s1.push_back(B.bn_bwd(OP_BN_BWD_REDUCE, Mof(p), p.cout, g, yref(p), Dp, stats(p), gref(p), bref(p), redr(p),
+                                          grad_ref(m, k, p.t_g), grad_ref(m, k, p.t_b), false));
+                    s2.push_back(B.bn_bwd(OP_BN_BWD_APPLY, Mof(p), p.cout, g, yref(p), Dp, stats(p), gref(p), bref(p), redr(p),
+                                          grad_ref(m, k, p.t_g), grad_ref(m, k, p.t_b), false));
+                }
+                Bw.push_back(s1);
+                Bw.push_back(s2);
+                // weight gradients (and the projection's data-gradient) of this level
+                Step s3;
+                const Ref uin = (j == 0) ? bp.in : mk(SP_WS, 0, bp.ws_act[j - 1]);
+                s3.push_back(B.wgrad(u, uin, Dm, grad_ref(m, k, u.t_w)));
+                if (lastu && bp.has_proj) {
+                    s3.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
+                    if (need_in_grad) B.conv_dgrad(bp.proj, Dp, mk(SP_WS, 0, bp.proj.ws_wt), Pp, Ref(), Ref(), s3);
+                }
+                // data-gradient of this unit
+                if (j > 0) {
+                    B.conv_dgrad(u, Dm, mk(SP_WS, 0, u.ws_wt), A, Ref(), Ref(), s3);
+                    Bw.push_back(s3);
+                    gcur = A;
+                } else {
+                    Bw.push_back(s3);
+                    if (need_in_grad) {
+                        Step s4;
+                        // skip path: identity adds the block-output gradient, projection adds its data-gradient.
+                        // (a unit with one main conv would need the projection result of the same step: split)
+                        B.conv_dgrad(u, Dm, mk(SP_WS, 0, u.ws_wt), gin, bp.has_proj ? Pp : g, Ref(), s4);
+                        Bw.push_back(s4);
+                    }
+                }
+            }
+            g = gin;
+        }
+        if (m.has_stem) {
+            const Unit& u = m.stem;
+            Ref gs = g;
+            if (d.stem == 2) {
+                Op o; o.type = OP_POOL_BWD;
+                memset(&o.pool, 0, sizeof(o.pool));
+                o.pool.N = d.N; o.pool.H = m.pH; o.pool.W = m.pW; o.pool.C = d.stem_cout;
+                o.pool.Ho = (m.pH + 2 - 3) / 2 + 1; o.pool.Wo = (m.pW + 2 - 3) / 2 + 1;
+                o.pool.R = 3; o.pool.stride = 2; o.pool.pad = 1;
+                o.r[2] = mk(SP_WS, 0, m.ws_pool_arg); o.r[3] = g; o.r[4] = mk(SP_WS, 0, m.ws_gpool);
+                Bw.push_back(Step{o});
+                gs = mk(SP_WS, 0, m.ws_gpool);
+            }
+            Bw.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gs, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
+                                       grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), true)});
+            Bw.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gs, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
+                                       grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), true)});
+            Bw.push_back(Step{B.wgrad(u, mk(SP_X, k, 0), Dm, grad_ref(m, k, u.t_w))});
+        }
+    }
+    return LP_OK;
+}
+
+static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
+    AuxPlan& a = net->aux[j];
+    const ModulePlan& m0 = net->mods[0];
+    const ModulePlan& mt = net->mods[j + 1];
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    if (a.d.cin != m0.d.C) return fail(LP_ERR_SHAPE, "aux %d: cin %d != image channels %d", j, a.d.cin, m0.d.C);
+    if (a.d.cout != mt.d.C || a.d.cout % epv) return fail(LP_ERR_SHAPE, "aux %d: cout %d != channels of x_%d (%d)", j, a.d.cout, j + 1, mt.d.C);
+    if (a.d.stride < 1 || m0.d.H != mt.d.H * a.d.stride || m0.d.W != mt.d.W * a.d.stride)
+        return fail(LP_ERR_SHAPE, "aux %d: stride %d does not map %dx%d to %dx%d", j, a.d.stride, m0.d.H, m0.d.W, mt.d.H, mt.d.W);
+    a.u = make_unit(3, a.d.cin, a.d.cout, a.d.stride, 1, m0.d.N, m0.d.H, m0.d.W, a.d.relu != 0);
+    if (a.u.Ho != mt.d.H || a.u.Wo != mt.d.W) return fail(LP_ERR_SHAPE, "aux %d: output %dx%d != %dx%d", j, a.u.Ho, a.u.Wo, mt.d.H, mt.d.W);
+    size_t poff = 0, goff = 0;
+    add_unit_tensors(a.tensors, poff, goff, a.u, -1, 0, net->dtype);
+    a.param_bytes = poff; a.grad_bytes = goff;
+    a.u.ws_stats = ws.take(sizeof(double) * 2 * a.u.cout);
+    a.u.ws_y = ws.take(a.u.out_elems() * net->esz);
+    Builder B{net};
+    const Ref st = mk(SP_WS, 0, a.u.ws_stats), y = mk(SP_WS, 0, a.u.ws_y);
+    a.fwd.push_back(Step{B.fill(st, sizeof(double) * 2 * a.u.cout)});
+    a.fwd.push_back(Step{B.conv_fwd(a.u, mk(SP_IMAGE, 0, 0), mk(SP_AUXP, j, a.tensors[a.u.t_w].offset), y, st)});
+    a.fwd.push_back(Step{B.bn_apply(a.u.N * a.u.Ho * a.u.Wo, a.u.cout, y, mk(SP_XOUT, j, 0), st,
+                                    mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), mk(SP_AUXP, j, a.tensors[a.u.t_b].offset),
+                                    a.d.relu != 0)});
+    return LP_OK;
+}
+
+// ----------------------------------------------------------------------------------------------------
+// scheduler: advance the selected programs in lock-step, merging equal operations into grouped launches
+// ----------------------------------------------------------------------------------------------------
+static int elem_blocks(size_t nvec) { return (int)((nvec + kElemVecsPerBlock - 1) / kElemVecsPerBlock); }
+
+static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const Bindings& b, hipStream_t s) {
+    const int type = ops[0]->type, dt = net->dtype;
+    const int epv = dt == LP_BF16 ? 8 : 4;
+    hipError_t err = hipSuccess;
+    for (size_t base = 0; base < ops.size() && err == hipSuccess; base += kMaxGroup) {
+        const int n = (int)std::min<size_t>(kMaxGroup, ops.size() - base);
+        switch (type) {
+            case OP_FILL: {
+                FillGroup g; g.nprob = n; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    g.p[i].ptr = resolve(o.r[0], b); g.p[i].bytes = o.fill_bytes; g.p[i].block_start = tot;
+                    tot += elem_blocks(o.fill_bytes / 16);
+                }
+                g.total_blocks = tot;
+                err = launch_fill(g, s);
+            } break;
+            case OP_WTRANS: {
+                WtransGroup g; g.nprob = n; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    g.p[i] = o.wt;
+                    g.p[i].w = resolve(o.r[0], b); g.p[i].wt = resolve(o.r[1], b); g.p[i].block_start = tot;
+                    tot += ((o.wt.Cin + 31) / 32) * ((o.wt.Cout + 31) / 32) * o.wt.RS;
+                }
+                g.total_blocks = tot;
+                err = launch_wtrans(g, dt, s);
+            } break;
+            case OP_CONV: {
+                ConvGroup g; g.nprob = n; int tot = 0;
+                const CfgInfo ci = conv_cfg_info(ops[0]->cfg, dt);
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    ConvProb& p = g.p[i]; p = o.conv;
+                    p.in = resolve(o.r[0], b); p.wt = resolve(o.r[1], b); p.out = resolve(o.r[2], b);
+                    p.add0 = resolve(o.r[3], b); p.add1 = resolve(o.r[4], b); p.stats = (double*)resolve(o.r[5], b);
+                    p.tiles_m = (p.M + ci.BM - 1) / ci.BM; p.tiles_n = (p.Ncol + ci.BN - 1) / ci.BN;
+                    p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
+                }
+                g.total_tiles = tot;
+                err = launch_conv(g, dt, ops[0]->cfg, ops[0]->vec, s);
+            } break;
+            case OP_WGRAD: {
+                WgradGroup g; g.nprob = n; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    WgradProb& p = g.p[i]; p = o.wg;
+                    p.x = resolve(o.r[0], b); p.dy = resolve(o.r[1], b); p.dw = (float*)resolve(o.r[2], b);
+                    p.tile_start = tot; tot += p.tiles_m * p.tiles_n * p.ksplit;
+                }
+                g.total_tiles = tot;
+                err = launch_wgrad(g, dt, ops[0]->cfg, ops[0]->vec, s);
+            } break;
+            case OP_BN_APPLY: {
+                BnApplyGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    BnApplyProb& p = g.p[i]; p = o.bna;
+                    p.y = resolve(o.r[0], b); p.out = resolve(o.r[1], b); p.stats = (const double*)resolve(o.r[2], b);
+                    p.gamma = (const float*)resolve(o.r[3], b); p.beta = (const float*)resolve(o.r[4], b);
+                    p.skip = resolve(o.r[5], b); p.sstats = (const double*)resolve(o.r[6], b);
+                    p.sgamma = (const float*)resolve(o.r[7], b); p.sbeta = (const float*)resolve(o.r[8], b);
+                    p.block_start = tot; p.nblocks = elem_blocks((size_t)p.M * p.C / epv); tot += p.nblocks;
+                }
+                g.total_blocks = tot;
+                err = launch_bn_apply(g, dt, s);
+            } break;
+            case OP_BN_BWD_REDUCE:
+            case OP_BN_BWD_APPLY: {
+                BnBwdGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    BnBwdProb& p = g.p[i]; p = o.bnb;
+                    p.g = resolve(o.r[0], b); p.y = resolve(o.r[1], b); p.dy = resolve(o.r[2], b);
+                    p.stats = (const double*)resolve(o.r[3], b); p.gamma = (const float*)resolve(o.r[4], b);
+                    p.beta = (const float*)resolve(o.r[5], b); p.red = (double*)resolve(o.r[6], b);
+                    p.dgamma = (float*)resolve(o.r[7], b); p.dbeta = (float*)resolve(o.r[8], b);
+                    p.block_start = tot;
+                    if (type == OP_BN_BWD_REDUCE) p.nblocks = std::max(1, std::min(256, (p.M + 63) / 64));
+                    else p.nblocks = elem_blocks((size_t)p.M * p.C / epv);
+                    tot += p.nblocks;
+                }
+                g.total_blocks = tot;
+                err = type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
+            } break;
+            case OP_POOL_FWD:
+            case OP_POOL_BWD:
+                for (int i = 0; i < n && err == hipSuccess; ++i) {
+                    const Op& o = *ops[base + i];
+                    PoolProb p = o.pool;
+                    p.x = resolve(o.r[0], b); p.y = resolve(o.r[1], b); p.arg = (uint8_t*)resolve(o.r[2], b);
+                    p.dy = resolve(o.r[3], b); p.dx = resolve(o.r[4], b);
+                    err = type == OP_POOL_FWD ? launch_maxpool_fwd(p, dt, s) : launch_maxpool_bwd(p, dt, s);
+                }
+                break;
+            case OP_HEAD_FWD:
+            case OP_HEAD_BWD:
+                for (int i = 0; i < n && err == hipSuccess; ++i) {
+                    const Op& o = *ops[base + i];
+                    HeadProb p = o.head;
+                    p.feat = resolve(o.r[0], b); p.pooled = (float*)resolve(o.r[1], b); p.w = (const float*)resolve(o.r[2], b);
+                    p.b = (const float*)resolve(o.r[3], b); p.logits = (float*)resolve(o.r[4], b);
+                    p.dlogits = (const float*)resolve(o.r[5], b); p.dw = (float*)resolve(o.r[6], b);
+                    p.db = (float*)resolve(o.r[7], b); p.dfeat = resolve(o.r[8], b);
+                    err = type == OP_HEAD_FWD ? launch_head_fwd(p, dt, s) : launch_head_bwd(p, dt, s);
+                }
+                break;
+            default: err = hipErrorInvalidValue;
+        }
+    }
+    return err;
+}
+
+static lp_status run_programs(lp_net* net, const std::vector<const Program*>& progs, const Bindings& b, hipStream_t s) {
+    const size_t np = progs.size();
+    std::vector<size_t> step(np, 0);
+    std::vector<std::vector<char>> issued(np);
+    for (size_t i = 0; i < np; ++i)
+        if (!progs[i]->empty()) issued[i].assign((*progs[i])[0].size(), 0);
+    for (;;) {
+        // candidate operations: everything not yet issued in the current step of every program
+        int best_key = -1, best_cnt = 0;
+        std::vector<std::pair<int, int>> keys;     // (key, count)
+        bool any = false;
+        for (size_t i = 0; i < np; ++i) {
+            if (step[i] >= progs[i]->size()) continue;
+            const Step& st = (*progs[i])[step[i]];
+            for (size_t j = 0; j < st.size(); ++j) {
+                if (issued[i][j]) continue;
+                any = true;
+                const int key = st[j].key();
+                bool found = false;
+                for (auto& kc : keys) if (kc.first == key) { ++kc.second; found = true; }
+                if (!found) keys.push_back({key, 1});
+            }
+        }
+        if (!any) break;
+        for (auto& kc : keys)
+            if (kc.second > best_cnt || (kc.second == best_cnt && kc.first < best_key)) { best_key = kc.first; best_cnt = kc.second; }
+        std::vector<const Op*> ops;
+        for (size_t i = 0; i < np; ++i) {
+            if (step[i] >= progs[i]->size()) continue;
+            const Step& st = (*progs[i])[step[i]];
+            for (size_t j = 0; j < st.size(); ++j)
+                if (!issued[i][j] && st[j].key() == best_key) { ops.push_back(&st[j]); issued[i][j] = 1; }
+        }
+        const hipError_t err = launch_group(net, ops, b, s);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+        for (size_t i = 0; i < np; ++i) {
+            if (step[i] >= progs[i]->size()) continue;
+            bool done = true;
+            for (char c : issued[i]) done = done && c;
+            if (done) {
+                ++step[i];
+                if (step[i] < progs[i]->size()) issued[i].assign((*progs[i])[step[i]].size(), 0);
+            }
+        }
+    }
+    return LP_OK;
+}
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace
+
+// ----------------------------------------------------------------------------------------------------
+// C ABI
+// ----------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* lp_last_error(void) { return g_err.c_str(); }
+const char* lp_version(void) { return "lp-gfx950 0.1"; }
+
+lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* aux, int dtype, float bn_eps,
+                        struct lp_net** out) {
+    if (!out) return fail(LP_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (K < 1 || K > 32) return fail(LP_ERR_INVALID_ARG, "K = %d outside [1, 32]", K);
+    if (!mods) return fail(LP_ERR_INVALID_ARG, "mods is NULL");
+    if (dtype != LP_F32 && dtype != LP_BF16) return fail(LP_ERR_DTYPE, "dtype %d is neither LP_F32 nor LP_BF16", dtype);
+    if (!(bn_eps > 0.f)) return fail(LP_ERR_INVALID_ARG, "bn_eps must be positive");
+    lp_net* net = new lp_net();
+    net->K = K; net->dtype = dtype; net->eps = bn_eps; net->esz = dtype == LP_BF16 ? 2 : 4;
+    net->mods.resize(K);
+    net->saved_x.assign(K, nullptr);
+    WsAlloc ws;
+    lp_status st = LP_OK;
+    for (int k = 0; k < K && st == LP_OK; ++k) {
+        ModulePlan& m = net->mods[k];
+        m.d = mods[k];
+        if (m.d.N < 1 || m.d.H < 1 || m.d.W < 1 || m.d.C < 1) { st = fail(LP_ERR_INVALID_ARG, "module %d: non-positive input shape", k); break; }
+        if (m.d.n_blocks < 1 || m.d.n_blocks > 64 || !m.d.blocks) { st = fail(LP_ERR_INVALID_ARG, "module %d: n_blocks %d or blocks NULL", k, m.d.n_blocks); break; }
+        m.blocks.assign(m.d.blocks, m.d.blocks + m.d.n_blocks);
+        m.d.blocks = nullptr;
+        st = build_module(net, k, ws);
+        if (st == LP_OK && k > 0) {
+            const ModulePlan& p = net->mods[k - 1];
+            if (p.oN != m.d.N || p.oH != m.d.H || p.oW != m.d.W || p.oC != m.d.C)
+                st = fail(LP_ERR_SHAPE, "module %d output [%d,%d,%d,%d] != module %d input [%d,%d,%d,%d]", k - 1, p.oN, p.oH,
+                          p.oW, p.oC, k, m.d.N, m.d.H, m.d.W, m.d.C);
+        }
+    }
+    if (st == LP_OK && aux) {
+        net->aux.resize(K - 1);
+        for (int j = 0; j < K - 1 && st == LP_OK; ++j) {
+            net->aux[j].d = aux[j];
+            st = build_aux(net, j, ws);
+        }
+    }
+    if (st != LP_OK) { delete net; return st; }
+    net->ws_bytes = ws.off;
+    *out = net;
+    return LP_OK;
+}
+
+lp_status lp_net_destroy(struct lp_net* net) {
+    delete net;
+    return LP_OK;
+}
+
+static lp_status table_of(const lp_net* net, int aux, int k, const std::vector<lp_tensor_info>** t, size_t* pb, size_t* gb) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (aux) {
+        if (k < 0 || k >= (int)net->aux.size()) return fail(LP_ERR_INVALID_ARG, "aux block %d out of range", k);
+        *t = &net->aux[k].tensors; *pb = net->aux[k].param_bytes; *gb = net->aux[k].grad_bytes;
+    } else {
+        if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
+        *t = &net->mods[k].tensors; *pb = net->mods[k].param_bytes; *gb = net->mods[k].grad_bytes;
+    }
+    return LP_OK;
+}
+lp_status lp_net_param_bytes(const struct lp_net* net, int aux, int k, size_t* param_bytes, size_t* grad_bytes) {
+    const std::vector<lp_tensor_info>* t; size_t pb, gb;
+    lp_status st = table_of(net, aux, k, &t, &pb, &gb);
+    if (st != LP_OK) return st;
+    if (param_bytes) *param_bytes = pb;
+    if (grad_bytes) *grad_bytes = gb;
+    return LP_OK;
+}
+lp_status lp_net_num_tensors(const struct lp_net* net, int aux, int k, int* n) {
+    const std::vector<lp_tensor_info>* t; size_t pb, gb;
+    lp_status st = table_of(net, aux, k, &t, &pb, &gb);
+    if (st != LP_OK) return st;
+    if (!n) return fail(LP_ERR_INVALID_ARG, "n is NULL");
+    *n = (int)t->size();
+    return LP_OK;
+}
+lp_status lp_net_tensor_info(const struct lp_net* net, int aux, int k, int i, lp_tensor_info* info) {
+    const std::vector<lp_tensor_info>* t; size_t pb, gb;
+    lp_status st = table_of(net, aux, k, &t, &pb, &gb);
+    if (st != LP_OK) return st;
+    if (!info || i < 0 || i >= (int)t->size()) return fail(LP_ERR_INVALID_ARG, "tensor index %d out of range", i);
+    *info = (*t)[i];
+    return LP_OK;
+}
+
+lp_status lp_net_workspace_bytes(const struct lp_net* net, size_t* bytes) {
+    if (!net || !bytes) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    *bytes = net->ws_bytes;
+    return LP_OK;
+}
+lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes) {
+    if (!net || !dev_ptr) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 255u) return fail(LP_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (bytes < net->ws_bytes) return fail(LP_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
+    net->ws = (char*)dev_ptr; net->ws_given = bytes; net->fwd_done = 0;
+    return LP_OK;
+}
+
+static lp_status check_common(const lp_net* net, uint32_t mask, bool need_mask) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!net->ws) return fail(LP_ERR_WORKSPACE, "no workspace set (lp_net_set_workspace)");
+    if (need_mask) {
+        if (mask == 0) return fail(LP_ERR_INVALID_ARG, "module_mask selects no module");
+        if (net->K < 32 && (mask >> net->K) != 0) return fail(LP_ERR_INVALID_ARG, "module_mask 0x%x has bits beyond K = %d", mask, net->K);
+    }
+    return LP_OK;
+}
+
+lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                            void* const* x_out) {
+    lp_status st = check_common(net, 0, false);
+    if (st != LP_OK) return st;
+    if (net->aux.empty()) return fail(LP_ERR_STATE, "the net was created without AuxNet descriptors");
+    if (!image || !aux_params || !x_out) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (misaligned(image)) return fail(LP_ERR_INVALID_ARG, "image is not 16-byte aligned");
+    std::vector<const Program*> progs;
+    for (int j = 0; j < net->K - 1; ++j) {
+        if (!aux_params[j] || !x_out[j]) return fail(LP_ERR_INVALID_ARG, "aux_params[%d] or x_out[%d] is NULL", j, j);
+        if (misaligned(aux_params[j]) || misaligned(x_out[j])) return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
+        progs.push_back(&net->aux[j].fwd);
+    }
+    Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.xout = x_out;
+    return run_programs(net, progs, b, (hipStream_t)stream);
+}
+
+lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* x,
+                            const void* const* params, void* const* y, float* logits) {
+    lp_status st = check_common(net, module_mask, true);
+    if (st != LP_OK) return st;
+    if (!x || !params) return fail(LP_ERR_INVALID_ARG, "x or params is NULL");
+    std::vector<const Program*> progs;
+    for (int k = 0; k < net->K; ++k) {
+        if (!((module_mask >> k) & 1u)) continue;
+        if (!x[k] || !params[k]) return fail(LP_ERR_INVALID_ARG, "x[%d] or params[%d] is NULL", k, k);
+        if (misaligned(x[k]) || misaligned(params[k])) return fail(LP_ERR_INVALID_ARG, "x[%d] or params[%d] is not 16-byte aligned", k, k);
+        if (k < net->K - 1) {
+            if (!y || !y[k]) return fail(LP_ERR_INVALID_ARG, "y[%d] is NULL", k);
+            if (misaligned(y[k])) return fail(LP_ERR_INVALID_ARG, "y[%d] is not 16-byte aligned", k);
+        } else if (!logits) return fail(LP_ERR_INVALID_ARG, "logits is NULL");
+        progs.push_back(&net->mods[k].fwd);
+    }
+    Bindings b; b.ws = net->ws; b.x = x; b.params = params; b.y = y; b.logits = logits;
+    st = run_programs(net, progs, b, (hipStream_t)stream);
+    if (st == LP_OK) {
+        for (int k = 0; k < net->K; ++k)
+            if ((module_mask >> k) & 1u) { net->saved_x[k] = x[k]; net->fwd_done |= (1u << k); }
+    }
+    return st;
+}
+
+lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* y,
+                             const void* const* x_next, const void* const* lam, float rho, float loss_scale,
+                             const float* logits, const int32_t* labels, float* loss, void* const* dy, float* dlogits) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (module_mask == 0) return fail(LP_ERR_INVALID_ARG, "module_mask selects no module");
+    if (net->K < 32 && (module_mask >> net->K) != 0) return fail(LP_ERR_INVALID_ARG, "module_mask 0x%x has bits beyond K = %d", module_mask, net->K);
+    if (!(rho >= 0.f)) return fail(LP_ERR_INVALID_ARG, "rho must be non-negative");
+    if (!loss) return fail(LP_ERR_INVALID_ARG, "loss is NULL");
+    hipStream_t s = (hipStream_t)stream;
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = rho; g.scale = loss_scale;
+    bool want_ce = false;
+    for (int k = 0; k < net->K; ++k) {
+        if (!((module_mask >> k) & 1u)) continue;
+        if (k == net->K - 1) { want_ce = true; continue; }
+        if (!y || !x_next || !dy || !y[k] || !x_next[k] || !dy[k]) return fail(LP_ERR_INVALID_ARG, "y/x_next/dy[%d] is NULL", k);
+        if (misaligned(y[k]) || misaligned(x_next[k]) || misaligned(dy[k]) || (lam && lam[k] && misaligned(lam[k])))
+            return fail(LP_ERR_INVALID_ARG, "interface tensor %d is not 16-byte aligned", k);
+    }
+    if (want_ce && (!logits || !labels || !dlogits)) return fail(LP_ERR_INVALID_ARG, "logits, labels or dlogits is NULL");
+    // loss[k] = 0 for the selected modules (the kernels below accumulate with atomics)
+    hipError_t err = launch_zero_selected(loss, module_mask, net->K, s);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    for (int k = 0; k < net->K - 1; ++k) {
+        if (!((module_mask >> k) & 1u)) continue;
+        const ModulePlan& m = net->mods[k];
+        LossProb& p = g.p[g.nprob];
+        p.y = y[k]; p.xn = x_next[k]; p.lam = (lam ? lam[k] : nullptr); p.dy = dy[k]; p.loss = loss + k;
+        p.numel = (size_t)m.oN * m.oH * m.oW * m.oC;
+        p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
+        if (++g.nprob == kMaxGroup) {
+            err = launch_loss(g, net->dtype, s);
+            if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+            g.nprob = 0; g.total_blocks = 0;
+        }
+    }
+    if (g.nprob) {
+        err = launch_loss(g, net->dtype, s);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    }
+    if (want_ce) {
+        const ModulePlan& m = net->mods[net->K - 1];
+        err = launch_ce(logits, labels, loss + (net->K - 1), dlogits, m.oN, m.d.n_classes, s);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    }
+    return LP_OK;
+}
+
+lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* dy,
+                             const float* dlogits, const void* const* params, float* const* dparams, void* const* dx) {
+    lp_status st = check_common(net, module_mask, true);
+    if (st != LP_OK) return st;
+    if (!params || !dparams) return fail(LP_ERR_INVALID_ARG, "params or dparams is NULL");
+    if ((net->fwd_done & module_mask) != module_mask)
+        return fail(LP_ERR_STATE, "lp_module_backward without a matching lp_module_forward (mask 0x%x, forward done 0x%x)", module_mask, net->fwd_done);
+    std::vector<const Program*> progs;
+    for (int k = 0; k < net->K; ++k) {
+        if (!((module_mask >> k) & 1u)) continue;
+        const ModulePlan& m = net->mods[k];
+        if (!params[k] || !dparams[k]) return fail(LP_ERR_INVALID_ARG, "params[%d] or dparams[%d] is NULL", k, k);
+        if (misaligned(params[k]) || misaligned(dparams[k])) return fail(LP_ERR_INVALID_ARG, "params[%d] or dparams[%d] is not 16-byte aligned", k, k);
+        if (k < net->K - 1) {
+            if (!dy || !dy[k]) return fail(LP_ERR_INVALID_ARG, "dy[%d] is NULL", k);
+            if (misaligned(dy[k])) return fail(LP_ERR_INVALID_ARG, "dy[%d] is not 16-byte aligned", k);
+        } else if (!dlogits) return fail(LP_ERR_INVALID_ARG, "dlogits is NULL");
+        const bool needs_dx = !m.has_stem && k > 0;
+        const bool opt_dx = !m.has_stem && k == 0 && dx && dx[0];
+        if (needs_dx && (!dx || !dx[k])) return fail(LP_ERR_INVALID_ARG, "dx[%d] is NULL", k);
+        if ((needs_dx || opt_dx) && misaligned(dx[k])) return fail(LP_ERR_INVALID_ARG, "dx[%d] is not 16-byte aligned", k);
+        progs.push_back(opt_dx ? &m.bwd_dx0 : &m.bwd);
+    }
+    Bindings b; b.ws = net->ws; b.x = net->saved_x.data(); b.params = params; b.dparams = dparams; b.dy = dy; b.dx = dx;
+    b.dlogits = dlogits;
+    st = run_programs(net, progs, b, (hipStream_t)stream);
+    if (st == LP_OK) net->fwd_done &= ~module_mask;
+    return st;
+}
+
+lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const* lam, const void* const* y,
+                                  const void* const* x_next, float step) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!lam || !y || !x_next) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    MultGroup g; g.nprob = 0; g.total_blocks = 0; g.step = step;
+    hipError_t err = hipSuccess;
+    for (int k = 0; k < net->K - 1; ++k) {
+        if (!lam[k]) continue;
+        if (!y[k] || !x_next[k]) return fail(LP_ERR_INVALID_ARG, "y[%d] or x_next[%d] is NULL", k, k);
+        if (misaligned(lam[k]) || misaligned(y[k]) || misaligned(x_next[k])) return fail(LP_ERR_INVALID_ARG, "interface tensor %d is not 16-byte aligned", k);
+        const ModulePlan& m = net->mods[k];
+        MultProb& p = g.p[g.nprob];
+        p.lam = lam[k]; p.y = y[k]; p.xn = x_next[k]; p.numel = (size_t)m.oN * m.oH * m.oW * m.oC;
+        p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
+        if (++g.nprob == kMaxGroup) {
+            err = launch_mult(g, net->dtype, (hipStream_t)stream);
+            if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+            g.nprob = 0; g.total_blocks = 0;
+        }
+    }
+    if (g.nprob) {
+        err = launch_mult(g, net->dtype, (hipStream_t)stream);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    }
+    return LP_OK;
+}
+
+lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, int S, int stride, int pad,
+                                  const int64_t* m, const int64_t* q, int64_t* out, int count) {
+    if (!m || !q || !out || count < 0) return fail(LP_ERR_INVALID_ARG, "NULL argument or negative count");
+    if (H < 1 || W < 1 || Cin < 1 || R < 1 || S < 1 || stride < 1 || pad < 0) return fail(LP_ERR_INVALID_ARG, "bad geometry");
+    const hipError_t err = launch_im2col_offsets(H, W, Cin, R, S, stride, pad, m, q, out, count, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    return LP_OK;
+}
+
+lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel) {
+    if (!net || !ptr || !numel) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
+    if (!net->ws) return fail(LP_ERR_WORKSPACE, "no workspace set");
+    const ModulePlan& m = net->mods[k];
+    if (which == 0) {
+        if (!m.has_stem) return fail(LP_ERR_INVALID_ARG, "module %d has no stem", k);
+        *ptr = net->ws + (m.d.stem == 2 ? m.ws_pool_out : m.ws_stem_act);
+        *numel = m.bp[0].in_elems;
+        return LP_OK;
+    }
+    const int bi = (which - 1) / 8, sub = (which - 1) % 8;
+    if (which < 0 || bi >= (int)m.bp.size()) return fail(LP_ERR_INVALID_ARG, "block %d out of range", bi);
+    const BlockPlan& bp = m.bp[bi];
+    if (sub < 3) {
+        if (sub >= (int)bp.main.size()) return fail(LP_ERR_INVALID_ARG, "conv slot %d out of range", sub);
+        *ptr = net->ws + bp.main[sub].ws_y; *numel = bp.main[sub].out_elems();
+    } else if (sub == 3) {
+        if (!bp.has_proj) return fail(LP_ERR_INVALID_ARG, "block %d has no projection", bi);
+        *ptr = net->ws + bp.proj.ws_y; *numel = bp.proj.out_elems();
+    } else if (sub == 4) {
+        if (bp.out.space != SP_WS) return fail(LP_ERR_INVALID_ARG, "block %d writes to the caller's y", bi);
+        *ptr = net->ws + bp.out.off; *numel = bp.out_elems;
+    } else return fail(LP_ERR_INVALID_ARG, "unknown tensor id %d", which);
+    return LP_OK;
+}
+
+}  // extern "C"

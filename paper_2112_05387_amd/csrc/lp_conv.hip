@@ -1,0 +1,587 @@
+// Grouped implicit-GEMM convolution kernels for gfx950: forward / data-gradient (one kernel, the
+// problem descriptor carries the tap geometry), weight-gradient (split over the reduction), the filter
+// re-layout that the data-gradient needs, and a debug kernel that exposes the im2col address function.
+//
+// These are the products P dX_{m+1}/dX_m and P dF/dW of the discrete adjoint recursion and of the weight
+// update (Sec. 4.1) and the convolutions inside F of the feature-flow equation; a dense contraction, so
+// they run on the matrix cores: operands are staged through LDS as [row][k] tiles (k contiguous, padded
+// pitch), read as 16-byte MFMA fragments, accumulated in fp32.
+#include "lp_kernels.h"
+#include "lp_mma.h"
+
+namespace lp {
+
+// -------------------------------------------------------------------------------------------------
+// forward / data-gradient
+// -------------------------------------------------------------------------------------------------
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MT, bool VEC>
+__global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGroup g) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int EPV = 16 / (int)sizeof(T);
+    constexpr int VPR = BK / EPV;
+    constexpr int PITCH = BK + EPV;
+    constexpr int A_VECS = BM * VPR, B_VECS = BN * VPR;
+    constexpr int A_PER_T = (A_VECS + NT - 1) / NT, B_PER_T = (B_VECS + NT - 1) / NT;
+    constexpr int TM = BM / WGM, TN = BN / WGN, FM = TM / MT, FN = TN / MT;
+    static_assert(NT % VPR == 0, "k-chunk of a thread must not depend on the pass");
+    static_assert(TM % MT == 0 && TN % MT == 0, "wave tile must be whole micro-tiles");
+    typedef typename AccT<MT>::type acc_t;
+
+    __shared__ __attribute__((aligned(16))) T As[2][BM * PITCH];
+    __shared__ __attribute__((aligned(16))) T Bs[2][BN * PITCH];
+    __shared__ int s_rowoff[BM];
+
+    // ---- which problem, which tile ------------------------------------------------------------
+    const int tid = threadIdx.x;
+    int pi = 0;
+    {
+        const int bid = blockIdx.x;
+        for (int i = 1; i < g.nprob; ++i)
+            if (bid >= g.p[i].tile_start) pi = i;
+    }
+    const ConvProb& P = g.p[pi];
+    const int t = blockIdx.x - P.tile_start;
+    const int tile_n = t % P.tiles_n, tile_m = t / P.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int M = P.M, Cin = P.Cin, IH = P.IH, IW = P.IW, ntr = P.ntr, nts = P.nts;
+    const T* __restrict__ in = reinterpret_cast<const T*>(P.in);
+    const T* __restrict__ wt = reinterpret_cast<const T*>(P.wt);
+
+    // ---- per-row output offsets (also used by the epilogue) ---------------------------------------
+    for (int r = tid; r < BM; r += NT) {
+        const int m = m0 + r;
+        int off = -1;
+        if (m < M) {
+            const int per = P.OA * P.OB;
+            const int n = m / per, rem = m - n * per;
+            const int a = rem / P.OB, b = rem - a * P.OB;
+            off = ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
+        }
+        s_rowoff[r] = off;
+    }
+
+    // ---- per-thread gather state ---------------------------------------------------------------
+    const int kv = tid % VPR;                // this thread's 16-byte k-chunk inside a k-tile
+    int a_pix[A_PER_T], a_ih[A_PER_T], a_iw[A_PER_T];
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+        const int v = tid + i * NT;
+        const int row = v / VPR;
+        const int m = m0 + row;
+        a_pix[i] = 0; a_ih[i] = -(1 << 28); a_iw[i] = 0;
+        if (v < A_VECS && m < M) {
+            const int per = P.OA * P.OB;
+            const int n = m / per, rem = m - n * per;
+            const int a = rem / P.OB, b = rem - a * P.OB;
+            a_pix[i] = n * IH * IW;
+            a_ih[i] = a * P.imul + P.dh0;
+            a_iw[i] = b * P.imul + P.dw0;
+        }
+    }
+    int b_off[B_PER_T];
+#pragma unroll
+    for (int i = 0; i < B_PER_T; ++i) {
+        const int v = tid + i * NT;
+        const int col = n0 + v / VPR;
+        b_off[i] = (v < B_VECS && col < P.Ncol) ? col * P.ldw : -1;
+    }
+    // (ci, tr, ts) of this thread's chunk, advanced by BK per k-tile (vector path only)
+    int ci, tr, ts;
+    {
+        const int q0 = kv * EPV;
+        const int tap = q0 / Cin;
+        ci = q0 - tap * Cin;
+        tr = tap / nts;
+        ts = tap - tr * nts;
+    }
+
+    u32x4 a_reg[A_PER_T], b_reg[B_PER_T];
+    auto load_tile = [&](int k0) {
+        if constexpr (VEC) {
+            const bool kok = tr < ntr;
+            const int dh = P.dhs * tr, dw = P.dws * ts;
+            const int wk = ((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci;
+#pragma unroll
+            for (int i = 0; i < A_PER_T; ++i) {
+                const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (kok && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
+                    v = *reinterpret_cast<const u32x4*>(in + ((size_t)(a_pix[i] + ih * IW + iw) * Cin + ci));
+                a_reg[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER_T; ++i) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (kok && b_off[i] >= 0) v = *reinterpret_cast<const u32x4*>(wt + ((size_t)b_off[i] + wk));
+                b_reg[i] = v;
+            }
+            // advance to the next k-tile
+            ci += BK;
+            while (ci >= Cin) {
+                ci -= Cin;
+                if (++ts == nts) { ts = 0; ++tr; }
+            }
+        } else {
+            // element-wise gather: any Cin (used for the image-facing convolutions, Cin = 3)
+            T av[A_PER_T][EPV], bv[B_PER_T][EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                const int q = k0 + kv * EPV + e;
+                const int tap = q / Cin, c = q - tap * Cin;
+                const int r = tap / nts, s = tap - r * nts;
+                const bool kok = q < P.Kg;
+                const int dh = P.dhs * r, dw = P.dws * s;
+                const int wk = ((P.r0 + P.rs * r) * P.S + (P.s0 + P.ss * s)) * Cin + c;
+#pragma unroll
+                for (int i = 0; i < A_PER_T; ++i) {
+                    const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+                    T v = from_float<T>(0.f);
+                    if (kok && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
+                        v = in[(size_t)(a_pix[i] + ih * IW + iw) * Cin + c];
+                    av[i][e] = v;
+                }
+#pragma unroll
+                for (int i = 0; i < B_PER_T; ++i) {
+                    T v = from_float<T>(0.f);
+                    if (kok && b_off[i] >= 0) v = wt[(size_t)b_off[i] + wk];
+                    bv[i][e] = v;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < A_PER_T; ++i) a_reg[i] = *reinterpret_cast<u32x4*>(&av[i][0]);
+#pragma unroll
+            for (int i = 0; i < B_PER_T; ++i) b_reg[i] = *reinterpret_cast<u32x4*>(&bv[i][0]);
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i) {
+            const int v = tid + i * NT;
+            if (A_VECS % NT == 0 || v < A_VECS)
+                *reinterpret_cast<u32x4*>(&As[buf][(v / VPR) * PITCH + kv * EPV]) = a_reg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i) {
+            const int v = tid + i * NT;
+            if (B_VECS % NT == 0 || v < B_VECS)
+                *reinterpret_cast<u32x4*>(&Bs[buf][(v / VPR) * PITCH + kv * EPV]) = b_reg[i];
+        }
+    };
+
+    // ---- main loop: register-staged prefetch, double-buffered LDS ---------------------------------
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < AccT<MT>::N; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = (P.Kg + BK - 1) / BK;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_tile((kt + 1) * BK);
+        mma_ktile<T, MT, FM, FN, BK, PITCH>(As[cur], Bs[cur], wm * TM, wn * TN, lane, acc);
+        if (kt + 1 < nk) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: [+ addends] -> store; per-column sum / sum of squares -------------------------------
+    T* __restrict__ out = reinterpret_cast<T*>(P.out);
+    const T* __restrict__ add0 = reinterpret_cast<const T*>(P.add0);
+    const T* __restrict__ add1 = reinterpret_cast<const T*>(P.add1);
+    const int lc = lane % MT;
+    float cs1[FN], cs2[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) { cs1[j] = 0.f; cs2[j] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = n0 + wn * TN + j * MT + lc;
+#pragma unroll
+            for (int r = 0; r < AccT<MT>::N; ++r) {
+                const int row = wm * TM + i * MT + acc_row<MT>(r, lane);
+                const int ro = s_rowoff[row];
+                float v = acc[i][j][r];
+                cs1[j] += v;
+                cs2[j] += v * v;
+                if (ro >= 0 && col < P.Ncol) {
+                    const size_t o = (size_t)ro + col;
+                    if (add0) v += to_float(add0[o]);
+                    if (add1) v += to_float(add1[o]);
+                    out[o] = from_float<T>(v);
+                }
+            }
+        }
+    if (P.stats) {
+        // rows beyond M hold zeros (their operand rows were zero), so they do not disturb the sums
+        float* red = reinterpret_cast<float*>(&As[0][0]);      // [WGM][BN][2], operands are dead by now
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            float s1 = cs1[j], s2 = cs2[j];
+#pragma unroll
+            for (int sh = MT; sh < 64; sh <<= 1) {
+                s1 += __shfl_xor(s1, sh, 64);
+                s2 += __shfl_xor(s2, sh, 64);
+            }
+            if (lane < MT) {
+                const int c = wn * TN + j * MT + lane;
+                red[(wm * BN + c) * 2 + 0] = s1;
+                red[(wm * BN + c) * 2 + 1] = s2;
+            }
+        }
+        __syncthreads();
+        for (int c = tid; c < BN; c += NT) {
+            const int col = n0 + c;
+            if (col < P.Ncol) {
+                float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+                for (int w = 0; w < WGM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
+                atomicAdd(&P.stats[col], (double)s1);
+                atomicAdd(&P.stats[P.Ncol + col], (double)s2);
+            }
+        }
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// weight gradient
+// -------------------------------------------------------------------------------------------------
+// GEMM rows = output channels (operand dY, read as [m][co]), GEMM columns j = (r,s,ci) (operand X gathered
+// as [m][ci] at the tap of j), reduction over m.  Both operands arrive with the reduction index slowest, so
+// each thread loads 4 consecutive m rows of one 16-byte channel vector and writes the 4 x EPV block
+// transposed, giving the same [row][k] LDS layout as the forward kernel.
+template <typename T, int BM, int BN, int BK, int WGM, int WGN, int MT, bool VEC>
+__global__ __launch_bounds__(WGM* WGN * 64) void conv_wgrad_kernel(const WgradGroup g) {
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int EPV = 16 / (int)sizeof(T);
+    constexpr int PITCH = BK + EPV;
+    constexpr int RG = BK / 4;                         // row groups (4 reduction rows each) per k-tile
+    constexpr int A_CV = BM / EPV, B_CV = BN / EPV;    // channel vectors per operand
+    constexpr int A_GROUPS = A_CV * RG, B_GROUPS = B_CV * RG;
+    constexpr int A_PER_T = (A_GROUPS + NT - 1) / NT, B_PER_T = (B_GROUPS + NT - 1) / NT;
+    constexpr int TM = BM / WGM, TN = BN / WGN, FM = TM / MT, FN = TN / MT;
+    static_assert(BM % EPV == 0 && BN % EPV == 0 && BK % 4 == 0, "tile shape");
+    static_assert(TM % MT == 0 && TN % MT == 0, "wave tile must be whole micro-tiles");
+    typedef typename AccT<MT>::type acc_t;
+
+    __shared__ __attribute__((aligned(16))) T As[2][BM * PITCH];
+    __shared__ __attribute__((aligned(16))) T Bs[2][BN * PITCH];
+
+    const int tid = threadIdx.x;
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if ((int)blockIdx.x >= g.p[i].tile_start) pi = i;
+    const WgradProb& P = g.p[pi];
+    int t = blockIdx.x - P.tile_start;
+    const int tile_n = t % P.tiles_n; t /= P.tiles_n;
+    const int tile_m = t % P.tiles_m;
+    const int split = t / P.tiles_m;
+    const int co0 = tile_m * BM, j0 = tile_n * BN;
+    const int k_begin = split * P.kchunk;
+    const int k_end = min(P.M, k_begin + P.kchunk);
+    const int Cin = P.Cin, Cout = P.Cout, Kg = P.Kg, IH = P.IH, IW = P.IW, Ho = P.Ho, Wo = P.Wo;
+    const T* __restrict__ x = reinterpret_cast<const T*>(P.x);
+    const T* __restrict__ dy = reinterpret_cast<const T*>(P.dy);
+
+    // thread -> (row group, channel vector); row group fastest so that the transposed LDS stores of a
+    // wave spread over banks
+    int a_rg[A_PER_T], a_cv[A_PER_T];
+    bool a_ok[A_PER_T];
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+        const int gi = tid + i * NT;
+        a_rg[i] = gi % RG; a_cv[i] = gi / RG;
+        a_ok[i] = gi < A_GROUPS && (co0 + a_cv[i] * EPV) < Cout;
+    }
+    int b_rg[B_PER_T], b_cv[B_PER_T];
+    int b_dh[B_PER_T][VEC ? 1 : EPV], b_dw[B_PER_T][VEC ? 1 : EPV], b_ci[B_PER_T][VEC ? 1 : EPV];
+#pragma unroll
+    for (int i = 0; i < B_PER_T; ++i) {
+        const int gi = tid + i * NT;
+        b_rg[i] = gi % RG; b_cv[i] = gi / RG;
+#pragma unroll
+        for (int e = 0; e < (VEC ? 1 : EPV); ++e) {
+            const int j = j0 + b_cv[i] * EPV + e;
+            if (gi < B_GROUPS && j < Kg) {
+                const int tap = j / Cin;
+                b_ci[i][e] = j - tap * Cin;
+                const int r = tap / P.S;
+                b_dh[i][e] = r - P.pad;
+                b_dw[i][e] = (tap - r * P.S) - P.pad;
+            } else {
+                b_ci[i][e] = -1; b_dh[i][e] = 0; b_dw[i][e] = 0;
+            }
+        }
+    }
+
+    u32x4 a_reg[A_PER_T][4], b_reg[B_PER_T][4];
+    auto load_tile = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int m = k0 + a_rg[i] * 4 + rr;
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (a_ok[i] && m < k_end) v = *reinterpret_cast<const u32x4*>(dy + ((size_t)m * Cout + co0 + a_cv[i] * EPV));
+                a_reg[i][rr] = v;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i) {
+            const int mb = k0 + b_rg[i] * 4;
+            // decode the first row of the group, then step
+            const int per = Ho * Wo;
+            int n = mb / per;
+            int rem = mb - n * per;
+            int ho = rem / Wo, wo = rem - ho * Wo;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int m = mb + rr;
+                if constexpr (VEC) {
+                    u32x4 v = {0u, 0u, 0u, 0u};
+                    const int ih = ho * P.stride + b_dh[i][0], iw = wo * P.stride + b_dw[i][0];
+                    if (b_ci[i][0] >= 0 && m < k_end && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
+                        v = *reinterpret_cast<const u32x4*>(x + ((size_t)((n * IH + ih) * IW + iw) * Cin + b_ci[i][0]));
+                    b_reg[i][rr] = v;
+                } else {
+                    T tmp[EPV];
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) {
+                        const int ih = ho * P.stride + b_dh[i][e], iw = wo * P.stride + b_dw[i][e];
+                        T v = from_float<T>(0.f);
+                        if (b_ci[i][e] >= 0 && m < k_end && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
+                            v = x[(size_t)((n * IH + ih) * IW + iw) * Cin + b_ci[i][e]];
+                        tmp[e] = v;
+                    }
+                    b_reg[i][rr] = *reinterpret_cast<u32x4*>(&tmp[0]);
+                }
+                if (++wo == Wo) { wo = 0; if (++ho == Ho) { ho = 0; ++n; } }
+            }
+        }
+    };
+    // transposed store of a 4 x EPV block: element e of the 4 rows -> LDS row (cv*EPV+e), k = rg*4..rg*4+3
+    auto store_block = [&](T* dst, int cv, int rg, const u32x4 (&v)[4]) {
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                u32x4 o = {v[0][e], v[1][e], v[2][e], v[3][e]};
+                *reinterpret_cast<u32x4*>(dst + (cv * EPV + e) * PITCH + rg * 4) = o;
+            }
+        } else {
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {       // dword e2 holds channels 2*e2 (low half) and 2*e2+1 (high half)
+                const unsigned d0 = v[0][e2], d1 = v[1][e2], d2 = v[2][e2], d3 = v[3][e2];
+                uint2 lo, hi;
+                lo.x = (d0 & 0xffffu) | (d1 << 16);
+                lo.y = (d2 & 0xffffu) | (d3 << 16);
+                hi.x = (d0 >> 16) | (d1 & 0xffff0000u);
+                hi.y = (d2 >> 16) | (d3 & 0xffff0000u);
+                *reinterpret_cast<uint2*>(dst + (cv * EPV + 2 * e2) * PITCH + rg * 4) = lo;
+                *reinterpret_cast<uint2*>(dst + (cv * EPV + 2 * e2 + 1) * PITCH + rg * 4) = hi;
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i)
+            if (A_GROUPS % NT == 0 || tid + i * NT < A_GROUPS) store_block(As[buf], a_cv[i], a_rg[i], a_reg[i]);
+#pragma unroll
+        for (int i = 0; i < B_PER_T; ++i)
+            if (B_GROUPS % NT == 0 || tid + i * NT < B_GROUPS) store_block(Bs[buf], b_cv[i], b_rg[i], b_reg[i]);
+    };
+
+    const int wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < AccT<MT>::N; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = (k_end - k_begin + BK - 1) / BK;
+    if (nk > 0) {
+        load_tile(k_begin);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_tile(k_begin + (kt + 1) * BK);
+        mma_ktile<T, MT, FM, FN, BK, PITCH>(As[cur], Bs[cur], wm * TM, wn * TN, lane, acc);
+        if (kt + 1 < nk) store_tile(cur ^ 1);
+        __syncthreads();
+    }
+
+    if (nk > 0) {
+        const int lc = lane % MT;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = j0 + wn * TN + j * MT + lc;
+#pragma unroll
+                for (int r = 0; r < AccT<MT>::N; ++r) {
+                    const int co = co0 + wm * TM + i * MT + acc_row<MT>(r, lane);
+                    if (co < Cout && col < Kg) {
+                        float* dst = P.dw + (size_t)co * Kg + col;
+                        if (P.ksplit == 1) *dst = acc[i][j][r];
+                        else atomicAdd(dst, acc[i][j][r]);
+                    }
+                }
+            }
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// filter re-layout for the data-gradient: w[co][rs][ci] -> wt[ci][rs][co]
+// -------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void wtrans_kernel(const WtransGroup g) {
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if ((int)blockIdx.x >= g.p[i].block_start) pi = i;
+    const WtransProb& P = g.p[pi];
+    const T* __restrict__ w = reinterpret_cast<const T*>(P.w);
+    T* __restrict__ wt = reinterpret_cast<T*>(P.wt);
+    // 32 x 32 (co, ci) tile of one tap through LDS so that both sides are coalesced
+    __shared__ T tile[32][33];
+    const int tiles_ci = (P.Cin + 31) / 32, tiles_co = (P.Cout + 31) / 32;
+    int b = blockIdx.x - P.block_start;
+    const int tci = b % tiles_ci; b /= tiles_ci;
+    const int tco = b % tiles_co;
+    const int rs = b / tiles_co;
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;   // 256 threads: ty in [0,8)
+    for (int r = ty; r < 32; r += 8) {
+        const int co = tco * 32 + r, ci = tci * 32 + tx;
+        if (co < P.Cout && ci < P.Cin) tile[r][tx] = w[((size_t)co * P.RS + rs) * P.Cin + ci];
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int ci = tci * 32 + r, co = tco * 32 + tx;
+        if (co < P.Cout && ci < P.Cin) wt[((size_t)ci * P.RS + rs) * P.Cout + co] = tile[tx][r];
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// the im2col address function of the forward kernel, evaluated with the same integer arithmetic
+// -------------------------------------------------------------------------------------------------
+__global__ void im2col_offsets_kernel(int H, int W, int Cin, int R, int S, int stride, int pad,
+                                      const int64_t* __restrict__ ms, const int64_t* __restrict__ qs,
+                                      int64_t* __restrict__ out, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
+    // row decode as in conv_igemm_kernel (OA = Ho, OB = Wo, imul = stride, dh0 = dw0 = -pad, dhs = dws = 1)
+    const int m = (int)ms[i], q = (int)qs[i];
+    const int per = Ho * Wo;
+    const int n = m / per, rem = m - n * per;
+    const int a = rem / Wo, b = rem - a * Wo;
+    const int a_pix = n * H * W, a_ih = a * stride - pad, a_iw = b * stride - pad;
+    const int tap = q / Cin, ci = q - tap * Cin;
+    const int tr = tap / S, ts = tap - tr * S;
+    const int ih = a_ih + tr, iw = a_iw + ts;
+    int64_t o = -1;
+    if (tr < R && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
+        o = (int64_t)((size_t)(a_pix + ih * W + iw) * Cin + ci);
+    out[i] = o;
+}
+
+// -------------------------------------------------------------------------------------------------
+// launchers
+// -------------------------------------------------------------------------------------------------
+namespace {
+template <typename T> struct CfgK { static constexpr int BK = sizeof(T) == 2 ? 32 : 16; };
+
+template <typename T, int BM, int BN, int WGM, int WGN, int MT, bool VEC>
+hipError_t conv_launch(const ConvGroup& g, hipStream_t s) {
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, CfgK<T>::BK, WGM, WGN, MT, VEC>), dim3(g.total_tiles),
+                       dim3(WGM * WGN * 64), 0, s, g);
+    return hipGetLastError();
+}
+template <typename T, bool VEC>
+hipError_t conv_dispatch(const ConvGroup& g, int cfg, hipStream_t s) {
+    switch (cfg) {
+        case CFG_N16: return conv_launch<T, 256, 16, 4, 1, 16, VEC>(g, s);
+        case CFG_N32: return conv_launch<T, 256, 32, 4, 1, 16, VEC>(g, s);
+        case CFG_N64: return conv_launch<T, 128, 64, 2, 2, 32, VEC>(g, s);
+        case CFG_N128: if constexpr (VEC) return conv_launch<T, 128, 128, 2, 2, 32, true>(g, s); else break;
+        case CFG_N160: if constexpr (VEC) return conv_launch<T, 128, 160, 2, 2, 16, true>(g, s); else break;
+        default: break;
+    }
+    return hipErrorInvalidValue;
+}
+template <typename T, int BM, int BN, int WGM, int WGN, int MT, bool VEC>
+hipError_t wgrad_launch(const WgradGroup& g, hipStream_t s) {
+    hipLaunchKernelGGL((conv_wgrad_kernel<T, BM, BN, CfgK<T>::BK, WGM, WGN, MT, VEC>), dim3(g.total_tiles),
+                       dim3(WGM * WGN * 64), 0, s, g);
+    return hipGetLastError();
+}
+template <typename T, bool VEC>
+hipError_t wgrad_dispatch(const WgradGroup& g, int cfg, hipStream_t s) {
+    switch (cfg) {
+        case CFG_N16: return wgrad_launch<T, 16, 128, 1, 4, 16, VEC>(g, s);
+        case CFG_N32: return wgrad_launch<T, 32, 128, 1, 4, 16, VEC>(g, s);
+        case CFG_N64: return wgrad_launch<T, 64, 128, 2, 2, 32, VEC>(g, s);
+        case CFG_N128: if constexpr (VEC) return wgrad_launch<T, 128, 128, 2, 2, 32, true>(g, s); else break;
+        case CFG_N160: if constexpr (VEC) return wgrad_launch<T, 160, 160, 2, 2, 16, true>(g, s); else break;
+        default: break;
+    }
+    return hipErrorInvalidValue;
+}
+}  // namespace
+
+CfgInfo conv_cfg_info(int cfg, int dtype) {
+    const int bk = dtype == 1 ? 32 : 16;
+    switch (cfg) {
+        case CFG_N16: return {256, 16, bk};
+        case CFG_N32: return {256, 32, bk};
+        case CFG_N64: return {128, 64, bk};
+        case CFG_N128: return {128, 128, bk};
+        default: return {128, 160, bk};
+    }
+}
+CfgInfo wgrad_cfg_info(int cfg, int dtype) {
+    const int bk = dtype == 1 ? 32 : 16;
+    switch (cfg) {
+        case CFG_N16: return {16, 128, bk};
+        case CFG_N32: return {32, 128, bk};
+        case CFG_N64: return {64, 128, bk};
+        case CFG_N128: return {128, 128, bk};
+        default: return {160, 160, bk};
+    }
+}
+
+hipError_t launch_conv(const ConvGroup& g, int dtype, int cfg, bool vec, hipStream_t s) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    if (dtype == 1) return vec ? conv_dispatch<bf16_t, true>(g, cfg, s) : conv_dispatch<bf16_t, false>(g, cfg, s);
+    return vec ? conv_dispatch<float, true>(g, cfg, s) : conv_dispatch<float, false>(g, cfg, s);
+}
+hipError_t launch_wgrad(const WgradGroup& g, int dtype, int cfg, bool vec, hipStream_t s) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    if (dtype == 1) return vec ? wgrad_dispatch<bf16_t, true>(g, cfg, s) : wgrad_dispatch<bf16_t, false>(g, cfg, s);
+    return vec ? wgrad_dispatch<float, true>(g, cfg, s) : wgrad_dispatch<float, false>(g, cfg, s);
+}
+hipError_t launch_wtrans(const WtransGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    if (dtype == 1) hipLaunchKernelGGL(wtrans_kernel<bf16_t>, dim3(g.total_blocks), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(wtrans_kernel<float>, dim3(g.total_blocks), dim3(256), 0, s, g);
+    return hipGetLastError();
+}
+hipError_t launch_im2col_offsets(int H, int W, int Cin, int R, int S, int stride, int pad,
+                                 const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(im2col_offsets_kernel, dim3((count + 255) / 256), dim3(256), 0, s, H, W, Cin, R, S, stride, pad,
+                       m, q, out, count);
+    return hipGetLastError();
+}
+
+}  // namespace lp

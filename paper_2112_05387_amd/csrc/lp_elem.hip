@@ -1,0 +1,501 @@
+// Grouped HBM-bound kernels of the local step: batch-norm apply (+ReLU, +skip), batch-norm backward
+// (reduce / apply), the local penalty / augmented-Lagrangian loss and terminal adjoint, the multiplier
+// update, the classification head, max pooling and buffer clears.  NHWC, 16-byte accesses with the
+// channel index fastest, fp32 arithmetic, wavefront/LDS reductions, one atomic per channel per workgroup.
+#include "lp_kernels.h"
+#include "lp_mma.h"
+
+namespace lp {
+
+namespace {
+
+template <typename T> struct Vec {
+    static constexpr int N = 16 / (int)sizeof(T);
+    __device__ static __forceinline__ void load(const T* p, float (&f)[N]) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(v[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f[2 * e] = __uint_as_float(v[e] << 16);
+                f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+            }
+        }
+    }
+    __device__ static __forceinline__ void store(T* p, const float (&f)[N]) {
+        u32x4 v;
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __float_as_uint(f[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[e] = (unsigned)float_to_bf16_bits(f[2 * e]) | ((unsigned)float_to_bf16_bits(f[2 * e + 1]) << 16);
+        }
+        *reinterpret_cast<u32x4*>(p) = v;
+    }
+};
+
+__device__ __forceinline__ void bn_coeffs(const double* stats, const float* gamma, const float* beta, int c, int C,
+                                          int M, float eps, float& sc, float& sh, float& mean, float& invstd) {
+    const double mu = stats[c] / (double)M;
+    double var = stats[C + c] / (double)M - mu * mu;
+    if (var < 0.0) var = 0.0;
+    mean = (float)mu;
+    invstd = rsqrtf((float)var + eps);
+    sc = gamma[c] * invstd;
+    sh = beta[c] - mean * sc;
+}
+
+template <typename G> __device__ __forceinline__ int find_problem(const G& g, int bid) {
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if (bid >= g.p[i].block_start) pi = i;
+    return pi;
+}
+
+constexpr int kMaxC = 2048;
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    __shared__ float s_sc[kMaxC], s_sh[kMaxC], s_ssc[kMaxC], s_ssh[kMaxC];
+    const BnApplyProb& P = g.p[find_problem(g, blockIdx.x)];
+    const int C = P.C, M = P.M;
+    for (int c = threadIdx.x; c < C; c += kElemBlock) {
+        float sc, sh, mu, is;
+        bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
+        s_sc[c] = sc; s_sh[c] = sh;
+        if (P.skip_mode == 2) {
+            bn_coeffs(P.sstats, P.sgamma, P.sbeta, c, C, M, g.eps, sc, sh, mu, is);
+            s_ssc[c] = sc; s_ssh[c] = sh;
+        }
+    }
+    __syncthreads();
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    const T* __restrict__ skip = reinterpret_cast<const T*>(P.skip);
+    T* __restrict__ out = reinterpret_cast<T*>(P.out);
+    const size_t nvec = (size_t)M * C / EPV;
+    const int cv = C / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        const int c0 = (int)(v % cv) * EPV;
+        float f[EPV], o[EPV];
+        Vec<T>::load(y + v * EPV, f);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[e], s_sh[c0 + e]);
+        if (P.skip_mode) {
+            float s[EPV];
+            Vec<T>::load(skip + v * EPV, s);
+            if (P.skip_mode == 2) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] += fmaf(s_ssc[c0 + e], s[e], s_ssh[c0 + e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] += s[e];
+            }
+        }
+        if (P.relu) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) o[e] = fmaxf(o[e], 0.f);
+        }
+        Vec<T>::store(out + v * EPV, o);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// red[c] += sum g', red[C+c] += sum g'*yhat over this workgroup's rows
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    __shared__ float s_red[kElemBlock * EPV * 2];
+    const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
+    const int C = P.C, M = P.M, cv = C / EPV;
+    const int b = blockIdx.x - P.block_start;
+    const int rows_pb = (M + P.nblocks - 1) / P.nblocks;
+    const int row0 = b * rows_pb, row1 = min(M, row0 + rows_pb);
+    const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    for (int cbase = 0; cbase < cv; cbase += kElemBlock) {
+        const int ncv = min(cv - cbase, kElemBlock);     // channel vectors in this pass
+        const int rl = kElemBlock / ncv;                 // row lanes
+        const int tcv = threadIdx.x % ncv, trl = threadIdx.x / ncv;
+        float a1[EPV], a2[EPV];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) { a1[e] = 0.f; a2[e] = 0.f; }
+        if (trl < rl) {
+            const int c0 = (cbase + tcv) * EPV;
+            float sc[EPV], sh[EPV], mu[EPV], is[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) bn_coeffs(P.stats, P.gamma, P.beta, c0 + e, C, M, g.eps, sc[e], sh[e], mu[e], is[e]);
+            for (int r = row0 + trl; r < row1; r += rl) {
+                float gv[EPV], yv[EPV];
+                Vec<T>::load(gp + (size_t)r * C + c0, gv);
+                Vec<T>::load(y + (size_t)r * C + c0, yv);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    float gg = gv[e];
+                    if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
+                    a1[e] += gg;
+                    a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
+                }
+            }
+        }
+        __syncthreads();
+        if (trl < rl) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                s_red[((trl * ncv + tcv) * EPV + e) * 2] = a1[e];
+                s_red[((trl * ncv + tcv) * EPV + e) * 2 + 1] = a2[e];
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < ncv * EPV; i += kElemBlock) {
+            float s1 = 0.f, s2 = 0.f;
+            for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
+            const int c = cbase * EPV + i;
+            atomicAdd(&P.red[c], (double)s1);
+            atomicAdd(&P.red[C + c], (double)s2);
+        }
+    }
+}
+
+// dy = gamma*invstd*(g' - red0/M - yhat*red1/M)
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    __shared__ float s_sc[kMaxC], s_sh[kMaxC], s_k1[kMaxC], s_k2[kMaxC], s_k3[kMaxC];
+    const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
+    const int C = P.C, M = P.M;
+    const bool first = (int)blockIdx.x == P.block_start;
+    for (int c = threadIdx.x; c < C; c += kElemBlock) {
+        float sc, sh, mu, is;
+        bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
+        const float r0 = (float)(P.red[c] / (double)M), r1 = (float)(P.red[C + c] / (double)M);
+        const float k1 = P.gamma[c] * is;
+        const float k2 = k1 * is * r1;
+        s_sc[c] = sc; s_sh[c] = sh;
+        s_k1[c] = k1; s_k2[c] = k2; s_k3[c] = k2 * mu - k1 * r0;
+        if (first) {
+            P.dgamma[c] = (float)P.red[C + c];
+            P.dbeta[c] = (float)P.red[c];
+        }
+    }
+    __syncthreads();
+    const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    T* __restrict__ dy = reinterpret_cast<T*>(P.dy);
+    const size_t nvec = (size_t)M * C / EPV;
+    const int cv = C / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        const int c0 = (int)(v % cv) * EPV;
+        float gv[EPV], yv[EPV], o[EPV];
+        Vec<T>::load(gp + v * EPV, gv);
+        Vec<T>::load(y + v * EPV, yv);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            float gg = gv[e];
+            if (P.relu && !(fmaf(s_sc[c0 + e], yv[e], s_sh[c0 + e]) > 0.f)) gg = 0.f;
+            o[e] = s_k1[c0 + e] * gg - s_k2[c0 + e] * yv[e] + s_k3[c0 + e];
+        }
+        Vec<T>::store(dy + v * EPV, o);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kElemBlock) void fill_kernel(const FillGroup g) {
+    const FillProb& P = g.p[find_problem(g, blockIdx.x)];
+    const size_t nvec = P.bytes / 16;
+    u32x4* p = reinterpret_cast<u32x4*>(P.ptr);
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        p[v] = z;
+    }
+}
+
+__device__ __forceinline__ float block_sum(float v, float* s_tmp) {
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) v += __shfl_xor(v, sh, 64);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) s_tmp[wave] = v;
+    __syncthreads();
+    float r = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) r += s_tmp[w];
+    return r;
+}
+
+// local penalty / augmented-Lagrangian term and terminal adjoint
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    __shared__ float s_tmp[kElemBlock / 64];
+    const LossProb& P = g.p[find_problem(g, blockIdx.x)];
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    const T* __restrict__ xn = reinterpret_cast<const T*>(P.xn);
+    const T* __restrict__ lam = reinterpret_cast<const T*>(P.lam);
+    T* __restrict__ dy = reinterpret_cast<T*>(P.dy);
+    const size_t nvec = P.numel / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        float a[EPV], b[EPV], l[EPV], o[EPV];
+        Vec<T>::load(y + v * EPV, a);
+        Vec<T>::load(xn + v * EPV, b);
+        if (lam) Vec<T>::load(lam + v * EPV, l);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            const float r = a[e] - b[e];
+            const float lm = lam ? l[e] : 0.f;
+            acc += 0.5f * g.rho * r * r + lm * r;
+            o[e] = g.scale * (g.rho * r + lm);
+        }
+        Vec<T>::store(dy + v * EPV, o);
+    }
+    const float tot = block_sum(acc, s_tmp);
+    if (threadIdx.x == 0 && tot != 0.f) atomicAdd(P.loss, g.scale * tot);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void mult_kernel(const MultGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    const MultProb& P = g.p[find_problem(g, blockIdx.x)];
+    T* __restrict__ lam = reinterpret_cast<T*>(P.lam);
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    const T* __restrict__ xn = reinterpret_cast<const T*>(P.xn);
+    const size_t nvec = P.numel / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        float a[EPV], b[EPV], l[EPV];
+        Vec<T>::load(y + v * EPV, a);
+        Vec<T>::load(xn + v * EPV, b);
+        Vec<T>::load(lam + v * EPV, l);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) l[e] = fmaf(g.step, a[e] - b[e], l[e]);
+        Vec<T>::store(lam + v * EPV, l);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// max pooling (first maximum in row-major window order wins)
+template <typename T>
+__global__ void maxpool_fwd_kernel(const PoolProb P) {
+    const size_t total = (size_t)P.N * P.Ho * P.Wo * P.C;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const T* __restrict__ x = reinterpret_cast<const T*>(P.x);
+    const int c = (int)(i % P.C);
+    size_t r = i / P.C;
+    const int wo = (int)(r % P.Wo); r /= P.Wo;
+    const int ho = (int)(r % P.Ho);
+    const int n = (int)(r / P.Ho);
+    float best = 0.f; int bi = -1;
+    for (int a = 0; a < P.R; ++a) {
+        const int hi = ho * P.stride - P.pad + a;
+        if (hi < 0 || hi >= P.H) continue;
+        for (int b = 0; b < P.R; ++b) {
+            const int wi = wo * P.stride - P.pad + b;
+            if (wi < 0 || wi >= P.W) continue;
+            const float v = to_float(x[((size_t)(n * P.H + hi) * P.W + wi) * P.C + c]);
+            if (bi < 0 || v > best) { best = v; bi = a * P.R + b; }
+        }
+    }
+    reinterpret_cast<T*>(P.y)[i] = from_float<T>(best);
+    P.arg[i] = (uint8_t)bi;
+}
+
+template <typename T>
+__global__ void maxpool_bwd_kernel(const PoolProb P) {
+    const size_t total = (size_t)P.N * P.H * P.W * P.C;
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const T* __restrict__ dy = reinterpret_cast<const T*>(P.dy);
+    const int c = (int)(i % P.C);
+    size_t r = i / P.C;
+    const int wi = (int)(r % P.W); r /= P.W;
+    const int hi = (int)(r % P.H);
+    const int n = (int)(r / P.H);
+    float acc = 0.f;
+    // windows (ho, wo) that contain (hi, wi): ho*stride - pad + a = hi
+    for (int a = 0; a < P.R; ++a) {
+        const int th = hi + P.pad - a;
+        if (th < 0 || th % P.stride) continue;
+        const int ho = th / P.stride;
+        if (ho >= P.Ho) continue;
+        for (int b = 0; b < P.R; ++b) {
+            const int tw = wi + P.pad - b;
+            if (tw < 0 || tw % P.stride) continue;
+            const int wo = tw / P.stride;
+            if (wo >= P.Wo) continue;
+            const size_t o = ((size_t)(n * P.Ho + ho) * P.Wo + wo) * P.C + c;
+            if (P.arg[o] == (uint8_t)(a * P.R + b)) acc += to_float(dy[o]);
+        }
+    }
+    reinterpret_cast<T*>(P.dx)[i] = from_float<T>(acc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// head: pooled[n,c] = mean_{hw} feat;  logits = pooled W^T + b
+template <typename T>
+__global__ void avgpool_kernel(const HeadProb P) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P.N * P.C) return;
+    const int n = i / P.C, c = i % P.C;
+    const T* __restrict__ f = reinterpret_cast<const T*>(P.feat) + (size_t)n * P.HW * P.C + c;
+    float s = 0.f;
+    for (int p = 0; p < P.HW; ++p) s += to_float(f[(size_t)p * P.C]);
+    P.pooled[i] = s / (float)P.HW;
+}
+__global__ void fc_fwd_kernel(const HeadProb P) {          // one wave per (n, class)
+    const int o = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (o >= P.N * P.classes) return;
+    const int n = o / P.classes, j = o % P.classes, lane = threadIdx.x & 63;
+    float s = 0.f;
+    for (int c = lane; c < P.C; c += 64) s += P.pooled[n * P.C + c] * P.w[(size_t)j * P.C + c];
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) s += __shfl_xor(s, sh, 64);
+    if (lane == 0) P.logits[o] = s + P.b[j];
+}
+__global__ void fc_bwd_w_kernel(const HeadProb P) {        // dW[j,c] = sum_n dz[n,j]*pooled[n,c]; db[j] = sum_n dz[n,j]
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P.classes * P.C) return;
+    const int j = i / P.C, c = i % P.C;
+    float s = 0.f, sb = 0.f;
+    for (int n = 0; n < P.N; ++n) {
+        const float d = P.dlogits[n * P.classes + j];
+        s += d * P.pooled[n * P.C + c];
+        sb += d;
+    }
+    P.dw[i] = s;
+    if (c == 0) P.db[j] = sb;
+}
+template <typename T>
+__global__ void fc_bwd_x_kernel(const HeadProb P) {        // dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P.N * P.C) return;
+    const int n = i / P.C, c = i % P.C;
+    float s = 0.f;
+    for (int j = 0; j < P.classes; ++j) s += P.dlogits[n * P.classes + j] * P.w[(size_t)j * P.C + c];
+    const T v = from_float<T>(s / (float)P.HW);
+    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * P.C + c;
+    for (int p = 0; p < P.HW; ++p) d[(size_t)p * P.C] = v;
+}
+
+// softmax cross-entropy, mini-batch mean; one workgroup per sample
+__global__ __launch_bounds__(kElemBlock) void ce_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                        float* loss, float* __restrict__ dlogits, int N, int classes) {
+    __shared__ float s_tmp[kElemBlock / 64];
+    __shared__ float s_max[kElemBlock / 64];
+    const int n = blockIdx.x;
+    const float* z = logits + (size_t)n * classes;
+    float mx = -INFINITY;
+    for (int j = threadIdx.x; j < classes; j += kElemBlock) mx = fmaxf(mx, z[j]);
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sh, 64));
+    if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = s_max[0];
+    for (int w = 1; w < kElemBlock / 64; ++w) mx = fmaxf(mx, s_max[w]);
+    float se = 0.f;
+    for (int j = threadIdx.x; j < classes; j += kElemBlock) se += __expf(z[j] - mx);
+    se = block_sum(se, s_tmp);
+    const int lab = labels[n];
+    const float inv = 1.f / se, invN = 1.f / (float)N;
+    for (int j = threadIdx.x; j < classes; j += kElemBlock) {
+        float p = __expf(z[j] - mx) * inv;
+        if (j == lab) p -= 1.f;
+        dlogits[(size_t)n * classes + j] = p * invN;
+    }
+    if (threadIdx.x == 0) atomicAdd(loss, (logf(se) + mx - z[lab]) * invN);
+}
+
+__global__ void zero_selected_kernel(float* v, uint32_t mask, int n) {
+    const int i = threadIdx.x;
+    if (i < n && ((mask >> i) & 1u)) v[i] = 0.f;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+#define LP_DISPATCH_T(dtype, KERNEL, grid, block, stream, ...)                                   \
+    do {                                                                                         \
+        if ((dtype) == 1) hipLaunchKernelGGL(KERNEL<bf16_t>, grid, block, 0, stream, __VA_ARGS__); \
+        else hipLaunchKernelGGL(KERNEL<float>, grid, block, 0, stream, __VA_ARGS__);             \
+    } while (0)
+
+hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, bn_apply_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, bn_bwd_reduce_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, bn_bwd_apply_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_fill(const FillGroup& g, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_kernel, dim3(g.total_blocks), dim3(kElemBlock), 0, s, g);
+    return hipGetLastError();
+}
+hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, loss_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, mult_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_maxpool_fwd(const PoolProb& p, int dtype, hipStream_t s) {
+    const size_t total = (size_t)p.N * p.Ho * p.Wo * p.C;
+    LP_DISPATCH_T(dtype, maxpool_fwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, p);
+    return hipGetLastError();
+}
+hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s) {
+    const size_t total = (size_t)p.N * p.H * p.W * p.C;
+    LP_DISPATCH_T(dtype, maxpool_bwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, p);
+    return hipGetLastError();
+}
+hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
+    LP_DISPATCH_T(dtype, avgpool_kernel, dim3((p.N * p.C + 255) / 256), dim3(256), s, p);
+    hipLaunchKernelGGL(fc_fwd_kernel, dim3((p.N * p.classes + 3) / 4), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
+    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256), dim3(256), 0, s, p);
+    LP_DISPATCH_T(dtype, fc_bwd_x_kernel, dim3((p.N * p.C + 255) / 256), dim3(256), s, p);
+    return hipGetLastError();
+}
+hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s) {
+    hipLaunchKernelGGL(zero_selected_kernel, dim3(1), dim3(64), 0, s, v, mask, n);
+    return hipGetLastError();
+}
+hipError_t launch_ce(const float* logits, const int32_t* labels, float* loss, float* dlogits, int N, int classes,
+                     hipStream_t s) {
+    hipLaunchKernelGGL(ce_kernel, dim3(N), dim3(kElemBlock), 0, s, logits, labels, loss, dlogits, N, classes);
+    return hipGetLastError();
+}
+
+}  // namespace lp

@@ -1,0 +1,152 @@
+// Device-side problem descriptors and launch entry points of the local-step kernels (gfx950).
+// Every kernel is a *grouped* launch: one grid covers the same operation of several modules, the
+// per-module problems travel by value in the kernel arguments, and a workgroup finds its problem from
+// a prefix table of tile counts.  That is how the K independent local steps of Sec. 4.1 share one GPU.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lp {
+
+constexpr int kMaxGroup = 16;   // problems per grouped launch (bounded by the 4 KiB kernel-argument block)
+
+// ---------------------------------------------------------------------------------------------------
+// Implicit-GEMM convolution, forward and data-gradient:  OUT[m, col] = sum_q A[m, q] * WT[col, q]
+//   m   -> (n, a, b) on a row grid [N][OA][OB];  q -> (tr, ts, ci) with ci fastest
+//   A[m,q] = IN[n, a*imul + dh0 + dhs*tr, b*imul + dw0 + dws*ts, ci]      (zero outside the image)
+//   WT[col,q] = wt[col*ldw + ((r0 + rs*tr)*S + (s0 + ss*ts))*Cin + ci]
+//   OUT pixel = (n, a*omul + ooh, b*omul + oow) of an [N][OH][OW][Ncol] tensor
+// Forward conv: imul = stride, dh0 = -pad, dhs = 1, full tap range, omul = 1.
+// Data-gradient: IN = dY, wt = filters re-laid-out as [Cin][R][S][Cout]; stride 1: dh0 = pad, dhs = -1;
+// stride 2: one problem per output parity class with the taps of matching parity (rs = 2).
+struct ConvProb {
+    const void* in;
+    const void* wt;
+    void* out;
+    const void* add0;     // optional addends with the layout of out (skip-path gradients)
+    const void* add1;
+    double* stats;        // optional: [2*Ncol] per-column sum and sum of squares of the fp32 results
+    int M, Ncol, Kg, Cin;
+    int OA, OB, IH, IW, imul;
+    int ntr, nts, dh0, dhs, dw0, dws;
+    int r0, rs, s0, ss, S, ldw;
+    int OH, OW, omul, ooh, oow;
+    int tiles_m, tiles_n, tile_start;
+};
+struct ConvGroup {
+    int nprob, total_tiles;
+    ConvProb p[kMaxGroup];
+};
+
+// Weight gradient:  dW[co, (r,s,ci)] (+)= sum_m dY[m, co] * X[n, ho*stride - pad + r, wo*stride - pad + s, ci]
+// split over `ksplit` slices of the reduction; partial results are added to dW with fp32 atomics.
+struct WgradProb {
+    const void* x;
+    const void* dy;
+    float* dw;
+    int M, Cout, Kg, Cin;
+    int Ho, Wo, IH, IW, stride, pad, R, S;
+    int ksplit, kchunk;
+    int tiles_m, tiles_n, tile_start;
+};
+struct WgradGroup {
+    int nprob, total_tiles;
+    WgradProb p[kMaxGroup];
+};
+
+// filters [Cout][R][S][Cin] -> [Cin][R][S][Cout]
+struct WtransProb {
+    const void* w;
+    void* wt;
+    int Cout, RS, Cin;
+    int block_start;
+};
+struct WtransGroup {
+    int nprob, total_blocks;
+    WtransProb p[kMaxGroup];
+};
+
+// out = act( bn(y) [+ skip] ),  bn(y) = gamma*(y-mean)*invstd + beta from the summed statistics.
+// skip_mode 0: none, 1: plain tensor, 2: bn_s(skip) with its own statistics.
+struct BnApplyProb {
+    const void* y; void* out;
+    const double* stats; const float* gamma; const float* beta;
+    const void* skip; const double* sstats; const float* sgamma; const float* sbeta;
+    int M, C, relu, skip_mode;
+    int block_start, nblocks;
+};
+struct BnApplyGroup {
+    int nprob, total_blocks; float eps;
+    BnApplyProb p[kMaxGroup];
+};
+
+// Batch-norm backward.  g' = g * [gamma*yhat + beta > 0] when relu is set.
+// reduce: red[0..C) += sum g', red[C..2C) += sum g'*yhat.   apply: dy = gamma*invstd*(g' - red0/M - yhat*red1/M),
+// and the first workgroup of each problem writes dgamma = red1, dbeta = red0.
+struct BnBwdProb {
+    const void* g; const void* y; void* dy;
+    const double* stats; const float* gamma; const float* beta;
+    double* red; float* dgamma; float* dbeta;
+    int M, C, relu;
+    int block_start, nblocks;
+};
+struct BnBwdGroup {
+    int nprob, total_blocks; float eps;
+    BnBwdProb p[kMaxGroup];
+};
+
+struct FillProb { void* ptr; size_t bytes; int block_start; };
+struct FillGroup { int nprob, total_blocks; FillProb p[kMaxGroup]; };
+
+// r = y - x_next;  dy = scale*(rho*r + lam);  loss += scale*(rho/2*sum r^2 + sum lam*r)
+struct LossProb {
+    const void* y; const void* xn; const void* lam; void* dy; float* loss;
+    size_t numel; int block_start, nblocks;
+};
+struct LossGroup { int nprob, total_blocks; float rho, scale; LossProb p[kMaxGroup]; };
+
+// lam += step*(y - x_next)
+struct MultProb { void* lam; const void* y; const void* xn; size_t numel; int block_start, nblocks; };
+struct MultGroup { int nprob, total_blocks; float step; MultProb p[kMaxGroup]; };
+
+struct PoolProb {        // max pooling R x R, stride, pad on NHWC
+    const void* x; void* y; uint8_t* arg; const void* dy; void* dx;
+    int N, H, W, C, Ho, Wo, R, stride, pad;
+};
+
+struct HeadProb {        // global average pool + linear
+    const void* feat; float* pooled; const float* w; const float* b; float* logits;
+    const float* dlogits; float* dw; float* db; void* dfeat;
+    int N, HW, C, classes;
+};
+
+// ---- launchers (host side; return hipError_t of the launch) ----------------------------------------
+// tile configuration ids of the implicit-GEMM kernels
+enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160, CFG_COUNT };
+struct CfgInfo { int BM, BN, BK; };
+CfgInfo conv_cfg_info(int cfg, int dtype);
+CfgInfo wgrad_cfg_info(int cfg, int dtype);
+
+hipError_t launch_conv(const ConvGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
+hipError_t launch_wgrad(const WgradGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
+hipError_t launch_wtrans(const WtransGroup& g, int dtype, hipStream_t s);
+hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s);
+hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s);
+hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s);
+hipError_t launch_fill(const FillGroup& g, hipStream_t s);
+hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s);
+hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s);
+hipError_t launch_maxpool_fwd(const PoolProb& p, int dtype, hipStream_t s);
+hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s);
+hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s);
+hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s);
+hipError_t launch_ce(const float* logits, const int32_t* labels, float* loss, float* dlogits,
+                     int N, int classes, hipStream_t s);
+hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s);
+hipError_t launch_im2col_offsets(int H, int W, int Cin, int R, int S, int stride, int pad,
+                                 const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s);
+
+constexpr int kElemBlock = 256;          // threads per workgroup of the elementwise kernels
+constexpr int kElemVecsPerBlock = 2048;  // 16-byte vectors handled by one workgroup
+
+}  // namespace lp

@@ -1,0 +1,166 @@
+"""Device-buffer holder for one local step.  PyTorch provides device memory and the stream; every
+computation happens in the HIP library behind `binding`."""
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _dev():
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: the local step runs on an MI355X only (there is no CPU fallback)")
+    return torch.device("cuda:0")
+
+
+class LocalStep:
+    """Owns the net handle, workspace, packed parameters and interface tensors of one configuration.
+
+    `desc` is any object with the attributes of the C descriptors (modules, aux, dtype, bn_eps, K)."""
+
+    def __init__(self, desc):
+        self.desc = desc
+        self.K = len(desc.modules)
+        self.dtype = desc.dtype
+        self.tdtype = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
+        self.net = B.lp_net_create(desc.modules, desc.aux, desc.dtype, desc.bn_eps)
+        self.dev = _dev()
+        self.ws_bytes = B.lp_net_workspace_bytes(self.net)
+        self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
+        B.lp_net_set_workspace(self.net, self.ws.data_ptr(), self.ws_bytes)
+        self.tables = [[B.lp_net_tensor_info(self.net, 0, k, i) for i in range(B.lp_net_num_tensors(self.net, 0, k))]
+                       for k in range(self.K)]
+        self.aux_tables = []
+        if desc.aux is not None:
+            self.aux_tables = [[B.lp_net_tensor_info(self.net, 1, j, i) for i in range(B.lp_net_num_tensors(self.net, 1, j))]
+                               for j in range(self.K - 1)]
+        m = desc.modules
+        self.x_shapes = [(mm.N, mm.H, mm.W, mm.C) for mm in m]
+        self.y_shapes = [self.x_shapes[k + 1] for k in range(self.K - 1)]
+        self.n_classes = m[-1].n_classes
+        self.N = m[-1].N
+        # device state
+        self.params = [None] * self.K
+        self.dparams = [None] * self.K
+        for k in range(self.K):
+            pb, gb = B.lp_net_param_bytes(self.net, 0, k)
+            self.params[k] = torch.zeros(pb, dtype=torch.uint8, device=self.dev)
+            self.dparams[k] = torch.zeros(gb // 4, dtype=torch.float32, device=self.dev)
+        self.aux_params = []
+        for j in range(len(self.aux_tables)):
+            pb, _ = B.lp_net_param_bytes(self.net, 1, j)
+            self.aux_params.append(torch.zeros(pb, dtype=torch.uint8, device=self.dev))
+        self.x = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.x_shapes]
+        self.y = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.y_shapes]
+        self.dy = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.y_shapes]
+        self.dx = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.x_shapes]
+        self.lam = None
+        self.logits = torch.zeros((self.N, self.n_classes), dtype=torch.float32, device=self.dev)
+        self.dlogits = torch.zeros_like(self.logits)
+        self.labels = torch.zeros((self.N,), dtype=torch.int32, device=self.dev)
+        self.loss = torch.zeros((self.K,), dtype=torch.float32, device=self.dev)
+
+    def close(self):
+        if self.net is not None:
+            torch.cuda.synchronize()
+            B.lp_net_destroy(self.net)
+            self.net = None
+
+    # ---- host <-> device marshalling ---------------------------------------------------------------
+    def to_dev(self, a, low=True):
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+        if low and self.dtype == "bf16":
+            t = t.to(torch.bfloat16)
+        return t.to(self.dev)
+
+    @staticmethod
+    def to_host(t):
+        return t.detach().float().cpu().numpy().astype(np.float64)
+
+    def _pack(self, buf, table, tensors):
+        assert len(table) == len(tensors)
+        for info, a in zip(table, tensors):
+            assert int(info.numel) == int(np.size(a)), "parameter tensor size mismatch"
+            n = int(info.numel)
+            if info.dtype == B.LP_BF16:
+                src = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1)).to(torch.bfloat16)
+                buf[info.offset:info.offset + 2 * n].view(torch.bfloat16).copy_(src)
+            else:
+                src = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32).reshape(-1))
+                buf[info.offset:info.offset + 4 * n].view(torch.float32).copy_(src)
+
+    def set_params(self, k, tensors):
+        self._pack(self.params[k], self.tables[k], tensors)
+
+    def set_aux_params(self, j, tensors):
+        self._pack(self.aux_params[j], self.aux_tables[j], tensors)
+
+    def get_grads(self, k):
+        out = []
+        for info in self.tables[k]:
+            o = info.grad_offset // 4
+            shape = tuple(info.dims[i] for i in range(info.ndim))
+            out.append(self.to_host(self.dparams[k][o:o + int(info.numel)]).reshape(shape))
+        return out
+
+    def set_x(self, k, a):
+        self.x[k].copy_(self.to_dev(a))
+
+    def set_lams(self, lams):
+        self.lam = None if lams is None else [self.to_dev(l) for l in lams]
+
+    def set_labels(self, labels):
+        self.labels.copy_(torch.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
+
+    def saved(self, k, which, shape):
+        """Copy of a saved activation (debug view)."""
+        ptr, n = B.lp_debug_saved_tensor(self.net, k, which)
+        assert n == int(np.prod(shape))
+        off = ptr - self.ws.data_ptr()
+        esz = 2 if self.dtype == "bf16" else 4
+        return self.to_host(self.ws[off:off + n * esz].view(self.tdtype).reshape(shape))
+
+    # ---- the five entry points ---------------------------------------------------------------------
+    @staticmethod
+    def _stream():
+        return torch.cuda.current_stream().cuda_stream
+
+    def _mask(self, mask):
+        return (1 << self.K) - 1 if mask is None else mask
+
+    @staticmethod
+    def _p(ts):
+        return [None if t is None else t.data_ptr() for t in ts]
+
+    def auxnet_forward(self, image=None):
+        img = self.x[0] if image is None else image
+        B.lp_auxnet_forward(self.net, self._stream(), img.data_ptr(), self._p(self.aux_params), self._p(self.x[1:]))
+
+    def module_forward(self, mask=None):
+        B.lp_module_forward(self.net, self._stream(), self._mask(mask), self._p(self.x), self._p(self.params),
+                            self._p(self.y), self.logits.data_ptr())
+
+    def local_loss_grad(self, rho, scale=1.0, mask=None):
+        lam = None if self.lam is None else self._p(self.lam)
+        B.lp_local_loss_grad(self.net, self._stream(), self._mask(mask), self._p(self.y), self._p(self.x[1:]), lam,
+                             rho, scale, self.logits.data_ptr(), self.labels.data_ptr(), self.loss.data_ptr(),
+                             self._p(self.dy), self.dlogits.data_ptr())
+
+    def module_backward(self, mask=None, want_dx0=False):
+        dx = self._p(self.dx)
+        if not want_dx0:
+            dx[0] = None
+        B.lp_module_backward(self.net, self._stream(), self._mask(mask), self._p(self.dy), self.dlogits.data_ptr(),
+                             self._p(self.params), self._p(self.dparams), dx)
+
+    def al_multiplier_update(self, step):
+        B.lp_al_multiplier_update(self.net, self._stream(), self._p(self.lam), self._p(self.y), self._p(self.x[1:]), step)
+
+    def step(self, rho, scale=1.0, mult_step=None, with_aux=False):
+        """One synchronous local step of all K modules."""
+        if with_aux:
+            self.auxnet_forward()
+        self.module_forward()
+        self.local_loss_grad(rho, scale)
+        self.module_backward()
+        if mult_step is not None and self.lam is not None:
+            self.al_multiplier_update(mult_step)

@@ -1,0 +1,208 @@
+"""GPU-side test plumbing: run one local step through the C ABI and compare with the oracle."""
+import sys
+
+import numpy as np
+
+import workloads as wl
+from oracle import lpref
+from tests.helpers import rel_err, step_inputs
+from workloads import configs as cfg
+from workloads.configs import Block
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # max|gpu-ref| / max|ref| per tensor
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def gpu_mini_basic(batch=3, dtype="f32"):
+    """K=3, channels multiple of 8, ragged M (6x6 images): stem, stride-2 projection block, head."""
+    blocks = [Block("basic", 8, 8, 8, 1, False), Block("basic", 8, 16, 16, 2, True),
+              Block("basic", 16, 16, 16, 1, False), Block("basic", 16, 16, 16, 1, False)]
+    net = cfg._assemble("gpu_mini_basic", [blocks[:2], blocks[2:3], blocks[3:]], batch, 6, 6, 3, 1, 8, 5, seed=21)
+    net.dtype = dtype
+    return net
+
+
+def gpu_mini_bottleneck(batch=2, dtype="f32"):
+    blocks = [Block("bottleneck", 8, 16, 8, 1, True), Block("bottleneck", 16, 32, 8, 2, True),
+              Block("bottleneck", 32, 32, 8, 1, False)]
+    net = cfg._assemble("gpu_mini_bottleneck", [blocks[:1], blocks[1:]], batch, 24, 24, 3, 2, 8, 6, seed=22)
+    net.dtype = dtype
+    return net
+
+
+def load_step(ls, net, inp):
+    for k in range(net.K):
+        ls.set_params(k, inp["params"][k])
+        ls.set_x(k, inp["xs"][k])
+    if inp.get("aux_params"):
+        for j in range(net.K - 1):
+            ls.set_aux_params(j, inp["aux_params"][j])
+    ls.set_lams(inp["lams"])
+    ls.set_labels(inp["labels"])
+
+
+class _PerturbedRounding:
+    """bf16 storage rounding preceded by a seeded relative perturbation of size 1e-6: a second, equally valid
+    bf16 evaluation (it differs from the first the way another fp32 summation order would)."""
+
+    def __init__(self, seed):
+        self.seed, self.n = seed, 0
+
+    def __call__(self, a):
+        self.n += 1
+        a = np.asarray(a, dtype=np.float64)
+        return wl.round_bf16(a * (1.0 + 1e-6 * wl.normal(self.seed, f"perturb{self.n}", a.shape)))
+
+
+def _oracle_pieces(net, inp, scale, want_dx0, q):
+    """Oracle run entry point by entry point: forward; loss/adjoint from the stored forward outputs;
+    backward from the stored adjoints."""
+    from tests.helpers import store
+    K = net.K
+    fwd = [lpref.module_forward(net.modules[k], inp["xs"][k], inp["params"][k], net.bn_eps, q) for k in range(K)]
+    o = {"y": [fwd[k][0] for k in range(K - 1)], "logits": fwd[K - 1][1]}
+    o["y_in"] = [store(net, y) for y in o["y"]]
+    o["logits_in"] = o["logits"].astype(np.float32).astype(np.float64)
+    o["lg"] = [lpref.local_loss_grad(o["y_in"][k], inp["xs"][k + 1], None if inp["lams"] is None else inp["lams"][k],
+                                     net.rho, scale) for k in range(K - 1)]
+    o["ce_loss"], o["dz"] = lpref.ce_loss_grad(o["logits_in"], inp["labels"])
+    o["dy_in"] = [store(net, g[1]) for g in o["lg"]]
+    o["dz_in"] = o["dz"].astype(np.float32).astype(np.float64)
+    o["bwd"] = []
+    for k in range(K):
+        need_dx = (k > 0) or want_dx0
+        if k < K - 1:
+            o["bwd"].append(lpref.module_backward(net.modules[k], fwd[k][2], dy=o["dy_in"][k], need_dx=need_dx, q=q))
+        else:
+            o["bwd"].append(lpref.module_backward(net.modules[k], fwd[k][2], dlogits=o["dz_in"], need_dx=need_dx, q=q))
+    return o
+
+
+def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True):
+    """Parity of the whole local step on identical seeded inputs.
+
+    fp32 mode: the oracle is the plain float64 definition, tolerance 1e-4 on every tensor.
+
+    bf16 mode: forward outputs are compared with the plain float64 definition too (2e-2).  Backward tensors
+    depend on decisions taken from stored bf16 values (ReLU masks), so the oracle rounds every stored tensor
+    to bf16 once, as the mode defines.  Even then a 1e-6 difference before a rounding (another fp32 summation
+    order) now and then lands on the other side of a rounding boundary or of a ReLU threshold, and through
+    several layers two equally valid bf16 evaluations drift apart.  The oracle measures that spread itself:
+    it is run a second time with a 1e-6 relative perturbation in front of every rounding, and a backward
+    tensor T passes if  err(T) <= max(tol, 2.5 * spread(T)).  The spread is printed when it widens a tolerance.
+
+    Pass 1 (entry point by entry point): the loss/terminal-adjoint call and the backward call are each fed the
+    ORACLE's value of their input (rounded to the storage type) on both sides.
+    Pass 2 (chained, as the product runs it): the device's own y feeds its loss and backward.  The residual
+    r = F_k(x_k) - x_{k+1} cancels leading digits, so an error eps*max|y| in y is an error of relative size
+    eps*rho*max|y|/max|dy| in dy and in everything back-propagated from it: the tolerance of modules
+    0..K-2 is scaled by that factor (the last module has no such cancellation).
+    """
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    tol = TOL[net.dtype] if tol is None else tol
+    K = net.K
+    inp = step_inputs(net, lpref)
+    specs = [wl.module_tensor_specs(m) for m in net.modules]
+    bf16 = net.dtype == "bf16"
+    q = wl.round_bf16 if bf16 else None
+    plain_fwd = [lpref.module_forward(net.modules[k], inp["xs"][k], inp["params"][k], net.bn_eps) for k in range(K)] if bf16 else None
+    o = _oracle_pieces(net, inp, scale, want_dx0, q)
+    spread = {}
+    if bf16:
+        o2 = _oracle_pieces(net, inp, scale, want_dx0, _PerturbedRounding(net.seed))
+        for k in range(K):
+            for sp, a, b in zip(specs[k], o2["bwd"][k][0], o["bwd"][k][0]):
+                spread[f"m{k}.{sp.name}"] = rel_err(a, b)
+            if o["bwd"][k][1] is not None:
+                spread[f"dx{k}"] = rel_err(o2["bwd"][k][1], o["bwd"][k][1])
+    chain = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], scale, need_dx0=want_dx0, q=q)
+    y_ref, logits_ref, lg, bwd = o["y"], o["logits"], o["lg"], o["bwd"]
+
+    def check(errs, label):
+        bad, widened = {}, {}
+        for name, v in errs.items():
+            t = max(tol, 2.5 * spread.get(name.replace("chain.", ""), 0.0))
+            if t > tol:
+                widened[name] = t
+            if not (v <= t):
+                bad[name] = (v, t)
+        top = sorted(errs.items(), key=lambda kv: -kv[1])[:5]
+        say(f"[{net.name} {net.dtype} N={net.modules[0].N}] {label}, worst: " + ", ".join(f"{k}={v:.2e}" for k, v in top))
+        if widened:
+            wt = sorted(widened.items(), key=lambda kv: -kv[1])[:4]
+            say(f"    tolerance widened by the oracle's own bf16 spread for {len(widened)} tensors, e.g. "
+                + ", ".join(f"{k}: {t:.2e}" for k, t in wt))
+        assert not bad, f"{label}: beyond tolerance (error, allowed): {bad}"
+
+    ls = LocalStep(net)
+    worst = {}
+    try:
+        load_step(ls, net, inp)
+        if net.aux is not None and check_aux:
+            ls.auxnet_forward()
+            torch.cuda.synchronize()
+            for j in range(K - 1):
+                want = lpref.auxnet_forward(net.aux[j], inp["image"], inp["aux_params"][j], net.bn_eps)
+                worst[f"aux{j}"] = rel_err(ls.to_host(ls.x[j + 1]), want)
+            for k in range(1, K):          # the step itself starts from the oracle-side x_k (already rounded)
+                ls.set_x(k, inp["xs"][k])
+        # ---- pass 1
+        ls.module_forward()
+        torch.cuda.synchronize()
+        for k in range(K - 1):
+            worst[f"y{k}"] = rel_err(ls.to_host(ls.y[k]), plain_fwd[k][0] if bf16 else y_ref[k])
+        worst["logits"] = rel_err(ls.to_host(ls.logits), plain_fwd[K - 1][1] if bf16 else logits_ref)
+        for k in range(K - 1):
+            ls.y[k].copy_(ls.to_dev(o["y_in"][k]))
+        ls.logits.copy_(ls.to_dev(o["logits_in"], low=False))
+        ls.local_loss_grad(net.rho, scale)
+        torch.cuda.synchronize()
+        for k in range(K - 1):
+            worst[f"dy{k}"] = rel_err(ls.to_host(ls.dy[k]), lg[k][1])
+            worst[f"loss{k}"] = abs(float(ls.loss[k].item()) - lg[k][0]) / max(abs(lg[k][0]), 1e-30)
+        worst[f"loss{K - 1}"] = abs(float(ls.loss[K - 1].item()) - o["ce_loss"]) / abs(o["ce_loss"])
+        worst["dlogits"] = rel_err(ls.to_host(ls.dlogits), o["dz"])
+        for k in range(K - 1):
+            ls.dy[k].copy_(ls.to_dev(o["dy_in"][k]))
+        ls.dlogits.copy_(ls.to_dev(o["dz_in"], low=False))
+        ls.module_backward(want_dx0=want_dx0)
+        torch.cuda.synchronize()
+        for k in range(K):
+            for sp, g, r in zip(specs[k], ls.get_grads(k), bwd[k][0]):
+                worst[f"m{k}.{sp.name}"] = rel_err(g, r)
+            if bwd[k][1] is not None:
+                worst[f"dx{k}"] = rel_err(ls.to_host(ls.dx[k]), bwd[k][1])
+        if net.al:
+            ls.al_multiplier_update(net.step)
+            torch.cuda.synchronize()
+            for k in range(K - 1):
+                want = lpref.multiplier_update(inp["lams"][k], o["y_in"][k], inp["xs"][k + 1], net.step)
+                worst[f"lam{k}"] = rel_err(ls.to_host(ls.lam[k]), want)
+            ls.set_lams(inp["lams"])
+        check(worst, "entry-point pass")
+        # ---- pass 2 (chained)
+        ls.module_forward()
+        ls.local_loss_grad(net.rho, scale)
+        ls.module_backward(want_dx0=want_dx0)
+        torch.cuda.synchronize()
+        cw = {}
+        for k in range(K):
+            amp = 1.0
+            if k < K - 1:
+                amp = max(1.0, scale * net.rho * np.max(np.abs(y_ref[k])) / np.max(np.abs(chain["dy"][k])))
+                cw[f"chain.dy{k}"] = rel_err(ls.to_host(ls.dy[k]), chain["dy"][k]) / amp
+                cw[f"chain.loss{k}"] = abs(float(ls.loss[k].item()) - chain["loss"][k]) / max(abs(chain["loss"][k]), 1e-30) / amp
+            for sp, g, r in zip(specs[k], ls.get_grads(k), chain["dparams"][k]):
+                cw[f"chain.m{k}.{sp.name}"] = rel_err(g, r) / amp
+            if chain["dx"][k] is not None:
+                cw[f"chain.dx{k}"] = rel_err(ls.to_host(ls.dx[k]), chain["dx"][k]) / amp
+        check(cw, "chained pass (scaled by the cancellation factor)")
+        worst.update(cw)
+    finally:
+        ls.close()
+    return worst

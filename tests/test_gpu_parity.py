@@ -1,0 +1,98 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import lpref
+from tests.gpu_common import compare_step, gpu_mini_basic, gpu_mini_bottleneck, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_im2col_offsets_bit_exact():
+    """The device's im2col address arithmetic equals the oracle's canonical index function exactly."""
+    import torch
+    from paper_2112_05387_amd import binding as B
+    rng = np.random.default_rng(0)
+    for (N, H, W, Cin, R, stride, pad) in [(4, 8, 8, 16, 3, 1, 1), (128, 32, 32, 160, 3, 1, 1), (128, 32, 32, 160, 3, 2, 1),
+                                            (64, 224, 224, 3, 7, 2, 3), (3, 6, 6, 8, 1, 2, 0), (128, 32, 32, 3, 3, 4, 1)]:
+        Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+        M, Kg = N * Ho * Wo, R * R * Cin
+        cnt = 4096
+        m = rng.integers(0, M, cnt); q = rng.integers(0, Kg, cnt)
+        m[:4] = [0, 0, M - 1, M - 1]; q[:4] = [0, Kg - 1, 0, Kg - 1]
+        want = np.array([lpref.im2col_index(int(a), int(b), H, W, Cin, R, R, stride, pad) for a, b in zip(m, q)], dtype=np.int64)
+        dm = torch.from_numpy(m.astype(np.int64)).cuda(); dq = torch.from_numpy(q.astype(np.int64)).cuda()
+        out = torch.empty(cnt, dtype=torch.int64, device="cuda")
+        B.lp_debug_im2col_offsets(torch.cuda.current_stream().cuda_stream, H, W, Cin, R, R, stride, pad,
+                                  dm.data_ptr(), dq.data_ptr(), out.data_ptr(), cnt)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny(dtype):
+    net = wl.make_config("tiny")
+    net.dtype = dtype
+    say("case tiny", dtype)
+    compare_step(net, want_dx0=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mini_basic_al(dtype):
+    net = gpu_mini_basic(dtype=dtype)
+    net.al, net.lam_sigma, net.rho = True, 0.05, 1.5
+    say("case mini_basic", dtype)
+    compare_step(net, scale=0.5)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mini_bottleneck(dtype):
+    net = gpu_mini_bottleneck(dtype=dtype)
+    say("case mini_bottleneck", dtype)
+    compare_step(net)
+
+
+def test_resnet20_full_size():
+    say("case resnet20 batch 128 fp32")
+    compare_step(wl.make_config("resnet20"))
+
+
+def test_resnet56_auxnet_al():
+    say("case resnet56 batch 16 bf16")
+    compare_step(wl.make_config("resnet56", batch=16))
+
+
+def test_wrn_reduced_batch():
+    say("case wrn28_10 batch 2 bf16")
+    compare_step(wl.make_config("wrn28_10", batch=2))
+
+
+def test_vanish_invariant_on_device():
+    """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
+    and dx of modules 0..K-2 are exactly zero."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.gpu_common import load_step
+    from tests.helpers import step_inputs
+    net = gpu_mini_basic(dtype="bf16")
+    inp = step_inputs(net, lpref)
+    ls = LocalStep(net)
+    try:
+        load_step(ls, net, inp)
+        for k in range(net.K - 1):          # serial pass on the device: x_{k+1} := F_k(x_k), one interface at a time
+            ls.module_forward()
+            ls.x[k + 1].copy_(ls.y[k])
+        ls.module_forward()
+        ls.local_loss_grad(3.0)
+        ls.module_backward()
+        torch.cuda.synchronize()
+        for k in range(net.K - 1):
+            assert float(ls.loss[k].item()) == 0.0
+            assert not ls.dy[k].float().abs().max().item() > 0
+            assert all(not np.any(g) for g in ls.get_grads(k))
+            if k > 0:
+                assert not ls.dx[k].float().abs().max().item() > 0
+        assert float(ls.loss[net.K - 1].item()) > 0
+    finally:
+        ls.close()

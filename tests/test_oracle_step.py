@@ -178,3 +178,30 @@ def test_workload_descriptors():
     assert [(m.H, m.C) for m in w.modules] == [(32, 3), (32, 160), (16, 320), (8, 640)]
     r = wl.make_config("resnet50")
     assert [(m.H, m.C) for m in r.modules] == [(224, 3), (56, 256), (28, 512), (14, 1024)]
+
+
+def test_storage_rounding_hook():
+    """q = identity reproduces the plain definition bit for bit; q = bf16 rounding stays close to it; the
+    bf16 rounding itself is round-to-nearest-even on the 8-bit significand."""
+    net = mini_basic()
+    net.al, net.lam_sigma = True, 0.1
+    inp = step_inputs(net, lpref)
+    a = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], 1.0)
+    b = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], 1.0, q=lambda t: t)
+    c = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], 1.0, q=wl.round_bf16)
+    for k in range(net.K):
+        for x, y, z in zip(a["dparams"][k], b["dparams"][k], c["dparams"][k]):
+            np.testing.assert_array_equal(x, y)
+            assert z.shape == x.shape and np.all(np.isfinite(z))
+        assert a["loss"][k] == b["loss"][k]
+    for k in range(net.K - 1):
+        assert rel_err(c["y"][k], a["y"][k]) < 0.02
+        np.testing.assert_array_equal(c["y"][k], wl.round_bf16(c["y"][k]))      # stored values are bf16 values
+    v = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7, -(1.0 + 2.0 ** -8 + 2.0 ** -20), 3.0e38, 0.0])
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -(1.0 + 2.0 ** -7), 3.0e38, 0.0])
+    got = wl.round_bf16(v)
+    np.testing.assert_array_equal(got[:5], want[:5])
+    assert got[6] == 0.0 and abs(got[5] - 3.0e38) <= 3.0e38 * 2.0 ** -8
+    r = np.random.default_rng(0).standard_normal(10000) * 10
+    assert np.max(np.abs(wl.round_bf16(r) - r) / np.abs(r)) <= 2.0 ** -8
+    np.testing.assert_array_equal(wl.round_bf16(wl.round_bf16(r)), wl.round_bf16(r))
