@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the module-parallel local step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic mini-batch, all K modules:
+[AuxNet forward if the config has one] + module forward + local loss / terminal adjoint + module-local
+backward + [multiplier update for augmented-Lagrangian configs].  Default workload: the WideResNet-28-10-shaped
+configuration (batch 128, bf16 storage / fp32 accumulate, K=4, augmented Lagrangian), which is the one the
+conv-TFLOP/s target is quoted on.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # dense MFMA, MI355X data sheet
+PEAK_HBM_GBS = 8000.0
+
+
+def build_state(net, seed_noise=True):
+    """Device state for timing: seeded parameters / image / labels; auxiliary variables = the device's own
+    serial forward states + N(0, sigma^2) (the CPU oracle cannot run the full-size forward in bench time)."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2112_05387_amd import LocalStep
+    ls = LocalStep(net)
+    for k in range(net.K):
+        ls.set_params(k, wl.make_params(net, k))
+    ls.set_x(0, wl.make_image(net))
+    ls.set_labels(wl.make_labels(net))
+    if net.aux is not None:
+        for j in range(net.K - 1):
+            ls.set_aux_params(j, wl.make_aux_params(net, j))
+        ls.auxnet_forward()
+    else:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(net.seed)
+        for k in range(net.K - 1):
+            ls.module_forward(mask=1 << k)
+            noise = torch.randn(ls.y[k].shape, generator=g, device="cuda", dtype=torch.float32) * net.noise_sigma
+            ls.x[k + 1].copy_((ls.y[k].float() + noise).to(ls.tdtype))
+    if net.al:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(net.seed + 1000)
+        ls.lam = [(torch.randn(s, generator=g, device="cuda", dtype=torch.float32) * net.lam_sigma).to(ls.tdtype)
+                  for s in ls.y_shapes]
+    torch.cuda.synchronize()
+    return ls
+
+
+def one_step(ls, net):
+    ls.step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
+
+
+def cpu_baseline(net_name, target_seconds=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same
+    network at a reduced mini-batch (the network, K and every layer shape are the configuration's)."""
+    import workloads as wl
+    from oracle import lpref
+    from tests.helpers import step_inputs
+    from workloads import configs as cfg
+    full = wl.make_config(net_name)
+    # the plain double loops reach roughly 1 GFLOP/s per thread; size the sample from that
+    per_sample = cfg.conv_flops_step(full) / full.modules[0].N
+    guess_rate = 1.0e9 * lpref.num_threads()
+    batch = int(max(1, min(full.modules[0].N, target_seconds * guess_rate / per_sample)))
+    batch = max(batch, 1)
+    net = wl.make_config(net_name, batch=batch)
+    params = [wl.make_params(net, k) for k in range(net.K)]
+    image, labels = wl.make_image(net), wl.make_labels(net)
+    # auxiliary variables with the module-input shapes (values do not change the cost)
+    xs = [image] + [wl.normal(net.seed, f"cpu_x{k}", (m.N, m.H, m.W, m.C)) for k, m in enumerate(net.modules) if k > 0]
+    lams = None
+    if net.al:
+        lams = [wl.normal(net.seed, f"cpu_lam{k}", xs[k + 1].shape, net.lam_sigma) for k in range(net.K - 1)]
+    t0 = time.perf_counter()
+    if net.aux is not None:
+        for j in range(net.K - 1):
+            lpref.auxnet_forward(net.aux[j], image, wl.make_aux_params(net, j), net.bn_eps)
+    out = lpref.local_step(net, xs, params, labels, lams, 1.0)
+    if lams is not None:
+        for k in range(net.K - 1):
+            lpref.multiplier_update(lams[k], out["y"][k], xs[k + 1], net.step)
+    dt = time.perf_counter() - t0
+    return {"value": batch / dt, "unit": "samples/s", "cores": lpref.num_threads(), "kind": "oracle",
+            "sample": f"one local step of {net_name} (all K={net.K} modules, every layer at its real width) at "
+                      f"mini-batch {batch} instead of {full.modules[0].N}, float64 plain loops, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="wrn28_10")
+    ap.add_argument("--batch", type=int, default=None, help="override the mini-batch (the result is then not the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel breakdown to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs the local step of all K modules on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU figure is produced).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2112_05387_amd import binding as B
+    from workloads import configs as cfg
+
+    net = wl.make_config(args.config, batch=args.batch)
+    N = net.modules[0].N
+    ls = build_state(net)
+    for _ in range(args.warmup):
+        one_step(ls, net)
+    torch.cuda.synchronize()
+
+    # timed region: EXACTLY --steps steps; every grouped launch is bracketed by hipEvents on the same stream
+    B.lp_profile_enable(ls.net, 1)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        one_step(ls, net)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    recs = B.lp_profile_fetch(ls.net)
+    B.lp_profile_enable(ls.net, 0)
+    ms_per_step = wall_ms / args.steps
+
+    # per-kernel aggregation (kind, tile configuration)
+    agg = {}
+    for r in recs:
+        a = agg.setdefault((r["kind"], r["cfg"]), {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        a["ms"] += r["ms"]; a["flops"] += r["flops"]; a["bytes"] += r["bytes"]; a["launches"] += 1
+    conv_ms = sum(a["ms"] for (k, _), a in agg.items() if k in (2, 10))
+    conv_flops = sum(a["flops"] for (k, _), a in agg.items() if k in (2, 10))
+    (dk, dcfg), dom = max(agg.items(), key=lambda kv: kv[1]["ms"])
+    peak = PEAK_TFLOPS[net.dtype]
+    if dk in (2, 10):
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak}
+    else:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
+    roof.update({"traffic": None, "kernel": f"{B.KIND_NAMES[dk]} cfg{dcfg}", "launches_per_step": dom["launches"] / args.steps,
+                 "avg_launch_ms": dom["ms"] / dom["launches"], "share_of_gpu_time": dom["ms"] / max(gpu_ms, 1e-9)})
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            roof["traffic"] = json.load(f).get(f"{args.config}:{B.KIND_NAMES[dk]} cfg{dcfg}")
+    if args.kernel_table:
+        for (k, c), a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
+            tf = a["flops"] / (a["ms"] * 1e-3) / 1e12 if a["ms"] > 0 else 0.0
+            gb = a["bytes"] / (a["ms"] * 1e-3) / 1e9 if a["ms"] > 0 else 0.0
+            print(f"  {B.KIND_NAMES[k]:24s} cfg{c} launches/step {a['launches'] / args.steps:6.1f}  ms/step {a['ms'] / args.steps:8.3f}"
+                  f"  TFLOP/s {tf:8.1f}  GB/s(alg) {gb:8.1f}", file=sys.stderr)
+        print(f"  GPU time/step by events {gpu_ms / args.steps:.3f} ms, wall {ms_per_step:.3f} ms", file=sys.stderr)
+
+    out = {
+        "metric": "module-parallel local-step samples/s (all K modules); conv TFLOP/s vs MFMA peak",
+        "value": N / (ms_per_step * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": net.dtype, "data": "synthetic",
+        "config": {"workload": f"{net.name} local step, K={net.K} modules, batch {N}, "
+                               f"{'augmented Lagrangian' if net.al else 'penalty'}, rho={net.rho}"
+                               f"{', AuxNet forward included' if net.aux is not None else ''}"},
+        "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else None,
+        "conv_frac_of_mfma_peak": (conv_flops / (conv_ms * 1e-3) / 1e12) / peak if conv_ms > 0 else None,
+        "conv_tflop_per_step": cfg.conv_flops_step(net) / 1e12,
+        "gpu_ms_per_step_events": gpu_ms / args.steps,
+        "roofline": roof,
+    }
+    ls.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -159,6 +159,17 @@ lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, in
  * the stem, 1 + 8*block + {0,1,2: pre-BN conv output of slot, 3: projection conv output, 4: block output}. */
 lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel);
 
+/* Optional per-launch timing.  While enabled, every grouped kernel launch made by lp_auxnet_forward,
+ * lp_module_forward and lp_module_backward is bracketed by two hipEvents on the caller's stream.
+ * lp_profile_fetch waits for the recorded launches, returns one record per launch in issue order and clears
+ * the list (out == NULL: only the count).  kind: 0 clear, 1 filter re-layout, 2 conv forward/data-gradient,
+ * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
+ * apply, 10 conv weight-gradient.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
+ * every operand tensor moved once). */
+typedef struct { int kind, cfg, nprob; float ms; double flops, bytes; } lp_profile_rec;
+lp_status lp_profile_enable(struct lp_net* net, int on);
+lp_status lp_profile_fetch(struct lp_net* net, lp_profile_rec* out, int max_recs, int* n_out);
+
 const char* lp_last_error(void);
 const char* lp_version(void);
 

@@ -14,7 +14,10 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_debug_im2col_offsets",
-           "lp_debug_saved_tensor", "lp_last_error", "lp_version"]
+           "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
+
+KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
+              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad"}
 
 
 class lp_block_desc(ctypes.Structure):
@@ -33,6 +36,11 @@ class lp_aux_desc(ctypes.Structure):
 class lp_tensor_info(ctypes.Structure):
     _fields_ = [("kind", c_int), ("block", c_int), ("slot", c_int), ("dtype", c_int), ("ndim", c_int),
                 ("dims", c_int * 4), ("offset", c_size_t), ("grad_offset", c_size_t), ("numel", c_size_t)]
+
+
+class lp_profile_rec(ctypes.Structure):
+    _fields_ = [("kind", c_int), ("cfg", c_int), ("nprob", c_int), ("ms", c_float), ("flops", ctypes.c_double),
+                ("bytes", ctypes.c_double)]
 
 
 class LpError(RuntimeError):
@@ -68,6 +76,8 @@ def lib():
         L.lp_al_multiplier_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, c_float]
         L.lp_debug_im2col_offsets.argtypes = [c_void_p] + [c_int] * 7 + [c_void_p, c_void_p, c_void_p, c_int]
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
+        L.lp_profile_enable.argtypes = [c_void_p, c_int]
+        L.lp_profile_fetch.argtypes = [c_void_p, POINTER(lp_profile_rec), c_int, POINTER(c_int)]
         L.lp_last_error.restype = c_char_p
         L.lp_version.restype = c_char_p
         for name in EXPORTS:
@@ -186,3 +196,17 @@ def lp_debug_saved_tensor(net, k, which):
     p, n = c_void_p(), c_size_t()
     _check(lib().lp_debug_saved_tensor(net, k, which, ctypes.byref(p), ctypes.byref(n)))
     return p.value, n.value
+
+
+def lp_profile_enable(net, on):
+    _check(lib().lp_profile_enable(net, int(on)))
+
+
+def lp_profile_fetch(net):
+    n = c_int()
+    _check(lib().lp_profile_fetch(net, None, 0, ctypes.byref(n)))
+    if n.value == 0:
+        return []
+    recs = (lp_profile_rec * n.value)()
+    _check(lib().lp_profile_fetch(net, recs, n.value, ctypes.byref(n)))
+    return [dict(kind=r.kind, cfg=r.cfg, nprob=r.nprob, ms=r.ms, flops=r.flops, bytes=r.bytes) for r in recs]

@@ -151,6 +151,11 @@ struct lp_net {
     size_t ws_given = 0;
     uint32_t fwd_done = 0;
     std::vector<const void*> saved_x;
+    // optional per-launch timing (hipEvents around every grouped launch)
+    bool prof = false;
+    struct ProfRec { hipEvent_t a, b; int type, cfg, nprob; double flops, bytes; };
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> prof_pool;
 };
 
 namespace {
@@ -642,12 +647,68 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
 // ----------------------------------------------------------------------------------------------------
 static int elem_blocks(size_t nvec) { return (int)((nvec + kElemVecsPerBlock - 1) / kElemVecsPerBlock); }
 
+// algorithmic work of one operation: flops of the contraction, minimum bytes each tensor moves once
+static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes) {
+    const double e = (double)net->esz;
+    flops = 0; bytes = 0;
+    switch (o.type) {
+        case OP_CONV: {
+            const ConvProb& c = o.conv;
+            flops = 2.0 * c.M * c.Ncol * c.Kg;
+            const double nimg = (double)c.M / ((double)c.OA * c.OB);
+            const double in_e = nimg * c.IH * c.IW * c.Cin / ((double)c.omul * c.omul);   // shared by the parity classes
+            const double w_e = (double)c.Ncol * c.Kg;
+            double out_e = (double)c.M * c.Ncol;
+            if (o.r[3].space != SP_NONE) out_e += (double)c.M * c.Ncol;
+            if (o.r[4].space != SP_NONE) out_e += (double)c.M * c.Ncol;
+            bytes = (in_e + w_e + out_e) * e;
+        } break;
+        case OP_WGRAD: {
+            const WgradProb& w = o.wg;
+            flops = 2.0 * w.M * w.Cout * w.Kg;
+            const double nimg = (double)w.M / ((double)w.Ho * w.Wo);
+            bytes = (nimg * w.IH * w.IW * w.Cin + (double)w.M * w.Cout) * e + (double)w.Cout * w.Kg * 4.0;
+        } break;
+        case OP_WTRANS: bytes = 2.0 * o.wt.Cout * o.wt.RS * o.wt.Cin * e; break;
+        case OP_FILL: bytes = (double)o.fill_bytes; break;
+        case OP_BN_APPLY: bytes = (double)o.bna.M * o.bna.C * e * (o.bna.skip_mode ? 3.0 : 2.0); break;
+        case OP_BN_BWD_REDUCE: bytes = (double)o.bnb.M * o.bnb.C * e * 2.0; break;
+        case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * 3.0; break;
+        case OP_POOL_FWD:
+        case OP_POOL_BWD: bytes = ((double)o.pool.N * o.pool.H * o.pool.W + (double)o.pool.N * o.pool.Ho * o.pool.Wo) * o.pool.C * e; break;
+        case OP_HEAD_FWD:
+        case OP_HEAD_BWD: bytes = (double)o.head.N * o.head.HW * o.head.C * e; break;
+        default: break;
+    }
+}
+
+static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s);
+
 static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const Bindings& b, hipStream_t s) {
-    const int type = ops[0]->type, dt = net->dtype;
-    const int epv = dt == LP_BF16 ? 8 : 4;
     hipError_t err = hipSuccess;
     for (size_t base = 0; base < ops.size() && err == hipSuccess; base += kMaxGroup) {
         const int n = (int)std::min<size_t>(kMaxGroup, ops.size() - base);
+        if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s); continue; }
+        lp_net::ProfRec r;
+        r.type = ops[base]->type; r.cfg = ops[base]->cfg; r.nprob = n; r.flops = 0; r.bytes = 0;
+        for (int i = 0; i < n; ++i) { double f, by; op_work(net, *ops[base + i], f, by); r.flops += f; r.bytes += by; }
+        for (hipEvent_t* e : {&r.a, &r.b}) {
+            if (!net->prof_pool.empty()) { *e = net->prof_pool.back(); net->prof_pool.pop_back(); }
+            else if ((err = hipEventCreate(e)) != hipSuccess) return err;
+        }
+        if ((err = hipEventRecord(r.a, s)) != hipSuccess) return err;
+        err = launch_group_impl(net, ops, base, n, b, s);
+        if (err == hipSuccess) err = hipEventRecord(r.b, s);
+        net->prof_recs.push_back(r);
+    }
+    return err;
+}
+
+static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s) {
+    const int type = ops[base]->type, dt = net->dtype;
+    const int epv = dt == LP_BF16 ? 8 : 4;
+    hipError_t err = hipSuccess;
+    {
         switch (type) {
             case OP_FILL: {
                 FillGroup g; g.nprob = n; int tot = 0;
@@ -672,7 +733,7 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
             } break;
             case OP_CONV: {
                 ConvGroup g; g.nprob = n; int tot = 0;
-                const CfgInfo ci = conv_cfg_info(ops[0]->cfg, dt);
+                const CfgInfo ci = conv_cfg_info(ops[base]->cfg, dt);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     ConvProb& p = g.p[i]; p = o.conv;
@@ -682,7 +743,7 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
-                err = launch_conv(g, dt, ops[0]->cfg, ops[0]->vec, s);
+                err = launch_conv(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;
@@ -693,7 +754,7 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n * p.ksplit;
                 }
                 g.total_tiles = tot;
-                err = launch_wgrad(g, dt, ops[0]->cfg, ops[0]->vec, s);
+                err = launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_BN_APPLY: {
                 BnApplyGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
@@ -858,7 +919,37 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
 }
 
 lp_status lp_net_destroy(struct lp_net* net) {
+    if (net) {
+        for (auto& r : net->prof_recs) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+        for (hipEvent_t e : net->prof_pool) hipEventDestroy(e);
+    }
     delete net;
+    return LP_OK;
+}
+
+lp_status lp_profile_enable(struct lp_net* net, int on) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    net->prof = on != 0;
+    return LP_OK;
+}
+
+lp_status lp_profile_fetch(struct lp_net* net, lp_profile_rec* out, int max_recs, int* n_out) {
+    if (!net || !n_out) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    const int n = (int)net->prof_recs.size();
+    *n_out = n;
+    if (!out) return LP_OK;                       // size query
+    if (max_recs < n) return fail(LP_ERR_INVALID_ARG, "room for %d records, %d recorded", max_recs, n);
+    for (int i = 0; i < n; ++i) {
+        lp_net::ProfRec& r = net->prof_recs[i];
+        hipError_t err = hipEventSynchronize(r.b);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, r.a, r.b);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "event timing failed: %s", hipGetErrorString(err));
+        out[i].kind = r.type; out[i].cfg = r.cfg; out[i].nprob = r.nprob;
+        out[i].ms = ms; out[i].flops = r.flops; out[i].bytes = r.bytes;
+        net->prof_pool.push_back(r.a); net->prof_pool.push_back(r.b);
+    }
+    net->prof_recs.clear();
     return LP_OK;
 }
 

@@ -1,0 +1,142 @@
+"""Host-side checks of the C ABI: exported symbols, descriptor validation, packed layouts, error paths.
+No kernel is launched here (no GPU needed)."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+import workloads as wl
+from paper_2112_05387_amd import binding as B
+from workloads.configs import Block, ModuleDesc, AuxDesc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_PTR = 0x10000000      # aligned, never dereferenced: every check below fails or returns before a launch
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lp.h")).read()
+    declared = set(re.findall(r"\b(lp_[a-z0-9_]+)\s*\(", hdr))
+    assert {"lp_module_forward", "lp_local_loss_grad", "lp_module_backward", "lp_auxnet_forward",
+            "lp_al_multiplier_update"} <= declared
+    L = B.lib()
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in lp.h but not exported"
+    assert set(B.EXPORTS) == declared
+    assert B.lp_version().startswith("lp-gfx950")
+
+
+def test_binding_refuses_missing_library(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liblp.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+def test_tensor_table_matches_workload_specs(name):
+    net = wl.make_config(name)
+    h = B.lp_net_create(net.modules, net.aux, net.dtype, net.bn_eps)
+    try:
+        kinds = {"conv": B.LP_T_CONV, "bn_gamma": B.LP_T_BN_GAMMA, "bn_beta": B.LP_T_BN_BETA, "fc_w": B.LP_T_FC_W, "fc_b": B.LP_T_FC_B}
+        for k, m in enumerate(net.modules):
+            specs = wl.module_tensor_specs(m)
+            assert B.lp_net_num_tensors(h, 0, k) == len(specs)
+            pb, gb = B.lp_net_param_bytes(h, 0, k)
+            prev_end = prev_gend = 0
+            for i, sp in enumerate(specs):
+                t = B.lp_net_tensor_info(h, 0, k, i)
+                assert t.kind == kinds[sp.kind] and t.block == sp.block and t.slot == sp.slot
+                assert tuple(t.dims[j] for j in range(t.ndim)) == tuple(sp.shape)
+                want_dt = B.LP_BF16 if (sp.kind == "conv" and net.dtype == "bf16") else B.LP_F32
+                assert t.dtype == want_dt
+                assert t.offset % 256 == 0 and t.grad_offset % 256 == 0
+                assert t.offset >= prev_end and t.grad_offset >= prev_gend
+                prev_end = t.offset + t.numel * (2 if t.dtype == B.LP_BF16 else 4)
+                prev_gend = t.grad_offset + t.numel * 4
+            assert prev_end <= pb and prev_gend <= gb
+        if net.aux is not None:
+            for j, a in enumerate(net.aux):
+                assert B.lp_net_num_tensors(h, 1, j) == 3
+                t = B.lp_net_tensor_info(h, 1, j, 0)
+                assert tuple(t.dims[i] for i in range(4)) == (a.cout, 3, 3, a.cin)
+        assert B.lp_net_workspace_bytes(h) > 0
+    finally:
+        B.lp_net_destroy(h)
+
+
+def _mod(blocks, N=2, H=8, W=8, C=8, stem=0, stem_cout=0, head=True, n_classes=4):
+    return ModuleDesc(stem=stem, stem_cout=stem_cout, blocks=blocks, head=head, n_classes=n_classes, N=N, H=H, W=W, C=C)
+
+
+def _expect(status, fn, *a):
+    with pytest.raises(B.LpError) as e:
+        fn(*a)
+    assert e.value.status == status, str(e.value)
+    assert B.lp_last_error() != ""
+
+
+def test_create_rejects_bad_descriptors():
+    ok = Block("basic", 8, 8, 8, 1, False)
+    _expect(B.LP_ERR_INVALID_ARG, B.lp_net_create, [], None, "f32", 1e-5)                      # K = 0
+    _expect(B.LP_ERR_DTYPE, B.lp_net_create, [_mod([ok])], None, 7, 1e-5)
+    _expect(B.LP_ERR_INVALID_ARG, B.lp_net_create, [_mod([ok])], None, "f32", 0.0)              # eps
+    _expect(B.LP_ERR_INVALID_ARG, B.lp_net_create, [_mod([])], None, "f32", 1e-5)               # no blocks
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 16, 16, 16, 1, False)])], None, "f32", 1e-5)   # cin != C
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 8, 16, 16, 1, False)])], None, "f32", 1e-5)    # proj missing
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 8, 8, 8, 2, False)])], None, "f32", 1e-5)      # stride w/o proj
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 8, 8, 8, 3, True)])], None, "f32", 1e-5)       # stride 3
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 8, 8, 8, 2, True)], H=7)], None, "f32", 1e-5)  # H % stride
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([Block("basic", 8, 12, 12, 1, True)])], None, "bf16", 1e-5)    # 12 % 8
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([ok], head=False)], None, "f32", 1e-5)       # last module needs the head
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([ok]), _mod([ok])], None, "f32", 1e-5)       # head on a non-last module
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, [_mod([ok], head=False), _mod([Block("basic", 16, 16, 16, 1, False)], C=16)],
+            None, "f32", 1e-5)                                                                     # interface mismatch
+    _expect(B.LP_ERR_INVALID_ARG, B.lp_net_create, [_mod([Block(5, 8, 8, 8, 1, False)])], None, "f32", 1e-5)     # kind
+    _expect(B.LP_ERR_INVALID_ARG, B.lp_net_create, [_mod([ok], stem=3)], None, "f32", 1e-5)
+    two = [_mod([ok], head=False), _mod([ok])]
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(3, 8, 1, False)], "f32", 1e-5)       # aux cin != image channels
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 16, 1, False)], "f32", 1e-5)      # aux cout
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 8, 2, False)], "f32", 1e-5)       # aux stride
+    h = B.lp_net_create(two, [AuxDesc(8, 8, 1, True)], "f32", 1e-5)
+    B.lp_net_destroy(h)
+
+
+def test_call_time_errors_without_touching_the_gpu():
+    net = wl.make_config("tiny")
+    h = B.lp_net_create(net.modules, None, "f32", 1e-5)
+    try:
+        K = net.K
+        ptrs = [FAKE_PTR] * K
+        _expect(B.LP_ERR_WORKSPACE, B.lp_module_forward, h, None, 3, ptrs, ptrs, ptrs[:1], FAKE_PTR)     # no workspace yet
+        need = B.lp_net_workspace_bytes(h)
+        _expect(B.LP_ERR_WORKSPACE, B.lp_net_set_workspace, h, FAKE_PTR, need - 1)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_workspace, h, FAKE_PTR + 8, need)
+        B.lp_net_set_workspace(h, FAKE_PTR, need)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 0, ptrs, ptrs, ptrs[:1], FAKE_PTR)   # empty mask
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 1 << K, ptrs, ptrs, ptrs[:1], FAKE_PTR)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 3, [None, FAKE_PTR], ptrs, ptrs[:1], FAKE_PTR)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 3, [FAKE_PTR + 4, FAKE_PTR], ptrs, ptrs[:1], FAKE_PTR)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 3, ptrs, ptrs, ptrs[:1], None)       # logits
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_module_forward, h, None, 1, ptrs, ptrs, [None], FAKE_PTR)     # y[0]
+        _expect(B.LP_ERR_STATE, B.lp_module_backward, h, None, 3, ptrs[:1], FAKE_PTR, ptrs, ptrs, ptrs)  # no forward
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_loss_grad, h, None, 3, ptrs[:1], ptrs[:1], None, -1.0, 1.0, FAKE_PTR,
+                FAKE_PTR, FAKE_PTR, ptrs[:1], FAKE_PTR)                                                   # rho < 0
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_loss_grad, h, None, 3, ptrs[:1], ptrs[:1], None, 1.0, 1.0, FAKE_PTR,
+                FAKE_PTR, None, ptrs[:1], FAKE_PTR)                                                       # loss NULL
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_loss_grad, h, None, 2, ptrs[:1], ptrs[:1], None, 1.0, 1.0, None,
+                FAKE_PTR, FAKE_PTR, ptrs[:1], FAKE_PTR)                                                   # logits NULL
+        _expect(B.LP_ERR_STATE, B.lp_auxnet_forward, h, None, FAKE_PTR, ptrs[:1], ptrs[:1])              # net has no AuxNet
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_al_multiplier_update, h, None, None, ptrs[:1], ptrs[:1], 0.1)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_tensor_info, h, 0, 0, 99)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_param_bytes, h, 0, 5)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_debug_saved_tensor, h, 0, 0)                                   # tiny has no stem
+    finally:
+        B.lp_net_destroy(h)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
