@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--batch", type=int, default=None, help="override the mini-batch (the result is then not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel breakdown to stderr")
+    ap.add_argument("--dump-launches", action="store_true", help="print every launch of the last timed step to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the local step of all K modules on ONE GPU; --gpus must be 1 "
@@ -156,6 +157,12 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             roof["traffic"] = json.load(f).get(f"{args.config}:{B.KIND_NAMES[dk]} cfg{dcfg}")
+    if args.dump_launches:
+        per = len(recs) // args.steps
+        for r in recs[-per:]:
+            tf = r["flops"] / (r["ms"] * 1e-3) / 1e12 if r["ms"] > 0 else 0.0
+            print(f"    {B.KIND_NAMES[r['kind']]:24s} cfg{r['cfg']} nprob {r['nprob']:2d}  {r['ms'] * 1e3:9.1f} us  {r['flops'] / 1e9:9.2f} GFLOP  {tf:8.1f} TFLOP/s"
+                  f"  {r['bytes'] / 1e6:9.2f} MB(alg)", file=sys.stderr)
     if args.kernel_table:
         for (k, c), a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
             tf = a["flops"] / (a["ms"] * 1e-3) / 1e12 if a["ms"] > 0 else 0.0

@@ -25,8 +25,8 @@ bf16 mode of the method stores a tensor (conv output before BN, activation after
 output, every stored gradient); q=None (the default) is the plain float64 definition, and that is
 what the pins exercise.  With q = round-to-bf16 the oracle is the same sequence of definitions with
 each stored tensor rounded once, so that decisions taken from stored values (the ReLU mask, the
-pooling argmax) are taken in the precision the bf16 mode defines.  Batch statistics are taken from
-the unrounded convolution result and applied to the stored one, as the bf16 mode specifies.
+pooling argmax) are taken in the precision the bf16 mode defines.  Batch statistics are those of the
+stored (rounded) convolution result.
 """
 import ctypes
 import os
@@ -146,11 +146,13 @@ def _id(a):
 
 def bn_fwd(y, gamma, beta, eps, q=None):
     """Training-mode batch norm: per-channel mean and biased variance over N*H*W.
-    With storage rounding q the statistics come from y and are applied to q(y)."""
+    With storage rounding q everything refers to the stored tensor q(y)."""
+    if q is not None:
+        y = q(y)
     mean = y.mean(axis=(0, 1, 2))
     var = ((y - mean) ** 2).mean(axis=(0, 1, 2))
     invstd = 1.0 / np.sqrt(var + eps)
-    yhat = ((y if q is None else q(y)) - mean) * invstd
+    yhat = (y - mean) * invstd
     return gamma * yhat + beta, (yhat, invstd)
 
 

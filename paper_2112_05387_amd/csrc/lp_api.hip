@@ -162,6 +162,15 @@ namespace {
 
 static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// the wide-layer bf16 kernel applies when a k-tile of 32 channels lies inside one tap and offsets fit 31 bits
+static bool conv_fast_ok(const lp_net* net, const ConvProb& c) {
+    if (net->dtype != LP_BF16 || c.Cin % 32 != 0 || c.Ncol % 160 != 0) return false;
+    if (c.ntr * c.nts > 32) return false;
+    const double in_bytes = (double)c.M / ((double)c.OA * c.OB) * c.IH * c.IW * c.Cin * 2.0;
+    const double w_bytes = (double)c.Ncol * c.ldw * 2.0;
+    return in_bytes < 2.0e9 && w_bytes < 2.0e9;
+}
+
 static int conv_cfg_for(int ncol, bool vec) {
     int cfg;
     if (ncol % 160 == 0) cfg = CFG_N160;
@@ -201,6 +210,7 @@ struct Builder {
         c.OH = u.Ho; c.OW = u.Wo; c.omul = 1; c.ooh = 0; c.oow = 0;
         o.vec = (u.cin % epv()) == 0;
         o.cfg = conv_cfg_for(c.Ncol, o.vec);
+        if (conv_fast_ok(net, c)) o.cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
         o.r[0] = in; o.r[1] = w; o.r[2] = out; o.r[5] = stats;
         return o;
     }
@@ -227,6 +237,7 @@ struct Builder {
                 c.Kg = c.ntr * c.nts * c.Cin;
                 o.vec = (u.cout % epv()) == 0;
                 o.cfg = conv_cfg_for(c.Ncol, o.vec);
+                if (conv_fast_ok(net, c)) o.cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
                 o.r[0] = dy; o.r[1] = wt; o.r[2] = dx; o.r[3] = add0; o.r[4] = add1;
                 step.push_back(o);
             }
@@ -733,7 +744,8 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             } break;
             case OP_CONV: {
                 ConvGroup g; g.nprob = n; int tot = 0;
-                const CfgInfo ci = conv_cfg_info(ops[base]->cfg, dt);
+                const bool fast = ops[base]->cfg >= FAST_256x320;
+                const CfgInfo ci = fast ? conv_fast_cfg_info(ops[base]->cfg) : conv_cfg_info(ops[base]->cfg, dt);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     ConvProb& p = g.p[i]; p = o.conv;
@@ -743,7 +755,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
-                err = launch_conv(g, dt, ops[base]->cfg, ops[base]->vec, s);
+                err = fast ? launch_conv_fast(g, ops[base]->cfg, s) : launch_conv(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;

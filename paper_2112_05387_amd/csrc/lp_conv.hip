@@ -209,8 +209,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
                 const int row = wm * TM + i * MT + acc_row<MT>(r, lane);
                 const int ro = s_rowoff[row];
                 float v = acc[i][j][r];
-                cs1[j] += v;
-                cs2[j] += v * v;
+                // the batch statistics describe the values as stored (rounded to T)
+                const float vs = to_float(from_float<T>(v));
+                cs1[j] += vs;
+                cs2[j] += vs * vs;
                 if (ro >= 0 && col < P.Ncol) {
                     const size_t o = (size_t)ro + col;
                     if (add0) v += to_float(add0[o]);

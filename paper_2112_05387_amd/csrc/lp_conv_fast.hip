@@ -1,0 +1,317 @@
+// bf16 implicit-GEMM convolution (forward / data-gradient) for the wide layers on gfx950.
+//
+// 512 threads; each wave owns a 64-pixel x 160-channel output tile (2 x 5 micro-tiles of
+// v_mfma_f32_32x32x16_bf16, 160 fp32 accumulators), waves arranged WGM x WGN.  What was measured on the
+// machine and shaped this kernel:
+//  * an MFMA loop fed from LDS is bound by LDS bandwidth (about 128 B/clk/CU), so the wave tile is as large
+//    as the register file allows at two waves per SIMD;
+//  * one k-tile of register-staged prefetch does not cover a miss to HBM, and every k-tile waits for its
+//    slowest load, so operands go global -> LDS directly (buffer_load ... lds, no staging registers) into a
+//    ring of STAGES k-tiles, with STAGES-1 tiles of loads in flight;
+//  * LDS rows are unpadded (64 B = 32 bf16) with an XOR swizzle of the 16-byte chunk, conflict-free for the
+//    fragment reads; the direct loads write lane l at slab + 16*l, so the swizzle is applied by choosing which
+//    global chunk each lane fetches;
+//  * the output tile goes back through LDS so that global stores are 16 bytes per lane and coalesced, and the
+//    per-channel batch statistics are taken from the staged values on the way out.
+// The zero padding of the convolution and the ragged edges of the GEMM are out-of-range buffer offsets, which
+// the hardware returns (and writes to LDS) as zeros.
+//
+// Restrictions (the caller falls back to the general kernel otherwise): bf16, Cin % 32 == 0 (a k-tile lies
+// inside one filter tap, so the tap geometry is wave-uniform), at most 32 taps, tensors < 2 GiB.
+#include "lp_kernels.h"
+#include "lp_mma.h"
+
+namespace lp {
+
+namespace {
+
+constexpr unsigned kOOB = 0x80000000u;      // byte offset beyond any buffer
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14])
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+template <int WGM, int WGN, int STAGES>
+__global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g) {
+    constexpr int MT = 32, FM = 2, FN = 5, NW = 8, NT = 512;
+    static_assert(WGM * WGN == NW, "eight waves");
+    constexpr int TM = FM * MT, TN = FN * MT, BM = WGM * TM, BN = WGN * TN, BK = 32;
+    constexpr int A_BYTES = BM * 64, STAGE_BYTES = (BM + BN) * 64;
+    constexpr int NSA = BM / 16 / NW;                 // 1 KiB slabs (16 rows) of A per wave
+    constexpr int NSBT = BN / 16;                     // slabs of B in total
+    constexpr int NSB = (NSBT + NW - 1) / NW;         // per wave (the last one may be absent)
+    constexpr int EP_PITCH = 336, EP_WAVE = 32 * EP_PITCH;
+    constexpr int RING = STAGES * STAGE_BYTES;
+    static_assert(NW * EP_WAVE <= RING, "epilogue staging must fit in the ring");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int* s_rowoff = reinterpret_cast<int*>(smem + RING);
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    int pi = 0;
+    for (int i = 1; i < g.nprob; ++i)
+        if ((int)blockIdx.x >= g.p[i].tile_start) pi = i;
+    const ConvProb& P = g.p[pi];
+    const int t = blockIdx.x - P.tile_start;
+    const int tile_n = t % P.tiles_n, tile_m = t / P.tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int M = P.M, Cin = P.Cin, IH = P.IH, IW = P.IW, ntr = P.ntr, nts = P.nts;
+    const int per = P.OA * P.OB;
+
+    for (int r = tid; r < BM; r += NT) {
+        const int m = m0 + r;
+        int off = -1;
+        if (m < M) {
+            const int n = m / per, rem = m - n * per;
+            const int a = rem / P.OB, b = rem - a * P.OB;
+            off = ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
+        }
+        s_rowoff[r] = off;
+    }
+
+    const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(P.in, (unsigned)((size_t)(M / per) * IH * IW * Cin * 2));
+    const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(P.wt, (unsigned)((size_t)P.Ncol * P.ldw * 2));
+
+    // ---- gather state.  Slab s covers tile rows 16s..16s+15; lane l writes LDS slot (row 16s + l/4, chunk l%4) and
+    // therefore fetches global chunk (l%4) ^ swizzle(row), swizzle(row) = (row >> 2) & 3 = (l >> 4) & 3.
+    const int lrow = lane >> 2;
+    const int kvg = (lane & 3) ^ ((lane >> 4) & 3);
+    int a_base[NSA];
+    unsigned a_mask[NSA];
+#pragma unroll
+    for (int i = 0; i < NSA; ++i) {
+        const int m = m0 + 16 * (wave + NW * i) + lrow;
+        a_base[i] = 0; a_mask[i] = 0u;
+        if (m < M) {
+            const int n = m / per, rem = m - n * per;
+            const int a = rem / P.OB, b = rem - a * P.OB;
+            const int ih0 = a * P.imul + P.dh0, iw0 = b * P.imul + P.dw0;
+            a_base[i] = (((n * IH + ih0) * IW + iw0) * Cin + kvg * 8) * 2;
+            unsigned mk = 0u;
+            for (int tr = 0; tr < ntr; ++tr)
+                for (int ts = 0; ts < nts; ++ts) {
+                    const int ih = ih0 + P.dhs * tr, iw = iw0 + P.dws * ts;
+                    if ((unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW) mk |= 1u << (tr * nts + ts);
+                }
+            a_mask[i] = mk;
+        }
+    }
+    // filter rows at or beyond Ncol start at or beyond the end of the buffer: no explicit check needed
+    const unsigned b_base0 = (unsigned)(((n0 + 16 * wave + lrow) * P.ldw + kvg * 8) * 2);
+    const unsigned b_step = (unsigned)(16 * NW * P.ldw * 2);
+    const bool last_b = (wave + NW * (NSB - 1)) < NSBT;          // does this wave own a slab in the last round?
+
+    const int nk = ntr * nts * (Cin / BK);
+    int tr = 0, ts = 0, ci0 = 0, issued = 0;
+    // one k-tile of direct-to-LDS loads into ring stage `st`; past the end every offset is out of range (zeros)
+    auto issue_loads = [&](int st) {
+        const bool live = issued < nk;
+        const int toff_a = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
+        const unsigned toff_b = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
+        const int tbit = tr * nts + ts;
+        unsigned char* S = smem + st * STAGE_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < NSA; ++i) {
+            const unsigned off = (live && ((a_mask[i] >> tbit) & 1u)) ? (unsigned)(a_base[i] + toff_a) : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(S + i * (NW * 1024)), 16, (int)off, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NSB; ++j) {
+            if (j + 1 < NSB || last_b) {
+                const unsigned off = live ? b_base0 : kOOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(S + A_BYTES + j * (NW * 1024)), 16, (int)off,
+                                                         (int)(toff_b + j * b_step), 0, 0);
+            }
+        }
+        ++issued;
+        // taps innermost: the shifted reads of one 32-channel slab follow each other while it is hot in L2
+        if (++ts == nts) {
+            ts = 0;
+            if (++tr == ntr) { tr = 0; ci0 += BK; }
+        }
+    };
+
+    // ---- fragment addressing: lane l reads tile row (l % 32) and chunk (2*ks + l/32) ^ swizzle(row) ----
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int lr = lane & 31, lkc = lane >> 5;
+    const int sw = (lr >> 2) & 3;
+    const int a_rd = (wm * TM + lr) * 64, b_rd = A_BYTES + (wn * TN + lr) * 64;
+    const int ck0 = ((0 + lkc) ^ sw) << 4, ck1 = ((2 + lkc) ^ sw) << 4;
+    u32x4 af[2][FM], bf[2][FN];
+    auto load_frags = [&](int st, int ck, int slot) {
+        const unsigned char* T = smem + st * STAGE_BYTES + ck;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[slot][i] = *reinterpret_cast<const u32x4*>(T + a_rd + i * (MT * 64));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bf[slot][j] = *reinterpret_cast<const u32x4*>(T + b_rd + j * (MT * 64));
+    };
+
+    // acc[j][i]: rows = channels of micro-tile j, columns = pixels of micro-tile i (filters are the row operand, so
+    // that a lane ends up with 4 consecutive channels of one pixel)
+    f32x16 acc[FN][FM];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+
+    __syncthreads();                     // row offsets visible; nothing in flight yet
+    if (nk > 0) {
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
+        // tile 0 landed: everything but the STAGES-2 younger tiles of this wave
+        if (last_b) wait_vmcnt<(STAGES - 2) * (NSA + NSB)>(); else wait_vmcnt<(STAGES - 2) * (NSA + NSB - 1)>();
+        __builtin_amdgcn_s_barrier();
+        load_frags(0, ck0, 0);
+        int st = 0;                      // ring stage of tile kt
+        for (int kt = 0; kt < nk; ++kt) {
+            int st_free = st + STAGES - 1;
+            if (st_free >= STAGES) st_free -= STAGES;
+            issue_loads(st_free);        // tile kt+STAGES-1 into the stage that tile kt-1 used
+            load_frags(st, ck1, 1);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[0][j], af[0][i], acc[j][i]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[1][j], af[1][i], acc[j][i]);
+            // tile kt+1 landed (this wave's share); the barrier makes every wave's share visible and frees stage st
+            if (last_b) wait_vmcnt<(STAGES - 2) * (NSA + NSB)>(); else wait_vmcnt<(STAGES - 2) * (NSA + NSB - 1)>();
+            __builtin_amdgcn_s_barrier();
+            if (++st == STAGES) st = 0;
+            if (kt + 1 < nk) load_frags(st, ck0, 0);
+        }
+    }
+    wait_vmcnt<0>();                     // the trailing (all out-of-range) loads still write zeros into the ring
+    __syncthreads();
+
+    // ---- epilogue: registers -> (addends) -> bf16 -> LDS [pixel][channel] -> 16-byte coalesced stores + statistics ----
+    bf16_t* __restrict__ out = reinterpret_cast<bf16_t*>(P.out);
+    const bf16_t* __restrict__ add0 = reinterpret_cast<const bf16_t*>(P.add0);
+    const bf16_t* __restrict__ add1 = reinterpret_cast<const bf16_t*>(P.add1);
+    unsigned char* E = smem + wave * EP_WAVE;
+    const int cg = lane % 20, pl = lane / 20;           // read-back: 16-byte channel group, pixel lane (pl == 3: idle)
+    const int colg = n0 + wn * TN + cg * 8;
+    float s1[8], s2[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s1[e] = 0.f; s2[e] = 0.f; }
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int prow = wm * TM + i * MT;              // first tile row of this pixel group
+        const int ro_w = s_rowoff[prow + lr];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int c0 = j * MT + 8 * rg + 4 * lkc;          // channel inside the wave tile
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[j][i][rg * 4 + e];
+                if (add0 || add1) {
+                    const int col = n0 + wn * TN + c0;
+                    if (ro_w >= 0 && col < P.Ncol) {
+                        const size_t o = (size_t)ro_w + col;
+                        if (add0) {
+                            const uint2 a = *reinterpret_cast<const uint2*>(add0 + o);
+                            v[0] += __uint_as_float(a.x << 16); v[1] += __uint_as_float(a.x & 0xffff0000u);
+                            v[2] += __uint_as_float(a.y << 16); v[3] += __uint_as_float(a.y & 0xffff0000u);
+                        }
+                        if (add1) {
+                            const uint2 a = *reinterpret_cast<const uint2*>(add1 + o);
+                            v[0] += __uint_as_float(a.x << 16); v[1] += __uint_as_float(a.x & 0xffff0000u);
+                            v[2] += __uint_as_float(a.y << 16); v[3] += __uint_as_float(a.y & 0xffff0000u);
+                        }
+                    }
+                }
+                uint2 pk;
+                pk.x = (unsigned)float_to_bf16_bits(v[0]) | ((unsigned)float_to_bf16_bits(v[1]) << 16);
+                pk.y = (unsigned)float_to_bf16_bits(v[2]) | ((unsigned)float_to_bf16_bits(v[3]) << 16);
+                *reinterpret_cast<uint2*>(E + lr * EP_PITCH + c0 * 2) = pk;
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_s_waitcnt(0xc07f);             // lgkmcnt(0): this wave's LDS writes are done
+        if (pl < 3) {
+            for (int p = pl; p < MT; p += 3) {
+                const u32x4 q = *reinterpret_cast<const u32x4*>(E + p * EP_PITCH + cg * 16);
+                const int ro = s_rowoff[prow + p];
+                if (ro >= 0) {
+                    if (colg < P.Ncol) *reinterpret_cast<u32x4*>(out + (size_t)ro + colg) = q;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = __uint_as_float(q[e] << 16), hi = __uint_as_float(q[e] & 0xffff0000u);
+                        s1[2 * e] += lo; s2[2 * e] += lo * lo;
+                        s1[2 * e + 1] += hi; s2[2 * e + 1] += hi * hi;
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        __builtin_amdgcn_s_waitcnt(0xc07f);             // reads done before the next group overwrites the staging area
+    }
+    if (P.stats) {
+        __syncthreads();                                // every wave is done with its staging area
+        float* red = reinterpret_cast<float*>(smem);    // [wave][pl][160][2]
+        if (pl < 3) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                red[(((wave * 3 + pl) * TN) + cg * 8 + e) * 2 + 0] = s1[e];
+                red[(((wave * 3 + pl) * TN) + cg * 8 + e) * 2 + 1] = s2[e];
+            }
+        }
+        __syncthreads();
+        for (int c = tid; c < BN; c += NT) {
+            const int col = n0 + c;
+            if (col < P.Ncol) {
+                const int wn_c = c / TN, cc = c % TN;
+                float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+                for (int w = 0; w < WGM; ++w)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) {
+                        const int idx = ((((w * WGN + wn_c) * 3 + q) * TN) + cc) * 2;
+                        a1 += red[idx]; a2 += red[idx + 1];
+                    }
+                atomicAdd(&P.stats[col], (double)a1);
+                atomicAdd(&P.stats[P.Ncol + col], (double)a2);
+            }
+        }
+    }
+}
+
+template <int WGM, int WGN, int STAGES>
+hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
+    constexpr int BM = WGM * 64, BN = WGN * 160;
+    constexpr size_t lds = (size_t)STAGES * (BM + BN) * 64 + BM * sizeof(int);
+    static bool configured = false;
+    auto kern = conv_igemm_fast_kernel<WGM, WGN, STAGES>;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(g.total_tiles), dim3(512), lds, s, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+CfgInfo conv_fast_cfg_info(int cfg) {
+    if (cfg == FAST_512x160) return {512, 160, 32};
+    return {256, 320, 32};
+}
+
+hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s) {
+    if (g.total_tiles <= 0) return hipSuccess;
+    if (cfg == FAST_512x160) return fast_launch<8, 1, 3>(g, s);
+    return fast_launch<4, 2, 4>(g, s);
+}
+
+}  // namespace lp

@@ -93,7 +93,7 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True):
     order) now and then lands on the other side of a rounding boundary or of a ReLU threshold, and through
     several layers two equally valid bf16 evaluations drift apart.  The oracle measures that spread itself:
     it is run a second time with a 1e-6 relative perturbation in front of every rounding, and a backward
-    tensor T passes if  err(T) <= max(tol, 2.5 * spread(T)).  The spread is printed when it widens a tolerance.
+    tensor T passes if  err(T) <= max(tol, 3 * spread(T)), spread = larger deviation of two perturbed runs.  The spread is printed when it widens a tolerance.
 
     Pass 1 (entry point by entry point): the loss/terminal-adjoint call and the backward call are each fed the
     ORACLE's value of their input (rounded to the storage type) on both sides.
@@ -114,19 +114,21 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True):
     o = _oracle_pieces(net, inp, scale, want_dx0, q)
     spread = {}
     if bf16:
-        o2 = _oracle_pieces(net, inp, scale, want_dx0, _PerturbedRounding(net.seed))
-        for k in range(K):
-            for sp, a, b in zip(specs[k], o2["bwd"][k][0], o["bwd"][k][0]):
-                spread[f"m{k}.{sp.name}"] = rel_err(a, b)
-            if o["bwd"][k][1] is not None:
-                spread[f"dx{k}"] = rel_err(o2["bwd"][k][1], o["bwd"][k][1])
+        for trial in range(2):          # two perturbed evaluations; the spread of a tensor is the larger deviation
+            o2 = _oracle_pieces(net, inp, scale, want_dx0, _PerturbedRounding(net.seed + 7919 * trial))
+            for k in range(K):
+                for sp, a, b in zip(specs[k], o2["bwd"][k][0], o["bwd"][k][0]):
+                    key = f"m{k}.{sp.name}"
+                    spread[key] = max(spread.get(key, 0.0), rel_err(a, b))
+                if o["bwd"][k][1] is not None:
+                    spread[f"dx{k}"] = max(spread.get(f"dx{k}", 0.0), rel_err(o2["bwd"][k][1], o["bwd"][k][1]))
     chain = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], scale, need_dx0=want_dx0, q=q)
     y_ref, logits_ref, lg, bwd = o["y"], o["logits"], o["lg"], o["bwd"]
 
     def check(errs, label):
         bad, widened = {}, {}
         for name, v in errs.items():
-            t = max(tol, 2.5 * spread.get(name.replace("chain.", ""), 0.0))
+            t = max(tol, 3.0 * spread.get(name.replace("chain.", ""), 0.0))
             if t > tol:
                 widened[name] = t
             if not (v <= t):
