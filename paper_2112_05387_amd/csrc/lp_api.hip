@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -171,6 +172,13 @@ static bool conv_fast_ok(const lp_net* net, const ConvProb& c) {
     return in_bytes < 2.0e9 && w_bytes < 2.0e9;
 }
 
+// pick the wide-layer configuration of a problem; returns false if the wide-layer kernel does not apply
+static bool pick_fast_cfg(const lp_net* net, const ConvProb& c, int& cfg) {
+    if (!conv_fast_ok(net, c)) return false;
+    cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
+    return true;
+}
+
 static int conv_cfg_for(int ncol, bool vec) {
     int cfg;
     if (ncol % 160 == 0) cfg = CFG_N160;
@@ -210,7 +218,7 @@ struct Builder {
         c.OH = u.Ho; c.OW = u.Wo; c.omul = 1; c.ooh = 0; c.oow = 0;
         o.vec = (u.cin % epv()) == 0;
         o.cfg = conv_cfg_for(c.Ncol, o.vec);
-        if (conv_fast_ok(net, c)) o.cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
+        pick_fast_cfg(net, c, o.cfg);
         o.r[0] = in; o.r[1] = w; o.r[2] = out; o.r[5] = stats;
         return o;
     }
@@ -237,7 +245,7 @@ struct Builder {
                 c.Kg = c.ntr * c.nts * c.Cin;
                 o.vec = (u.cout % epv()) == 0;
                 o.cfg = conv_cfg_for(c.Ncol, o.vec);
-                if (conv_fast_ok(net, c)) o.cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
+                pick_fast_cfg(net, c, o.cfg);
                 o.r[0] = dy; o.r[1] = wt; o.r[2] = dx; o.r[3] = add0; o.r[4] = add1;
                 step.push_back(o);
             }
@@ -250,13 +258,17 @@ struct Builder {
         o.vec = (u.cin % epv()) == 0;
         o.cfg = wgrad_cfg_for(u.cout, w.Kg, o.vec);
         const CfgInfo ci = wgrad_cfg_info(o.cfg, net->dtype);
+        w.tiles_m = (w.Cout + ci.BM - 1) / ci.BM; w.tiles_n = (w.Kg + ci.BN - 1) / ci.BN;
+        // split the pixel dimension: about 4096 pixels per block, more splits (down to 512 pixels) when the filter
+        // has so few output tiles that the launch would not fill the chip
         int ks = (w.M + 4095) / 4096;
-        ks = std::max(1, std::min(ks, 64));
+        const int want = (512 + w.tiles_m * w.tiles_n - 1) / (w.tiles_m * w.tiles_n);
+        ks = std::max(ks, std::min(want, (w.M + 511) / 512));
+        ks = std::max(1, std::min(ks, 256));
         int chunk = (w.M + ks - 1) / ks;
         chunk = (chunk + ci.BK - 1) / ci.BK * ci.BK;
         ks = (w.M + chunk - 1) / chunk;
         w.ksplit = ks; w.kchunk = chunk;
-        w.tiles_m = (w.Cout + ci.BM - 1) / ci.BM; w.tiles_n = (w.Kg + ci.BN - 1) / ci.BN;
         o.r[0] = x; o.r[1] = dy; o.r[2] = dw;
         return o;
     }

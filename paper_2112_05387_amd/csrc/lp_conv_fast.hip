@@ -18,6 +18,8 @@
 //
 // Restrictions (the caller falls back to the general kernel otherwise): bf16, Cin % 32 == 0 (a k-tile lies
 // inside one filter tap, so the tap geometry is wave-uniform), at most 32 taps, tensors < 2 GiB.
+#include <algorithm>
+
 #include "lp_kernels.h"
 #include "lp_mma.h"
 
@@ -37,6 +39,22 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n
+__device__ __forceinline__ void wait_vmcnt_rt(int n) {
+    switch (n) {
+        case 0: wait_vmcnt<0>(); break;   case 1: wait_vmcnt<1>(); break;   case 2: wait_vmcnt<2>(); break;
+        case 3: wait_vmcnt<3>(); break;   case 4: wait_vmcnt<4>(); break;   case 5: wait_vmcnt<5>(); break;
+        case 6: wait_vmcnt<6>(); break;   case 7: wait_vmcnt<7>(); break;   case 8: wait_vmcnt<8>(); break;
+        case 9: wait_vmcnt<9>(); break;   case 10: wait_vmcnt<10>(); break; case 11: wait_vmcnt<11>(); break;
+        case 12: wait_vmcnt<12>(); break; case 13: wait_vmcnt<13>(); break; case 14: wait_vmcnt<14>(); break;
+        case 15: wait_vmcnt<15>(); break; case 16: wait_vmcnt<16>(); break; case 17: wait_vmcnt<17>(); break;
+        case 18: wait_vmcnt<18>(); break; case 19: wait_vmcnt<19>(); break; case 20: wait_vmcnt<20>(); break;
+        default: wait_vmcnt<0>(); break;
+    }
+}
+
+}  // namespace
+
 template <int WGM, int WGN, int STAGES>
 __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g) {
     constexpr int MT = 32, FM = 2, FN = 5, NW = 8, NT = 512;
@@ -47,12 +65,12 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
     constexpr int NSBT = BN / 16;                     // slabs of B in total
     constexpr int NSB = (NSBT + NW - 1) / NW;         // per wave (the last one may be absent)
     constexpr int EP_PITCH = 336, EP_WAVE = 32 * EP_PITCH;
-    constexpr int RING = STAGES * STAGE_BYTES;
-    static_assert(NW * EP_WAVE <= RING, "epilogue staging must fit in the ring");
+    constexpr int EP_BYTES = NW * EP_WAVE;            // epilogue staging, over the dead operand area
+    constexpr int OP_BYTES = STAGES * STAGE_BYTES > EP_BYTES ? STAGES * STAGE_BYTES : EP_BYTES;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    int* s_rowoff = reinterpret_cast<int*>(smem + RING);
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction: keep it in an SGPR
     int pi = 0;
     for (int i = 1; i < g.nprob; ++i)
         if ((int)blockIdx.x >= g.p[i].tile_start) pi = i;
@@ -62,6 +80,8 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int M = P.M, Cin = P.Cin, IH = P.IH, IW = P.IW, ntr = P.ntr, nts = P.nts;
     const int per = P.OA * P.OB;
+    // LDS map: [ring of STAGES x (A tile, B tile)] [output row offsets]
+    int* s_rowoff = reinterpret_cast<int*>(smem + OP_BYTES);
 
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
@@ -111,10 +131,10 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
     // one k-tile of direct-to-LDS loads into ring stage `st`; past the end every offset is out of range (zeros)
     auto issue_loads = [&](int st) {
         const bool live = issued < nk;
-        const int toff_a = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
         const unsigned toff_b = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
-        const int tbit = tr * nts + ts;
         unsigned char* S = smem + st * STAGE_BYTES + wave * 1024;
+        const int toff_a = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
+        const int tbit = tr * nts + ts;
 #pragma unroll
         for (int i = 0; i < NSA; ++i) {
             const unsigned off = (live && ((a_mask[i] >> tbit) & 1u)) ? (unsigned)(a_base[i] + toff_a) : kOOB;
@@ -124,12 +144,12 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
         for (int j = 0; j < NSB; ++j) {
             if (j + 1 < NSB || last_b) {
                 const unsigned off = live ? b_base0 : kOOB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(S + A_BYTES + j * (NW * 1024)), 16, (int)off,
-                                                         (int)(toff_b + j * b_step), 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(S + A_BYTES + j * (NW * 1024)), 16,
+                                                         (int)off, (int)(toff_b + j * b_step), 0, 0);
             }
         }
         ++issued;
-        // taps innermost: the shifted reads of one 32-channel slab follow each other while it is hot in L2
+        // taps innermost: the shifted reads of one 32-channel slab follow each other and hit the same cache lines
         if (++ts == nts) {
             ts = 0;
             if (++tr == ntr) { tr = 0; ci0 += BK; }
@@ -143,8 +163,8 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
     const int a_rd = (wm * TM + lr) * 64, b_rd = A_BYTES + (wn * TN + lr) * 64;
     const int ck0 = ((0 + lkc) ^ sw) << 4, ck1 = ((2 + lkc) ^ sw) << 4;
     u32x4 af[2][FM], bf[2][FN];
-    auto load_frags = [&](int st, int ck, int slot) {
-        const unsigned char* T = smem + st * STAGE_BYTES + ck;
+    auto load_frags = [&](int st, int ks, int slot) {
+        const unsigned char* T = smem + st * STAGE_BYTES + (ks ? ck1 : ck0);
 #pragma unroll
         for (int i = 0; i < FM; ++i) af[slot][i] = *reinterpret_cast<const u32x4*>(T + a_rd + i * (MT * 64));
 #pragma unroll
@@ -163,18 +183,22 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
 
     __syncthreads();                     // row offsets visible; nothing in flight yet
     if (nk > 0) {
+        const int LT = NSA + (last_b ? NSB : NSB - 1);         // loads per k-tile of this wave
 #pragma unroll
         for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
-        // tile 0 landed: everything but the STAGES-2 younger tiles of this wave
-        if (last_b) wait_vmcnt<(STAGES - 2) * (NSA + NSB)>(); else wait_vmcnt<(STAGES - 2) * (NSA + NSB - 1)>();
+        wait_vmcnt_rt((STAGES - 2) * LT);                      // tile 0 landed: all but the STAGES-2 younger tiles
         __builtin_amdgcn_s_barrier();
-        load_frags(0, ck0, 0);
+        load_frags(0, 0, 0);
         int st = 0;                      // ring stage of tile kt
+        // Waves w and w+4 share a SIMD.  The first four waves issue their loads before their MFMAs, the last four
+        // after, so that on every SIMD one wave feeds the matrix core while the other does address arithmetic.
+        const bool early = wave < NW / 2;
         for (int kt = 0; kt < nk; ++kt) {
             int st_free = st + STAGES - 1;
             if (st_free >= STAGES) st_free -= STAGES;
-            issue_loads(st_free);        // tile kt+STAGES-1 into the stage that tile kt-1 used
-            load_frags(st, ck1, 1);
+            if (early) issue_loads(st_free);                   // tile kt+STAGES-1 into the stage that tile kt-1 used
+            load_frags(st, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -183,21 +207,22 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[1][j], af[1][i], acc[j][i]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!early) issue_loads(st_free);
             // tile kt+1 landed (this wave's share); the barrier makes every wave's share visible and frees stage st
-            if (last_b) wait_vmcnt<(STAGES - 2) * (NSA + NSB)>(); else wait_vmcnt<(STAGES - 2) * (NSA + NSB - 1)>();
+            wait_vmcnt_rt((STAGES - 2) * LT);
             __builtin_amdgcn_s_barrier();
             if (++st == STAGES) st = 0;
-            if (kt + 1 < nk) load_frags(st, ck0, 0);
+            if (kt + 1 < nk) load_frags(st, 0, 0);
         }
     }
     wait_vmcnt<0>();                     // the trailing (all out-of-range) loads still write zeros into the ring
     __syncthreads();
-
     // ---- epilogue: registers -> (addends) -> bf16 -> LDS [pixel][channel] -> 16-byte coalesced stores + statistics ----
     bf16_t* __restrict__ out = reinterpret_cast<bf16_t*>(P.out);
     const bf16_t* __restrict__ add0 = reinterpret_cast<const bf16_t*>(P.add0);
     const bf16_t* __restrict__ add1 = reinterpret_cast<const bf16_t*>(P.add1);
-    unsigned char* E = smem + wave * EP_WAVE;
+    unsigned char* E = smem + wave * EP_WAVE;            // staging over the (dead) operand area; the host sizes LDS for it
     const int cg = lane % 20, pl = lane / 20;           // read-back: 16-byte channel group, pixel lane (pl == 3: idle)
     const int colg = n0 + wn * TN + cg * 8;
     float s1[8], s2[8];
@@ -232,8 +257,8 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
                     }
                 }
                 uint2 pk;
-                pk.x = (unsigned)float_to_bf16_bits(v[0]) | ((unsigned)float_to_bf16_bits(v[1]) << 16);
-                pk.y = (unsigned)float_to_bf16_bits(v[2]) | ((unsigned)float_to_bf16_bits(v[3]) << 16);
+                pk.x = pack_bf16x2(v[0], v[1]);
+                pk.y = pack_bf16x2(v[2], v[3]);
                 *reinterpret_cast<uint2*>(E + lr * EP_PITCH + c0 * 2) = pk;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -286,14 +311,18 @@ __global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g)
     }
 }
 
+namespace {
+
 template <int WGM, int WGN, int STAGES>
 hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
     constexpr int BM = WGM * 64, BN = WGN * 160;
-    constexpr size_t lds = (size_t)STAGES * (BM + BN) * 64 + BM * sizeof(int);
+    const size_t operands = std::max((size_t)STAGES * (BM + BN) * 64, (size_t)8 * 32 * 336);   // ring / epilogue staging
+    const size_t lds = operands + BM * sizeof(int);
+    static_assert((size_t)STAGES * (BM + BN) * 64 + BM * sizeof(int) <= 160 * 1024, "LDS budget");
     static bool configured = false;
     auto kern = conv_igemm_fast_kernel<WGM, WGN, STAGES>;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -310,8 +339,11 @@ CfgInfo conv_fast_cfg_info(int cfg) {
 
 hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s) {
     if (g.total_tiles <= 0) return hipSuccess;
-    if (cfg == FAST_512x160) return fast_launch<8, 1, 3>(g, s);
-    return fast_launch<4, 2, 4>(g, s);
+    switch (cfg) {
+        case FAST_512x160: return fast_launch<8, 1, 3>(g, s);
+        case FAST_256x320: return fast_launch<4, 2, 4>(g, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace lp

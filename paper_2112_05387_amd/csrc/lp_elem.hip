@@ -32,7 +32,7 @@ template <typename T> struct Vec {
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                v[e] = (unsigned)float_to_bf16_bits(f[2 * e]) | ((unsigned)float_to_bf16_bits(f[2 * e + 1]) << 16);
+                v[e] = pack_bf16x2(f[2 * e], f[2 * e + 1]);
         }
         *reinterpret_cast<u32x4*>(p) = v;
     }

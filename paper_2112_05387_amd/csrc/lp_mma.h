@@ -32,6 +32,13 @@ __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {   // rou
     u += 0x7fffu + ((u >> 16) & 1u);
     return (unsigned short)(u >> 16);
 }
+// two floats -> packed bf16 pair (low half = a), round to nearest even in hardware (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
 template <typename T> __device__ __forceinline__ T from_float(float f);
 template <> __device__ __forceinline__ float from_float<float>(float f) { return f; }
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float f) { bf16_t r; r.v = float_to_bf16_bits(f); return r; }
