@@ -100,7 +100,7 @@ struct Unit {
     int N = 0, H = 0, W = 0, Ho = 0, Wo = 0;
     bool relu = false, need_dgrad = true;
     int t_w = -1, t_g = -1, t_b = -1;      // tensor table indices
-    size_t ws_y = 0, ws_stats = 0, ws_red = 0, ws_wt = 0;
+    size_t ws_y = 0, ws_dy = 0, ws_stats = 0, ws_red = 0, ws_wt = 0;
     size_t out_elems() const { return (size_t)N * Ho * Wo * cout; }
     size_t in_elems() const { return (size_t)N * H * W * cin; }
 };
@@ -128,7 +128,7 @@ struct ModulePlan {
     size_t ws_pooled = 0, ws_dfeat = 0;
     int t_fcw = -1, t_fcb = -1;
     size_t ws_stats0 = 0, ws_stats_bytes = 0, ws_red0 = 0, ws_red_bytes = 0;
-    size_t ws_G[2] = {0, 0}, ws_D = 0, ws_Dp = 0, ws_A = 0, ws_P = 0, ws_gpool = 0;
+    size_t ws_G[2] = {0, 0}, ws_A = 0, ws_P = 0, ws_gpool = 0;
     Program fwd, bwd, bwd_dx0;             // bwd_dx0: variant that also produces dx for a stem-less module 0
 };
 struct AuxPlan {
@@ -256,6 +256,25 @@ struct Builder {
         w.M = u.N * u.Ho * u.Wo; w.Cout = u.cout; w.Cin = u.cin; w.Kg = u.R * u.R * u.cin;
         w.Ho = u.Ho; w.Wo = u.Wo; w.IH = u.H; w.IW = u.W; w.stride = u.stride; w.pad = u.pad; w.R = u.R; w.S = u.R;
         o.vec = (u.cin % epv()) == 0;
+        // wide 3x3 stride-1 layers in bf16: the direct-to-LDS kernel with 160 x (3 taps x 160) tiles
+        const int t160m = (u.cout + 159) / 160, t160n = (u.cin + 159) / 160;
+        const double fill160 = (double)u.cout * u.cin / ((double)t160m * t160n * 160.0 * 160.0);
+        const bool fast = net->dtype == LP_BF16 && u.R == 3 && u.stride == 1 && u.pad == 1 && u.Ho == u.H && u.Wo == u.W &&
+                          u.cin % 8 == 0 && u.cout % 8 == 0 && fill160 >= 0.7 &&
+                          (double)w.M * std::max(u.cin, u.cout) * 2.0 < 2.0e9;
+        if (fast) {
+            o.cfg = WGRAD_FAST;
+            w.tiles_m = t160m; w.tiles_n = 3 * t160n;
+            fastdiv_make((unsigned)u.W, &w.mulW, &w.shW);
+            fastdiv_make((unsigned)u.H, &w.mulH, &w.shH);
+            // one block per CU: as many pixel chunks as fill the chip once, but at least 512 pixels each
+            int ks = std::max(1, 256 / (w.tiles_m * w.tiles_n));
+            int chunk = std::max(512, (w.M + ks - 1) / ks);
+            chunk = (chunk + 31) / 32 * 32;
+            w.kchunk = chunk; w.ksplit = (w.M + chunk - 1) / chunk;
+            o.r[0] = x; o.r[1] = dy; o.r[2] = dw;
+            return o;
+        }
         o.cfg = wgrad_cfg_for(u.cout, w.Kg, o.vec);
         const CfgInfo ci = wgrad_cfg_info(o.cfg, net->dtype);
         w.tiles_m = (w.Cout + ci.BM - 1) / ci.BM; w.tiles_n = (w.Kg + ci.BN - 1) / ci.BN;
@@ -436,6 +455,7 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
     size_t maxD = 0, maxA = 0, maxG = 0, maxP = 0;
     for (Unit* u : units) {
         u->ws_y = ws.take(u->out_elems() * esz);
+        u->ws_dy = ws.take(u->out_elems() * esz);     // its own gradient buffer: the filter gradients run at the end
         if (u->need_dgrad) u->ws_wt = ws.take((size_t)u->cout * u->R * u->R * u->cin * esz);
         maxD = std::max(maxD, u->out_elems());
     }
@@ -473,7 +493,6 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
     }
     if (m.bp.empty()) return fail(LP_ERR_SHAPE, "module %d: at least one residual block is required", k);
     m.ws_G[0] = ws.take(maxG * esz); m.ws_G[1] = ws.take(maxG * esz);
-    m.ws_D = ws.take(maxD * esz); m.ws_Dp = ws.take(maxD * esz);
     m.ws_A = ws.take(std::max<size_t>(maxA, 1) * esz);
     m.ws_P = ws.take(std::max<size_t>(maxP, 1) * esz);
     if (last) {
@@ -565,7 +584,11 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             Bw.push_back(Step{o});
             g = mk(SP_WS, 0, m.ws_dfeat);
         } else g = mk(SP_DY, k, 0);
-        const Ref Dm = mk(SP_WS, 0, m.ws_D), Dp = mk(SP_WS, 0, m.ws_Dp), A = mk(SP_WS, 0, m.ws_A), Pp = mk(SP_WS, 0, m.ws_P);
+        const Ref A = mk(SP_WS, 0, m.ws_A), Pp = mk(SP_WS, 0, m.ws_P);
+        auto dyref = [&](const Unit& u) { return mk(SP_WS, 0, u.ws_dy); };
+        // The filter gradients depend on nothing but a unit's input and its output gradient, and nothing depends on
+        // them: they are collected and run as the last step, where the scheduler groups them into few large launches.
+        Step wg_tail;
         for (int i = (int)m.bp.size() - 1; i >= 0; --i) {
             BlockPlan& bp = m.bp[i];
             const bool need_in_grad = (i > 0) || m.has_stem || want_dx_first;
@@ -577,6 +600,7 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             for (int j = nm - 1; j >= 0; --j) {
                 const Unit& u = bp.main[j];
                 const bool lastu = (j == nm - 1);
+                const Ref Dm = dyref(u), Dp = bp.has_proj ? dyref(bp.proj) : Ref();
                 Step s1{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
                                  grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), u.relu)};
                 Step s2{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
@@ -593,9 +617,9 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
                 // weight gradients (and the projection's data-gradient) of this level
                 Step s3;
                 const Ref uin = (j == 0) ? bp.in : mk(SP_WS, 0, bp.ws_act[j - 1]);
-                s3.push_back(B.wgrad(u, uin, Dm, grad_ref(m, k, u.t_w)));
+                wg_tail.push_back(B.wgrad(u, uin, Dm, grad_ref(m, k, u.t_w)));
                 if (lastu && bp.has_proj) {
-                    s3.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
+                    wg_tail.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
                     if (need_in_grad) B.conv_dgrad(bp.proj, Dp, mk(SP_WS, 0, bp.proj.ws_wt), Pp, Ref(), Ref(), s3);
                 }
                 // data-gradient of this unit
@@ -604,7 +628,7 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
                     Bw.push_back(s3);
                     gcur = A;
                 } else {
-                    Bw.push_back(s3);
+                    if (!s3.empty()) Bw.push_back(s3);
                     if (need_in_grad) {
                         Step s4;
                         // skip path: identity adds the block-output gradient, projection adds its data-gradient.
@@ -629,12 +653,14 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
                 Bw.push_back(Step{o});
                 gs = mk(SP_WS, 0, m.ws_gpool);
             }
+            const Ref Dm = dyref(u);
             Bw.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gs, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
                                        grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), true)});
             Bw.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gs, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
                                        grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), true)});
-            Bw.push_back(Step{B.wgrad(u, mk(SP_X, k, 0), Dm, grad_ref(m, k, u.t_w))});
+            wg_tail.push_back(B.wgrad(u, mk(SP_X, k, 0), Dm, grad_ref(m, k, u.t_w)));
         }
+        Bw.push_back(wg_tail);
     }
     return LP_OK;
 }
@@ -705,6 +731,34 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
     }
 }
 
+// Split-K of a grouped launch of the wide-layer filter-gradient kernel.  Every block has the same tile, so its time
+// is its number of 32-pixel k-tiles plus a fixed epilogue (the atomic adds of its 160 x 480 partial sums, which
+// cost about as much as 24 k-tiles); one block runs per CU.  Pick the common chunk length that minimises
+// rounds x (chunk + epilogue).  The gradients were zeroed at the start of the backward pass and are accumulated
+// atomically, so the split may differ from launch to launch.
+static void plan_wgrad_fast_splits(WgradGroup& g) {
+    const int kEpilogue = 24, kCUs = 256;
+    int best_chunk = 16; double best_cost = 1e300;
+    int max_kt = 1;
+    for (int i = 0; i < g.nprob; ++i) max_kt = std::max(max_kt, (g.p[i].M + 31) / 32);
+    for (int chunk = 16; chunk <= std::max(16, max_kt); ++chunk) {
+        long blocks = 0;
+        for (int i = 0; i < g.nprob; ++i) {
+            const int kt = (g.p[i].M + 31) / 32;
+            blocks += (long)g.p[i].tiles_m * g.p[i].tiles_n * ((kt + chunk - 1) / chunk);
+        }
+        const double cost = (double)((blocks + kCUs - 1) / kCUs) * (chunk + kEpilogue);
+        if (cost < best_cost) { best_cost = cost; best_chunk = chunk; }
+    }
+    for (int i = 0; i < g.nprob; ++i) {
+        WgradProb& p = g.p[i];
+        const int kt = (p.M + 31) / 32;
+        const int ks = (kt + best_chunk - 1) / best_chunk;
+        p.ksplit = ks;
+        p.kchunk = (kt + ks - 1) / ks * 32;          // equal chunks
+    }
+}
+
 static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s);
 
 static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const Bindings& b, hipStream_t s) {
@@ -771,14 +825,17 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;
+                for (int i = 0; i < n; ++i) g.p[i] = ops[base + i]->wg;
+                if (ops[base]->cfg == WGRAD_FAST) plan_wgrad_fast_splits(g);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
-                    WgradProb& p = g.p[i]; p = o.wg;
+                    WgradProb& p = g.p[i];
                     p.x = resolve(o.r[0], b); p.dy = resolve(o.r[1], b); p.dw = (float*)resolve(o.r[2], b);
-                    p.tile_start = tot; tot += p.tiles_m * p.tiles_n * p.ksplit;
+                    p.tile_start = tot;
+                    tot += ops[base]->cfg == WGRAD_FAST ? wgrad_fast_blocks(p) : p.tiles_m * p.tiles_n * p.ksplit;
                 }
                 g.total_tiles = tot;
-                err = launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
+                err = ops[base]->cfg == WGRAD_FAST ? launch_wgrad_fast(g, s) : launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_BN_APPLY: {
                 BnApplyGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
@@ -864,8 +921,14 @@ static lp_status run_programs(lp_net* net, const std::vector<const Program*>& pr
             }
         }
         if (!any) break;
-        for (auto& kc : keys)
+        // the most common operation first; filter gradients only when nothing else is ready, so that the tails of all
+        // programs meet and merge
+        bool only_wgrad = true;
+        for (auto& kc : keys) only_wgrad = only_wgrad && (kc.first / 64 == OP_WGRAD);
+        for (auto& kc : keys) {
+            if (!only_wgrad && kc.first / 64 == OP_WGRAD) continue;
             if (kc.second > best_cnt || (kc.second == best_cnt && kc.first < best_key)) { best_key = kc.first; best_cnt = kc.second; }
+        }
         std::vector<const Op*> ops;
         for (size_t i = 0; i < np; ++i) {
             if (step[i] >= progs[i]->size()) continue;

@@ -48,6 +48,7 @@ struct WgradProb {
     int Ho, Wo, IH, IW, stride, pad, R, S;
     int ksplit, kchunk;
     int tiles_m, tiles_n, tile_start;
+    unsigned mulW, shW, mulH, shH;   // fast division by IW and IH (wide-layer kernel)
 };
 struct WgradGroup {
     int nprob, total_tiles;
@@ -123,7 +124,8 @@ struct HeadProb {        // global average pool + linear
 // ---- launchers (host side; return hipError_t of the launch) ----------------------------------------
 // tile configuration ids of the implicit-GEMM kernels
 enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160, CFG_COUNT,
-               FAST_256x320 = 8, FAST_512x160 = 9 };   // bf16 wide-layer kernel (lp_conv_fast.hip)
+               FAST_256x320 = 8, FAST_512x160 = 9,     // bf16 wide-layer kernel (lp_conv_fast.hip)
+               WGRAD_FAST = 8 };                       // bf16 wide-layer filter-gradient kernel (lp_wgrad_fast.hip)
 struct CfgInfo { int BM, BN, BK; };
 CfgInfo conv_cfg_info(int cfg, int dtype);
 CfgInfo wgrad_cfg_info(int cfg, int dtype);
@@ -131,6 +133,9 @@ CfgInfo conv_fast_cfg_info(int cfg);
 
 hipError_t launch_conv(const ConvGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
 hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s);
+hipError_t launch_wgrad_fast(const WgradGroup& g, hipStream_t s);
+int wgrad_fast_blocks(const WgradProb& p);
+void fastdiv_make(unsigned d, unsigned* mul, unsigned* shift);
 hipError_t launch_wgrad(const WgradGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
 hipError_t launch_wtrans(const WtransGroup& g, int dtype, hipStream_t s);
 hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s);

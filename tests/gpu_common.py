@@ -34,6 +34,16 @@ def gpu_mini_bottleneck(batch=2, dtype="f32"):
     return net
 
 
+def gpu_mini_wide(batch=3):
+    """bf16, widths 136 and 296 on 6x10 images: the wide-layer filter-gradient kernel with ragged channel tiles
+    (136 of 160; 296 = 160 + 136), a ragged last k-tile (180 pixels) and image sizes that are not powers of two."""
+    blocks = [Block("basic", 136, 136, 136, 1, False), Block("basic", 136, 296, 296, 1, True),
+              Block("basic", 296, 296, 296, 1, False)]
+    net = cfg._assemble("gpu_mini_wide", [blocks[:1], blocks[1:]], batch, 6, 10, 3, 1, 136, 7, seed=23)
+    net.dtype = "bf16"
+    return net
+
+
 def load_step(ls, net, inp):
     for k in range(net.K):
         ls.set_params(k, inp["params"][k])

@@ -4,7 +4,7 @@ import pytest
 
 import workloads as wl
 from oracle import lpref
-from tests.gpu_common import compare_step, gpu_mini_basic, gpu_mini_bottleneck, say
+from tests.gpu_common import compare_step, gpu_mini_basic, gpu_mini_bottleneck, gpu_mini_wide, say
 
 pytestmark = pytest.mark.gpu
 
@@ -51,6 +51,11 @@ def test_mini_bottleneck(dtype):
     net = gpu_mini_bottleneck(dtype=dtype)
     say("case mini_bottleneck", dtype)
     compare_step(net)
+
+
+def test_mini_wide_ragged_tiles():
+    say("case mini_wide bf16")
+    compare_step(gpu_mini_wide())
 
 
 def test_resnet20_full_size():
