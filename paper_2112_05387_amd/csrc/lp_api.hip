@@ -759,13 +759,14 @@ static void plan_wgrad_fast_splits(WgradGroup& g) {
     }
 }
 
-static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s);
+static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s,
+                                    int* used_cfg);
 
 static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const Bindings& b, hipStream_t s) {
     hipError_t err = hipSuccess;
     for (size_t base = 0; base < ops.size() && err == hipSuccess; base += kMaxGroup) {
         const int n = (int)std::min<size_t>(kMaxGroup, ops.size() - base);
-        if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s); continue; }
+        if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s, nullptr); continue; }
         lp_net::ProfRec r;
         r.type = ops[base]->type; r.cfg = ops[base]->cfg; r.nprob = n; r.flops = 0; r.bytes = 0;
         for (int i = 0; i < n; ++i) { double f, by; op_work(net, *ops[base + i], f, by); r.flops += f; r.bytes += by; }
@@ -774,14 +775,15 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
             else if ((err = hipEventCreate(e)) != hipSuccess) return err;
         }
         if ((err = hipEventRecord(r.a, s)) != hipSuccess) return err;
-        err = launch_group_impl(net, ops, base, n, b, s);
+        err = launch_group_impl(net, ops, base, n, b, s, &r.cfg);
         if (err == hipSuccess) err = hipEventRecord(r.b, s);
         net->prof_recs.push_back(r);
     }
     return err;
 }
 
-static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s) {
+static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s,
+                                    int* used_cfg) {
     const int type = ops[base]->type, dt = net->dtype;
     const int epv = dt == LP_BF16 ? 8 : 4;
     hipError_t err = hipSuccess;
@@ -810,8 +812,23 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             } break;
             case OP_CONV: {
                 ConvGroup g; g.nprob = n; int tot = 0;
-                const bool fast = ops[base]->cfg >= FAST_256x320;
-                const CfgInfo ci = fast ? conv_fast_cfg_info(ops[base]->cfg) : conv_cfg_info(ops[base]->cfg, dt);
+                int cfg = ops[base]->cfg;
+                const bool fast = cfg >= FAST_256x320;
+                if (cfg == FAST_256x320) {
+                    // too few 256x320 tiles for the chip: the four-wave variant with 128x320 tiles, or the two-wave one
+                    long t256 = 0, t128 = 0;
+                    for (int i = 0; i < n; ++i) {
+                        const ConvProb& c = ops[base + i]->conv;
+                        t256 += (long)((c.M + 255) / 256) * ((c.Ncol + 319) / 320);
+                        t128 += (long)((c.M + 127) / 128) * ((c.Ncol + 319) / 320);
+                    }
+                    if (t256 < 200) cfg = t128 < 200 ? FAST_128x160 : FAST_128x320;
+                }
+                if (used_cfg) *used_cfg = cfg;
+                const CfgInfo ci = fast ? conv_fast_cfg_info(cfg) : conv_cfg_info(cfg, dt);
+                // longest tiles first: the blocks of a launch are dispatched in order
+                std::stable_sort(ops.begin() + base, ops.begin() + base + n,
+                                 [](const Op* a, const Op* b2) { return a->conv.Kg > b2->conv.Kg; });
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     ConvProb& p = g.p[i]; p = o.conv;
@@ -821,7 +838,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
-                err = fast ? launch_conv_fast(g, ops[base]->cfg, s) : launch_conv(g, dt, ops[base]->cfg, ops[base]->vec, s);
+                err = fast ? launch_conv_fast(g, cfg, s) : launch_conv(g, dt, cfg, ops[base]->vec, s);
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;
@@ -921,13 +938,31 @@ static lp_status run_programs(lp_net* net, const std::vector<const Program*>& pr
             }
         }
         if (!any) break;
-        // the most common operation first; filter gradients only when nothing else is ready, so that the tails of all
-        // programs meet and merge
+        // The program with the most steps left is the critical path: one of its pending operations goes next (the one
+        // most programs share), and every other program with the same operation pending joins the launch.  Filter
+        // gradients only when nothing else is ready, so that the tails of all programs meet and merge.
         bool only_wgrad = true;
         for (auto& kc : keys) only_wgrad = only_wgrad && (kc.first / 64 == OP_WGRAD);
-        for (auto& kc : keys) {
-            if (!only_wgrad && kc.first / 64 == OP_WGRAD) continue;
-            if (kc.second > best_cnt || (kc.second == best_cnt && kc.first < best_key)) { best_key = kc.first; best_cnt = kc.second; }
+        size_t lead = np, lead_left = 0;
+        for (size_t i = 0; i < np; ++i) {
+            if (step[i] >= progs[i]->size()) continue;
+            const Step& st = (*progs[i])[step[i]];
+            bool eligible = false;
+            for (size_t j = 0; j < st.size(); ++j)
+                eligible = eligible || (!issued[i][j] && (only_wgrad || st[j].key() / 64 != OP_WGRAD));
+            const size_t left = progs[i]->size() - step[i];
+            if (eligible && left > lead_left) { lead = i; lead_left = left; }
+        }
+        {
+            const Step& st = (*progs[lead])[step[lead]];
+            for (size_t j = 0; j < st.size(); ++j) {
+                if (issued[lead][j]) continue;
+                const int key = st[j].key();
+                if (!only_wgrad && key / 64 == OP_WGRAD) continue;
+                int cnt = 0;
+                for (auto& kc : keys) if (kc.first == key) cnt = kc.second;
+                if (cnt > best_cnt || (cnt == best_cnt && key < best_key)) { best_key = key; best_cnt = cnt; }
+            }
         }
         std::vector<const Op*> ops;
         for (size_t i = 0; i < np; ++i) {

@@ -1,7 +1,8 @@
 // bf16 implicit-GEMM convolution (forward / data-gradient) for the wide layers on gfx950.
 //
-// 512 threads; each wave owns a 64-pixel x 160-channel output tile (2 x 5 micro-tiles of
-// v_mfma_f32_32x32x16_bf16, 160 fp32 accumulators), waves arranged WGM x WGN.  What was measured on the
+// Each wave owns a 64-pixel x 160-channel output tile (2 x 5 micro-tiles of v_mfma_f32_32x32x16_bf16, 160 fp32
+// accumulators); a block is WGM x WGN waves: eight (512x160 or 256x320 tiles), or four (128x320) or two (128x160)
+// for launches that would otherwise have fewer tiles than the chip has CUs.  What was measured on the
 // machine and shaped this kernel:
 //  * an MFMA loop fed from LDS is bound by LDS bandwidth (about 128 B/clk/CU), so the wave tile is as large
 //    as the register file allows at two waves per SIMD;
@@ -56,9 +57,9 @@ __device__ __forceinline__ void wait_vmcnt_rt(int n) {
 }  // namespace
 
 template <int WGM, int WGN, int STAGES>
-__global__ __launch_bounds__(512) void conv_igemm_fast_kernel(const ConvGroup g) {
-    constexpr int MT = 32, FM = 2, FN = 5, NW = 8, NT = 512;
-    static_assert(WGM * WGN == NW, "eight waves");
+__global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const ConvGroup g) {
+    constexpr int MT = 32, FM = 2, FN = 5, NW = WGM * WGN, NT = NW * 64;
+    static_assert(NW == 8 || NW == 4 || NW == 2, "eight waves (two per SIMD), four or two");
     constexpr int TM = FM * MT, TN = FN * MT, BM = WGM * TM, BN = WGN * TN, BK = 32;
     constexpr int A_BYTES = BM * 64, STAGE_BYTES = (BM + BN) * 64;
     constexpr int NSA = BM / 16 / NW;                 // 1 KiB slabs (16 rows) of A per wave
@@ -316,7 +317,7 @@ namespace {
 template <int WGM, int WGN, int STAGES>
 hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
     constexpr int BM = WGM * 64, BN = WGN * 160;
-    const size_t operands = std::max((size_t)STAGES * (BM + BN) * 64, (size_t)8 * 32 * 336);   // ring / epilogue staging
+    const size_t operands = std::max((size_t)STAGES * (BM + BN) * 64, (size_t)WGM * WGN * 32 * 336);   // ring / epilogue staging
     const size_t lds = operands + BM * sizeof(int);
     static_assert((size_t)STAGES * (BM + BN) * 64 + BM * sizeof(int) <= 160 * 1024, "LDS budget");
     static bool configured = false;
@@ -326,7 +327,7 @@ hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(g.total_tiles), dim3(512), lds, s, g);
+    hipLaunchKernelGGL(kern, dim3(g.total_tiles), dim3(WGM * WGN * 64), lds, s, g);
     return hipGetLastError();
 }
 
@@ -334,6 +335,8 @@ hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
 
 CfgInfo conv_fast_cfg_info(int cfg) {
     if (cfg == FAST_512x160) return {512, 160, 32};
+    if (cfg == FAST_128x320) return {128, 320, 32};
+    if (cfg == FAST_128x160) return {128, 160, 32};
     return {256, 320, 32};
 }
 
@@ -342,6 +345,8 @@ hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s) {
     switch (cfg) {
         case FAST_512x160: return fast_launch<8, 1, 3>(g, s);
         case FAST_256x320: return fast_launch<4, 2, 4>(g, s);
+        case FAST_128x320: return fast_launch<2, 2, 4>(g, s);
+        case FAST_128x160: return fast_launch<2, 1, 4>(g, s);
         default: return hipErrorInvalidValue;
     }
 }
