@@ -823,6 +823,9 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                         t128 += (long)((c.M + 127) / 128) * ((c.Ncol + 319) / 320);
                     }
                     if (t256 < 200) cfg = t128 < 200 ? FAST_128x160 : FAST_128x320;
+                    bool k64 = true;                  // k-tiles of 64 channels where every problem allows them
+                    for (int i = 0; i < n; ++i) k64 = k64 && (ops[base + i]->conv.Cin % 64 == 0);
+                    if (k64) cfg = cfg == FAST_256x320 ? FAST64_256x320 : cfg == FAST_128x320 ? FAST64_128x320 : FAST64_128x160;
                 }
                 if (used_cfg) *used_cfg = cfg;
                 const CfgInfo ci = fast ? conv_fast_cfg_info(cfg) : conv_cfg_info(cfg, dt);
@@ -1042,8 +1045,8 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
 
 lp_status lp_net_destroy(struct lp_net* net) {
     if (net) {
-        for (auto& r : net->prof_recs) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
-        for (hipEvent_t e : net->prof_pool) hipEventDestroy(e);
+        for (auto& r : net->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (hipEvent_t e : net->prof_pool) (void)hipEventDestroy(e);
     }
     delete net;
     return LP_OK;

@@ -17,7 +17,11 @@
 // The zero padding of the convolution and the ragged edges of the GEMM are out-of-range buffer offsets, which
 // the hardware returns (and writes to LDS) as zeros.
 //
-// Restrictions (the caller falls back to the general kernel otherwise): bf16, Cin % 32 == 0 (a k-tile lies
+// k-tiles of 64 channels (128-byte rows, two ring stages) are used where Cin allows: a CU's L1 accepts about one
+// cache line per four clocks whatever part of the line is used, so the 64-byte gathers of the 32-channel k-tile
+// reach half the bytes per clock of 128-byte ones.
+//
+// Restrictions (the caller falls back to the general kernel otherwise): bf16, Cin % BK == 0 (a k-tile lies
 // inside one filter tap, so the tap geometry is wave-uniform), at most 32 taps, tensors < 2 GiB.
 #include <algorithm>
 
@@ -56,14 +60,19 @@ __device__ __forceinline__ void wait_vmcnt_rt(int n) {
 
 }  // namespace
 
-template <int WGM, int WGN, int STAGES>
+template <int WGM, int WGN, int STAGES, int BK>
 __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const ConvGroup g) {
     constexpr int MT = 32, FM = 2, FN = 5, NW = WGM * WGN, NT = NW * 64;
     static_assert(NW == 8 || NW == 4 || NW == 2, "eight waves (two per SIMD), four or two");
-    constexpr int TM = FM * MT, TN = FN * MT, BM = WGM * TM, BN = WGN * TN, BK = 32;
-    constexpr int A_BYTES = BM * 64, STAGE_BYTES = (BM + BN) * 64;
-    constexpr int NSA = BM / 16 / NW;                 // 1 KiB slabs (16 rows) of A per wave
-    constexpr int NSBT = BN / 16;                     // slabs of B in total
+    static_assert(BK == 32 || BK == 64, "k-tile of 32 or 64 channels");
+    constexpr int TM = FM * MT, TN = FN * MT, BM = WGM * TM, BN = WGN * TN;
+    constexpr int ROWB = BK * 2;                      // bytes of an LDS row (one tile row, BK channels)
+    constexpr int RPS = 1024 / ROWB;                  // rows per 1 KiB slab (one wave-load): 16 or 8
+    constexpr int CPR = ROWB / 16;                    // 16-byte chunks per row: 4 or 8
+    constexpr int KS = BK / 16;                       // MFMA k-steps per k-tile
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    constexpr int NSA = BM / RPS / NW;                // slabs of A per wave
+    constexpr int NSBT = BN / RPS;                    // slabs of B in total
     constexpr int NSB = (NSBT + NW - 1) / NW;         // per wave (the last one may be absent)
     constexpr int EP_PITCH = 336, EP_WAVE = 32 * EP_PITCH;
     constexpr int EP_BYTES = NW * EP_WAVE;            // epilogue staging, over the dead operand area
@@ -98,15 +107,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(P.in, (unsigned)((size_t)(M / per) * IH * IW * Cin * 2));
     const __amdgpu_buffer_rsrc_t rsrc_b = make_rsrc(P.wt, (unsigned)((size_t)P.Ncol * P.ldw * 2));
 
-    // ---- gather state.  Slab s covers tile rows 16s..16s+15; lane l writes LDS slot (row 16s + l/4, chunk l%4) and
-    // therefore fetches global chunk (l%4) ^ swizzle(row), swizzle(row) = (row >> 2) & 3 = (l >> 4) & 3.
-    const int lrow = lane >> 2;
-    const int kvg = (lane & 3) ^ ((lane >> 4) & 3);
+    // ---- gather state.  Slab s covers tile rows RPS*s .. RPS*s+RPS-1; lane l writes LDS slot (row RPS*s + l/CPR,
+    // chunk l%CPR) and therefore fetches global chunk (l%CPR) ^ swizzle(row).  64-byte rows: swizzle(row) = (row>>2)&3;
+    // 128-byte rows: (row>>1)&7, which inside a slab is 4*(s&1) + (l>>4), and s&1 = wave&1 for every slab of a wave.
+    const int lrow = lane / CPR;
+    const int kvg = BK == 32 ? ((lane & 3) ^ ((lane >> 4) & 3)) : ((lane & 7) ^ (4 * (wave & 1) + (lane >> 4)));
     int a_base[NSA];
     unsigned a_mask[NSA];
 #pragma unroll
     for (int i = 0; i < NSA; ++i) {
-        const int m = m0 + 16 * (wave + NW * i) + lrow;
+        const int m = m0 + RPS * (wave + NW * i) + lrow;
         a_base[i] = 0; a_mask[i] = 0u;
         if (m < M) {
             const int n = m / per, rem = m - n * per;
@@ -123,8 +133,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         }
     }
     // filter rows at or beyond Ncol start at or beyond the end of the buffer: no explicit check needed
-    const unsigned b_base0 = (unsigned)(((n0 + 16 * wave + lrow) * P.ldw + kvg * 8) * 2);
-    const unsigned b_step = (unsigned)(16 * NW * P.ldw * 2);
+    const unsigned b_base0 = (unsigned)(((n0 + RPS * wave + lrow) * P.ldw + kvg * 8) * 2);
+    const unsigned b_step = (unsigned)(RPS * NW * P.ldw * 2);
     const bool last_b = (wave + NW * (NSB - 1)) < NSBT;          // does this wave own a slab in the last round?
 
     const int nk = ntr * nts * (Cin / BK);
@@ -150,7 +160,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
             }
         }
         ++issued;
-        // taps innermost: the shifted reads of one 32-channel slab follow each other and hit the same cache lines
+        // taps innermost: the shifted reads of one channel slab follow each other and hit the same cache lines
         if (++ts == nts) {
             ts = 0;
             if (++tr == ntr) { tr = 0; ci0 += BK; }
@@ -160,16 +170,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     // ---- fragment addressing: lane l reads tile row (l % 32) and chunk (2*ks + l/32) ^ swizzle(row) ----
     const int wm = wave / WGN, wn = wave % WGN;
     const int lr = lane & 31, lkc = lane >> 5;
-    const int sw = (lr >> 2) & 3;
-    const int a_rd = (wm * TM + lr) * 64, b_rd = A_BYTES + (wn * TN + lr) * 64;
-    const int ck0 = ((0 + lkc) ^ sw) << 4, ck1 = ((2 + lkc) ^ sw) << 4;
+    const int sw = BK == 32 ? ((lr >> 2) & 3) : ((lr >> 1) & 7);
+    const int a_rd = (wm * TM + lr) * ROWB, b_rd = A_BYTES + (wn * TN + lr) * ROWB;
+    int ck[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ck[ks] = ((2 * ks + lkc) ^ sw) << 4;
     u32x4 af[2][FM], bf[2][FN];
     auto load_frags = [&](int st, int ks, int slot) {
-        const unsigned char* T = smem + st * STAGE_BYTES + (ks ? ck1 : ck0);
+        const unsigned char* T = smem + st * STAGE_BYTES + ck[ks];
 #pragma unroll
-        for (int i = 0; i < FM; ++i) af[slot][i] = *reinterpret_cast<const u32x4*>(T + a_rd + i * (MT * 64));
+        for (int i = 0; i < FM; ++i) af[slot][i] = *reinterpret_cast<const u32x4*>(T + a_rd + i * (MT * ROWB));
 #pragma unroll
-        for (int j = 0; j < FN; ++j) bf[slot][j] = *reinterpret_cast<const u32x4*>(T + b_rd + j * (MT * 64));
+        for (int j = 0; j < FN; ++j) bf[slot][j] = *reinterpret_cast<const u32x4*>(T + b_rd + j * (MT * ROWB));
     };
 
     // acc[j][i]: rows = channels of micro-tile j, columns = pixels of micro-tile i (filters are the row operand, so
@@ -185,6 +197,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     __syncthreads();                     // row offsets visible; nothing in flight yet
     if (nk > 0) {
         const int LT = NSA + (last_b ? NSB : NSB - 1);         // loads per k-tile of this wave
+        // Ring of STAGES k-tiles: STAGES-1 tiles of loads are in flight, and the tile issued in iteration kt goes into
+        // the stage that tile kt-1 used (free since the barrier that ended iteration kt-1).
 #pragma unroll
         for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
         wait_vmcnt_rt((STAGES - 2) * LT);                      // tile 0 landed: all but the STAGES-2 younger tiles
@@ -193,21 +207,21 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         int st = 0;                      // ring stage of tile kt
         // Waves w and w+4 share a SIMD.  The first four waves issue their loads before their MFMAs, the last four
         // after, so that on every SIMD one wave feeds the matrix core while the other does address arithmetic.
-        const bool early = wave < NW / 2;
+        // (With two stages the loads have only this k-tile's MFMAs to land in: everybody issues first.)
+        const bool early = STAGES == 2 || wave < NW / 2;
         for (int kt = 0; kt < nk; ++kt) {
             int st_free = st + STAGES - 1;
             if (st_free >= STAGES) st_free -= STAGES;
-            if (early) issue_loads(st_free);                   // tile kt+STAGES-1 into the stage that tile kt-1 used
-            load_frags(st, 1, 1);
-            __builtin_amdgcn_sched_barrier(0);
+            if (early) issue_loads(st_free);
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) load_frags(st, ks + 1, (ks + 1) & 1);     // next k-step's fragments behind these MFMAs
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[0][j], af[0][i], acc[j][i]);
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[1][j], af[1][i], acc[j][i]);
+                    for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[ks & 1][j], af[ks & 1][i], acc[j][i]);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (!early) issue_loads(st_free);
             // tile kt+1 landed (this wave's share); the barrier makes every wave's share visible and frees stage st
@@ -314,14 +328,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
 
 namespace {
 
-template <int WGM, int WGN, int STAGES>
+template <int WGM, int WGN, int STAGES, int BK>
 hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
     constexpr int BM = WGM * 64, BN = WGN * 160;
-    const size_t operands = std::max((size_t)STAGES * (BM + BN) * 64, (size_t)WGM * WGN * 32 * 336);   // ring / epilogue staging
+    const size_t operands = std::max((size_t)STAGES * (BM + BN) * BK * 2, (size_t)WGM * WGN * 32 * 336);   // ring / epilogue staging
     const size_t lds = operands + BM * sizeof(int);
-    static_assert((size_t)STAGES * (BM + BN) * 64 + BM * sizeof(int) <= 160 * 1024, "LDS budget");
+    static_assert((size_t)STAGES * (BM + BN) * BK * 2 + BM * sizeof(int) <= 160 * 1024, "LDS budget");
     static bool configured = false;
-    auto kern = conv_igemm_fast_kernel<WGM, WGN, STAGES>;
+    auto kern = conv_igemm_fast_kernel<WGM, WGN, STAGES, BK>;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
@@ -334,19 +348,27 @@ hipError_t fast_launch(const ConvGroup& g, hipStream_t s) {
 }  // namespace
 
 CfgInfo conv_fast_cfg_info(int cfg) {
-    if (cfg == FAST_512x160) return {512, 160, 32};
-    if (cfg == FAST_128x320) return {128, 320, 32};
-    if (cfg == FAST_128x160) return {128, 160, 32};
-    return {256, 320, 32};
+    switch (cfg) {
+        case FAST_512x160: return {512, 160, 32};
+        case FAST_128x320: return {128, 320, 32};
+        case FAST_128x160: return {128, 160, 32};
+        case FAST64_256x320: return {256, 320, 64};
+        case FAST64_128x320: return {128, 320, 64};
+        case FAST64_128x160: return {128, 160, 64};
+        default: return {256, 320, 32};
+    }
 }
 
 hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s) {
     if (g.total_tiles <= 0) return hipSuccess;
     switch (cfg) {
-        case FAST_512x160: return fast_launch<8, 1, 3>(g, s);
-        case FAST_256x320: return fast_launch<4, 2, 4>(g, s);
-        case FAST_128x320: return fast_launch<2, 2, 4>(g, s);
-        case FAST_128x160: return fast_launch<2, 1, 4>(g, s);
+        case FAST_512x160: return fast_launch<8, 1, 3, 32>(g, s);
+        case FAST_256x320: return fast_launch<4, 2, 4, 32>(g, s);
+        case FAST_128x320: return fast_launch<2, 2, 4, 32>(g, s);
+        case FAST_128x160: return fast_launch<2, 1, 4, 32>(g, s);
+        case FAST64_256x320: return fast_launch<4, 2, 2, 64>(g, s);
+        case FAST64_128x320: return fast_launch<2, 2, 2, 64>(g, s);
+        case FAST64_128x160: return fast_launch<2, 1, 2, 64>(g, s);
         default: return hipErrorInvalidValue;
     }
 }
