@@ -65,9 +65,9 @@ def cpu_baseline(net_name, target_seconds=20.0):
     from tests.helpers import step_inputs
     from workloads import configs as cfg
     full = wl.make_config(net_name)
-    # the plain double loops reach roughly 1 GFLOP/s per thread; size the sample from that
+    # the plain double loops reach roughly 4 GFLOP/s per thread on the GPU machine's host; size the sample from that
     per_sample = cfg.conv_flops_step(full) / full.modules[0].N
-    guess_rate = 1.0e9 * lpref.num_threads()
+    guess_rate = 4.0e9 * lpref.num_threads()
     batch = int(max(1, min(full.modules[0].N, target_seconds * guess_rate / per_sample)))
     batch = max(batch, 1)
     net = wl.make_config(net_name, batch=batch)
@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel breakdown to stderr")
     ap.add_argument("--dump-launches", action="store_true", help="print every launch of the last timed step to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run three plain 256 MiB device copies (a known-size kernel that scales "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the local step of all K modules on ONE GPU; --gpus must be 1 "
@@ -186,6 +189,12 @@ def main():
         "roofline": roof,
     }
     ls.close()
+    if args.calibrate_copy:
+        src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))
