@@ -40,8 +40,9 @@ template <typename T> struct Vec {
 
 __device__ __forceinline__ void bn_coeffs(const double* stats, const float* gamma, const float* beta, int c, int C,
                                           int M, float eps, float& sc, float& sh, float& mean, float& invstd) {
-    const double mu = stats[c] / (double)M;
-    double var = stats[C + c] / (double)M - mu * mu;
+    const double inv_m = 1.0 / (double)M;          // the same for every channel: the compiler hoists it out of loops
+    const double mu = stats[c] * inv_m;
+    double var = stats[C + c] * inv_m - mu * mu;
     if (var < 0.0) var = 0.0;
     mean = (float)mu;
     invstd = rsqrtf((float)var + eps);
@@ -81,30 +82,41 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
     const size_t nvec = (size_t)M * C / EPV;
     const int cv = C / EPV;
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
-    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
-        const size_t v = base + i;
-        if (v >= nvec) break;
-        const int c0 = (int)(v % cv) * EPV;
-        float f[EPV], o[EPV];
-        Vec<T>::load(y + v * EPV, f);
+    // four vectors per trip, loads first: up to eight independent 16-byte loads in flight per thread
+    constexpr int U = 4;
+    for (int i0 = threadIdx.x; i0 < kElemVecsPerBlock; i0 += U * kElemBlock) {
+        float f[U][EPV], sk[U][EPV];
+        bool ok[U];
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[e], s_sh[c0 + e]);
-        if (P.skip_mode) {
-            float s[EPV];
-            Vec<T>::load(skip + v * EPV, s);
-            if (P.skip_mode == 2) {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) o[e] += fmaf(s_ssc[c0 + e], s[e], s_ssh[c0 + e]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) o[e] += s[e];
+        for (int u = 0; u < U; ++u) {
+            const size_t v = base + i0 + u * kElemBlock;
+            ok[u] = v < nvec;
+            if (ok[u]) {
+                Vec<T>::load(y + v * EPV, f[u]);
+                if (P.skip_mode) Vec<T>::load(skip + v * EPV, sk[u]);
             }
         }
-        if (P.relu) {
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) o[e] = fmaxf(o[e], 0.f);
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            const size_t v = base + i0 + u * kElemBlock;
+            const int c0 = (int)(v % cv) * EPV;
+            float o[EPV];
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[u][e], s_sh[c0 + e]);
+            if (P.skip_mode == 2) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] += fmaf(s_ssc[c0 + e], sk[u][e], s_ssh[c0 + e]);
+            } else if (P.skip_mode == 1) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] += sk[u][e];
+            }
+            if (P.relu) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) o[e] = fmaxf(o[e], 0.f);
+            }
+            Vec<T>::store(out + v * EPV, o);
         }
-        Vec<T>::store(out + v * EPV, o);
     }
 }
 
@@ -133,7 +145,26 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
             float sc[EPV], sh[EPV], mu[EPV], is[EPV];
 #pragma unroll
             for (int e = 0; e < EPV; ++e) bn_coeffs(P.stats, P.gamma, P.beta, c0 + e, C, M, g.eps, sc[e], sh[e], mu[e], is[e]);
-            for (int r = row0 + trl; r < row1; r += rl) {
+            // four rows per trip: eight independent 16-byte loads in flight per thread
+            int r = row0 + trl;
+            for (; r + 3 * rl < row1; r += 4 * rl) {
+                float gv[4][EPV], yv[4][EPV];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    Vec<T>::load(gp + (size_t)(r + u * rl) * C + c0, gv[u]);
+                    Vec<T>::load(y + (size_t)(r + u * rl) * C + c0, yv[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) {
+                        float gg = gv[u][e];
+                        if (P.relu && !(fmaf(sc[e], yv[u][e], sh[e]) > 0.f)) gg = 0.f;
+                        a1[e] += gg;
+                        a2[e] += gg * ((yv[u][e] - mu[e]) * is[e]);
+                    }
+            }
+            for (; r < row1; r += rl) {
                 float gv[EPV], yv[EPV];
                 Vec<T>::load(gp + (size_t)r * C + c0, gv);
                 Vec<T>::load(y + (size_t)r * C + c0, yv);
@@ -176,7 +207,8 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGro
     for (int c = threadIdx.x; c < C; c += kElemBlock) {
         float sc, sh, mu, is;
         bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
-        const float r0 = (float)(P.red[c] / (double)M), r1 = (float)(P.red[C + c] / (double)M);
+        const double inv_m = 1.0 / (double)M;
+        const float r0 = (float)(P.red[c] * inv_m), r1 = (float)(P.red[C + c] * inv_m);
         const float k1 = P.gamma[c] * is;
         const float k2 = k1 * is * r1;
         s_sc[c] = sc; s_sh[c] = sh;
