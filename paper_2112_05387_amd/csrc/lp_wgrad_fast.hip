@@ -2,7 +2,7 @@
 //
 //   dW[co][r][s][ci] = sum over pixels m=(n,oh,ow) of dY[m][co] * X[n, oh+r-1, ow+s-1][ci]
 //
-// The reduction runs over pixels, and both operands are stored pixel-major ([pixel][channel]), so a k-tile of 32
+// The reduction runs over pixels, and both operands are stored pixel-major ([pixel][channel]), so a k-tile of
 // pixels of either operand is a run of whole channel rows: it is fetched with direct-to-LDS loads of 1 KiB per wave
 // instruction (contiguous in memory, not the 64-byte gathers of the forward operand) and lands in LDS in its
 // natural [pixel][channel] order.  The MFMA wants the reduction index contiguous inside a lane, i.e. the
@@ -12,8 +12,15 @@
 // One block (768 threads, 12 waves, three per SIMD) owns a 160 (co) x 160 (ci) filter tile for the three taps of
 // one filter row r and a chunk of the pixel range; partial sums are added to dW with fp32 atomics (split-K).
 // Wave (wc, wj): co half wc, tap s = wj/2, ci half wj%2 -> an 80 x 80 tile of 5 x 5 v_mfma_f32_16x16x32_bf16
-// micro-tiles (100 accumulators).  Per k-tile a block stages the dY tile and one X tile per tap (the same pixels
-// shifted by one column; the zero padding is written by the loads themselves as out-of-range offsets).
+// micro-tiles (100 accumulators).
+//
+// A ring stage holds 64 pixels: the dY rows of pixels m0..m0+63 and ONE window of X shared by the three taps,
+// the 66 pixels m0-1+(r-1)W .. m0+64+(r-1)W (flattened pixel index; tap s of pixel m reads window row m-m0+s).
+// What the flattened window cannot express is patched in two places: window pixels whose image row is outside the
+// image for this filter row are loaded as zeros (out-of-range offsets), and the column wrap of taps 0 and 2 (the
+// left neighbour of column 0 is the last pixel of the previous row) is masked in the fragments.  One barrier per
+// stage; inside a stage the two 32-pixel k-steps of a wave follow each other, so that after the first k-step the
+// waves of a SIMD are out of phase and LDS reads overlap MFMAs.
 // LDS rows are 320 B; the 32-byte channel pairs of a row swap places in rows with bit 3 set, which keeps the
 // transposing reads of a half-wave (pixel rows p..p+3 and p+8..p+11) on distinct banks.
 //
@@ -46,13 +53,16 @@ __device__ __forceinline__ unsigned fastdiv(unsigned n, unsigned mul, unsigned s
     return (__umulhi(n, mul) + n) >> shift;
 }
 
-constexpr int WF_NW = 12, WF_NT = 768, WF_BK = 32;
+constexpr int WF_NW = 12, WF_NT = 768, WF_BK = 64;   // pixels per ring stage (two MFMA k-steps of 32)
 constexpr int WF_TILE = 160;                         // channels per operand tile
 constexpr int WF_ROW = WF_TILE * 2;                  // bytes per LDS row
-constexpr int WF_TILE_BYTES = WF_BK * WF_ROW;        // 10 KiB
-constexpr int WF_STAGE_BYTES = 4 * WF_TILE_BYTES;    // dY + three taps of X
+constexpr int WF_Y_BYTES = WF_BK * WF_ROW;           // dY rows of a stage: 20 KiB = 20 wave-loads
+constexpr int WF_Y_SLABS = WF_Y_BYTES / 1024;
+constexpr int WF_X_ROWS = WF_BK + 2;                 // window rows of a stage
+constexpr int WF_X_SLABS = (WF_X_ROWS * WF_ROW + 1023) / 1024;     // 21 wave-loads
+constexpr int WF_STAGE_BYTES = WF_Y_BYTES + WF_X_SLABS * 1024;
 constexpr int WF_STAGES = 3;
-constexpr int WF_SLABS = 4 * WF_TILE_BYTES / 1024;   // 40 wave-loads per stage
+constexpr int WF_SLABS = WF_Y_SLABS + WF_X_SLABS;    // 41 wave-loads per stage
 constexpr int WF_LPW = (WF_SLABS + WF_NW - 1) / WF_NW;   // at most 4 per wave
 
 }  // namespace
@@ -90,51 +100,38 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
     const __amdgpu_buffer_rsrc_t rsrc_y = make_rsrc(P.dy, (unsigned)((size_t)P.M * Cout * 2));
     const __amdgpu_buffer_rsrc_t rsrc_x = make_rsrc(P.x, (unsigned)((size_t)P.M * Cin * 2));
 
-    // ---- load plan: wave-load q = wave + 12*i covers bytes [1024*(q%10), +1024) of operand tile q/10 of the stage;
-    // lane l supplies the 16 bytes that land at +16*l, i.e. pixel row krow and (swizzled) channel chunk of that row.
-    int ld_base[WF_LPW];      // byte offset of the lane's chunk for pixel 0 of the chunk's tap-shifted position
-    int ld_krow[WF_LPW];      // pixel row inside the k-tile, or -1 if the lane's channels lie beyond the tensor
-    int nld = 0;
-#pragma unroll
-    for (int i = 0; i < WF_LPW; ++i) {
-        const int q = wave + WF_NW * i;
-        ld_base[i] = 0; ld_krow[i] = -1;
-        if (q < WF_SLABS) {
-            ++nld;
-            const int op = q / 10, slab = q - op * 10;
-            const int b = slab * 1024 + lane * 16;
-            const int krow = b / WF_ROW, cb = b - krow * WF_ROW;
-            const int gb = ((((cb >> 5) ^ ((krow >> 3) & 1)) << 5) | (cb & 31));     // byte of the channel row fetched
-            const int ce = gb >> 1;
-            if (op == 0) {
-                if (co0 + ce < Cout) { ld_krow[i] = krow; ld_base[i] = (krow * Cout + co0 + ce) * 2; }
-            } else {
-                if (ci0 + ce < Cin) { ld_krow[i] = krow; ld_base[i] = ((krow + (r - 1) * W + (op - 2)) * Cin + ci0 + ce) * 2; }
-            }
-        }
-    }
+    // ---- loads: wave-load q = wave + 12*i; q < 20: bytes [1024*q, +1024) of the dY rows, else of the X window.
+    // Lane l supplies the 16 bytes that land at +16*l, i.e. row b/320 and the (swizzled) channel chunk of that row.
+    // (Everything is recomputed per stage rather than kept in registers: the accumulators need them.)
+    const int nld = wave + WF_NW * (WF_LPW - 1) < WF_SLABS ? WF_LPW : WF_LPW - 1;
+    const int Mtot = P.M;
     auto issue_loads = [&](int st, int kt) {
-        const int mt = k_begin + kt * WF_BK;                 // first pixel of the k-tile (beyond k_end: all zeros)
+        const int mt = k_begin + kt * WF_BK;                 // first pixel of the stage (beyond k_end: all zeros)
+        const bool live = mt < k_end;
 #pragma unroll
         for (int i = 0; i < WF_LPW; ++i) {
             const int q = wave + WF_NW * i;
             if (q < WF_SLABS) {
-                const int op = q / 10, slab = q - op * 10;
-                const int m = mt + ld_krow[i];
-                bool ok = ld_krow[i] >= 0 && m < k_end;
+                const bool isx = q >= WF_Y_SLABS;
+                const int b = (isx ? q - WF_Y_SLABS : q) * 1024 + lane * 16;
+                const int row = b / WF_ROW, cb = b - row * WF_ROW;
+                const int ce = ((((cb >> 5) ^ ((row >> 3) & 1)) << 5) | (cb & 31)) >> 1;   // first channel fetched
+                bool ok = live;
                 unsigned off;
-                if (op == 0) {
-                    off = (unsigned)(ld_base[i] + mt * Cout * 2);
+                if (!isx) {
+                    ok = ok && (co0 + ce < Cout) && (mt + row < k_end);
+                    off = (unsigned)(((mt + row) * Cout + co0 + ce) * 2);
                 } else {
-                    const unsigned t = fastdiv((unsigned)m, P.mulW, P.shW);
-                    const int ow = m - (int)t * W;
-                    const int oh = (int)t - (int)fastdiv(t, P.mulH, P.shH) * H;
-                    ok = ok && (unsigned)(oh + r - 1) < (unsigned)H && (unsigned)(ow + op - 2) < (unsigned)W;
-                    off = (unsigned)(ld_base[i] + mt * Cin * 2);
+                    // window pixel p; zero unless it exists and its image row hp has hp-(r-1) inside the image
+                    const int p = mt + row - 1 + (r - 1) * W;
+                    const unsigned t = fastdiv((unsigned)p, P.mulW, P.shW);
+                    const int hp = (int)t - (int)fastdiv(t, P.mulH, P.shH) * H;
+                    ok = ok && row < WF_X_ROWS && (ci0 + ce < Cin) && p >= 0 && p < Mtot && (unsigned)(hp - (r - 1)) < (unsigned)H;
+                    off = (unsigned)((p * Cin + ci0 + ce) * 2);
                 }
                 if (!ok) off = kOOB;
-                unsigned char* dst = smem + st * WF_STAGE_BYTES + op * WF_TILE_BYTES + slab * 1024;
-                if (op == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
+                unsigned char* dst = smem + st * WF_STAGE_BYTES + q * 1024;
+                if (!isx) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
                 else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_ptr_t)dst, 16, (int)off, 0, 0, 0);
             }
         }
@@ -142,23 +139,20 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
 
     // ---- fragment addressing (transposing reads): lane l, l' = l%16, g = l/16 supplies pixel row 8g + 4h + l'/4
     // (h = which half of the 8 reduction elements) and channels cbase + 4*(l'%4)..+3, and receives channel cbase + l'.
+    // The 32-byte channel pair P of a row sits at pair slot P ^ s, s = bit 3 of the LDS row: P + s for even P, P - s
+    // for odd P.  So a fragment address is one of two lane registers (even / odd pair) plus a compile-time offset.
     const int wc = wave & 1, wj = wave >> 1;
     const int tap_s = wj >> 1, half = wj & 1;
     const int lq = lane & 15, lg = lane >> 4;
-    const int row_off = (8 * lg + (lq >> 2)) * WF_ROW + 8 * (lq & 3);
-    const int sw = lg & 1;
-    int a_off[5], b_off[5];
-#pragma unroll
-    for (int i = 0; i < 5; ++i) {
-        a_off[i] = row_off + (((5 * wc + i) ^ sw) << 5);
-        b_off[i] = (1 + tap_s) * WF_TILE_BYTES + row_off + (((5 * half + i) ^ sw) << 5);
-    }
-    auto read_frag = [&](const unsigned char* base) -> u32x4 {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(lds_ptr_t)const_cast<unsigned char*>(base));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(lds_ptr_t)const_cast<unsigned char*>(base + 4 * WF_ROW));
-        const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
-        u32x4 f = {l2.x, l2.y, h2.x, h2.y};
-        return f;
+    const int lrow = 8 * lg + (lq >> 2);                 // this lane's row inside a 32-pixel k-step (h = 0)
+    // dY: pairs 5*wc + i, row bit 3 = g & 1 in both halves
+    const int a_row_off = lrow * WF_ROW + 8 * (lq & 3) + 160 * wc;
+    const int a_sw = (lg & 1) * 32;
+    const int a_even = a_row_off + ((wc & 1) ? -a_sw : a_sw);      // pair parity of i = 0 is wc & 1
+    const int a_odd = a_row_off + ((wc & 1) ? a_sw : -a_sw);
+    const int b_row_off = WF_Y_BYTES + (lrow + tap_s) * WF_ROW + 8 * (lq & 3) + 160 * half;
+    auto tr_read = [&](const unsigned char* p) -> uint2 {
+        return __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(lds_ptr_t)const_cast<unsigned char*>(p)));
     };
 
     f32x4 acc[5][5];
@@ -170,25 +164,69 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
     if (nk > 0) {
         issue_loads(0, 0);
         issue_loads(1, 1);
-        // this wave's share of tile 0 landed once at most one tile of its loads (nld of them) is outstanding
+        // this wave's share of stage 0 landed once at most one stage of its loads (nld of them) is outstanding
         if (nld == 4) wait_vmcnt<4>(); else wait_vmcnt<3>();
         __builtin_amdgcn_s_barrier();
         int st = 0;
         for (int kt = 0; kt < nk; ++kt) {
             int st_free = st + WF_STAGES - 1;
             if (st_free >= WF_STAGES) st_free -= WF_STAGES;
-            issue_loads(st_free, kt + WF_STAGES - 1);          // into the stage tile kt-1 used
+            issue_loads(st_free, kt + WF_STAGES - 1);          // into the stage that stage kt-1 used
             const unsigned char* S = smem + st * WF_STAGE_BYTES;
-            u32x4 af[5];
+#pragma unroll 1
+            for (int sub = 0; sub < 2; ++sub) {     // not unrolled: the second k-step's addresses would be kept in registers
+                const unsigned char* Ss = S + sub * (32 * WF_ROW);
+                // column wrap: pixel k of this lane's 8 reduction elements is invalid for tap 0 at column 0 and for
+                // tap 2 at column W-1 (tap 1 never)
+                unsigned km0 = 0xffffffffu, km1 = 0xffffffffu, km2 = 0xffffffffu, km3 = 0xffffffffu;
+                if (tap_s != 1) {
+                    const int k0 = k_begin + kt * WF_BK + sub * 32 + 8 * lg;
+                    int ow = k0 - (int)fastdiv((unsigned)k0, P.mulW, P.shW) * W;
+                    const int bad = tap_s == 0 ? 0 : W - 1;
+                    unsigned bits = 0;
 #pragma unroll
-            for (int i = 0; i < 5; ++i) af[i] = read_frag(S + a_off[i]);
+                    for (int e = 0; e < 8; ++e) {
+                        if (ow != bad) bits |= 1u << e;
+                        if (++ow == W) ow = 0;
+                    }
+                    km0 = ((bits & 1u) ? 0xffffu : 0u) | ((bits & 2u) ? 0xffff0000u : 0u);
+                    km1 = ((bits & 4u) ? 0xffffu : 0u) | ((bits & 8u) ? 0xffff0000u : 0u);
+                    km2 = ((bits & 16u) ? 0xffffu : 0u) | ((bits & 32u) ? 0xffff0000u : 0u);
+                    km3 = ((bits & 64u) ? 0xffffu : 0u) | ((bits & 128u) ? 0xffff0000u : 0u);
+                }
+                u32x4 af[5];
 #pragma unroll
-            for (int j = 0; j < 5; ++j) {
-                const u32x4 bfj = read_frag(S + b_off[j]);
+                for (int i = 0; i < 5; ++i) {
+                    const unsigned char* pa = Ss + ((i & 1) ? a_odd : a_even) + 32 * i;
+                    const uint2 lo = tr_read(pa), hi = tr_read(pa + 4 * WF_ROW);
+                    af[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                }
+                // window rows of this lane for h = 0 and h = 1; the pair swizzle follows the actual LDS row
+                const int wr0 = 32 * sub + lrow + tap_s, wr1 = wr0 + 4;
+                const int s0 = ((wr0 >> 3) & 1) * 32, s1 = ((wr1 >> 3) & 1) * 32;
+                const unsigned char* B0 = Ss + b_row_off;
+                const unsigned char* B1 = B0 + 4 * WF_ROW;
+                // pair 5*half + j: its parity for j = 0 is half & 1
+                const unsigned char* B0e = B0 + ((half & 1) ? -s0 : s0);
+                const unsigned char* B0o = B0 + ((half & 1) ? s0 : -s0);
+                const unsigned char* B1e = B1 + ((half & 1) ? -s1 : s1);
+                const unsigned char* B1o = B1 + ((half & 1) ? s1 : -s1);
+                // the X fragments one ahead of the MFMAs that use them (and no further: registers)
+                uint2 lo = tr_read(B0e), hi = tr_read(B1e);
 #pragma unroll
-                for (int i = 0; i < 5; ++i) Mma<bf16_t, 16>::run(af[i], bfj, acc[i][j]);
+                for (int j = 0; j < 5; ++j) {
+                    const u32x4 bfj = {lo.x & km0, lo.y & km1, hi.x & km2, hi.y & km3};
+                    if (j + 1 < 5) {
+                        lo = tr_read((((j + 1) & 1) ? B0o : B0e) + 32 * (j + 1));
+                        hi = tr_read((((j + 1) & 1) ? B1o : B1e) + 32 * (j + 1));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < 5; ++i) Mma<bf16_t, 16>::run(af[i], bfj, acc[i][j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            if (nld == 4) wait_vmcnt<4>(); else wait_vmcnt<3>();    // tile kt+1 landed (this wave's share)
+            if (nld == 4) wait_vmcnt<4>(); else wait_vmcnt<3>();    // stage kt+1 landed (this wave's share)
             __builtin_amdgcn_s_barrier();                         // ... everyone's; and stage st is free again
             if (++st == WF_STAGES) st = 0;
         }
