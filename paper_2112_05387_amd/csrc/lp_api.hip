@@ -805,7 +805,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     const Op& o = *ops[base + i];
                     g.p[i] = o.wt;
                     g.p[i].w = resolve(o.r[0], b); g.p[i].wt = resolve(o.r[1], b); g.p[i].block_start = tot;
-                    tot += ((o.wt.Cin + 31) / 32) * ((o.wt.Cout + 31) / 32) * o.wt.RS;
+                    tot += ((o.wt.Cin + 63) / 64) * ((o.wt.Cout + 63) / 64) * o.wt.RS;
                 }
                 g.total_blocks = tot;
                 err = launch_wtrans(g, dt, s);

@@ -454,22 +454,34 @@ __global__ void wtrans_kernel(const WtransGroup g) {
     const WtransProb& P = g.p[pi];
     const T* __restrict__ w = reinterpret_cast<const T*>(P.w);
     T* __restrict__ wt = reinterpret_cast<T*>(P.wt);
-    // 32 x 32 (co, ci) tile of one tap through LDS so that both sides are coalesced
-    __shared__ T tile[32][33];
-    const int tiles_ci = (P.Cin + 31) / 32, tiles_co = (P.Cout + 31) / 32;
+    // 64 x 64 (co, ci) tile of one tap through LDS; both sides move 4 consecutive elements per thread (channel counts
+    // are multiples of 4), so a wave reads and writes whole 128-byte (bf16) or 256-byte (fp32) rows
+    constexpr int TS = 64;
+    __shared__ T tile[TS][TS + 4];
+    const int tiles_ci = (P.Cin + TS - 1) / TS, tiles_co = (P.Cout + TS - 1) / TS;
     int b = blockIdx.x - P.block_start;
     const int tci = b % tiles_ci; b /= tiles_ci;
     const int tco = b % tiles_co;
     const int rs = b / tiles_co;
-    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;   // 256 threads: ty in [0,8)
-    for (int r = ty; r < 32; r += 8) {
-        const int co = tco * 32 + r, ci = tci * 32 + tx;
-        if (co < P.Cout && ci < P.Cin) tile[r][tx] = w[((size_t)co * P.RS + rs) * P.Cin + ci];
+    const int tx = (threadIdx.x % 16) * 4, ty = threadIdx.x / 16;   // 256 threads: 16 column groups x 16 rows
+    struct alignas(4 * sizeof(T)) V4 { T v[4]; };
+    for (int r = ty; r < TS; r += 16) {
+        const int co = tco * TS + r, ci = tci * TS + tx;
+        if (co < P.Cout && ci < P.Cin) {
+            const V4 q = *reinterpret_cast<const V4*>(w + ((size_t)co * P.RS + rs) * P.Cin + ci);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tile[r][tx + e] = q.v[e];
+        }
     }
     __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        const int ci = tci * 32 + r, co = tco * 32 + tx;
-        if (co < P.Cout && ci < P.Cin) wt[((size_t)ci * P.RS + rs) * P.Cout + co] = tile[tx][r];
+    for (int r = ty; r < TS; r += 16) {
+        const int ci = tci * TS + r, co = tco * TS + tx;
+        if (co < P.Cout && ci < P.Cin) {
+            V4 q;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q.v[e] = tile[tx + e][r];
+            *reinterpret_cast<V4*>(wt + ((size_t)ci * P.RS + rs) * P.Cout + co) = q;
+        }
     }
 }
 

@@ -384,14 +384,34 @@ __global__ void maxpool_bwd_kernel(const PoolProb P) {
 // ------------------------------------------------------------------------------------------------
 // head: pooled[n,c] = mean_{hw} feat;  logits = pooled W^T + b
 template <typename T>
-__global__ void avgpool_kernel(const HeadProb P) {
+__global__ void avgpool_kernel(const HeadProb P) {           // one thread per (n, 16-byte channel vector)
+    constexpr int EPV = Vec<T>::N;
+    const int cv = P.C / EPV;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P.N * P.C) return;
-    const int n = i / P.C, c = i % P.C;
-    const T* __restrict__ f = reinterpret_cast<const T*>(P.feat) + (size_t)n * P.HW * P.C + c;
-    float s = 0.f;
-    for (int p = 0; p < P.HW; ++p) s += to_float(f[(size_t)p * P.C]);
-    P.pooled[i] = s / (float)P.HW;
+    if (i >= P.N * cv) return;
+    const int n = i / cv, c0 = (i % cv) * EPV;
+    const T* __restrict__ f = reinterpret_cast<const T*>(P.feat) + (size_t)n * P.HW * P.C + c0;
+    float s[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) s[e] = 0.f;
+    int p = 0;
+    for (; p + 4 <= P.HW; p += 4) {                      // four independent loads in flight
+        float v[4][EPV];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Vec<T>::load(f + (size_t)(p + u) * P.C, v[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) s[e] += v[u][e];
+    }
+    for (; p < P.HW; ++p) {
+        float v[EPV];
+        Vec<T>::load(f + (size_t)p * P.C, v);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) s[e] += v[e];
+    }
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) P.pooled[n * P.C + c0 + e] = s[e] / (float)P.HW;
 }
 __global__ void fc_fwd_kernel(const HeadProb P) {          // one wave per (n, class)
     const int o = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -403,29 +423,48 @@ __global__ void fc_fwd_kernel(const HeadProb P) {          // one wave per (n, c
     for (int sh = 32; sh > 0; sh >>= 1) s += __shfl_xor(s, sh, 64);
     if (lane == 0) P.logits[o] = s + P.b[j];
 }
-__global__ void fc_bwd_w_kernel(const HeadProb P) {        // dW[j,c] = sum_n dz[n,j]*pooled[n,c]; db[j] = sum_n dz[n,j]
+// dW[j,c] += sum_n dz[n,j]*pooled[n,c]; db[j] += sum_n dz[n,j].  blockIdx.y takes a slice of 16 samples; the
+// gradient buffer was cleared at the start of the backward pass.
+__global__ void fc_bwd_w_kernel(const HeadProb P) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= P.classes * P.C) return;
     const int j = i / P.C, c = i % P.C;
+    const int n0 = blockIdx.y * 16, n1 = min(P.N, n0 + 16);
     float s = 0.f, sb = 0.f;
-    for (int n = 0; n < P.N; ++n) {
+#pragma unroll 16
+    for (int n = n0; n < n1; ++n) {
         const float d = P.dlogits[n * P.classes + j];
         s += d * P.pooled[n * P.C + c];
         sb += d;
     }
-    P.dw[i] = s;
-    if (c == 0) P.db[j] = sb;
+    atomicAdd(&P.dw[i], s);
+    if (c == 0) atomicAdd(&P.db[j], sb);
 }
+// dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW: one thread per (n, pixel lane of 8, 16-byte channel vector); it
+// computes its vector once and stores it to every eighth pixel
 template <typename T>
-__global__ void fc_bwd_x_kernel(const HeadProb P) {        // dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P.N * P.C) return;
-    const int n = i / P.C, c = i % P.C;
-    float s = 0.f;
-    for (int j = 0; j < P.classes; ++j) s += P.dlogits[n * P.classes + j] * P.w[(size_t)j * P.C + c];
-    const T v = from_float<T>(s / (float)P.HW);
-    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * P.C + c;
-    for (int p = 0; p < P.HW; ++p) d[(size_t)p * P.C] = v;
+__global__ void fc_bwd_x_kernel(const HeadProb P) {
+    constexpr int EPV = Vec<T>::N, PL = 8;
+    const int cv = P.C / EPV;
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (unsigned)(P.N * PL * cv)) return;
+    const int c0 = (int)(i % (unsigned)cv) * EPV;
+    const int pl = (int)(i / (unsigned)cv) % PL;
+    const int n = (int)(i / (unsigned)(PL * cv));
+    float s[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) s[e] = 0.f;
+    for (int j = 0; j < P.classes; ++j) {
+        const float d = P.dlogits[n * P.classes + j];
+        const float* __restrict__ wr = P.w + (size_t)j * P.C + c0;
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) s[e] += d * wr[e];
+    }
+    const float inv = 1.f / (float)P.HW;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) s[e] *= inv;
+    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * P.C + c0;
+    for (int p = pl; p < P.HW; p += PL) Vec<T>::store(d + (size_t)p * P.C, s);
 }
 
 // softmax cross-entropy, mini-batch mean; one workgroup per sample
@@ -511,13 +550,16 @@ hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
-    LP_DISPATCH_T(dtype, avgpool_kernel, dim3((p.N * p.C + 255) / 256), dim3(256), s, p);
+    const int epv = dtype == 1 ? 8 : 4;
+    LP_DISPATCH_T(dtype, avgpool_kernel, dim3((p.N * (p.C / epv) + 63) / 64), dim3(64), s, p);
     hipLaunchKernelGGL(fc_fwd_kernel, dim3((p.N * p.classes + 3) / 4), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
-    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256), dim3(256), 0, s, p);
-    LP_DISPATCH_T(dtype, fc_bwd_x_kernel, dim3((p.N * p.C + 255) / 256), dim3(256), s, p);
+    const int epv = dtype == 1 ? 8 : 4;
+    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + 15) / 16), dim3(256), 0, s, p);
+    const size_t nthr = (size_t)p.N * 8 * (p.C / epv);
+    LP_DISPATCH_T(dtype, fc_bwd_x_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), s, p);
     return hipGetLastError();
 }
 hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s) {
