@@ -139,32 +139,45 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
 
     const int nk = ntr * nts * (Cin / BK);
     int tr = 0, ts = 0, ci0 = 0, issued = 0;
-    // one k-tile of direct-to-LDS loads into ring stage `st`; past the end every offset is out of range (zeros)
-    auto issue_loads = [&](int st) {
-        const bool live = issued < nk;
-        const unsigned toff_b = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
-        unsigned char* S = smem + st * STAGE_BYTES + wave * 1024;
-        const int toff_a = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
-        const int tbit = tr * nts + ts;
-#pragma unroll
-        for (int i = 0; i < NSA; ++i) {
-            const unsigned off = (live && ((a_mask[i] >> tbit) & 1u)) ? (unsigned)(a_base[i] + toff_a) : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(S + i * (NW * 1024)), 16, (int)off, 0, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < NSB; ++j) {
-            if (j + 1 < NSB || last_b) {
-                const unsigned off = live ? b_base0 : kOOB;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(S + A_BYTES + j * (NW * 1024)), 16,
-                                                         (int)off, (int)(toff_b + j * b_step), 0, 0);
-            }
-        }
+    // One k-tile of direct-to-LDS loads, one wave-load at a time: a wave that issues a load stalls until the address
+    // unit takes it (about 30 clocks per wave-load with every wave of the CU loading), so the loads are spread
+    // between the MFMAs of the k-tile and the matrix core keeps running on what this and the other wave of the SIMD
+    // issued before.  tile_begin fixes the tap geometry of the tile, issue_one(i) issues wave-load i of it.
+    // Past the end every offset is out of range (zeros).
+    bool t_live = false;
+    unsigned t_offb = 0;
+    int t_offa = 0, t_bit = 0;
+    unsigned char* t_dst = smem;
+    auto tile_begin = [&](int st) {
+        t_live = issued < nk;
+        t_offb = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
+        t_offa = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
+        t_bit = tr * nts + ts;
+        t_dst = smem + st * STAGE_BYTES + wave * 1024;
         ++issued;
         // taps innermost: the shifted reads of one channel slab follow each other and hit the same cache lines
         if (++ts == nts) {
             ts = 0;
             if (++tr == ntr) { tr = 0; ci0 += BK; }
         }
+    };
+    auto issue_one = [&](int i) {
+        if (i < NSA) {
+            const unsigned off = (t_live && ((a_mask[i] >> t_bit) & 1u)) ? (unsigned)(a_base[i] + t_offa) : kOOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(t_dst + i * (NW * 1024)), 16, (int)off, 0, 0, 0);
+        } else if (i < NSA + NSB) {
+            const int j = i - NSA;
+            if (j + 1 < NSB || last_b) {
+                const unsigned off = t_live ? b_base0 : kOOB;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(t_dst + A_BYTES + j * (NW * 1024)), 16,
+                                                         (int)off, (int)(t_offb + j * b_step), 0, 0);
+            }
+        }
+    };
+    auto issue_loads = [&](int st) {
+        tile_begin(st);
+#pragma unroll
+        for (int i = 0; i < NSA + NSB; ++i) issue_one(i);
     };
 
     // ---- fragment addressing: lane l reads tile row (l % 32) and chunk (2*ks + l/32) ^ swizzle(row) ----
@@ -197,39 +210,58 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     __syncthreads();                     // row offsets visible; nothing in flight yet
     if (nk > 0) {
         const int LT = NSA + (last_b ? NSB : NSB - 1);         // loads per k-tile of this wave
-        // Ring of STAGES k-tiles: STAGES-1 tiles of loads are in flight, and the tile issued in iteration kt goes into
-        // the stage that tile kt-1 used (free since the barrier that ended iteration kt-1).
+        // Ring of STAGES k-tiles, all of them filled before the loop.  The barrier of an iteration sits BEFORE the
+        // MFMAs of its last k-step (whose fragments are in registers by then): it says that every wave has read all
+        // of stage st and that tile kt+1 is visible.  Behind it come the first fragments of tile kt+1 and the loads
+        // of tile kt+STAGES into stage st, two per MFMA pair until the tile is issued: they start under the last
+        // k-step of this iteration and end under the first k-steps of the next one.
 #pragma unroll
-        for (int s = 0; s < STAGES - 1; ++s) issue_loads(s);
-        wait_vmcnt_rt((STAGES - 2) * LT);                      // tile 0 landed: all but the STAGES-2 younger tiles
+        for (int s = 0; s < STAGES; ++s) issue_loads(s);
+        wait_vmcnt_rt((STAGES - 1) * LT);                      // tile 0 landed: all but the STAGES-1 younger tiles
         __builtin_amdgcn_s_barrier();
         load_frags(0, 0, 0);
         int st = 0;                      // ring stage of tile kt
-        // Waves w and w+4 share a SIMD.  The first four waves issue their loads before their MFMAs, the last four
-        // after, so that on every SIMD one wave feeds the matrix core while the other does address arithmetic.
-        // (With two stages the loads have only this k-tile's MFMAs to land in: everybody issues first.)
-        const bool early = STAGES == 2 || wave < NW / 2;
+        constexpr int NL = NSA + NSB;    // wave-loads per k-tile
+        static_assert(NL <= 2 * KS * FN, "more loads than slots between the MFMAs");
+        t_live = false;                  // nothing pending before the first barrier of the loop
         for (int kt = 0; kt < nk; ++kt) {
-            int st_free = st + STAGES - 1;
-            if (st_free >= STAGES) st_free -= STAGES;
-            if (early) issue_loads(st_free);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                if (ks + 1 < KS) load_frags(st, ks + 1, (ks + 1) & 1);     // next k-step's fragments behind these MFMAs
+            for (int ks = 0; ks + 1 < KS; ++ks) {
+                load_frags(st, ks + 1, (ks + 1) & 1);          // next k-step's fragments behind these MFMAs
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < FN; ++j) {
 #pragma unroll
                     for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[ks & 1][j], af[ks & 1][i], acc[j][i]);
+                    // slots FN.. of the tile whose issue began under the last k-step of the previous iteration
+                    if (kt > 0) {
+                        issue_one(2 * (FN + ks * FN + j));
+                        issue_one(2 * (FN + ks * FN + j) + 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
-            if (!early) issue_loads(st_free);
-            // tile kt+1 landed (this wave's share); the barrier makes every wave's share visible and frees stage st
-            wait_vmcnt_rt((STAGES - 2) * LT);
+            __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): the last fragments of stage st are in registers
+            wait_vmcnt_rt((STAGES - 2) * LT);                  // tile kt+1 landed (this wave's share)
             __builtin_amdgcn_s_barrier();
-            if (++st == STAGES) st = 0;
-            if (kt + 1 < nk) load_frags(st, 0, 0);
+            int nst = st + 1;
+            if (nst == STAGES) nst = 0;
+            if (kt + 1 < nk) load_frags(nst, 0, 0);
+            tile_begin(st);                                    // tile kt+STAGES into the stage just freed
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[(KS - 1) & 1][j], af[(KS - 1) & 1][i], acc[j][i]);
+                issue_one(2 * j);
+                issue_one(2 * j + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            st = nst;
         }
+        // the last tile_begin's loads that were due under the next iteration: issue what is left (all out of range)
+#pragma unroll
+        for (int i = 2 * FN; i < NL; ++i) issue_one(i);
     }
     wait_vmcnt<0>();                     // the trailing (all out-of-range) loads still write zeros into the ring
     __syncthreads();
