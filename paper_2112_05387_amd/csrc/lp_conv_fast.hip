@@ -213,8 +213,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         // Ring of STAGES k-tiles, all of them filled before the loop.  The barrier of an iteration sits BEFORE the
         // MFMAs of its last k-step (whose fragments are in registers by then): it says that every wave has read all
         // of stage st and that tile kt+1 is visible.  Behind it come the first fragments of tile kt+1 and the loads
-        // of tile kt+STAGES into stage st, two per MFMA pair until the tile is issued: they start under the last
-        // k-step of this iteration and end under the first k-steps of the next one.
+        // of tile kt+STAGES into stage st, spread evenly over the MFMA pairs of one k-tile (the address unit takes
+        // about as long for a tile's loads as the matrix core for its MFMAs): they start under the last k-step of this
+        // iteration and end under the first k-steps of the next one.
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) issue_loads(s);
         wait_vmcnt_rt((STAGES - 1) * LT);                      // tile 0 landed: all but the STAGES-1 younger tiles
@@ -222,7 +223,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         load_frags(0, 0, 0);
         int st = 0;                      // ring stage of tile kt
         constexpr int NL = NSA + NSB;    // wave-loads per k-tile
-        static_assert(NL <= 2 * KS * FN, "more loads than slots between the MFMAs");
+        constexpr int NSLOT = KS * FN;   // MFMA pairs of a k-tile = places to issue a load
+        constexpr int PER = (NL + 2 * FN - 1) / (2 * FN);      // loads per place: the tile is issued within 2*FN places
+        static_assert(NL <= PER * NSLOT, "more loads than places");
         t_live = false;                  // nothing pending before the first barrier of the loop
         for (int kt = 0; kt < nk; ++kt) {
 #pragma unroll
@@ -235,8 +238,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
                     for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[ks & 1][j], af[ks & 1][i], acc[j][i]);
                     // slots FN.. of the tile whose issue began under the last k-step of the previous iteration
                     if (kt > 0) {
-                        issue_one(2 * (FN + ks * FN + j));
-                        issue_one(2 * (FN + ks * FN + j) + 1);
+                        const int slot = FN + ks * FN + j;      // a constant after unrolling
+#pragma unroll
+                        for (int i = slot * PER; i < (slot + 1) * PER; ++i) issue_one(i);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -253,15 +257,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
             for (int j = 0; j < FN; ++j) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i) Mma<bf16_t, 32>::run(bf[(KS - 1) & 1][j], af[(KS - 1) & 1][i], acc[j][i]);
-                issue_one(2 * j);
-                issue_one(2 * j + 1);
+#pragma unroll
+                for (int i = j * PER; i < (j + 1) * PER; ++i) issue_one(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
             st = nst;
         }
         // the last tile_begin's loads that were due under the next iteration: issue what is left (all out of range)
 #pragma unroll
-        for (int i = 2 * FN; i < NL; ++i) issue_one(i);
+        for (int i = FN * PER; i < NL; ++i) issue_one(i);
     }
     wait_vmcnt<0>();                     // the trailing (all out-of-range) loads still write zeros into the ring
     __syncthreads();
