@@ -165,8 +165,11 @@ static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // the wide-layer bf16 kernel applies when a k-tile of 32 channels lies inside one tap and offsets fit 31 bits
 static bool conv_fast_ok(const lp_net* net, const ConvProb& c) {
-    if (net->dtype != LP_BF16 || c.Cin % 32 != 0 || c.Ncol % 160 != 0) return false;
+    if (net->dtype != LP_BF16 || c.Cin % 32 != 0 || c.Ncol % 8 != 0) return false;
     if (c.ntr * c.nts > 32) return false;
+    // output channels are tiled by 160 or 320: worth it when at least three quarters of the last tile are used
+    const int tn = c.Ncol > 160 ? 320 : 160;
+    if (4 * c.Ncol < 3 * ((c.Ncol + tn - 1) / tn) * tn) return false;
     const double in_bytes = (double)c.M / ((double)c.OA * c.OB) * c.IH * c.IW * c.Cin * 2.0;
     const double w_bytes = (double)c.Ncol * c.ldw * 2.0;
     return in_bytes < 2.0e9 && w_bytes < 2.0e9;
@@ -175,7 +178,7 @@ static bool conv_fast_ok(const lp_net* net, const ConvProb& c) {
 // pick the wide-layer configuration of a problem; returns false if the wide-layer kernel does not apply
 static bool pick_fast_cfg(const lp_net* net, const ConvProb& c, int& cfg) {
     if (!conv_fast_ok(net, c)) return false;
-    cfg = (c.Ncol % 320 == 0) ? FAST_256x320 : FAST_512x160;
+    cfg = c.Ncol > 160 ? FAST_256x320 : FAST_512x160;
     return true;
 }
 
@@ -814,18 +817,27 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 ConvGroup g; g.nprob = n; int tot = 0;
                 int cfg = ops[base]->cfg;
                 const bool fast = cfg >= FAST_256x320;
-                if (cfg == FAST_256x320) {
-                    // too few 256x320 tiles for the chip: the four-wave variant with 128x320 tiles, or the two-wave one
-                    long t256 = 0, t128 = 0;
+                if (cfg == FAST_256x320 || cfg == FAST_512x160) {
+                    // Too few full-size tiles for the chip: the four-wave variants (and the two-wave one of the
+                    // 320-wide family).  k-tiles of 64 channels where every problem allows them and the tile fits.
+                    long big = 0, mid = 0;
+                    bool k64 = true;
                     for (int i = 0; i < n; ++i) {
                         const ConvProb& c = ops[base + i]->conv;
-                        t256 += (long)((c.M + 255) / 256) * ((c.Ncol + 319) / 320);
-                        t128 += (long)((c.M + 127) / 128) * ((c.Ncol + 319) / 320);
+                        if (cfg == FAST_256x320) {
+                            big += (long)((c.M + 255) / 256) * ((c.Ncol + 319) / 320);
+                            mid += (long)((c.M + 127) / 128) * ((c.Ncol + 319) / 320);
+                        } else {
+                            big += (long)((c.M + 511) / 512) * ((c.Ncol + 159) / 160);
+                        }
+                        k64 = k64 && (c.Cin % 64 == 0);
                     }
-                    if (t256 < 200) cfg = t128 < 200 ? FAST_128x160 : FAST_128x320;
-                    bool k64 = true;                  // k-tiles of 64 channels where every problem allows them
-                    for (int i = 0; i < n; ++i) k64 = k64 && (ops[base + i]->conv.Cin % 64 == 0);
-                    if (k64) cfg = cfg == FAST_256x320 ? FAST64_256x320 : cfg == FAST_128x320 ? FAST64_128x320 : FAST64_128x160;
+                    if (cfg == FAST_256x320) {
+                        if (big < 200) cfg = mid < 200 ? FAST_128x160 : FAST_128x320;
+                        if (k64) cfg = cfg == FAST_256x320 ? FAST64_256x320 : cfg == FAST_128x320 ? FAST64_128x320 : FAST64_128x160;
+                    } else if (big < 200) {
+                        cfg = k64 ? FAST64_256x160 : FAST_256x160;
+                    }
                 }
                 if (used_cfg) *used_cfg = cfg;
                 const CfgInfo ci = fast ? conv_fast_cfg_info(cfg) : conv_cfg_info(cfg, dt);

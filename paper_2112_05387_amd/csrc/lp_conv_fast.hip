@@ -391,6 +391,8 @@ CfgInfo conv_fast_cfg_info(int cfg) {
         case FAST64_256x320: return {256, 320, 64};
         case FAST64_128x320: return {128, 320, 64};
         case FAST64_128x160: return {128, 160, 64};
+        case FAST_256x160: return {256, 160, 32};
+        case FAST64_256x160: return {256, 160, 64};
         default: return {256, 320, 32};
     }
 }
@@ -405,6 +407,8 @@ hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s) {
         case FAST64_256x320: return fast_launch<4, 2, 2, 64>(g, s);
         case FAST64_128x320: return fast_launch<2, 2, 2, 64>(g, s);
         case FAST64_128x160: return fast_launch<2, 1, 2, 64>(g, s);
+        case FAST_256x160: return fast_launch<4, 1, 4, 32>(g, s);
+        case FAST64_256x160: return fast_launch<4, 1, 2, 64>(g, s);
         default: return hipErrorInvalidValue;
     }
 }

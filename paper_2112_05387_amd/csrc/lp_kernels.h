@@ -127,6 +127,7 @@ enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160, CFG_COUNT,
                FAST_256x320 = 8, FAST_512x160 = 9,     // bf16 wide-layer kernel (lp_conv_fast.hip)
                FAST_128x320 = 10, FAST_128x160 = 11,   // ... its four- and two-wave variants, chosen per launch
                FAST64_256x320 = 12, FAST64_128x320 = 13, FAST64_128x160 = 14,   // ... with k-tiles of 64 channels
+               FAST_256x160 = 15, FAST64_256x160 = 16,  // four-wave variants of the 160-wide family
                WGRAD_FAST = 8 };                       // bf16 wide-layer filter-gradient kernel (lp_wgrad_fast.hip)
 struct CfgInfo { int BM, BN, BK; };
 CfgInfo conv_cfg_info(int cfg, int dtype);
