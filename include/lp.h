@@ -149,6 +149,17 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
 lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const* lam,
                                   const void* const* y, const void* const* x_next, float step);
 
+/* Correction of the auxiliary variables that follows the adjoint recursion in Sec. 4.1 (the update of lambda_k,
+ * 1 <= k <= K-1): one gradient step of the relaxed objective with respect to x_k,
+ *     x[k] <- x[k] - eta * ( scale*(rho*(x[k] - y_prev[k-1]) - lam_prev[k-1]) + dx[k] ),
+ * where y_prev[k-1] = F_{k-1}(x_{k-1}) (K-1 entries, as y of lp_module_forward), dx[k] is the input gradient
+ * lp_module_backward wrote (K entries, entry 0 ignored), lam_prev[k-1] the multiplier of that interface
+ * (lam_prev == NULL or an entry NULL: penalty method), scale the loss_scale of lp_local_loss_grad.
+ * x: K entries, entry 0 ignored, a NULL entry skips that variable; updated in place.  All tensors device
+ * memory in the storage type, 16-byte aligned.  Errors: LP_ERR_INVALID_ARG; LP_ERR_HIP if a launch fails. */
+lp_status lp_aux_variable_update(struct lp_net* net, void* stream, void* const* x, const void* const* y_prev,
+                                 const void* const* dx, const void* const* lam_prev, float rho, float scale, float eta);
+
 /* Flat NHWC offset read by element (m, q) of the implicit-GEMM operand of a forward convolution as the
  * device kernels compute it (m = output pixel index, q = (r*S+s)*Cin+ci), -1 in the padding.  Evaluated on
  * the device for `count` (m,q) pairs; out: int64 [count] device.  For bit-exact address checks. */

@@ -327,6 +327,21 @@ def multiplier_update(lam, y, x_next, step):
     return _c64(lam) + step * (_c64(y) - _c64(x_next))
 
 
+def aux_variable_update(x, y_prev, dx, lam_prev, rho, eta, scale=1.0):
+    """Correction of the auxiliary variable x_k, 1 <= k <= K-1 (Sec. 4.1, the update of lambda_k that follows the
+    adjoint recursion): a gradient step on the relaxed objective with respect to x_k.  x_k enters the term of
+    interface k-1, scale*(rho/2*|y_{k-1} - x_k|^2 + <lam_{k-1}, y_{k-1} - x_k>), whose derivative is
+    scale*(rho*(x_k - y_{k-1}) - lam_{k-1}), and the local loss of module k, whose derivative dx_k the
+    module-local backward pass returns:
+        x_k <- x_k - eta * ( scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k ).
+    lam_prev=None: penalty method."""
+    x = _c64(x)
+    g = rho * (x - _c64(y_prev))
+    if lam_prev is not None:
+        g = g - _c64(lam_prev)
+    return x - eta * (scale * g + _c64(dx))
+
+
 def auxnet_forward(a: AuxDesc, image, params, eps=1e-5, q=None):
     """x = [ReLU](BN(conv3x3_stride(image)))."""
     out, _ = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]),

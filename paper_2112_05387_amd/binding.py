@@ -13,7 +13,8 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
-           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_debug_im2col_offsets",
+           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update",
+           "lp_debug_im2col_offsets",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
@@ -74,6 +75,7 @@ def lib():
                                          c_void_p, c_void_p, vpp, c_void_p]
         L.lp_module_backward.argtypes = [c_void_p, c_void_p, c_uint32, vpp, c_void_p, vpp, vpp, vpp]
         L.lp_al_multiplier_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, c_float]
+        L.lp_aux_variable_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
         L.lp_debug_im2col_offsets.argtypes = [c_void_p] + [c_int] * 7 + [c_void_p, c_void_p, c_void_p, c_int]
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
         L.lp_profile_enable.argtypes = [c_void_p, c_int]
@@ -182,6 +184,11 @@ def lp_local_loss_grad(net, stream, module_mask, y, x_next, lam, rho, loss_scale
 def lp_module_backward(net, stream, module_mask, dy, dlogits, params, dparams, dx):
     _check(lib().lp_module_backward(net, stream, module_mask, _ptr_array(dy), dlogits, _ptr_array(params),
                                     _ptr_array(dparams), _ptr_array(dx)))
+
+
+def lp_aux_variable_update(net, stream, x, y_prev, dx, lam_prev, rho, scale, eta):
+    _check(lib().lp_aux_variable_update(net, stream, _ptr_array(x), _ptr_array(y_prev), _ptr_array(dx),
+                                        None if lam_prev is None else _ptr_array(lam_prev), float(rho), float(scale), float(eta)))
 
 
 def lp_al_multiplier_update(net, stream, lam, y, x_next, step):

@@ -1297,6 +1297,37 @@ lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const*
     return LP_OK;
 }
 
+lp_status lp_aux_variable_update(struct lp_net* net, void* stream, void* const* x, const void* const* y_prev,
+                                 const void* const* dx, const void* const* lam_prev, float rho, float scale, float eta) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!x || !y_prev || !dx) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    AuxVarGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = rho; g.scale = scale; g.eta = eta;
+    hipError_t err = hipSuccess;
+    for (int k = 1; k < net->K; ++k) {
+        if (!x[k]) continue;
+        if (!y_prev[k - 1] || !dx[k]) return fail(LP_ERR_INVALID_ARG, "y_prev[%d] or dx[%d] is NULL", k - 1, k);
+        const void* lam = lam_prev ? lam_prev[k - 1] : nullptr;
+        if (misaligned(x[k]) || misaligned(y_prev[k - 1]) || misaligned(dx[k]) || misaligned(lam))
+            return fail(LP_ERR_INVALID_ARG, "interface tensor %d is not 16-byte aligned", k);
+        const ModulePlan& m = net->mods[k];
+        AuxVarProb& p = g.p[g.nprob];
+        p.x = x[k]; p.yprev = y_prev[k - 1]; p.dx = dx[k]; p.lam = lam;
+        p.numel = (size_t)m.d.N * m.d.H * m.d.W * m.d.C;
+        p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
+        if (++g.nprob == kMaxGroup) {
+            err = launch_auxvar(g, net->dtype, (hipStream_t)stream);
+            if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+            g.nprob = 0; g.total_blocks = 0;
+        }
+    }
+    if (g.nprob) {
+        err = launch_auxvar(g, net->dtype, (hipStream_t)stream);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    }
+    return LP_OK;
+}
+
 lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, int S, int stride, int pad,
                                   const int64_t* m, const int64_t* q, int64_t* out, int count) {
     if (!m || !q || !out || count < 0) return fail(LP_ERR_INVALID_ARG, "NULL argument or negative count");

@@ -323,6 +323,34 @@ __global__ __launch_bounds__(kElemBlock) void mult_kernel(const MultGroup g) {
     }
 }
 
+// correction of the auxiliary variables: one gradient step of the relaxed objective with respect to x_k
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void auxvar_kernel(const AuxVarGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    const AuxVarProb& P = g.p[find_problem(g, blockIdx.x)];
+    T* __restrict__ x = reinterpret_cast<T*>(P.x);
+    const T* __restrict__ yp = reinterpret_cast<const T*>(P.yprev);
+    const T* __restrict__ dx = reinterpret_cast<const T*>(P.dx);
+    const T* __restrict__ lam = reinterpret_cast<const T*>(P.lam);
+    const size_t nvec = P.numel / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        float a[EPV], b[EPV], d[EPV], l[EPV];
+        Vec<T>::load(x + v * EPV, a);
+        Vec<T>::load(yp + v * EPV, b);
+        Vec<T>::load(dx + v * EPV, d);
+        if (lam) Vec<T>::load(lam + v * EPV, l);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) {
+            const float gr = g.rho * (a[e] - b[e]) - (lam ? l[e] : 0.f);
+            a[e] -= g.eta * (g.scale * gr + d[e]);
+        }
+        Vec<T>::store(x + v * EPV, a);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // max pooling (first maximum in row-major window order wins)
 template <typename T>
@@ -532,6 +560,11 @@ hipError_t launch_fill(const FillGroup& g, hipStream_t s) {
 hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     LP_DISPATCH_T(dtype, loss_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_auxvar(const AuxVarGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, auxvar_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
     return hipGetLastError();
 }
 hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s) {

@@ -155,6 +155,13 @@ class LocalStep:
     def al_multiplier_update(self, step):
         B.lp_al_multiplier_update(self.net, self._stream(), self._p(self.lam), self._p(self.y), self._p(self.x[1:]), step)
 
+    def aux_variable_update(self, rho, scale, eta):
+        """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) for k = 1..K-1 (in place)."""
+        x = [None] + [t.data_ptr() for t in self.x[1:]]
+        dx = [None] + [t.data_ptr() for t in self.dx[1:]]
+        B.lp_aux_variable_update(self.net, self._stream(), x, self._p(self.y), dx,
+                                 None if self.lam is None else self._p(self.lam), rho, scale, eta)
+
     def step(self, rho, scale=1.0, mult_step=None, with_aux=False):
         """One synchronous local step of all K modules."""
         if with_aux:

@@ -73,6 +73,39 @@ def test_wrn_reduced_batch():
     compare_step(wl.make_config("wrn28_10", batch=2))
 
 
+@pytest.mark.parametrize("dtype,al", [("f32", True), ("f32", False), ("bf16", True)])
+def test_aux_variable_update(dtype, al):
+    """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) on seeded tensors, element by element
+    (ragged size: the 6x6 mini network)."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err, store
+    net = gpu_mini_basic(dtype=dtype)
+    rho, scale, eta = 1.5, 0.5, 0.3
+    say("case aux_variable_update", dtype, "AL" if al else "penalty")
+    ls = LocalStep(net)
+    try:
+        xs = [store(net, wl.normal(31, f"x{k}", s)) for k, s in enumerate(ls.x_shapes)]
+        ys = [store(net, wl.normal(31, f"y{k}", s)) for k, s in enumerate(ls.y_shapes)]
+        dxs = [store(net, wl.normal(31, f"dx{k}", s, 0.3)) for k, s in enumerate(ls.x_shapes)]
+        lams = [store(net, wl.normal(31, f"lam{k}", s, 0.2)) for k, s in enumerate(ls.y_shapes)] if al else None
+        for k in range(net.K):
+            ls.set_x(k, xs[k])
+            ls.dx[k].copy_(ls.to_dev(dxs[k]))
+        for k in range(net.K - 1):
+            ls.y[k].copy_(ls.to_dev(ys[k]))
+        ls.set_lams(lams)
+        ls.aux_variable_update(rho, scale, eta)
+        torch.cuda.synchronize()
+        tol = 1e-6 if dtype == "f32" else 4e-3          # fp32: a few roundings; bf16: one storage rounding of the result
+        assert np.array_equal(ls.to_host(ls.x[0]), xs[0])            # x_0 is the mini-batch: untouched
+        for k in range(1, net.K):
+            want = lpref.aux_variable_update(xs[k], ys[k - 1], dxs[k], None if lams is None else lams[k - 1], rho, eta, scale)
+            assert rel_err(ls.to_host(ls.x[k]), want) <= tol, (k, rel_err(ls.to_host(ls.x[k]), want))
+    finally:
+        ls.close()
+
+
 def test_vanish_invariant_on_device():
     """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
     and dx of modules 0..K-2 are exactly zero."""

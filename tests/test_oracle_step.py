@@ -205,3 +205,36 @@ def test_storage_rounding_hook():
     r = np.random.default_rng(0).standard_normal(10000) * 10
     assert np.max(np.abs(wl.round_bf16(r) - r) / np.abs(r)) <= 2.0 ** -8
     np.testing.assert_array_equal(wl.round_bf16(wl.round_bf16(r)), wl.round_bf16(r))
+
+
+def test_aux_variable_update_is_a_gradient_step_of_the_relaxed_objective():
+    """(x_k - x_k_new)/eta equals the central-difference gradient of the whole relaxed objective
+    sum_k loss_k with respect to x_k (x_k appears in the terms of interface k-1 and of module k), and the two
+    fixed-point cases: consistent variables with zero multipliers and zero dx do not move; the penalty-only
+    step pulls x_k towards F_{k-1}(x_{k-1}) by the factor eta*scale*rho."""
+    net = mini_basic()
+    net.rho, net.al, net.lam_sigma = 1.7, True, 0.4
+    inp = step_inputs(net, lpref)
+    scale, eta, h = 0.6, 0.05, 1e-6
+    rng = np.random.default_rng(3)
+    out = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], scale)
+
+    def objective(xs):
+        return sum(_local_loss(net, k, xs[k], inp["params"][k], xs[k + 1] if k < net.K - 1 else None,
+                               inp["lams"][k] if k < net.K - 1 else None, inp["labels"], scale) for k in range(net.K))
+
+    for k in range(1, net.K):
+        new = lpref.aux_variable_update(inp["xs"][k], out["y"][k - 1], out["dx"][k], inp["lams"][k - 1], net.rho, eta, scale)
+        grad = (inp["xs"][k] - new) / eta
+        for _ in range(3):
+            d = rng.standard_normal(inp["xs"][k].shape)
+            xp, xm = list(inp["xs"]), list(inp["xs"])
+            xp[k], xm[k] = inp["xs"][k] + h * d, inp["xs"][k] - h * d
+            fd = (objective(xp) - objective(xm)) / (2 * h)
+            an = float(np.sum(grad * d))
+            assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, fd, an)
+    x = rng.standard_normal((2, 3, 3, 4))
+    assert np.array_equal(lpref.aux_variable_update(x, x, np.zeros_like(x), np.zeros_like(x), 2.0, 0.1), x)
+    y = rng.standard_normal(x.shape)
+    got = lpref.aux_variable_update(x, y, np.zeros_like(x), None, 2.0, 0.1, 0.5)
+    np.testing.assert_allclose(got - y, (1 - 0.1 * 0.5 * 2.0) * (x - y), rtol=1e-13)
