@@ -116,6 +116,18 @@ lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes);
 lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
                             const void* const* aux_params, void* const* x_out);
 
+/* Gradient of the AuxNet distillation objective of Sec. 4.2 (theta_{k-1} <- argmin |x_k - AuxNet_{k-1}(x_0; theta)|^2,
+ * one descent step per iteration; the step itself is the caller's).  For every j with daux_params[j] != NULL:
+ *     loss[j] = loss_scale * sum (AuxNet_j(image) - x_target[j])^2,   daux_params[j] = d loss[j] / d theta_j,
+ * back-propagated through [ReLU,] batch norm (batch statistics) and the convolution.  daux_params[j]: fp32
+ * gradient buffer of AuxNet j (second size of lp_net_param_bytes(net, 1, j, ...), tensor table as the
+ * parameters'), overwritten.  x_target[j]: K-1 device tensors shaped like x_{j+1}, storage type.  loss: K-1 device
+ * floats, entries j overwritten.  Uses the pre-BN output and statistics lp_auxnet_forward saved in the workspace:
+ * LP_ERR_STATE if lp_auxnet_forward has not run since the workspace was set (or the net has no AuxNet); image and
+ * aux_params must be the ones of that call.  Errors: LP_ERR_INVALID_ARG, LP_ERR_WORKSPACE, LP_ERR_HIP. */
+lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                                 const void* const* x_target, float loss_scale, float* loss, float* const* daux_params);
+
 /* Decoupled forward pass of the selected modules (feature-flow equation of Sec. 4.1):
  * X = x_k; X <- skip(X) + F(X, W) for every block; y[k] = F_k(x_k) for k < K-1; the last module writes
  * logits [N, n_classes] (fp32).  Saves what the backward pass needs in the workspace. */

@@ -349,6 +349,21 @@ def auxnet_forward(a: AuxDesc, image, params, eps=1e-5, q=None):
     return out if q is None else q(out)
 
 
+def auxnet_distill_grad(a: AuxDesc, image, params, target, eps=1e-5, scale=1.0, q=None):
+    """Distillation objective of an AuxNet (Sec. 4.2: theta <- argmin |x_k - AuxNet(x_0; theta)|^2, one descent step
+    per iteration; the step is the caller's):  loss = scale * sum (AuxNet(image) - target)^2  and its gradient with
+    respect to theta = (filter, gamma, beta), back-propagated through [ReLU,] BN (batch statistics) and the conv.
+    Returns (loss, [dW, dgamma, dbeta])."""
+    qq = q or _id
+    out, cache = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]), a.stride, 1, a.relu, eps, q)
+    out = qq(out)
+    r = out - _c64(target)
+    loss = scale * float(np.sum(r * r))
+    g = qq(2.0 * scale * r)
+    _, grads = _cbr_bwd(g, cache, need_dx=False, q=q)
+    return loss, grads
+
+
 # ----------------------------------------------------------------------------- whole step / serial net
 def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=False, q=None):
     """One synchronous local step of all K modules.

@@ -13,7 +13,7 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
-           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update",
+           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad",
            "lp_debug_im2col_offsets",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
@@ -70,6 +70,7 @@ def lib():
         L.lp_net_workspace_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
         L.lp_net_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
         L.lp_auxnet_forward.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp]
+        L.lp_auxnet_distill_grad.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp, c_float, c_void_p, vpp]
         L.lp_module_forward.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, c_void_p]
         L.lp_local_loss_grad.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, c_float, c_float, c_void_p,
                                          c_void_p, c_void_p, vpp, c_void_p]
@@ -184,6 +185,11 @@ def lp_local_loss_grad(net, stream, module_mask, y, x_next, lam, rho, loss_scale
 def lp_module_backward(net, stream, module_mask, dy, dlogits, params, dparams, dx):
     _check(lib().lp_module_backward(net, stream, module_mask, _ptr_array(dy), dlogits, _ptr_array(params),
                                     _ptr_array(dparams), _ptr_array(dx)))
+
+
+def lp_auxnet_distill_grad(net, stream, image, aux_params, x_target, loss_scale, loss, daux_params):
+    _check(lib().lp_auxnet_distill_grad(net, stream, image, _ptr_array(aux_params), _ptr_array(x_target), float(loss_scale),
+                                        loss, _ptr_array(daux_params)))
 
 
 def lp_aux_variable_update(net, stream, x, y_prev, dx, lam_prev, rho, scale, eta):

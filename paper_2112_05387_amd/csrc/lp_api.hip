@@ -38,7 +38,7 @@ static lp_status fail(lp_status st, const char* fmt, ...) {
 namespace {
 
 enum Space { SP_NONE = 0, SP_WS, SP_X, SP_Y, SP_PARAM, SP_DPARAM, SP_DY, SP_DX, SP_LOGITS, SP_DLOGITS,
-             SP_AUXP, SP_XOUT, SP_IMAGE };
+             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG };
 struct Ref { int space = SP_NONE; int idx = 0; size_t off = 0; };
 static Ref mk(int sp, int idx, size_t off) { Ref r; r.space = sp; r.idx = idx; r.off = off; return r; }
 
@@ -55,6 +55,7 @@ struct Bindings {
     const void* const* auxp = nullptr;
     void* const* xout = nullptr;
     const void* image = nullptr;
+    float* const* auxg = nullptr;
 };
 static void* resolve(const Ref& r, const Bindings& b) {
     switch (r.space) {
@@ -70,6 +71,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
         case SP_AUXP: return (char*)b.auxp[r.idx] + r.off;
         case SP_XOUT: return (char*)b.xout[r.idx] + r.off;
         case SP_IMAGE: return (char*)b.image + r.off;
+        case SP_AUXG: return (char*)b.auxg[r.idx] + r.off;
         default: return nullptr;
     }
 }
@@ -136,7 +138,8 @@ struct AuxPlan {
     Unit u;
     std::vector<lp_tensor_info> tensors;
     size_t param_bytes = 0, grad_bytes = 0;
-    Program fwd;
+    size_t ws_out = 0, ws_g = 0;           // recomputed AuxNet output and the gradient on it (distillation)
+    Program fwd, bwd_a, bwd_b;             // distillation: before / after the loss kernel
 };
 
 }  // namespace
@@ -151,6 +154,7 @@ struct lp_net {
     char* ws = nullptr;
     size_t ws_given = 0;
     uint32_t fwd_done = 0;
+    bool aux_fwd_done = false;
     std::vector<const void*> saved_x;
     // optional per-launch timing (hipEvents around every grouped launch)
     bool prof = false;
@@ -691,6 +695,20 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     a.fwd.push_back(Step{B.bn_apply(a.u.N * a.u.Ho * a.u.Wo, a.u.cout, y, mk(SP_XOUT, j, 0), st,
                                     mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), mk(SP_AUXP, j, a.tensors[a.u.t_b].offset),
                                     a.d.relu != 0)});
+    // distillation gradient: recompute the output from the saved pre-BN tensor, (loss kernel), BN backward, filter gradient
+    a.u.ws_red = ws.take(sizeof(double) * 2 * a.u.cout);
+    a.u.ws_dy = ws.take(a.u.out_elems() * net->esz);
+    a.ws_out = ws.take(a.u.out_elems() * net->esz);
+    a.ws_g = ws.take(a.u.out_elems() * net->esz);
+    const int M = a.u.N * a.u.Ho * a.u.Wo;
+    const Ref gam = mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), bet = mk(SP_AUXP, j, a.tensors[a.u.t_b].offset);
+    const Ref red = mk(SP_WS, 0, a.u.ws_red), dyc = mk(SP_WS, 0, a.u.ws_dy), g = mk(SP_WS, 0, a.ws_g);
+    a.bwd_a.push_back(Step{B.fill(red, sizeof(double) * 2 * a.u.cout), B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)});
+    a.bwd_a.push_back(Step{B.bn_apply(M, a.u.cout, y, mk(SP_WS, 0, a.ws_out), st, gam, bet, a.d.relu != 0)});
+    const Ref dgam = mk(SP_AUXG, j, a.tensors[a.u.t_g].grad_offset), dbet = mk(SP_AUXG, j, a.tensors[a.u.t_b].grad_offset);
+    a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
+    a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
+    a.bwd_b.push_back(Step{B.wgrad(a.u, mk(SP_IMAGE, 0, 0), dyc, mk(SP_AUXG, j, a.tensors[a.u.t_w].grad_offset))});
     return LP_OK;
 }
 
@@ -1135,7 +1153,7 @@ lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes) 
     if (!net || !dev_ptr) return fail(LP_ERR_INVALID_ARG, "NULL argument");
     if (reinterpret_cast<uintptr_t>(dev_ptr) & 255u) return fail(LP_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
     if (bytes < net->ws_bytes) return fail(LP_ERR_WORKSPACE, "workspace of %zu bytes, %zu needed", bytes, net->ws_bytes);
-    net->ws = (char*)dev_ptr; net->ws_given = bytes; net->fwd_done = 0;
+    net->ws = (char*)dev_ptr; net->ws_given = bytes; net->fwd_done = 0; net->aux_fwd_done = false;
     return LP_OK;
 }
 
@@ -1163,7 +1181,48 @@ lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
         progs.push_back(&net->aux[j].fwd);
     }
     Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.xout = x_out;
-    return run_programs(net, progs, b, (hipStream_t)stream);
+    st = run_programs(net, progs, b, (hipStream_t)stream);
+    if (st == LP_OK) net->aux_fwd_done = true;
+    return st;
+}
+
+lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                                 const void* const* x_target, float loss_scale, float* loss, float* const* daux_params) {
+    lp_status st = check_common(net, 0, false);
+    if (st != LP_OK) return st;
+    if (net->aux.empty()) return fail(LP_ERR_STATE, "the net was created without AuxNet descriptors");
+    if (!net->aux_fwd_done) return fail(LP_ERR_STATE, "lp_auxnet_forward has not run: no saved AuxNet activations");
+    if (!image || !aux_params || !x_target || !loss || !daux_params) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (misaligned(image)) return fail(LP_ERR_INVALID_ARG, "image is not 16-byte aligned");
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<const Program*> pa, pb;
+    uint32_t mask = 0;
+    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = 2.f; g.scale = loss_scale;   // rho/2 * r^2 with rho = 2: |r|^2
+    std::vector<LossGroup> groups;
+    for (int j = 0; j < net->K - 1; ++j) {
+        if (!daux_params[j]) continue;
+        if (!aux_params[j] || !x_target[j]) return fail(LP_ERR_INVALID_ARG, "aux_params[%d] or x_target[%d] is NULL", j, j);
+        if (misaligned(aux_params[j]) || misaligned(x_target[j]) || misaligned(daux_params[j]))
+            return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
+        const AuxPlan& a = net->aux[j];
+        pa.push_back(&a.bwd_a); pb.push_back(&a.bwd_b);
+        mask |= 1u << j;
+        LossProb& p = g.p[g.nprob];
+        p.y = net->ws + a.ws_out; p.xn = x_target[j]; p.lam = nullptr; p.dy = net->ws + a.ws_g; p.loss = loss + j;
+        p.numel = a.u.out_elems();
+        p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
+        if (++g.nprob == kMaxGroup) { groups.push_back(g); g.nprob = 0; g.total_blocks = 0; }
+    }
+    if (g.nprob) groups.push_back(g);
+    if (!mask) return LP_OK;
+    Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.auxg = daux_params;
+    st = run_programs(net, pa, b, s);
+    if (st != LP_OK) return st;
+    hipError_t err = launch_zero_selected(loss, mask, net->K - 1, s);
+    for (size_t i = 0; i < groups.size() && err == hipSuccess; ++i) err = launch_loss(groups[i], net->dtype, s);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    return run_programs(net, pb, b, s);
 }
 
 lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* x,

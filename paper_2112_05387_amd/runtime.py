@@ -45,10 +45,12 @@ class LocalStep:
             pb, gb = B.lp_net_param_bytes(self.net, 0, k)
             self.params[k] = torch.zeros(pb, dtype=torch.uint8, device=self.dev)
             self.dparams[k] = torch.zeros(gb // 4, dtype=torch.float32, device=self.dev)
-        self.aux_params = []
+        self.aux_params, self.daux_params = [], []
         for j in range(len(self.aux_tables)):
-            pb, _ = B.lp_net_param_bytes(self.net, 1, j)
+            pb, gb = B.lp_net_param_bytes(self.net, 1, j)
             self.aux_params.append(torch.zeros(pb, dtype=torch.uint8, device=self.dev))
+            self.daux_params.append(torch.zeros(gb // 4, dtype=torch.float32, device=self.dev))
+        self.aux_loss = torch.zeros((max(self.K - 1, 1),), dtype=torch.float32, device=self.dev)
         self.x = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.x_shapes]
         self.y = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.y_shapes]
         self.dy = [torch.zeros(s, dtype=self.tdtype, device=self.dev) for s in self.y_shapes]
@@ -93,6 +95,14 @@ class LocalStep:
 
     def set_aux_params(self, j, tensors):
         self._pack(self.aux_params[j], self.aux_tables[j], tensors)
+
+    def get_aux_grads(self, j):
+        out = []
+        for info in self.aux_tables[j]:
+            o = info.grad_offset // 4
+            shape = tuple(info.dims[i] for i in range(info.ndim))
+            out.append(self.to_host(self.daux_params[j][o:o + int(info.numel)]).reshape(shape))
+        return out
 
     def get_grads(self, k):
         out = []
@@ -154,6 +164,13 @@ class LocalStep:
 
     def al_multiplier_update(self, step):
         B.lp_al_multiplier_update(self.net, self._stream(), self._p(self.lam), self._p(self.y), self._p(self.x[1:]), step)
+
+    def auxnet_distill_grad(self, scale=1.0, image=None, targets=None):
+        """loss_j = scale*|AuxNet_j(image) - x_{j+1}|^2 and its gradient (after auxnet_forward)."""
+        img = self.x[0] if image is None else image
+        tg = self.x[1:] if targets is None else targets
+        B.lp_auxnet_distill_grad(self.net, self._stream(), img.data_ptr(), self._p(self.aux_params), self._p(tg), scale,
+                                 self.aux_loss.data_ptr(), self._p(self.daux_params))
 
     def aux_variable_update(self, rho, scale, eta):
         """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) for k = 1..K-1 (in place)."""

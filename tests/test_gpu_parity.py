@@ -106,6 +106,48 @@ def test_aux_variable_update(dtype, al):
         ls.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_auxnet_distill_grad(dtype):
+    """loss_j = scale*|AuxNet_j(image) - target_j|^2 and d loss_j / d theta_j for every AuxNet of the ResNet-56
+    configuration (strides 1, 2, 4; batch 8), target = seeded perturbation of the oracle's AuxNet output."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err, store
+    net = wl.make_config("resnet56", batch=8)
+    net.dtype = dtype
+    scale = 0.5
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    q = None if dtype == "f32" else wl.round_bf16
+    say("case auxnet_distill_grad", dtype)
+    image = wl.make_image(net)
+    auxp = [wl.make_aux_params(net, j) for j in range(net.K - 1)]
+    ls = LocalStep(net)
+    try:
+        ls.set_x(0, image)
+        targets = []
+        for j in range(net.K - 1):
+            ls.set_aux_params(j, auxp[j])
+            out = lpref.auxnet_forward(net.aux[j], image, auxp[j], net.bn_eps, q)
+            targets.append(store(net, out + wl.normal(41, f"distill{j}", out.shape, 0.5)))
+        ls.auxnet_forward()
+        for j in range(net.K - 1):
+            ls.x[j + 1].copy_(ls.to_dev(targets[j]))        # the corrected auxiliary variables are the targets
+        ls.auxnet_distill_grad(scale)
+        torch.cuda.synchronize()
+        errs = {}
+        for j in range(net.K - 1):
+            loss, grads = lpref.auxnet_distill_grad(net.aux[j], image, auxp[j], targets[j], net.bn_eps, scale, q)
+            errs[f"aux{j}.loss"] = abs(float(ls.aux_loss[j].item()) - loss) / abs(loss)
+            for name, g, r in zip(("dW", "dgamma", "dbeta"), ls.get_aux_grads(j), grads):
+                errs[f"aux{j}.{name}"] = rel_err(g, r)
+        top = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+        say("    worst: " + ", ".join(f"{k}={v:.2e}" for k, v in top))
+        bad = {k: v for k, v in errs.items() if not v <= tol}
+        assert not bad, bad
+    finally:
+        ls.close()
+
+
 def test_vanish_invariant_on_device():
     """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
     and dx of modules 0..K-2 are exactly zero."""

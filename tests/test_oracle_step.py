@@ -238,3 +238,37 @@ def test_aux_variable_update_is_a_gradient_step_of_the_relaxed_objective():
     y = rng.standard_normal(x.shape)
     got = lpref.aux_variable_update(x, y, np.zeros_like(x), None, 2.0, 0.1, 0.5)
     np.testing.assert_allclose(got - y, (1 - 0.1 * 0.5 * 2.0) * (x - y), rtol=1e-13)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_auxnet_distill_grad_finite_differences(relu):
+    """loss = scale*|AuxNet(image) - target|^2 by its definition, and d loss / d(filter, gamma, beta) against central
+    differences (directional and single coordinates); at target = AuxNet(image) loss and gradients vanish."""
+    import copy
+    net = wl.make_config("resnet56", batch=2)
+    a = copy.copy(net.aux[3])           # stride 2, 3 -> 32 channels
+    a.relu = relu
+    img = wl.make_image(net)
+    p = wl.make_aux_params(net, 3)
+    out = lpref.auxnet_forward(a, img, p, net.bn_eps)
+    target = out + wl.normal(5, "distill_target", out.shape, 0.3)
+    scale, h = 0.25, 1e-6
+    loss, grads = lpref.auxnet_distill_grad(a, img, p, target, net.bn_eps, scale)
+    assert abs(loss - scale * np.sum((out - target) ** 2)) <= 1e-12 * abs(loss)
+    f = lambda pp: scale * np.sum((lpref.auxnet_forward(a, img, pp, net.bn_eps) - target) ** 2)
+    rng = np.random.default_rng(11)
+    for i in range(3):
+        assert grads[i].shape == p[i].shape
+        d = rng.standard_normal(p[i].shape)
+        pp, pm = list(p), list(p)
+        pp[i], pm[i] = p[i] + h * d, p[i] - h * d
+        fd = (f(pp) - f(pm)) / (2 * h)
+        an = float(np.sum(grads[i] * d))
+        assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (i, fd, an)
+        j = tuple(rng.integers(0, s) for s in p[i].shape)
+        e = np.zeros_like(p[i]); e[j] = h
+        pp[i], pm[i] = p[i] + e, p[i] - e
+        fd = (f(pp) - f(pm)) / (2 * h)
+        assert abs(fd - grads[i][j]) <= 5e-6 * max(1.0, abs(fd)), (i, j, fd, grads[i][j])
+    loss0, g0 = lpref.auxnet_distill_grad(a, img, p, out, net.bn_eps, scale)
+    assert loss0 == 0.0 and all(np.all(g == 0.0) for g in g0)
