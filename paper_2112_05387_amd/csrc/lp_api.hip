@@ -888,7 +888,8 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 err = ops[base]->cfg == WGRAD_FAST ? launch_wgrad_fast(g, s) : launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_BN_APPLY: {
-                BnApplyGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
+                BnApplyGroup g; g.nprob = n; g.eps = net->eps; g.cmax = 0; int tot = 0;
+                for (int i = 0; i < n; ++i) g.cmax = std::max(g.cmax, ops[base + i]->bna.C);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     BnApplyProb& p = g.p[i]; p = o.bna;
@@ -903,7 +904,8 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             } break;
             case OP_BN_BWD_REDUCE:
             case OP_BN_BWD_APPLY: {
-                BnBwdGroup g; g.nprob = n; g.eps = net->eps; int tot = 0;
+                BnBwdGroup g; g.nprob = n; g.eps = net->eps; g.cmax = 0; int tot = 0;
+                for (int i = 0; i < n; ++i) g.cmax = std::max(g.cmax, ops[base + i]->bnb.C);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     BnBwdProb& p = g.p[i]; p = o.bnb;

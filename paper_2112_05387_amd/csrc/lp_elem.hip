@@ -63,7 +63,9 @@ constexpr int kMaxC = 2048;
 template <typename T>
 __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup g) {
     constexpr int EPV = Vec<T>::N;
-    __shared__ float s_sc[kMaxC], s_sh[kMaxC], s_ssc[kMaxC], s_ssh[kMaxC];
+    // per-channel coefficients: 4 arrays of g.cmax floats (sized by the launch: the LDS footprint limits occupancy)
+    extern __shared__ float s_coef[];
+    float* s_sc = s_coef; float* s_sh = s_sc + g.cmax; float* s_ssc = s_sh + g.cmax; float* s_ssh = s_ssc + g.cmax;
     const BnApplyProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M;
     for (int c = threadIdx.x; c < C; c += kElemBlock) {
@@ -84,6 +86,10 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
     // four vectors per trip, loads first: up to eight independent 16-byte loads in flight per thread
     constexpr int U = 4;
+    // channel vector of this thread's first vector; it advances by kElemBlock (mod cv) from vector to vector, which
+    // avoids a 64-bit remainder per vector
+    const unsigned cstep = (unsigned)kElemBlock % (unsigned)cv;
+    unsigned cidx = (unsigned)((base + threadIdx.x) % (size_t)cv);
     for (int i0 = threadIdx.x; i0 < kElemVecsPerBlock; i0 += U * kElemBlock) {
         float f[U][EPV], sk[U][EPV];
         bool ok[U];
@@ -98,9 +104,11 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            const int c0 = (int)cidx * EPV;
+            cidx += cstep;
+            if (cidx >= (unsigned)cv) cidx -= (unsigned)cv;
             if (!ok[u]) continue;
             const size_t v = base + i0 + u * kElemBlock;
-            const int c0 = (int)(v % cv) * EPV;
             float o[EPV];
 #pragma unroll
             for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[u][e], s_sh[c0 + e]);
@@ -200,7 +208,10 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
 template <typename T>
 __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGroup g) {
     constexpr int EPV = Vec<T>::N;
-    __shared__ float s_sc[kMaxC], s_sh[kMaxC], s_k1[kMaxC], s_k2[kMaxC], s_k3[kMaxC];
+    // per-channel coefficients: 5 arrays of g.cmax floats (sized by the launch: the LDS footprint limits occupancy)
+    extern __shared__ float s_coef[];
+    float* s_sc = s_coef; float* s_sh = s_sc + g.cmax; float* s_k1 = s_sh + g.cmax; float* s_k2 = s_k1 + g.cmax;
+    float* s_k3 = s_k2 + g.cmax;
     const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M;
     const bool first = (int)blockIdx.x == P.block_start;
@@ -225,10 +236,14 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGro
     const size_t nvec = (size_t)M * C / EPV;
     const int cv = C / EPV;
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    const unsigned cstep = (unsigned)kElemBlock % (unsigned)cv;     // channel vector advances by kElemBlock (mod cv)
+    unsigned cidx = (unsigned)((base + threadIdx.x) % (size_t)cv);
     for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
         const size_t v = base + i;
         if (v >= nvec) break;
-        const int c0 = (int)(v % cv) * EPV;
+        const int c0 = (int)cidx * EPV;
+        cidx += cstep;
+        if (cidx >= (unsigned)cv) cidx -= (unsigned)cv;
         float gv[EPV], yv[EPV], o[EPV];
         Vec<T>::load(gp + v * EPV, gv);
         Vec<T>::load(y + v * EPV, yv);
@@ -539,7 +554,9 @@ __global__ void zero_selected_kernel(float* v, uint32_t mask, int n) {
 
 hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
-    LP_DISPATCH_T(dtype, bn_apply_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    const size_t lds = (size_t)4 * g.cmax * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
+    else hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
     return hipGetLastError();
 }
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
@@ -549,7 +566,9 @@ hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
 }
 hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
-    LP_DISPATCH_T(dtype, bn_bwd_apply_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    const size_t lds = (size_t)5 * g.cmax * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL(bn_bwd_apply_kernel<bf16_t>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
+    else hipLaunchKernelGGL(bn_bwd_apply_kernel<float>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
     return hipGetLastError();
 }
 hipError_t launch_fill(const FillGroup& g, hipStream_t s) {

@@ -78,6 +78,7 @@ struct BnApplyProb {
 };
 struct BnApplyGroup {
     int nprob, total_blocks; float eps;
+    int cmax;             // largest channel count of the group (sizes the coefficient arrays in LDS)
     BnApplyProb p[kMaxGroup];
 };
 
@@ -93,6 +94,7 @@ struct BnBwdProb {
 };
 struct BnBwdGroup {
     int nprob, total_blocks; float eps;
+    int cmax;             // largest channel count of the group (sizes the coefficient arrays in LDS)
     BnBwdProb p[kMaxGroup];
 };
 
