@@ -64,8 +64,12 @@ template <typename T>
 __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup g) {
     constexpr int EPV = Vec<T>::N;
     // per-channel coefficients: 4 arrays of g.cmax floats (sized by the launch: the LDS footprint limits occupancy)
-    extern __shared__ float s_coef[];
-    float* s_sc = s_coef; float* s_sh = s_sc + g.cmax; float* s_ssc = s_sh + g.cmax; float* s_ssh = s_ssc + g.cmax;
+    extern __shared__ __attribute__((aligned(16))) float s_coef[];
+    const int cm = 4 * (g.cmax >> 2);      // written as a multiple of 4 so that the arrays are visibly 16-byte aligned
+    float* s_sc = s_coef;
+    float* s_sh = s_coef + cm;
+    float* s_ssc = s_coef + 2 * cm;
+    float* s_ssh = s_coef + 3 * cm;
     const BnApplyProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M;
     for (int c = threadIdx.x; c < C; c += kElemBlock) {
@@ -209,9 +213,13 @@ template <typename T>
 __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGroup g) {
     constexpr int EPV = Vec<T>::N;
     // per-channel coefficients: 5 arrays of g.cmax floats (sized by the launch: the LDS footprint limits occupancy)
-    extern __shared__ float s_coef[];
-    float* s_sc = s_coef; float* s_sh = s_sc + g.cmax; float* s_k1 = s_sh + g.cmax; float* s_k2 = s_k1 + g.cmax;
-    float* s_k3 = s_k2 + g.cmax;
+    extern __shared__ __attribute__((aligned(16))) float s_coef[];
+    const int cm = 4 * (g.cmax >> 2);      // written as a multiple of 4 so that the arrays are visibly 16-byte aligned
+    float* s_sc = s_coef;
+    float* s_sh = s_coef + cm;
+    float* s_k1 = s_coef + 2 * cm;
+    float* s_k2 = s_coef + 3 * cm;
+    float* s_k3 = s_coef + 4 * cm;
     const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M;
     const bool first = (int)blockIdx.x == P.block_start;
@@ -247,11 +255,21 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGro
         float gv[EPV], yv[EPV], o[EPV];
         Vec<T>::load(gp + v * EPV, gv);
         Vec<T>::load(y + v * EPV, yv);
+        // the five coefficient vectors of these EPV channels, as 16-byte LDS reads
+        float sc[EPV], sh[EPV], k1[EPV], k2[EPV], k3[EPV];
+#pragma unroll
+        for (int q4 = 0; q4 < EPV / 4; ++q4) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(s_sc + c0 + 4 * q4), b = *reinterpret_cast<const f32x4*>(s_sh + c0 + 4 * q4);
+            const f32x4 c = *reinterpret_cast<const f32x4*>(s_k1 + c0 + 4 * q4), d = *reinterpret_cast<const f32x4*>(s_k2 + c0 + 4 * q4);
+            const f32x4 f = *reinterpret_cast<const f32x4*>(s_k3 + c0 + 4 * q4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { sc[4 * q4 + e] = a[e]; sh[4 * q4 + e] = b[e]; k1[4 * q4 + e] = c[e]; k2[4 * q4 + e] = d[e]; k3[4 * q4 + e] = f[e]; }
+        }
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
             float gg = gv[e];
-            if (P.relu && !(fmaf(s_sc[c0 + e], yv[e], s_sh[c0 + e]) > 0.f)) gg = 0.f;
-            o[e] = s_k1[c0 + e] * gg - s_k2[c0 + e] * yv[e] + s_k3[c0 + e];
+            if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
+            o[e] = k1[e] * gg - k2[e] * yv[e] + k3[e];
         }
         Vec<T>::store(dy + v * EPV, o);
     }
