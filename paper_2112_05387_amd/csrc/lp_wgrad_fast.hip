@@ -181,18 +181,24 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
                 unsigned km0 = 0xffffffffu, km1 = 0xffffffffu, km2 = 0xffffffffu, km3 = 0xffffffffu;
                 if (tap_s != 1) {
                     const int k0 = k_begin + kt * WF_BK + sub * 32 + 8 * lg;
-                    int ow = k0 - (int)fastdiv((unsigned)k0, P.mulW, P.shW) * W;
+                    const int ow0 = k0 - (int)fastdiv((unsigned)k0, P.mulW, P.shW) * W;
                     const int bad = tap_s == 0 ? 0 : W - 1;
-                    unsigned bits = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        if (ow != bad) bits |= 1u << e;
-                        if (++ow == W) ow = 0;
+                    int e = bad - ow0;                        // first of this lane's 8 elements in the bad column
+                    if (e < 0) e += W;
+                    if (W >= 8) {
+                        // at most one of the 8 is bad: one half of one mask register
+                        const unsigned half = (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                        const int d = e >> 1;
+                        km0 = d == 0 ? half : 0xffffffffu; km1 = d == 1 ? half : 0xffffffffu;
+                        km2 = d == 2 ? half : 0xffffffffu; km3 = d == 3 ? half : 0xffffffffu;
+                    } else {
+                        unsigned bits = 0xffu;
+                        for (; e < 8; e += W) bits &= ~(1u << e);
+                        km0 = ((bits & 1u) ? 0xffffu : 0u) | ((bits & 2u) ? 0xffff0000u : 0u);
+                        km1 = ((bits & 4u) ? 0xffffu : 0u) | ((bits & 8u) ? 0xffff0000u : 0u);
+                        km2 = ((bits & 16u) ? 0xffffu : 0u) | ((bits & 32u) ? 0xffff0000u : 0u);
+                        km3 = ((bits & 64u) ? 0xffffu : 0u) | ((bits & 128u) ? 0xffff0000u : 0u);
                     }
-                    km0 = ((bits & 1u) ? 0xffffu : 0u) | ((bits & 2u) ? 0xffff0000u : 0u);
-                    km1 = ((bits & 4u) ? 0xffffu : 0u) | ((bits & 8u) ? 0xffff0000u : 0u);
-                    km2 = ((bits & 16u) ? 0xffffu : 0u) | ((bits & 32u) ? 0xffff0000u : 0u);
-                    km3 = ((bits & 64u) ? 0xffffu : 0u) | ((bits & 128u) ? 0xffff0000u : 0u);
                 }
                 u32x4 af[5];
 #pragma unroll
