@@ -161,6 +161,19 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
 lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const* lam,
                                   const void* const* y, const void* const* x_next, float step);
 
+/* Parameter update of Sec. 4.1 (W <- W - eta * dW for every tensor of a module, right after the module's adjoint
+ * recursion).  The paper states plain gradient descent; the two usual extensions are off at 0:
+ *     g' = dW + weight_decay * W;   v <- momentum * v + g'  (when momentum != 0);   W <- W - lr * (v or g').
+ * aux = 0: modules (mask bit k, K sets), aux = 1: AuxNet blocks (K-1 sets).  params[k]: packed parameters, updated in
+ * place (bf16 tensors are re-rounded); dparams[k]: fp32 gradients; velocity[k]: fp32, layout of dparams[k], required
+ * (and updated) when momentum != 0, zero it before the first step; master[k]: optional fp32 copy of the parameters with
+ * the layout of dparams[k]: when given, the update is applied to it and params[k] receives the rounded result
+ * (master == NULL or an entry NULL: the stored parameters themselves are read).  Device memory, 16-byte aligned.
+ * Errors: LP_ERR_INVALID_ARG; LP_ERR_HIP if a launch fails. */
+lp_status lp_sgd_update(struct lp_net* net, void* stream, int aux, uint32_t mask, void* const* params,
+                        const float* const* dparams, float* const* velocity, float* const* master, float lr,
+                        float momentum, float weight_decay);
+
 /* Correction of the auxiliary variables that follows the adjoint recursion in Sec. 4.1 (the update of lambda_k,
  * 1 <= k <= K-1): one gradient step of the relaxed objective with respect to x_k,
  *     x[k] <- x[k] - eta * ( scale*(rho*(x[k] - y_prev[k-1]) - lam_prev[k-1]) + dx[k] ),

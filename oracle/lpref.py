@@ -327,6 +327,18 @@ def multiplier_update(lam, y, x_next, step):
     return _c64(lam) + step * (_c64(y) - _c64(x_next))
 
 
+def sgd_update(p, g, lr, v=None, momentum=0.0, weight_decay=0.0):
+    """Parameter update of Sec. 4.1, W <- W - eta * dW, applied right after a module's adjoint recursion.  The paper
+    states plain gradient descent; the two usual extensions are off at 0:  g' = g + weight_decay*W,
+    v <- momentum*v + g' (v starts at 0), W <- W - lr*v.  Returns (W_new, v_new); v_new is None without momentum."""
+    p = _c64(p)
+    gg = _c64(g) + weight_decay * p
+    if momentum != 0.0:
+        v = gg if v is None else momentum * _c64(v) + gg
+        return p - lr * v, v
+    return p - lr * gg, None
+
+
 def aux_variable_update(x, y_prev, dx, lam_prev, rho, eta, scale=1.0):
     """Correction of the auxiliary variable x_k, 1 <= k <= K-1 (Sec. 4.1, the update of lambda_k that follows the
     adjoint recursion): a gradient step on the relaxed objective with respect to x_k.  x_k enters the term of

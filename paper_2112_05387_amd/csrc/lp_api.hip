@@ -1358,6 +1358,52 @@ lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const*
     return LP_OK;
 }
 
+lp_status lp_sgd_update(struct lp_net* net, void* stream, int aux, uint32_t mask, void* const* params,
+                        const float* const* dparams, float* const* velocity, float* const* master, float lr,
+                        float momentum, float weight_decay) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!params || !dparams) return fail(LP_ERR_INVALID_ARG, "params or dparams is NULL");
+    if (momentum != 0.f && !velocity) return fail(LP_ERR_INVALID_ARG, "momentum != 0 needs velocity buffers");
+    if (aux && net->aux.empty()) return fail(LP_ERR_STATE, "the net was created without an AuxNet");
+    const int n = aux ? (int)net->aux.size() : net->K;
+    if (mask == 0 || (n < 32 && (mask >> n) != 0)) return fail(LP_ERR_INVALID_ARG, "mask 0x%x does not fit %d parameter sets", mask, n);
+    SgdGroup g; g.nprob = 0; g.total_blocks = 0; g.lr = lr; g.momentum = momentum; g.wd = weight_decay;
+    hipError_t err = hipSuccess;
+    for (int k = 0; k < n; ++k) {
+        if (!((mask >> k) & 1u)) continue;
+        const std::vector<lp_tensor_info>* t; size_t pb, gb;
+        lp_status st = table_of(net, aux, k, &t, &pb, &gb);
+        if (st != LP_OK) return st;
+        if (!params[k] || !dparams[k]) return fail(LP_ERR_INVALID_ARG, "params[%d] or dparams[%d] is NULL", k, k);
+        float* vel = (momentum != 0.f) ? velocity[k] : nullptr;
+        if (momentum != 0.f && !vel) return fail(LP_ERR_INVALID_ARG, "velocity[%d] is NULL", k);
+        float* mas = master ? master[k] : nullptr;
+        if (misaligned(params[k]) || misaligned(dparams[k]) || misaligned(vel) || misaligned(mas))
+            return fail(LP_ERR_INVALID_ARG, "parameter set %d: a buffer is not 16-byte aligned", k);
+        for (const lp_tensor_info& ti : *t) {
+            SgdProb& p = g.p[g.nprob];
+            p.p = (char*)params[k] + ti.offset; p.lowp = ti.dtype == LP_BF16;
+            p.g = (const float*)((const char*)dparams[k] + ti.grad_offset);
+            p.v = vel ? (float*)((char*)vel + ti.grad_offset) : nullptr;
+            p.master = mas ? (float*)((char*)mas + ti.grad_offset) : nullptr;
+            p.numel = ti.numel;
+            p.block_start = g.total_blocks;
+            p.nblocks = (int)((ti.numel + kSgdElemsPerBlock - 1) / kSgdElemsPerBlock);
+            g.total_blocks += p.nblocks;
+            if (++g.nprob == kMaxGroup) {
+                err = launch_sgd(g, (hipStream_t)stream);
+                if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+                g.nprob = 0; g.total_blocks = 0;
+            }
+        }
+    }
+    if (g.nprob) {
+        err = launch_sgd(g, (hipStream_t)stream);
+        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    }
+    return LP_OK;
+}
+
 lp_status lp_aux_variable_update(struct lp_net* net, void* stream, void* const* x, const void* const* y_prev,
                                  const void* const* dx, const void* const* lam_prev, float rho, float scale, float eta) {
     if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");

@@ -356,6 +356,26 @@ __global__ __launch_bounds__(kElemBlock) void mult_kernel(const MultGroup g) {
     }
 }
 
+// parameter update, one tensor per problem (bf16 or fp32 parameter, fp32 gradient / velocity / master copy)
+__global__ __launch_bounds__(kElemBlock) void sgd_kernel(const SgdGroup g) {
+    const SgdProb& P = g.p[find_problem(g, blockIdx.x)];
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kSgdElemsPerBlock;
+    for (int i = threadIdx.x; i < kSgdElemsPerBlock; i += kElemBlock) {
+        const size_t e = base + i;
+        if (e >= P.numel) break;
+        float w;
+        if (P.master) w = P.master[e];
+        else if (P.lowp) w = bf16_bits_to_float(reinterpret_cast<const unsigned short*>(P.p)[e]);
+        else w = reinterpret_cast<const float*>(P.p)[e];
+        float d = fmaf(g.wd, w, P.g[e]);
+        if (P.v) { d = fmaf(g.momentum, P.v[e], d); P.v[e] = d; }
+        w = fmaf(-g.lr, d, w);
+        if (P.master) P.master[e] = w;
+        if (P.lowp) reinterpret_cast<unsigned short*>(P.p)[e] = float_to_bf16_bits(w);
+        else reinterpret_cast<float*>(P.p)[e] = w;
+    }
+}
+
 // correction of the auxiliary variables: one gradient step of the relaxed objective with respect to x_k
 template <typename T>
 __global__ __launch_bounds__(kElemBlock) void auxvar_kernel(const AuxVarGroup g) {
@@ -597,6 +617,11 @@ hipError_t launch_fill(const FillGroup& g, hipStream_t s) {
 hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     LP_DISPATCH_T(dtype, loss_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_sgd(const SgdGroup& g, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    hipLaunchKernelGGL(sgd_kernel, dim3(g.total_blocks), dim3(kElemBlock), 0, s, g);
     return hipGetLastError();
 }
 hipError_t launch_auxvar(const AuxVarGroup& g, int dtype, hipStream_t s) {

@@ -111,6 +111,9 @@ struct LossGroup { int nprob, total_blocks; float rho, scale; LossProb p[kMaxGro
 // lam += step*(y - x_next)
 struct MultProb { void* lam; const void* y; const void* xn; size_t numel; int block_start, nblocks; };
 struct MultGroup { int nprob, total_blocks; float step; MultProb p[kMaxGroup]; };
+// parameter update of one tensor: g' = g + wd*W; v = mu*v + g' (if v); W -= lr*(v or g'); master (fp32 copy) optional
+struct SgdProb { void* p; const float* g; float* v; float* master; size_t numel; int lowp; int block_start, nblocks; };
+struct SgdGroup { int nprob, total_blocks; float lr, momentum, wd; SgdProb p[kMaxGroup]; };
 // correction of an auxiliary variable: x <- x - eta*(scale*(rho*(x - yprev) - lam) + dx), lam may be NULL
 struct AuxVarProb { void* x; const void* yprev; const void* dx; const void* lam; size_t numel; int block_start, nblocks; };
 struct AuxVarGroup { int nprob, total_blocks; float rho, scale, eta; AuxVarProb p[kMaxGroup]; };
@@ -153,6 +156,8 @@ hipError_t launch_fill(const FillGroup& g, hipStream_t s);
 hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s);
 hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s);
 hipError_t launch_auxvar(const AuxVarGroup& g, int dtype, hipStream_t s);
+hipError_t launch_sgd(const SgdGroup& g, hipStream_t s);
+constexpr int kSgdElemsPerBlock = 4096;
 hipError_t launch_maxpool_fwd(const PoolProb& p, int dtype, hipStream_t s);
 hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s);
 hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s);

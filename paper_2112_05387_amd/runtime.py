@@ -172,6 +172,12 @@ class LocalStep:
         B.lp_auxnet_distill_grad(self.net, self._stream(), img.data_ptr(), self._p(self.aux_params), self._p(tg), scale,
                                  self.aux_loss.data_ptr(), self._p(self.daux_params))
 
+    def sgd_update(self, lr, momentum=0.0, weight_decay=0.0, velocity=None, master=None, mask=None):
+        """W <- W - lr*(dW [+ wd*W, + momentum]) for the modules in `mask` (default all), in place."""
+        B.lp_sgd_update(self.net, self._stream(), 0, self._mask(mask), self._p(self.params), self._p(self.dparams),
+                        None if velocity is None else self._p(velocity), None if master is None else self._p(master),
+                        lr, momentum, weight_decay)
+
     def aux_variable_update(self, rho, scale, eta):
         """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) for k = 1..K-1 (in place)."""
         x = [None] + [t.data_ptr() for t in self.x[1:]]

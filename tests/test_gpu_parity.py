@@ -106,6 +106,73 @@ def test_aux_variable_update(dtype, al):
         ls.close()
 
 
+@pytest.mark.parametrize("dtype,momentum,wd,use_master", [("f32", 0.0, 0.0, False), ("f32", 0.9, 5e-4, False),
+                                                          ("bf16", 0.0, 0.0, False), ("bf16", 0.9, 5e-4, True)])
+def test_sgd_update(dtype, momentum, wd, use_master):
+    """Two parameter updates in a row from seeded gradients, every tensor of every module, element by element
+    (tensor sizes from 4 to a few thousand elements: ragged tails of the 4096-element blocks).  bf16 parameters
+    without a master copy are re-rounded after each update, as the oracle's inputs are."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err
+    net = gpu_mini_basic(dtype=dtype)
+    lr = 0.05
+    say("case sgd_update", dtype, momentum, wd, "master" if use_master else "")
+    ls = LocalStep(net)
+    try:
+        W = [wl.make_params(net, k) for k in range(net.K)]
+        for k in range(net.K):
+            ls.set_params(k, W[k])
+        from paper_2112_05387_amd import binding as B
+        lowp = [[info.dtype == B.LP_BF16 for info in ls.tables[k]] for k in range(net.K)]
+        stored = [[wl.round_bf16(w) if lp else np.asarray(w, np.float32).astype(np.float64) for w, lp in zip(W[k], lowp[k])]
+                  for k in range(net.K)]
+        vel = [torch.zeros_like(d) for d in ls.dparams] if momentum else None
+        master = None
+        if use_master:
+            master = [torch.zeros_like(d) for d in ls.dparams]
+            for k in range(net.K):
+                for info, w in zip(ls.tables[k], W[k]):
+                    o = info.grad_offset // 4
+                    master[k][o:o + int(info.numel)].copy_(torch.from_numpy(np.asarray(w, np.float32).reshape(-1)))
+        cur = [[np.asarray(w, np.float32).astype(np.float64) for w in W[k]] for k in range(net.K)] if use_master else stored
+        v = [[None] * len(W[k]) for k in range(net.K)]
+        for it in range(2):
+            G = [[np.asarray(wl.normal(77 + it, f"g{k}.{i}", np.shape(w), 0.5), np.float32).astype(np.float64)
+                  for i, w in enumerate(W[k])] for k in range(net.K)]
+            for k in range(net.K):
+                for info, g in zip(ls.tables[k], G[k]):
+                    o = info.grad_offset // 4
+                    ls.dparams[k][o:o + int(info.numel)].copy_(torch.from_numpy(g.astype(np.float32).reshape(-1)))
+            ls.sgd_update(lr, momentum, wd, velocity=vel, master=master)
+            torch.cuda.synchronize()
+            for k in range(net.K):
+                for i, info in enumerate(ls.tables[k]):
+                    w_new, v_new = lpref.sgd_update(cur[k][i], G[k][i], lr, v[k][i], momentum, wd)
+                    v[k][i] = v_new
+                    n = int(info.numel)
+                    if info.dtype == B.LP_BF16:
+                        got = ls.params[k][info.offset:info.offset + 2 * n].view(torch.bfloat16)
+                    else:
+                        got = ls.params[k][info.offset:info.offset + 4 * n].view(torch.float32)
+                    got = ls.to_host(got).reshape(np.shape(w_new))
+                    tol = 4e-3 if info.dtype == B.LP_BF16 else 1e-6
+                    assert rel_err(got, w_new) <= tol, (it, k, i, rel_err(got, w_new))
+                    if use_master:
+                        o = info.grad_offset // 4
+                        gm = ls.to_host(master[k][o:o + n]).reshape(np.shape(w_new))
+                        assert rel_err(gm, w_new) <= 1e-6, (it, k, i, "master", rel_err(gm, w_new))
+                        cur[k][i] = w_new
+                    else:
+                        cur[k][i] = got              # the next update starts from the stored (re-rounded) parameters
+                    if momentum:
+                        o = info.grad_offset // 4
+                        gv = ls.to_host(vel[k][o:o + n]).reshape(np.shape(w_new))
+                        assert rel_err(gv, v_new) <= 1e-6, (it, k, i, "velocity", rel_err(gv, v_new))
+    finally:
+        ls.close()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_auxnet_distill_grad(dtype):
     """loss_j = scale*|AuxNet_j(image) - target_j|^2 and d loss_j / d theta_j for every AuxNet of the ResNet-56

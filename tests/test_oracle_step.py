@@ -272,3 +272,33 @@ def test_auxnet_distill_grad_finite_differences(relu):
         assert abs(fd - grads[i][j]) <= 5e-6 * max(1.0, abs(fd)), (i, j, fd, grads[i][j])
     loss0, g0 = lpref.auxnet_distill_grad(a, img, p, out, net.bn_eps, scale)
     assert loss0 == 0.0 and all(np.all(g == 0.0) for g in g0)
+
+
+def test_sgd_update_closed_forms():
+    """Plain descent on f = 1/2 |W|^2 (gradient W) contracts by (1 - lr) per step; weight decay on a zero gradient
+    contracts by (1 - lr*wd); momentum on a constant gradient accumulates the geometric series; and a small enough
+    step on the mini network's local loss decreases it (descent direction)."""
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((3, 4))
+    a = w
+    for _ in range(5):
+        a, v = lpref.sgd_update(a, a, 0.1)
+        assert v is None
+    np.testing.assert_allclose(a, w * 0.9 ** 5, rtol=1e-14)
+    b, _ = lpref.sgd_update(w, np.zeros_like(w), 0.1, weight_decay=0.5)
+    np.testing.assert_allclose(b, w * (1 - 0.05), rtol=1e-14)
+    g = rng.standard_normal(w.shape)
+    c, v = w, None
+    for n in range(1, 5):
+        c, v = lpref.sgd_update(c, g, 0.2, v, momentum=0.5)
+        np.testing.assert_allclose(v, g * (1 - 0.5 ** n) / (1 - 0.5), rtol=1e-14)
+    np.testing.assert_allclose(c, w - 0.2 * g * sum((1 - 0.5 ** n) / 0.5 for n in range(1, 5)), rtol=1e-13)
+    net = mini_basic()
+    inp = step_inputs(net, lpref)
+    out = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], None, 1.0)
+    k = net.K - 1
+    before = _local_loss(net, k, inp["xs"][k], inp["params"][k], None, None, inp["labels"], 1.0)
+    stepped = [lpref.sgd_update(p, g, 1e-3)[0] for p, g in zip(inp["params"][k], out["dparams"][k])]
+    after = _local_loss(net, k, inp["xs"][k], stepped, None, None, inp["labels"], 1.0)
+    gn2 = sum(float(np.sum(g * g)) for g in out["dparams"][k])
+    assert after < before and abs((before - after) - 1e-3 * gn2) <= 0.05 * 1e-3 * gn2
