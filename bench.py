@@ -188,6 +188,18 @@ def main():
         "gpu_ms_per_step_events": gpu_ms / args.steps,
         "roofline": roof,
     }
+    # the parameter update that follows a step (not part of `value`): momentum form, fp32 velocity, timed by events
+    vel = [torch.zeros_like(d) for d in ls.dparams]
+    ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
+    e1.record()
+    torch.cuda.synchronize()
+    sgd_ms = e0.elapsed_time(e1) / 10
+    sgd_bytes = sum(int(t.numel) * ((4 if t.dtype == B.LP_BF16 else 8) + 12) for tab in ls.tables for t in tab)
+    out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
     ls.close()
     if args.calibrate_copy:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")

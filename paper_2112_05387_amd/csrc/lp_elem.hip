@@ -356,23 +356,53 @@ __global__ __launch_bounds__(kElemBlock) void mult_kernel(const MultGroup g) {
     }
 }
 
-// parameter update, one tensor per problem (bf16 or fp32 parameter, fp32 gradient / velocity / master copy)
+// parameter update, one tensor per problem (bf16 or fp32 parameter, fp32 gradient / velocity / master copy).
+// Every tensor starts on a 16-byte boundary of its buffer: four elements per lane and access, scalar tail.
+__device__ __forceinline__ float sgd_elem(const SgdGroup& g, float w, float grad, float* v) {
+    float d = fmaf(g.wd, w, grad);
+    if (v) { d = fmaf(g.momentum, *v, d); *v = d; }
+    return fmaf(-g.lr, d, w);
+}
 __global__ __launch_bounds__(kElemBlock) void sgd_kernel(const SgdGroup g) {
     const SgdProb& P = g.p[find_problem(g, blockIdx.x)];
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kSgdElemsPerBlock;
-    for (int i = threadIdx.x; i < kSgdElemsPerBlock; i += kElemBlock) {
-        const size_t e = base + i;
-        if (e >= P.numel) break;
-        float w;
-        if (P.master) w = P.master[e];
-        else if (P.lowp) w = bf16_bits_to_float(reinterpret_cast<const unsigned short*>(P.p)[e]);
-        else w = reinterpret_cast<const float*>(P.p)[e];
-        float d = fmaf(g.wd, w, P.g[e]);
-        if (P.v) { d = fmaf(g.momentum, P.v[e], d); P.v[e] = d; }
-        w = fmaf(-g.lr, d, w);
-        if (P.master) P.master[e] = w;
-        if (P.lowp) reinterpret_cast<unsigned short*>(P.p)[e] = float_to_bf16_bits(w);
-        else reinterpret_cast<float*>(P.p)[e] = w;
+    unsigned short* pl = reinterpret_cast<unsigned short*>(P.p);
+    float* pf = reinterpret_cast<float*>(P.p);
+#pragma unroll
+    for (int i = 0; i < kSgdElemsPerBlock / (4 * kElemBlock); ++i) {
+        const size_t e = base + 4 * ((size_t)i * kElemBlock + threadIdx.x);
+        if (e + 4 <= P.numel) {
+            f32x4 w;
+            if (P.master) w = *reinterpret_cast<const f32x4*>(P.master + e);
+            else if (P.lowp) {
+                const u32x2 r = *reinterpret_cast<const u32x2*>(pl + e);
+                w[0] = __uint_as_float(r[0] << 16); w[1] = __uint_as_float(r[0] & 0xffff0000u);
+                w[2] = __uint_as_float(r[1] << 16); w[3] = __uint_as_float(r[1] & 0xffff0000u);
+            } else w = *reinterpret_cast<const f32x4*>(pf + e);
+            const f32x4 gr = *reinterpret_cast<const f32x4*>(P.g + e);
+            f32x4 v;
+            if (P.v) v = *reinterpret_cast<const f32x4*>(P.v + e);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float vq = P.v ? v[q] : 0.f;
+                w[q] = sgd_elem(g, w[q], gr[q], P.v ? &vq : nullptr);
+                v[q] = vq;
+            }
+            if (P.v) *reinterpret_cast<f32x4*>(P.v + e) = v;
+            if (P.master) *reinterpret_cast<f32x4*>(P.master + e) = w;
+            if (P.lowp) {
+                u32x2 r; r[0] = pack_bf16x2(w[0], w[1]); r[1] = pack_bf16x2(w[2], w[3]);
+                *reinterpret_cast<u32x2*>(pl + e) = r;
+            } else *reinterpret_cast<f32x4*>(pf + e) = w;
+        } else {
+            for (size_t t = e; t < P.numel; ++t) {
+                float w = P.master ? P.master[t] : (P.lowp ? bf16_bits_to_float(pl[t]) : pf[t]);
+                w = sgd_elem(g, w, P.g[t], P.v ? P.v + t : nullptr);
+                if (P.master) P.master[t] = w;
+                if (P.lowp) pl[t] = float_to_bf16_bits(w);
+                else pf[t] = w;
+            }
+        }
     }
 }
 
