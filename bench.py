@@ -57,6 +57,69 @@ def one_step(ls, net):
     ls.step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
 
 
+def speedup_terms(name, batch, reps):
+    """One-GPU measurement of the terms of the paper's speed-up model (Sec. 4.3): the layer-serial network
+    (K = 1) gives T_f and T_b; the K-module network, one module at a time, gives what each of K devices would
+    run; the interface work gives t_psi and the AuxNet work t_f^lambda, t_b^lambda.  Data loading T_d is not
+    modelled (0): the result is the model's upper bound for this network on this device."""
+    import torch
+    import workloads as wl
+    from workloads.configs import AuxDesc
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    net = wl.make_config(name, batch=batch)
+    nblocks = sum(len(m.blocks) for m in net.modules)
+    serial = wl.make_config(name, batch=batch, split=[nblocks])
+    ls = build_state(serial)
+    T_f = timed(lambda: ls.module_forward())
+    # a backward pass consumes its forward pass: time both and subtract
+    T_b = timed(lambda: (ls.module_forward(), ls.local_loss_grad(serial.rho, 1.0), ls.module_backward())) - T_f
+    T_u = timed(lambda: ls.sgd_update(0.0))
+    ls.close()
+    del ls
+    if net.aux is None:
+        m0 = net.modules[0]
+        net.aux = [AuxDesc(cin=m0.C, cout=m.C, stride=m0.H // m.H, relu=False) for m in net.modules[1:]]
+    ls = build_state(net)
+    K = net.K
+    f = [timed(lambda k=k: ls.module_forward(mask=1 << k)) for k in range(K)]
+    ls.local_loss_grad(net.rho, 1.0)
+    b = [timed(lambda k=k: (ls.module_forward(mask=1 << k), ls.module_backward(mask=1 << k))) - f[k]
+         for k in range(K - 1)]                                                              # interface loss: in t_psi
+    last = 1 << (K - 1)
+    b.append(timed(lambda: (ls.module_forward(mask=last), ls.local_loss_grad(net.rho, 1.0, mask=last),
+                            ls.module_backward(mask=last))) - f[K - 1])
+    t_loss = timed(lambda: ls.local_loss_grad(net.rho, 1.0, mask=(1 << (K - 1)) - 1))
+    x_keep = [t.clone() for t in ls.x]
+    t_corr = timed(lambda: ls.aux_variable_update(net.rho, 1.0, 0.0))
+    t_mult = timed(lambda: ls.al_multiplier_update(0.0)) if net.al else 0.0
+    t_lf = timed(lambda: ls.auxnet_forward())
+    for t, keep in zip(ls.x, x_keep):
+        t.copy_(keep)
+    t_lb = timed(lambda: ls.auxnet_distill_grad(1.0))
+    ls.close()
+    t_psi = t_loss + t_corr + t_mult
+    over = t_psi + t_lf + t_lb
+    model = 1.0 / ((T_f + T_b) / K / (T_f + T_b) + over / (T_f + T_b))
+    slowest = max(fk + bk for fk, bk in zip(f, b))
+    return {"workload": f"{name}, batch {net.modules[0].N}, K={K}", "ms": {
+                "T_f": T_f, "T_b": T_b, "T_update": T_u, "module_forward": f, "module_backward": b,
+                "t_psi": t_psi, "t_psi_parts": {"loss_adjoint": t_loss, "aux_variable_update": t_corr, "multiplier_update": t_mult},
+                "t_f_lambda": t_lf, "t_b_lambda": t_lb},
+            "speedup_model_T_d_0": model,
+            "speedup_with_measured_module_balance": (T_f + T_b) / (slowest + over),
+            "note": "every term measured on ONE GPU; the K devices of the model are not run"}
+
+
 def cpu_baseline(net_name, target_seconds=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same
     network at a reduced mini-batch (the network, K and every layer shape are the configuration's)."""
@@ -105,6 +168,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run three plain 256 MiB device copies (a known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--speedup-terms", action="store_true",
+                    help="also time the terms of the paper's speed-up model (K = 1 network, single modules, interface "
+                         "and AuxNet work) and add them to the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs the local step of all K modules on ONE GPU; --gpus must be 1 "
@@ -201,6 +267,8 @@ def main():
     sgd_bytes = sum(int(t.numel) * ((4 if t.dtype == B.LP_BF16 else 8) + 12) for tab in ls.tables for t in tab)
     out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
     ls.close()
+    if args.speedup_terms:
+        out["speedup_model"] = speedup_terms(args.config, args.batch, max(3, args.steps // 2))
     if args.calibrate_copy:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

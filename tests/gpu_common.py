@@ -17,11 +17,13 @@ def say(*a):
     sys.stdout.flush()
 
 
-def gpu_mini_basic(batch=3, dtype="f32"):
-    """K=3, channels multiple of 8, ragged M (6x6 images): stem, stride-2 projection block, head."""
+def gpu_mini_basic(batch=3, dtype="f32", serial=False):
+    """K=3, channels multiple of 8, ragged M (6x6 images): stem, stride-2 projection block, head.
+    serial=True: the same network as one module (K=1, ordinary back-propagation)."""
     blocks = [Block("basic", 8, 8, 8, 1, False), Block("basic", 8, 16, 16, 2, True),
               Block("basic", 16, 16, 16, 1, False), Block("basic", 16, 16, 16, 1, False)]
-    net = cfg._assemble("gpu_mini_basic", [blocks[:2], blocks[2:3], blocks[3:]], batch, 6, 6, 3, 1, 8, 5, seed=21)
+    per_module = [blocks] if serial else [blocks[:2], blocks[2:3], blocks[3:]]
+    net = cfg._assemble("gpu_mini_basic", per_module, batch, 6, 6, 3, 1, 8, 5, seed=21)
     net.dtype = dtype
     return net
 

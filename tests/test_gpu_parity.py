@@ -53,6 +53,19 @@ def test_mini_bottleneck(dtype):
     compare_step(net)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_serial_k1(dtype):
+    """K = 1: one module holds the whole network, the step is ordinary back-propagation of the cross-entropy
+    (no interface, no auxiliary variable, no multiplier)."""
+    say("case mini_basic K=1", dtype)
+    compare_step(gpu_mini_basic(dtype=dtype, serial=True))
+
+
+def test_wrn_layer_serial_reduced_batch():
+    say("case wrn28_10 K=1 batch 2 bf16")
+    compare_step(wl.make_config("wrn28_10", batch=2, split=[12]))
+
+
 def test_mini_wide_ragged_tiles():
     say("case mini_wide bf16")
     compare_step(gpu_mini_wide())

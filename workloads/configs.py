@@ -110,8 +110,20 @@ def _assemble(name, per_module, n, h, w, c_img, stem, stem_cout, n_classes, **kw
     return NetDesc(name=name, K=K, modules=mods, aux=None, dtype="f32", **kw)
 
 
-def make_config(name: str, batch: Optional[int] = None) -> NetDesc:
-    """The five synthetic workloads; `batch` overrides the mini-batch size only."""
+def make_config(name: str, batch: Optional[int] = None, split: Optional[List[int]] = None) -> NetDesc:
+    """The five synthetic workloads; `batch` overrides the mini-batch size only, `split` the number of residual
+    blocks per module (same network, other K: `[12]` is the layer-serial K=1 form of the 12-block networks)."""
+    if split is not None:
+        net = make_config(name, batch)
+        blocks = [b for m in net.modules for b in m.blocks]
+        m0 = net.modules[0]
+        out = _assemble(name, _split(blocks, list(split)), m0.N, m0.H, m0.W, m0.C, m0.stem, m0.stem_cout,
+                        net.modules[-1].n_classes, seed=net.seed, al=net.al, lam_sigma=net.lam_sigma, rho=net.rho,
+                        step=net.step, bn_eps=net.bn_eps)
+        out.dtype = net.dtype
+        if net.aux is not None:
+            out.aux = [AuxDesc(cin=m0.C, cout=m.C, stride=m0.H // m.H, relu=False) for m in out.modules[1:]]
+        return out
     if name == "tiny":
         n = batch or 4
         blk = lambda: Block("basic", 16, 16, 16, 1, False)
