@@ -161,6 +161,23 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
 lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const* lam,
                                   const void* const* y, const void* const* x_next, float step);
 
+/* Update direction of a recursive AuxNet (Sec. 4.4, the rule given there for xi_k when the auxiliary variable is
+ * generated from the mini-batch, x_k = ReAuxNet_k(x_0; xi_k), instead of being a free variable): the gradient of the
+ * relaxed objective with respect to x_k,
+ *     g_k = scale*(rho*(x_k - y_prev[k-1]) - lam_prev[k-1]) + dx[k],
+ * pulled back through the AuxNet block ([ReLU,] BN with batch statistics, conv3x3) into daux_params[k-1]
+ * (overwritten; layout of lp_net_param_bytes(net, 1, k-1)).  x_k is the AuxNet output of the last lp_auxnet_forward
+ * (recomputed from its saved activations: that call must have run with the same image and aux_params, else
+ * LP_ERR_STATE); y_prev[k-1] = F_{k-1}(x_{k-1}) as written by lp_module_forward; dx[k] as written by
+ * lp_module_backward for the step whose x_k was that AuxNet output (dx[0] is not read); lam_prev NULL or an entry
+ * NULL: penalty method, as the paper states the rule.  daux_params[j] == NULL skips AuxNet j.  Depth of the
+ * recursion: one block from the image, as the AuxNet descriptors define it.  The descent step is lp_sgd_update with
+ * aux = 1.  Device memory, 16-byte aligned, activation dtype.
+ * Errors: LP_ERR_INVALID_ARG, LP_ERR_STATE, LP_ERR_WORKSPACE; LP_ERR_HIP if a launch fails. */
+lp_status lp_reauxnet_grad(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                           const void* const* y_prev, const void* const* dx, const void* const* lam_prev, float rho,
+                           float scale, float* const* daux_params);
+
 /* Parameter update of Sec. 4.1 (W <- W - eta * dW for every tensor of a module, right after the module's adjoint
  * recursion).  The paper states plain gradient descent; the two usual extensions are off at 0:
  *     g' = dW + weight_decay * W;   v <- momentum * v + g'  (when momentum != 0);   W <- W - lr * (v or g').

@@ -376,6 +376,27 @@ def auxnet_distill_grad(a: AuxDesc, image, params, target, eps=1e-5, scale=1.0, 
     return loss, grads
 
 
+def reauxnet_grad(a: AuxDesc, image, params, y_prev, dx, lam_prev, rho, scale=1.0, eps=1e-5, q=None):
+    """Update direction of a recursive AuxNet (Sec. 4.4, the rule that replaces the separate correction and
+    distillation when x_k = ReAuxNet_k(x_0; xi_k) is generated from the mini-batch): the gradient of the relaxed
+    objective with respect to x_k,
+        g = scale*(rho*(x_k - F_{k-1}(x_{k-1})) - lam_{k-1}) + dx_k,        x_k = ReAuxNet_k(x_0; xi_k),
+    (interface term k-1 plus the local loss of module k, whose input gradient dx_k the module-local backward pass
+    returns) pulled back through the AuxNet: d/d xi_k = g * dReAuxNet_k/d xi_k.  The paper states the rule for the
+    penalty method; lam_prev=None is that case, a multiplier enters as in the correction of x_k.  Depth one (a single
+    conv3x3 + BN [+ ReLU] block from the image), as the configurations define the AuxNet.
+    Returns [dW, dgamma, dbeta]."""
+    qq = q or _id
+    out, cache = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]), a.stride, 1, a.relu, eps, q)
+    out = qq(out)
+    g = rho * (out - _c64(y_prev))
+    if lam_prev is not None:
+        g = g - _c64(lam_prev)
+    g = qq(scale * g + _c64(dx))
+    _, grads = _cbr_bwd(g, cache, need_dx=False, q=q)
+    return grads
+
+
 # ----------------------------------------------------------------------------- whole step / serial net
 def local_step(net: NetDesc, xs, params, labels, lams=None, scale=1.0, need_dx0=False, q=None):
     """One synchronous local step of all K modules.

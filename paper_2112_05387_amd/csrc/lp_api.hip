@@ -1227,6 +1227,46 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
     return run_programs(net, pb, b, s);
 }
 
+lp_status lp_reauxnet_grad(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                           const void* const* y_prev, const void* const* dx, const void* const* lam_prev, float rho,
+                           float scale, float* const* daux_params) {
+    lp_status st = check_common(net, 0, false);
+    if (st != LP_OK) return st;
+    if (net->aux.empty()) return fail(LP_ERR_STATE, "the net was created without AuxNet descriptors");
+    if (!net->aux_fwd_done) return fail(LP_ERR_STATE, "lp_auxnet_forward has not run: no saved AuxNet activations");
+    if (!image || !aux_params || !y_prev || !dx || !daux_params) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (!(rho >= 0.f)) return fail(LP_ERR_INVALID_ARG, "rho must be non-negative");
+    if (misaligned(image)) return fail(LP_ERR_INVALID_ARG, "image is not 16-byte aligned");
+    const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<const Program*> pa, pb;
+    AuxVarGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = rho; g.scale = scale; g.eta = 0.f;
+    std::vector<AuxVarGroup> groups;
+    for (int j = 0; j < net->K - 1; ++j) {
+        if (!daux_params[j]) continue;
+        if (!aux_params[j] || !y_prev[j] || !dx[j + 1]) return fail(LP_ERR_INVALID_ARG, "aux_params[%d], y_prev[%d] or dx[%d] is NULL", j, j, j + 1);
+        const void* lam = lam_prev ? lam_prev[j] : nullptr;
+        if (misaligned(aux_params[j]) || misaligned(y_prev[j]) || misaligned(dx[j + 1]) || misaligned(lam) || misaligned(daux_params[j]))
+            return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
+        AuxPlan& a = net->aux[j];
+        pa.push_back(&a.bwd_a); pb.push_back(&a.bwd_b);
+        AuxVarProb& p = g.p[g.nprob];
+        p.x = net->ws + a.ws_out; p.yprev = y_prev[j]; p.dx = dx[j + 1]; p.lam = lam; p.gout = net->ws + a.ws_g;
+        p.numel = a.u.out_elems();
+        p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
+        if (++g.nprob == kMaxGroup) { groups.push_back(g); g.nprob = 0; g.total_blocks = 0; }
+    }
+    if (g.nprob) groups.push_back(g);
+    if (pa.empty()) return LP_OK;
+    Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.auxg = daux_params;
+    st = run_programs(net, pa, b, s);          // recomputed AuxNet output x_k (BN apply of the saved conv output)
+    if (st != LP_OK) return st;
+    hipError_t err = hipSuccess;
+    for (size_t i = 0; i < groups.size() && err == hipSuccess; ++i) err = launch_auxvar(groups[i], net->dtype, s);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    return run_programs(net, pb, b, s);        // [ReLU,] BN backward, filter gradient
+}
+
 lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* x,
                             const void* const* params, void* const* y, float* logits) {
     lp_status st = check_common(net, module_mask, true);
@@ -1419,7 +1459,7 @@ lp_status lp_aux_variable_update(struct lp_net* net, void* stream, void* const* 
             return fail(LP_ERR_INVALID_ARG, "interface tensor %d is not 16-byte aligned", k);
         const ModulePlan& m = net->mods[k];
         AuxVarProb& p = g.p[g.nprob];
-        p.x = x[k]; p.yprev = y_prev[k - 1]; p.dx = dx[k]; p.lam = lam;
+        p.x = x[k]; p.yprev = y_prev[k - 1]; p.dx = dx[k]; p.lam = lam; p.gout = nullptr;
         p.numel = (size_t)m.d.N * m.d.H * m.d.W * m.d.C;
         p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
         if (++g.nprob == kMaxGroup) {

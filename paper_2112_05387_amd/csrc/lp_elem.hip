@@ -415,6 +415,7 @@ __global__ __launch_bounds__(kElemBlock) void auxvar_kernel(const AuxVarGroup g)
     const T* __restrict__ yp = reinterpret_cast<const T*>(P.yprev);
     const T* __restrict__ dx = reinterpret_cast<const T*>(P.dx);
     const T* __restrict__ lam = reinterpret_cast<const T*>(P.lam);
+    T* __restrict__ gout = reinterpret_cast<T*>(P.gout);
     const size_t nvec = P.numel / EPV;
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
     for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
@@ -427,10 +428,10 @@ __global__ __launch_bounds__(kElemBlock) void auxvar_kernel(const AuxVarGroup g)
         if (lam) Vec<T>::load(lam + v * EPV, l);
 #pragma unroll
         for (int e = 0; e < EPV; ++e) {
-            const float gr = g.rho * (a[e] - b[e]) - (lam ? l[e] : 0.f);
-            a[e] -= g.eta * (g.scale * gr + d[e]);
+            const float gr = g.scale * (g.rho * (a[e] - b[e]) - (lam ? l[e] : 0.f)) + d[e];
+            a[e] = gout ? gr : a[e] - g.eta * gr;
         }
-        Vec<T>::store(x + v * EPV, a);
+        Vec<T>::store((gout ? gout : x) + v * EPV, a);
     }
 }
 

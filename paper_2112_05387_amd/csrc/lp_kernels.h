@@ -115,7 +115,9 @@ struct MultGroup { int nprob, total_blocks; float step; MultProb p[kMaxGroup]; }
 struct SgdProb { void* p; const float* g; float* v; float* master; size_t numel; int lowp; int block_start, nblocks; };
 struct SgdGroup { int nprob, total_blocks; float lr, momentum, wd; SgdProb p[kMaxGroup]; };
 // correction of an auxiliary variable: x <- x - eta*(scale*(rho*(x - yprev) - lam) + dx), lam may be NULL
-struct AuxVarProb { void* x; const void* yprev; const void* dx; const void* lam; size_t numel; int block_start, nblocks; };
+struct AuxVarProb {      // gout != NULL: the gradient scale*(rho*(x - yprev) - lam) + dx is written there and x is left as it is
+    void* x; const void* yprev; const void* dx; const void* lam; void* gout; size_t numel; int block_start, nblocks;
+};
 struct AuxVarGroup { int nprob, total_blocks; float rho, scale, eta; AuxVarProb p[kMaxGroup]; };
 
 struct PoolProb {        // max pooling R x R, stride, pad on NHWC

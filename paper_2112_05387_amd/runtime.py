@@ -172,6 +172,19 @@ class LocalStep:
         B.lp_auxnet_distill_grad(self.net, self._stream(), img.data_ptr(), self._p(self.aux_params), self._p(tg), scale,
                                  self.aux_loss.data_ptr(), self._p(self.daux_params))
 
+    def reauxnet_grad(self, rho, scale=1.0, image=None):
+        """Gradient of the relaxed objective with respect to the AuxNet parameters when x_k = AuxNet_k(image)
+        (after auxnet_forward, module_forward, local_loss_grad and module_backward of the same step)."""
+        img = self.x[0] if image is None else image
+        dx = [None] + [t.data_ptr() for t in self.dx[1:]]
+        B.lp_reauxnet_grad(self.net, self._stream(), img.data_ptr(), self._p(self.aux_params), self._p(self.y), dx,
+                           None if self.lam is None else self._p(self.lam), rho, scale, self._p(self.daux_params))
+
+    def sgd_update_aux(self, lr, momentum=0.0, weight_decay=0.0, velocity=None):
+        B.lp_sgd_update(self.net, self._stream(), 1, (1 << (self.K - 1)) - 1, self._p(self.aux_params),
+                        self._p(self.daux_params), None if velocity is None else self._p(velocity), None,
+                        lr, momentum, weight_decay)
+
     def sgd_update(self, lr, momentum=0.0, weight_decay=0.0, velocity=None, master=None, mask=None):
         """W <- W - lr*(dW [+ wd*W, + momentum]) for the modules in `mask` (default all), in place."""
         B.lp_sgd_update(self.net, self._stream(), 0, self._mask(mask), self._p(self.params), self._p(self.dparams),

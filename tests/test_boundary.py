@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "lp.h")).read()
     declared = set(re.findall(r"\b(lp_[a-z0-9_]+)\s*\(", hdr))
     assert {"lp_module_forward", "lp_local_loss_grad", "lp_module_backward", "lp_auxnet_forward",
-            "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update"} <= declared
+            "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad"} <= declared
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), f"{name} declared in lp.h but not exported"
@@ -134,6 +134,7 @@ def test_call_time_errors_without_touching_the_gpu():
         _expect(B.LP_ERR_INVALID_ARG, B.lp_aux_variable_update, h, None, None, ptrs[:1], ptrs, None, 1.0, 1.0, 0.1)   # x NULL
         _expect(B.LP_ERR_INVALID_ARG, B.lp_aux_variable_update, h, None, ptrs, ptrs[:1], [FAKE_PTR, None], None, 1.0, 1.0, 0.1)   # dx[1]
         _expect(B.LP_ERR_INVALID_ARG, B.lp_aux_variable_update, h, None, [None, FAKE_PTR + 2], ptrs[:1], ptrs, None, 1.0, 1.0, 0.1)   # alignment
+        _expect(B.LP_ERR_STATE, B.lp_reauxnet_grad, h, None, FAKE_PTR, ptrs[:1], ptrs[:1], ptrs, None, 1.0, 1.0, ptrs[:1])   # no AuxNet
         _expect(B.LP_ERR_INVALID_ARG, B.lp_sgd_update, h, None, 0, 1, None, ptrs, None, None, 0.1, 0.0, 0.0)            # params NULL
         _expect(B.LP_ERR_INVALID_ARG, B.lp_sgd_update, h, None, 0, 1, ptrs, ptrs, None, None, 0.1, 0.9, 0.0)            # momentum, no velocity
         _expect(B.LP_ERR_INVALID_ARG, B.lp_sgd_update, h, None, 0, 0, ptrs, ptrs, None, None, 0.1, 0.0, 0.0)            # empty mask

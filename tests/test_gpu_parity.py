@@ -228,6 +228,68 @@ def test_auxnet_distill_grad(dtype):
         ls.close()
 
 
+@pytest.mark.parametrize("dtype,al", [("f32", True), ("f32", False), ("bf16", True)])
+def test_reauxnet_grad(dtype, al):
+    """Gradient of the relaxed objective with respect to the parameters of every AuxNet of the ResNet-56
+    configuration (strides 1, 2, 4; batch 8) when x_k = AuxNet_k(image): seeded F_{k-1}(x_{k-1}), dx_k and
+    multipliers, then the sequence AuxNet gradient -> descent step on the AuxNet parameters."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err, store
+    net = wl.make_config("resnet56", batch=8)
+    net.dtype = dtype
+    rho, scale, lr = 1.3, 0.5, 0.05
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    q = None if dtype == "f32" else wl.round_bf16
+    say("case reauxnet_grad", dtype, "AL" if al else "penalty")
+    image = wl.make_image(net)
+    auxp = [wl.make_aux_params(net, j) for j in range(net.K - 1)]
+    ls = LocalStep(net)
+    try:
+        ls.set_x(0, image)
+        yp, dxs, lams = [], [], []
+        for j in range(net.K - 1):
+            ls.set_aux_params(j, auxp[j])
+            shp = ls.y_shapes[j]
+            yp.append(store(net, wl.normal(43, f"yprev{j}", shp)))
+            dxs.append(store(net, wl.normal(43, f"dx{j}", shp, 0.3)))
+            lams.append(store(net, wl.normal(43, f"lam{j}", shp, 0.2)))
+            ls.y[j].copy_(ls.to_dev(yp[j]))
+            ls.dx[j + 1].copy_(ls.to_dev(dxs[j]))
+        ls.set_lams(lams if al else None)
+        ls.auxnet_forward()
+        ls.reauxnet_grad(rho, scale)
+        torch.cuda.synchronize()
+        errs = {}
+        want = []
+        for j in range(net.K - 1):
+            grads = lpref.reauxnet_grad(net.aux[j], image, auxp[j], yp[j], dxs[j], lams[j] if al else None, rho, scale,
+                                        net.bn_eps, q)
+            want.append(grads)
+            for name, g, r in zip(("dW", "dgamma", "dbeta"), ls.get_aux_grads(j), grads):
+                errs[f"aux{j}.{name}"] = rel_err(g, r)
+        top = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+        say("    worst: " + ", ".join(f"{k}={v:.2e}" for k, v in top))
+        bad = {k: v for k, v in errs.items() if not v <= tol}
+        assert not bad, bad
+        # descent step on the AuxNet parameters from the device's own gradients
+        dev_g = [ls.get_aux_grads(j) for j in range(net.K - 1)]
+        ls.sgd_update_aux(lr)
+        torch.cuda.synchronize()
+        from paper_2112_05387_amd import binding as B
+        for j in range(net.K - 1):
+            for info, w, g in zip(ls.aux_tables[j], auxp[j], dev_g[j]):
+                n = int(info.numel)
+                lowp = info.dtype == B.LP_BF16
+                w0 = wl.round_bf16(w) if lowp else np.asarray(w, np.float32).astype(np.float64)
+                w_new, _ = lpref.sgd_update(w0, g, lr)
+                raw = ls.aux_params[j][info.offset:info.offset + (2 if lowp else 4) * n]
+                got = ls.to_host(raw.view(torch.bfloat16 if lowp else torch.float32)).reshape(np.shape(w_new))
+                assert rel_err(got, w_new) <= (4e-3 if lowp else 1e-6), (j, info.ndim, rel_err(got, w_new))
+    finally:
+        ls.close()
+
+
 def test_vanish_invariant_on_device():
     """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
     and dx of modules 0..K-2 are exactly zero."""

@@ -274,6 +274,43 @@ def test_auxnet_distill_grad_finite_differences(relu):
     assert loss0 == 0.0 and all(np.all(g == 0.0) for g in g0)
 
 
+@pytest.mark.parametrize("al,relu", [(True, False), (False, True)])
+def test_reauxnet_grad_finite_differences(al, relu):
+    """With x_k = AuxNet(image; xi) substituted, the relaxed objective depends on xi through the interface term k-1
+    and through the local loss of module k.  reauxnet_grad (fed with the oracle's dx_k at that x_k) must equal the
+    central-difference gradient of that composite, for the middle module (interface loss below it) and for the
+    last one (cross-entropy below it)."""
+    from workloads.configs import AuxDesc
+    net = mini_basic()
+    net.rho, net.al, net.lam_sigma = 1.4, al, 0.3
+    net.aux = [AuxDesc(cin=3, cout=m.C, stride=net.modules[0].H // m.H, relu=relu) for m in net.modules[1:]]
+    inp = step_inputs(net, lpref)
+    scale, h = 0.7, 1e-6
+    rng = np.random.default_rng(17)
+    for k in range(1, net.K):          # the exact AuxNet outputs (the shared recipe rounds them to the storage type)
+        inp["xs"][k] = lpref.auxnet_forward(net.aux[k - 1], inp["image"], inp["aux_params"][k - 1], net.bn_eps)
+    out = lpref.local_step(net, inp["xs"], inp["params"], inp["labels"], inp["lams"], scale)
+    for k in range(1, net.K):
+        a, theta = net.aux[k - 1], inp["aux_params"][k - 1]
+        lam_prev = inp["lams"][k - 1] if al else None
+        grads = lpref.reauxnet_grad(a, inp["image"], theta, out["y"][k - 1], out["dx"][k], lam_prev, net.rho, scale, net.bn_eps)
+
+        def objective(th):
+            x = lpref.auxnet_forward(a, inp["image"], th, net.bn_eps)
+            below = lpref.local_loss_grad(out["y"][k - 1], x, lam_prev, net.rho, scale)[0]
+            return below + _local_loss(net, k, x, inp["params"][k], inp["xs"][k + 1] if k < net.K - 1 else None,
+                                       inp["lams"][k] if (al and k < net.K - 1) else None, inp["labels"], scale)
+
+        for i in range(3):
+            assert grads[i].shape == theta[i].shape
+            d = rng.standard_normal(theta[i].shape)
+            tp, tm = list(theta), list(theta)
+            tp[i], tm[i] = theta[i] + h * d, theta[i] - h * d
+            fd = (objective(tp) - objective(tm)) / (2 * h)
+            an = float(np.sum(grads[i] * d))
+            assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (k, i, fd, an)
+
+
 def test_sgd_update_closed_forms():
     """Plain descent on f = 1/2 |W|^2 (gradient W) contracts by (1 - lr) per step; weight decay on a zero gradient
     contracts by (1 - lr*wd); momentum on a constant gradient accumulates the geometric series; and a small enough
