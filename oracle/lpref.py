@@ -230,9 +230,111 @@ def block_backward(dout, cache, need_dx=True, q=None):
     return dx, grads
 
 
+# ----------------------------------------------------------------------------- pre-activation order
+def _bn_relu_fwd(x, gamma, beta, eps, q=None):
+    """ReLU(BN(x)) with batch statistics of the stored x.  Not rounded here."""
+    z, bc = bn_fwd(x, gamma, beta, eps, q)
+    return np.maximum(z, 0.0), (bc, z, gamma)
+
+
+def _bn_relu_bwd(do, cache):
+    bc, z, gamma = cache
+    return bn_bwd(do * (z > 0.0), bc, gamma)
+
+
+def block_forward_pre(x, p, b: Block, eps, q=None):
+    """Residual block in the order the paper's architecture figure draws (Fig. 2):
+    X_{m+1} = skip + conv2(ReLU(BN2(conv1(ReLU(BN1(X_m)))))), skip = X_m or conv1x1(ReLU(BN1(X_m))).
+    p = [gamma1, beta1, W1, gamma2, beta2, W2, (Wproj)]."""
+    qq = q or _id
+    o1, c1 = _bn_relu_fwd(x, p[0], p[1], eps, q)
+    o1 = qq(o1)
+    y1 = qq(conv_fwd(o1, p[2], b.stride, 1))
+    o2, c2 = _bn_relu_fwd(y1, p[3], p[4], eps, q)
+    o2 = qq(o2)
+    z = conv_fwd(o2, p[5], 1, 1)
+    skip = qq(conv_fwd(o1, p[6], b.stride, 0)) if b.proj else x
+    return qq(z + skip), (x.shape, o1, o2, c1, c2, p[2], p[5], p[6] if b.proj else None, b.stride)
+
+
+def block_backward_pre(dout, cache, q=None):
+    """Always returns the input gradient: the statistics of BN1 depend on X_m, and gamma1, beta1 need the gradient
+    that reaches BN1's output."""
+    qq = q or _id
+    xshape, o1, o2, c1, c2, w1, w2, wp, stride = cache
+    dw2 = conv_wgrad(o2, dout, w2.shape, 1, 1)
+    do2 = qq(conv_dgrad(dout, w2, o2.shape, 1, 1))
+    dy1, dg2, db2 = _bn_relu_bwd(do2, c2)
+    dy1 = qq(dy1)
+    dw1 = conv_wgrad(o1, dy1, w1.shape, stride, 1)
+    do1 = conv_dgrad(dy1, w1, o1.shape, stride, 1)
+    grads_p = []
+    if wp is not None:
+        grads_p = [conv_wgrad(o1, dout, wp.shape, stride, 0)]
+        do1 = do1 + qq(conv_dgrad(dout, wp, o1.shape, stride, 0))
+    do1 = qq(do1)
+    dx, dg1, db1 = _bn_relu_bwd(do1, c1)
+    if wp is None:
+        dx = dx + dout
+    return qq(dx), [dg1, db1, dw1, dg2, db2, dw2] + grads_p
+
+
+def _module_forward_pre(m: ModuleDesc, x, params, eps, q):
+    qq = q or _id
+    p = [_c64(t) for t in params]
+    a = _c64(x)
+    cache = {"stem": None, "blocks": [], "head": None, "in_shape": a.shape, "order": "pre"}
+    i = 0
+    if m.stem == 1:
+        cache["stem"] = (a, p[0])
+        a = qq(conv_fwd(a, p[0], 1, 1))
+        i = 1
+    elif m.stem != 0:
+        raise ValueError("pre-activation order: stem 0 or 1")
+    for b in m.blocks:
+        n = 7 if b.proj else 6
+        a, c = block_forward_pre(a, p[i:i + n], b, eps, q)
+        cache["blocks"].append(c)
+        i += n
+    logits = None
+    if m.head:
+        f, hc = _bn_relu_fwd(a, p[i], p[i + 1], eps, q)
+        f = qq(f)
+        pooled = f.mean(axis=(1, 2))
+        logits = pooled @ p[i + 2].T + p[i + 3]
+        cache["head"] = (pooled, p[i + 2], f.shape, hc)
+    return a, logits, cache
+
+
+def _module_backward_pre(m: ModuleDesc, cache, dy, dlogits, need_dx, q):
+    qq = q or _id
+    tail = []
+    if m.head:
+        pooled, wfc, shp, hc = cache["head"]
+        dwfc = dlogits.T @ pooled
+        dbfc = dlogits.sum(axis=0)
+        df = qq(np.broadcast_to((dlogits @ wfc)[:, None, None, :] / (shp[1] * shp[2]), shp).copy())
+        g, dgh, dbh = _bn_relu_bwd(df, hc)
+        g = qq(g)
+        tail = [dgh, dbh, dwfc, dbfc]
+    else:
+        g = _c64(dy)
+    grads = []
+    for j in range(len(cache["blocks"]) - 1, -1, -1):
+        g, bg = block_backward_pre(g, cache["blocks"][j], q=q)
+        grads = bg + grads
+    if cache["stem"] is not None:
+        img, w = cache["stem"]
+        grads = [conv_wgrad(img, g, w.shape, 1, 1)] + grads
+        g = qq(conv_dgrad(g, w, img.shape, 1, 1)) if need_dx else None
+    return grads + tail, (g if need_dx else None)
+
+
 # ----------------------------------------------------------------------------- module
 def module_forward(m: ModuleDesc, x, params, eps=1e-5, q=None):
     """Returns (F_k(x_k), logits or None, cache).  params: list in workloads.module_tensor_specs order."""
+    if m.order == "pre":
+        return _module_forward_pre(m, x, params, eps, q)
     qq = q or _id
     p = [_c64(t) for t in params]
     a = _c64(x)
@@ -267,6 +369,8 @@ def module_backward(m: ModuleDesc, cache, dy=None, dlogits=None, need_dx=True, q
     """Module-local back-propagation from the terminal adjoint: dy (on F_k(x_k)) or dlogits (last module).
 
     Returns (dparams list in packing order, dx_k or None)."""
+    if cache.get("order") == "pre":
+        return _module_backward_pre(m, cache, dy, dlogits, need_dx, q)
     qq = q or _id
     tail = []
     if m.head:

@@ -15,6 +15,11 @@ def mini_basic(batch=3, dtype="f32"):
     return net
 
 
+def mini_basic_pre(batch=3, dtype="f32"):
+    """mini_basic in the pre-activation order: bare conv stem, BN-ReLU-conv blocks, BN-ReLU in front of the head."""
+    return cfg.with_order(mini_basic(batch, dtype), "pre")
+
+
 def mini_bottleneck(batch=2, dtype="f32"):
     """K=2 with the 7x7 stride-2 stem + maxpool and bottleneck blocks (one strided with projection)."""
     blocks = [Block("bottleneck", 4, 8, 2, 1, True), Block("bottleneck", 8, 16, 4, 2, True),

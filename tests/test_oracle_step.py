@@ -4,7 +4,7 @@ import pytest
 
 import workloads as wl
 from oracle import lpref
-from tests.helpers import mini_basic, mini_bottleneck, step_inputs, rel_err
+from tests.helpers import mini_basic, mini_basic_pre, mini_bottleneck, step_inputs, rel_err
 
 
 def _local_loss(net, k, x, params, x_next, lam, labels, scale):
@@ -15,7 +15,7 @@ def _local_loss(net, k, x, params, x_next, lam, labels, scale):
     return lpref.ce_loss_grad(logits, labels)[0]
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
 def test_module_backward_finite_differences(mk):
     """Every parameter tensor and the module input: directional derivatives, one tensor at a time,
     plus single coordinates, against central differences of the local loss (float64)."""
@@ -53,7 +53,7 @@ def test_module_backward_finite_differences(mk):
         assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, "dx", fd, an)
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
 def test_vanish_invariant(mk):
     """x_{k+1} = F_k(x_k) and zero multipliers: every penalty term, its terminal adjoint, every weight
     gradient and every dx of modules 0..K-2 vanish exactly (the relaxed problem reduces to the original)."""
@@ -70,7 +70,7 @@ def test_vanish_invariant(mk):
     assert out["loss"][-1] > 0.0
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
 def test_last_module_equals_end_to_end_and_serial_fd(mk):
     """With consistent auxiliary variables the last module's local gradients are those of end-to-end
     back-propagation; the end-to-end gradients themselves are pinned by finite differences of the
@@ -105,7 +105,7 @@ def test_last_module_equals_end_to_end_and_serial_fd(mk):
     assert abs(fd - float(np.sum(adj[0] * d))) <= 2e-6
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
 def test_multiplier_equal_to_adjoint_reproduces_end_to_end(mk):
     """Consistent auxiliary variables, arbitrary rho, multiplier on each interface := end-to-end adjoint
     there: every module's weight gradients and dx equal end-to-end back-propagation."""
@@ -272,6 +272,55 @@ def test_auxnet_distill_grad_finite_differences(relu):
         assert abs(fd - grads[i][j]) <= 5e-6 * max(1.0, abs(fd)), (i, j, fd, grads[i][j])
     loss0, g0 = lpref.auxnet_distill_grad(a, img, p, out, net.bn_eps, scale)
     assert loss0 == 0.0 and all(np.all(g == 0.0) for g in g0)
+
+
+@pytest.mark.parametrize("order", ["post", "pre"])
+def test_module_forward_against_library_layers(order):
+    """The forward pass of every module, re-composed from a library's float64 layers (conv2d, training-mode
+    batch_norm, relu, adaptive average pool, linear) in NCHW: pins the sequencing of both block orders (where BN
+    sits, what the projection reads, no ReLU after the sum, the head)."""
+    import torch
+    import torch.nn.functional as F
+    net = (mini_basic_pre if order == "pre" else mini_basic)()
+    inp = step_inputs(net, lpref)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))
+    act = lambda a: t(a).permute(0, 3, 1, 2)
+    filt = lambda w: t(w).permute(0, 3, 1, 2)
+    bn = lambda a, g, b: F.batch_norm(a, None, None, t(g), t(b), True, 0.0, net.bn_eps)
+    for k, m in enumerate(net.modules):
+        p = inp["params"][k]
+        a = act(inp["xs"][k])
+        i = 0
+        if order == "pre":
+            if m.stem:
+                a = F.conv2d(a, filt(p[0]), padding=1); i = 1
+            for b in m.blocks:
+                o1 = F.relu(bn(a, p[i], p[i + 1]))
+                y1 = F.conv2d(o1, filt(p[i + 2]), stride=b.stride, padding=1)
+                o2 = F.relu(bn(y1, p[i + 3], p[i + 4]))
+                z = F.conv2d(o2, filt(p[i + 5]), padding=1)
+                skip = F.conv2d(o1, filt(p[i + 6]), stride=b.stride) if b.proj else a
+                a = z + skip
+                i += 7 if b.proj else 6
+            feat = a
+            if m.head:
+                a = F.relu(bn(a, p[i], p[i + 1])); i += 2
+        else:
+            if m.stem:
+                a = F.relu(bn(F.conv2d(a, filt(p[0]), padding=1), p[1], p[2])); i = 3
+            for b in m.blocks:
+                y = F.relu(bn(F.conv2d(a, filt(p[i]), stride=b.stride, padding=1), p[i + 1], p[i + 2]))
+                z = bn(F.conv2d(y, filt(p[i + 3]), padding=1), p[i + 4], p[i + 5])
+                skip = bn(F.conv2d(a, filt(p[i + 6]), stride=b.stride), p[i + 7], p[i + 8]) if b.proj else a
+                a = z + skip
+                i += 9 if b.proj else 6
+            feat = a
+        y, logits, _ = lpref.module_forward(m, inp["xs"][k], p, net.bn_eps)
+        np.testing.assert_allclose(y, feat.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
+        if m.head:
+            want = F.linear(F.adaptive_avg_pool2d(a, 1).flatten(1), t(p[i]), t(p[i + 1]))
+            np.testing.assert_allclose(logits, want.numpy(), rtol=0, atol=1e-11)
+        assert i + (2 if m.head else 0) == len(p)
 
 
 @pytest.mark.parametrize("al,relu", [(True, False), (False, True)])

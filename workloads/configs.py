@@ -32,6 +32,8 @@ class ModuleDesc:
     H: int
     W: int
     C: int             # dims of the module input x_k, NHWC
+    order: str = "post"  # "post": conv-BN-ReLU-conv-BN + skip;  "pre": BN-ReLU-conv-BN-ReLU-conv + skip (Fig. 2);
+                         # with "pre" the stem is the bare conv3x3 and the head is BN-ReLU-avgpool-linear
 
     def out_shape(self) -> Tuple[int, int, int, int]:
         n, h, w, c = self.N, self.H, self.W, self.C
@@ -97,17 +99,24 @@ def _basic_stages(c0: int, widths: List[int], per_stage: int) -> List[Block]:
     return blocks
 
 
-def _assemble(name, per_module, n, h, w, c_img, stem, stem_cout, n_classes, **kw) -> NetDesc:
+def _assemble(name, per_module, n, h, w, c_img, stem, stem_cout, n_classes, order="post", **kw) -> NetDesc:
     mods = []
     K = len(per_module)
     shape = (n, h, w, c_img)
     for k, blks in enumerate(per_module):
         m = ModuleDesc(stem=stem if k == 0 else 0, stem_cout=stem_cout if k == 0 else 0,
                        blocks=blks, head=(k == K - 1), n_classes=n_classes,
-                       N=shape[0], H=shape[1], W=shape[2], C=shape[3])
+                       N=shape[0], H=shape[1], W=shape[2], C=shape[3], order=order)
         shape = m.out_shape()
         mods.append(m)
     return NetDesc(name=name, K=K, modules=mods, aux=None, dtype="f32", **kw)
+
+
+def with_order(net: NetDesc, order: str) -> NetDesc:
+    """The same network with every module in the given block order (parameter tensors change with it)."""
+    for m in net.modules:
+        m.order = order
+    return net
 
 
 def make_config(name: str, batch: Optional[int] = None, split: Optional[List[int]] = None) -> NetDesc:
@@ -118,7 +127,7 @@ def make_config(name: str, batch: Optional[int] = None, split: Optional[List[int
         blocks = [b for m in net.modules for b in m.blocks]
         m0 = net.modules[0]
         out = _assemble(name, _split(blocks, list(split)), m0.N, m0.H, m0.W, m0.C, m0.stem, m0.stem_cout,
-                        net.modules[-1].n_classes, seed=net.seed, al=net.al, lam_sigma=net.lam_sigma, rho=net.rho,
+                        net.modules[-1].n_classes, order=m0.order, seed=net.seed, al=net.al, lam_sigma=net.lam_sigma, rho=net.rho,
                         step=net.step, bn_eps=net.bn_eps)
         out.dtype = net.dtype
         if net.aux is not None:
@@ -180,6 +189,25 @@ def block_convs(b: Block):
 def module_tensor_specs(m: ModuleDesc) -> List[TensorSpec]:
     """Parameter tensors of one module in packing order.  Filters are KRSC."""
     t: List[TensorSpec] = []
+    if m.order == "pre":
+        assert m.stem in (0, 1) and all(b.kind == "basic" for b in m.blocks), "pre-activation: conv3x3 stem, basic blocks"
+        if m.stem:
+            t.append(TensorSpec("stem.conv", "conv", (m.stem_cout, 3, 3, m.C), 9 * m.C, -1, 0))
+        for i, b in enumerate(m.blocks):
+            for slot, r, ci, co, _, _ in block_convs(b):
+                nm = f"block{i}." + ("proj" if slot == 3 else f"conv{slot + 1}")
+                if slot != 3:          # the BN in front of the conv normalises the conv's input channels
+                    t.append(TensorSpec(nm + ".bn.gamma", "bn_gamma", (ci,), 0, i, slot))
+                    t.append(TensorSpec(nm + ".bn.beta", "bn_beta", (ci,), 0, i, slot))
+                t.append(TensorSpec(nm, "conv", (co, r, r, ci), r * r * ci, i, slot))
+        if m.head:
+            c = m.out_shape()[3]
+            nb = len(m.blocks)
+            t.append(TensorSpec("head.bn.gamma", "bn_gamma", (c,), 0, nb, 0))
+            t.append(TensorSpec("head.bn.beta", "bn_beta", (c,), 0, nb, 0))
+            t.append(TensorSpec("head.fc.w", "fc_w", (m.n_classes, c), c, nb, 0))
+            t.append(TensorSpec("head.fc.b", "fc_b", (m.n_classes,), c, nb, 0))
+        return t
     if m.stem:
         r = 3 if m.stem == 1 else 7
         t.append(TensorSpec("stem.conv", "conv", (m.stem_cout, r, r, m.C), r * r * m.C, -1, 0))
