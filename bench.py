@@ -168,6 +168,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run three plain 256 MiB device copies (a known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--order", choices=["post", "pre"], default="post",
+                    help="block order: post = conv-BN-ReLU (the headline configuration), pre = BN-ReLU-conv (Fig. 2)")
     ap.add_argument("--speedup-terms", action="store_true",
                     help="also time the terms of the paper's speed-up model (K = 1 network, single modules, interface "
                          "and AuxNet work) and add them to the JSON line")
@@ -183,6 +185,8 @@ def main():
     from workloads import configs as cfg
 
     net = wl.make_config(args.config, batch=args.batch)
+    if args.order == "pre":
+        cfg.with_order(net, "pre")
     N = net.modules[0].N
     ls = build_state(net)
     for _ in range(args.warmup):
@@ -247,7 +251,8 @@ def main():
         "dtype": net.dtype, "data": "synthetic",
         "config": {"workload": f"{net.name} local step, K={net.K} modules, batch {N}, "
                                f"{'augmented Lagrangian' if net.al else 'penalty'}, rho={net.rho}"
-                               f"{', AuxNet forward included' if net.aux is not None else ''}"},
+                               f"{', AuxNet forward included' if net.aux is not None else ''}"
+                               f"{', pre-activation block order' if args.order == 'pre' else ''}"},
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12 if conv_ms > 0 else None,
         "conv_frac_of_mfma_peak": (conv_flops / (conv_ms * 1e-3) / 1e12) / peak if conv_ms > 0 else None,
         "conv_tflop_per_step": cfg.conv_flops_step(net) / 1e12,

@@ -49,6 +49,17 @@ typedef enum {
 typedef enum { LP_F32 = 0, LP_BF16 = 1 } lp_dtype;
 typedef enum { LP_BLOCK_BASIC = 0, LP_BLOCK_BOTTLENECK = 1 } lp_block_kind;
 
+/* Order of the layers inside a residual block.
+ * LP_ORDER_POST: conv - BN - ReLU ... conv - BN, then the sum (described below at lp_block_desc).
+ * LP_ORDER_PRE : the order the architecture figure of the paper draws (Fig. 2), basic blocks only:
+ *     X_{m+1} = skip + conv3x3(ReLU(BN2(conv3x3(stride)(ReLU(BN1(X_m)))))),
+ *     skip = X_m, or conv1x1(stride)(ReLU(BN1(X_m))) without BN when `proj` is set;
+ *   the stem (1 only) is the bare conv3x3 and the head is BN - ReLU - average pool - linear.  BN1 normalises cin
+ *   channels with the batch statistics of X_m; parameter order per block: gamma1, beta1, W1, gamma2, beta2, W2,
+ *   [Wproj]; stem: W; head: gamma, beta, fc weight, fc bias.  dx[k] is always computed inside the module (the
+ *   statistics of BN1 depend on X_m) and handed out under the same rule as for LP_ORDER_POST. */
+typedef enum { LP_ORDER_POST = 0, LP_ORDER_PRE = 1 } lp_block_order;
+
 /* Residual block X_{m+1} = skip(X_m) + F(X_m, W_m)  (Sec. 2.1 and the feature flow of Sec. 4.1).
  * basic:      F = conv3x3(stride) - BN - ReLU - conv3x3 - BN
  * bottleneck: F = conv1x1 - BN - ReLU - conv3x3(stride) - BN - ReLU - conv1x1 - BN   (inner width `width`)
@@ -71,6 +82,7 @@ typedef struct {
     const lp_block_desc* blocks;   /* host pointer, copied by lp_net_create */
     int head, n_classes;
     int N, H, W, C;
+    int order;                     /* lp_block_order */
 } lp_module_desc;
 
 /* One AuxNet block generating x_{j+1} from the mini-batch (Sec. 4.2, forward map of the auxiliary-variable

@@ -9,6 +9,7 @@ LIB_PATH = os.path.join(_HERE, "liblp.so")
 LP_OK = 0
 LP_ERR_INVALID_ARG, LP_ERR_SHAPE, LP_ERR_DTYPE, LP_ERR_WORKSPACE, LP_ERR_STATE, LP_ERR_HIP = 1, 2, 3, 4, 5, 6
 LP_F32, LP_BF16 = 0, 1
+LP_ORDER_POST, LP_ORDER_PRE = 0, 1
 LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
@@ -18,7 +19,7 @@ EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
-              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad"}
+              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats"}
 
 
 class lp_block_desc(ctypes.Structure):
@@ -27,7 +28,8 @@ class lp_block_desc(ctypes.Structure):
 
 class lp_module_desc(ctypes.Structure):
     _fields_ = [("stem", c_int), ("stem_cout", c_int), ("n_blocks", c_int), ("blocks", POINTER(lp_block_desc)),
-                ("head", c_int), ("n_classes", c_int), ("N", c_int), ("H", c_int), ("W", c_int), ("C", c_int)]
+                ("head", c_int), ("n_classes", c_int), ("N", c_int), ("H", c_int), ("W", c_int), ("C", c_int),
+                ("order", c_int)]
 
 
 class lp_aux_desc(ctypes.Structure):
@@ -127,7 +129,8 @@ def lp_net_create(modules, aux, dtype, bn_eps):
             kind = b.kind if isinstance(b.kind, int) else {"basic": 0, "bottleneck": 1}[b.kind]
             blks[i] = lp_block_desc(kind, b.cin, b.cout, b.width, b.stride, int(b.proj))
         keep.append(blks)
-        mods[k] = lp_module_desc(int(m.stem), int(m.stem_cout), nb, blks, int(m.head), int(m.n_classes), m.N, m.H, m.W, m.C)
+        mods[k] = lp_module_desc(int(m.stem), int(m.stem_cout), nb, blks, int(m.head), int(m.n_classes), m.N, m.H, m.W, m.C,
+                                 {"post": LP_ORDER_POST, "pre": LP_ORDER_PRE}[getattr(m, "order", "post")])
     auxp = None
     if aux is not None:
         auxp = (lp_aux_desc * max(len(aux), 1))()

@@ -77,7 +77,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
 }
 
 enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
-              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD };
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS };
 
 struct Op {
     int type = 0, cfg = 0;
@@ -112,6 +112,7 @@ struct BlockPlan {
     Unit proj;
     std::vector<size_t> ws_act;            // activations between main convs
     Ref in, out;                           // block input / output tensors
+    Ref gout;                              // pre-activation order: gradient with respect to the block output (kept for the filter gradients)
     size_t in_elems = 0, out_elems = 0;
 };
 struct ModulePlan {
@@ -129,6 +130,8 @@ struct ModulePlan {
     size_t ws_feat = 0;                    // last module: F_k(x_k)
     size_t ws_pooled = 0, ws_dfeat = 0;
     int t_fcw = -1, t_fcb = -1;
+    int t_hg = -1, t_hb = -1;              // pre-activation order: BN in front of the head
+    size_t ws_hstats = 0, ws_hred = 0, ws_hf = 0, ws_ghead = 0, ws_gstem = 0;
     size_t ws_stats0 = 0, ws_stats_bytes = 0, ws_red0 = 0, ws_red_bytes = 0;
     size_t ws_G[2] = {0, 0}, ws_A = 0, ws_P = 0, ws_gpool = 0;
     Program fwd, bwd, bwd_dx0;             // bwd_dx0: variant that also produces dx for a stem-less module 0
@@ -321,6 +324,13 @@ struct Builder {
         o.bnb.M = M; o.bnb.C = C; o.bnb.relu = relu;
         o.r[0] = g; o.r[1] = y; o.r[2] = dy; o.r[3] = stats; o.r[4] = gamma; o.r[5] = beta; o.r[6] = red;
         o.r[7] = dgamma; o.r[8] = dbeta;
+        return o;
+    }
+    Op bn_stats(int M, int C, Ref y, Ref stats) const {
+        Op o; o.type = OP_BN_STATS;
+        memset(&o.bnb, 0, sizeof(o.bnb));
+        o.bnb.M = M; o.bnb.C = C;
+        o.r[1] = y; o.r[6] = stats;
         return o;
     }
 };
@@ -672,6 +682,252 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
     return LP_OK;
 }
 
+// ---- build one module in the pre-activation order (Fig. 2): every conv3x3 of a block is preceded by BN-ReLU, the
+// skip is the block input (or a bare conv1x1 of the activated input), the stem is a bare conv3x3 and the head is
+// BN-ReLU-avgpool-linear.  Unit fields: t_g/t_b and ws_stats/ws_red belong to the BN in FRONT of the conv (cin channels).
+static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
+    ModulePlan& m = net->mods[k];
+    const lp_module_desc& d = m.d;
+    const int dt = net->dtype;
+    const size_t esz = net->esz;
+    const int epv = dt == LP_BF16 ? 8 : 4;
+    const bool last = (k == net->K - 1);
+    size_t poff = 0, goff = 0;
+    int N = d.N, H = d.H, W = d.W, C = d.C;
+    auto check_c = [&](int c, const char* what) -> lp_status {
+        if (c <= 0 || c % epv != 0 || c > 2048)
+            return fail(LP_ERR_SHAPE, "module %d: %s = %d must be a positive multiple of %d and at most 2048", k, what, c, epv);
+        return LP_OK;
+    };
+    lp_status st;
+    if (d.stem == 1) {
+        if ((st = check_c(d.stem_cout, "stem_cout")) != LP_OK) return st;
+        m.has_stem = true;
+        m.stem = make_unit(3, C, d.stem_cout, 1, 1, N, H, W, false);
+        m.stem.need_dgrad = false;
+        m.stem.t_w = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_CONV, -1, 0, dt, {d.stem_cout, 3, 3, C});
+        C = d.stem_cout;
+    } else if (d.stem != 0) {
+        return fail(LP_ERR_SHAPE, "module %d: the pre-activation order supports stem 0 or 1", k);
+    } else if ((st = check_c(C, "input channels C")) != LP_OK) return st;
+
+    for (int i = 0; i < d.n_blocks; ++i) {
+        const lp_block_desc& b = m.blocks[i];
+        if (b.kind != LP_BLOCK_BASIC) return fail(LP_ERR_SHAPE, "module %d block %d: the pre-activation order supports basic blocks", k, i);
+        if (b.cin != C) return fail(LP_ERR_SHAPE, "module %d block %d: cin %d does not match incoming %d channels", k, i, b.cin, C);
+        if (b.stride != 1 && b.stride != 2) return fail(LP_ERR_SHAPE, "module %d block %d: stride %d (1 or 2)", k, i, b.stride);
+        if (H % b.stride || W % b.stride) return fail(LP_ERR_SHAPE, "module %d block %d: %dx%d not divisible by stride", k, i, H, W);
+        if ((b.stride != 1 || b.cin != b.cout) && !b.proj)
+            return fail(LP_ERR_SHAPE, "module %d block %d: shape changes, projection required", k, i);
+        if ((st = check_c(b.cout, "cout")) != LP_OK) return st;
+        BlockPlan bp;
+        bp.main.push_back(make_unit(3, b.cin, b.cout, b.stride, 1, N, H, W, true));
+        bp.main.push_back(make_unit(3, b.cout, b.cout, 1, 1, N, H / b.stride, W / b.stride, true));
+        for (int j = 0; j < 2; ++j) {
+            Unit& u = bp.main[j];
+            u.t_g = (int)m.tensors.size();
+            add_tensor(m.tensors, poff, goff, LP_T_BN_GAMMA, i, j, LP_F32, {u.cin});
+            u.t_b = (int)m.tensors.size();
+            add_tensor(m.tensors, poff, goff, LP_T_BN_BETA, i, j, LP_F32, {u.cin});
+            u.t_w = (int)m.tensors.size();
+            add_tensor(m.tensors, poff, goff, LP_T_CONV, i, j, dt, {u.cout, 3, 3, u.cin});
+        }
+        if (b.proj) {
+            bp.has_proj = true;
+            bp.proj = make_unit(1, b.cin, b.cout, b.stride, 0, N, H, W, false);
+            bp.proj.t_w = (int)m.tensors.size();
+            add_tensor(m.tensors, poff, goff, LP_T_CONV, i, 3, dt, {b.cout, 1, 1, b.cin});
+        }
+        bp.in_elems = (size_t)N * H * W * C;
+        H /= b.stride; W /= b.stride; C = b.cout;
+        bp.out_elems = (size_t)N * H * W * C;
+        if (bp.in_elems >= (1u << 31) || bp.out_elems >= (1u << 31))
+            return fail(LP_ERR_SHAPE, "module %d block %d: tensor beyond 2^31 elements", k, i);
+        m.bp.push_back(bp);
+    }
+    if (m.bp.empty()) return fail(LP_ERR_SHAPE, "module %d: at least one residual block is required", k);
+    m.oN = N; m.oH = H; m.oW = W; m.oC = C;
+    if (d.head != (last ? 1 : 0))
+        return fail(LP_ERR_SHAPE, "module %d: head must be set on the last module and only there", k);
+    if (last) {
+        if (d.n_classes < 1) return fail(LP_ERR_INVALID_ARG, "module %d: n_classes %d", k, d.n_classes);
+        m.t_hg = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_BN_GAMMA, d.n_blocks, 0, LP_F32, {C});
+        m.t_hb = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_BN_BETA, d.n_blocks, 0, LP_F32, {C});
+        m.t_fcw = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_FC_W, d.n_blocks, 0, LP_F32, {d.n_classes, C});
+        m.t_fcb = (int)m.tensors.size();
+        add_tensor(m.tensors, poff, goff, LP_T_FC_B, d.n_blocks, 0, LP_F32, {d.n_classes});
+    }
+    m.param_bytes = poff; m.grad_bytes = goff;
+
+    // ---- workspace ------------------------------------------------------------------------------
+    const bool first_block_dx_optional = (k == 0 && !m.has_stem);
+    const size_t nb = m.bp.size();
+    m.ws_stats0 = ws.off;
+    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_stats = ws.take(sizeof(double) * 2 * u.cin);
+    if (last) m.ws_hstats = ws.take(sizeof(double) * 2 * C);
+    m.ws_stats_bytes = ws.off - m.ws_stats0;
+    m.ws_red0 = ws.off;
+    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_red = ws.take(sizeof(double) * 2 * u.cin);
+    if (last) m.ws_hred = ws.take(sizeof(double) * 2 * C);
+    m.ws_red_bytes = ws.off - m.ws_red0;
+    if (m.has_stem) {
+        m.ws_stem_act = ws.take(m.stem.out_elems() * esz);      // the bare stem output = input of the first block
+        m.ws_gstem = ws.take(m.stem.out_elems() * esz);
+    }
+    size_t maxIn = 0, maxMid = 0;
+    for (size_t i = 0; i < nb; ++i) {
+        BlockPlan& bp = m.bp[i];
+        Unit& u0 = bp.main[0];
+        Unit& u1 = bp.main[1];
+        bp.ws_act.push_back(ws.take(bp.in_elems * esz));         // o1 = ReLU(BN1(block input))
+        u0.ws_y = ws.take(u0.out_elems() * esz);                 // y1 = conv1(o1)
+        bp.ws_act.push_back(ws.take(u0.out_elems() * esz));      // o2 = ReLU(BN2(y1))
+        u0.ws_dy = ws.take(u0.out_elems() * esz);                // gradient on y1 (kept for the filter gradient)
+        u0.ws_wt = ws.take((size_t)u0.cout * 9 * u0.cin * esz);
+        u1.ws_wt = ws.take((size_t)u1.cout * 9 * u1.cin * esz);
+        if (bp.has_proj) {
+            bp.proj.ws_y = ws.take(bp.out_elems * esz);
+            bp.proj.ws_wt = ws.take((size_t)bp.proj.cout * bp.proj.cin * esz);
+        }
+        if (i == 0) bp.in = m.has_stem ? mk(SP_WS, 0, m.ws_stem_act) : mk(SP_X, k, 0);
+        else bp.in = m.bp[i - 1].out;
+        if (i + 1 == nb && !last) bp.out = mk(SP_Y, k, 0);
+        else {
+            const size_t o = ws.take(bp.out_elems * esz);
+            bp.out = mk(SP_WS, 0, o);
+            if (i + 1 == nb) m.ws_feat = o;
+        }
+        if (i + 1 == nb) {
+            if (last) { m.ws_ghead = ws.take(bp.out_elems * esz); bp.gout = mk(SP_WS, 0, m.ws_ghead); }
+            else bp.gout = mk(SP_DY, k, 0);
+        } else bp.gout = mk(SP_WS, 0, ws.take(bp.out_elems * esz));
+        maxIn = std::max(maxIn, bp.in_elems);
+        maxMid = std::max(maxMid, u0.out_elems());
+    }
+    m.ws_G[0] = ws.take(maxIn * esz);          // gradient on o1
+    m.ws_G[1] = ws.take(maxIn * esz);          // unwanted dx of a stem-less module 0
+    m.ws_A = ws.take(maxMid * esz);            // gradient on o2
+    m.ws_P = ws.take(maxIn * esz);             // data-gradient of the projection
+    if (last) {
+        m.ws_hf = ws.take((size_t)N * H * W * C * esz);
+        m.ws_pooled = ws.take((size_t)N * C * 4);
+        m.ws_dfeat = ws.take((size_t)N * H * W * C * esz);
+    }
+
+    // ---- forward program ----------------------------------------------------------------------------
+    Builder B{net};
+    auto W_ = [&](size_t off) { return mk(SP_WS, 0, off); };
+    auto wref = [&](const Unit& u) { return param_ref(m, k, u.t_w); };
+    auto gref = [&](const Unit& u) { return param_ref(m, k, u.t_g); };
+    auto bref = [&](const Unit& u) { return param_ref(m, k, u.t_b); };
+    auto Min = [&](const Unit& u) { return u.N * u.H * u.W; };
+    Program& F = m.fwd;
+    F.push_back(Step{B.fill(W_(m.ws_stats0), m.ws_stats_bytes)});
+    {
+        const Unit& f0 = m.bp[0].main[0];
+        if (m.has_stem) F.push_back(Step{B.conv_fwd(m.stem, mk(SP_X, k, 0), wref(m.stem), W_(m.ws_stem_act), W_(f0.ws_stats))});
+        else F.push_back(Step{B.bn_stats(Min(f0), f0.cin, mk(SP_X, k, 0), W_(f0.ws_stats))});
+    }
+    for (size_t i = 0; i < nb; ++i) {
+        BlockPlan& bp = m.bp[i];
+        const Unit& u0 = bp.main[0];
+        const Unit& u1 = bp.main[1];
+        const Ref o1 = W_(bp.ws_act[0]), y1 = W_(u0.ws_y), o2 = W_(bp.ws_act[1]);
+        F.push_back(Step{B.bn_apply(Min(u0), u0.cin, bp.in, o1, W_(u0.ws_stats), gref(u0), bref(u0), true)});
+        Step s{B.conv_fwd(u0, o1, wref(u0), y1, W_(u1.ws_stats))};
+        if (bp.has_proj) s.push_back(B.conv_fwd(bp.proj, o1, wref(bp.proj), W_(bp.proj.ws_y), Ref()));
+        F.push_back(s);
+        F.push_back(Step{B.bn_apply(Min(u1), u1.cin, y1, o2, W_(u1.ws_stats), gref(u1), bref(u1), true)});
+        // the statistics of the block output belong to whoever normalises it next: the following block or the head
+        Ref nstats;
+        if (i + 1 < nb) nstats = W_(m.bp[i + 1].main[0].ws_stats);
+        else if (last) nstats = W_(m.ws_hstats);
+        Op c2 = B.conv_fwd(u1, o2, wref(u1), bp.out, nstats);
+        c2.r[3] = bp.has_proj ? W_(bp.proj.ws_y) : bp.in;
+        F.push_back(Step{c2});
+    }
+    const int Mout = N * H * W;
+    if (last) {
+        F.push_back(Step{B.bn_apply(Mout, C, W_(m.ws_feat), W_(m.ws_hf), W_(m.ws_hstats), param_ref(m, k, m.t_hg),
+                                    param_ref(m, k, m.t_hb), true)});
+        Op o; o.type = OP_HEAD_FWD;
+        memset(&o.head, 0, sizeof(o.head));
+        o.head.N = N; o.head.HW = H * W; o.head.C = C; o.head.classes = d.n_classes;
+        o.r[0] = W_(m.ws_hf); o.r[1] = W_(m.ws_pooled);
+        o.r[2] = param_ref(m, k, m.t_fcw); o.r[3] = param_ref(m, k, m.t_fcb); o.r[4] = mk(SP_LOGITS, 0, 0);
+        F.push_back(Step{o});
+    }
+
+    // ---- backward program -----------------------------------------------------------------------------
+    for (int variant = 0; variant < (first_block_dx_optional ? 2 : 1); ++variant) {
+        const bool want_dx_first = first_block_dx_optional ? (variant == 1) : true;
+        Program& Bw = variant == 0 ? m.bwd : m.bwd_dx0;
+        Bw.push_back(Step{B.fill(W_(m.ws_red0), m.ws_red_bytes), B.fill(mk(SP_DPARAM, k, 0), m.grad_bytes)});
+        {
+            Step s;
+            for (auto& bp : m.bp) {
+                for (auto& u : bp.main) s.push_back(B.wtrans(u, wref(u), W_(u.ws_wt)));
+                if (bp.has_proj) s.push_back(B.wtrans(bp.proj, wref(bp.proj), W_(bp.proj.ws_wt)));
+            }
+            Bw.push_back(s);
+        }
+        if (last) {
+            Op o; o.type = OP_HEAD_BWD;
+            memset(&o.head, 0, sizeof(o.head));
+            o.head.N = N; o.head.HW = H * W; o.head.C = C; o.head.classes = d.n_classes;
+            o.r[1] = W_(m.ws_pooled); o.r[2] = param_ref(m, k, m.t_fcw); o.r[5] = mk(SP_DLOGITS, 0, 0);
+            o.r[6] = grad_ref(m, k, m.t_fcw); o.r[7] = grad_ref(m, k, m.t_fcb); o.r[8] = W_(m.ws_dfeat);
+            Bw.push_back(Step{o});
+            for (int type : {OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY})
+                Bw.push_back(Step{B.bn_bwd(type, Mout, C, W_(m.ws_dfeat), W_(m.ws_feat), W_(m.ws_ghead), W_(m.ws_hstats),
+                                           param_ref(m, k, m.t_hg), param_ref(m, k, m.t_hb), W_(m.ws_hred),
+                                           grad_ref(m, k, m.t_hg), grad_ref(m, k, m.t_hb), true)});
+        }
+        const Ref A = W_(m.ws_A), D1 = W_(m.ws_G[0]), Pp = W_(m.ws_P);
+        Step wg_tail;
+        for (int i = (int)nb - 1; i >= 0; --i) {
+            BlockPlan& bp = m.bp[i];
+            const Unit& u0 = bp.main[0];
+            const Unit& u1 = bp.main[1];
+            const Ref o1 = W_(bp.ws_act[0]), y1 = W_(u0.ws_y), o2 = W_(bp.ws_act[1]), dy1 = W_(u0.ws_dy);
+            Ref gin;                                 // gradient with respect to the block input
+            if (i > 0) gin = m.bp[i - 1].gout;
+            else if (m.has_stem) gin = W_(m.ws_gstem);
+            else gin = (k > 0 || want_dx_first) ? mk(SP_DX, k, 0) : W_(m.ws_G[1]);
+            {   // through conv2 (and the projection) into the two activations
+                Step s;
+                B.conv_dgrad(u1, bp.gout, W_(u1.ws_wt), A, Ref(), Ref(), s);
+                if (bp.has_proj) B.conv_dgrad(bp.proj, bp.gout, W_(bp.proj.ws_wt), Pp, Ref(), Ref(), s);
+                Bw.push_back(s);
+            }
+            wg_tail.push_back(B.wgrad(u1, o2, bp.gout, grad_ref(m, k, u1.t_w)));
+            if (bp.has_proj) wg_tail.push_back(B.wgrad(bp.proj, o1, bp.gout, grad_ref(m, k, bp.proj.t_w)));
+            for (int type : {OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY})
+                Bw.push_back(Step{B.bn_bwd(type, Min(u1), u1.cin, A, y1, dy1, W_(u1.ws_stats), gref(u1), bref(u1), W_(u1.ws_red),
+                                           grad_ref(m, k, u1.t_g), grad_ref(m, k, u1.t_b), true)});
+            wg_tail.push_back(B.wgrad(u0, o1, dy1, grad_ref(m, k, u0.t_w)));
+            {
+                Step s;
+                B.conv_dgrad(u0, dy1, W_(u0.ws_wt), D1, bp.has_proj ? Pp : Ref(), Ref(), s);
+                Bw.push_back(s);
+            }
+            for (int type : {OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY}) {
+                Op o = B.bn_bwd(type, Min(u0), u0.cin, D1, bp.in, gin, W_(u0.ws_stats), gref(u0), bref(u0), W_(u0.ws_red),
+                                grad_ref(m, k, u0.t_g), grad_ref(m, k, u0.t_b), true);
+                if (type == OP_BN_BWD_APPLY && !bp.has_proj) o.r[9] = bp.gout;      // identity skip
+                Bw.push_back(Step{o});
+            }
+        }
+        if (m.has_stem) wg_tail.push_back(B.wgrad(m.stem, mk(SP_X, k, 0), W_(m.ws_gstem), grad_ref(m, k, m.stem.t_w)));
+        Bw.push_back(wg_tail);
+    }
+    return LP_OK;
+}
+
 static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     AuxPlan& a = net->aux[j];
     const ModulePlan& m0 = net->mods[0];
@@ -743,7 +999,8 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
         case OP_FILL: bytes = (double)o.fill_bytes; break;
         case OP_BN_APPLY: bytes = (double)o.bna.M * o.bna.C * e * (o.bna.skip_mode ? 3.0 : 2.0); break;
         case OP_BN_BWD_REDUCE: bytes = (double)o.bnb.M * o.bnb.C * e * 2.0; break;
-        case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * 3.0; break;
+        case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * (o.r[9].space != SP_NONE ? 4.0 : 3.0); break;
+        case OP_BN_STATS: bytes = (double)o.bnb.M * o.bnb.C * e; break;
         case OP_POOL_FWD:
         case OP_POOL_BWD: bytes = ((double)o.pool.N * o.pool.H * o.pool.W + (double)o.pool.N * o.pool.Ho * o.pool.Wo) * o.pool.C * e; break;
         case OP_HEAD_FWD:
@@ -902,6 +1159,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 g.total_blocks = tot;
                 err = launch_bn_apply(g, dt, s);
             } break;
+            case OP_BN_STATS:
             case OP_BN_BWD_REDUCE:
             case OP_BN_BWD_APPLY: {
                 BnBwdGroup g; g.nprob = n; g.eps = net->eps; g.cmax = 0; int tot = 0;
@@ -913,13 +1171,15 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.stats = (const double*)resolve(o.r[3], b); p.gamma = (const float*)resolve(o.r[4], b);
                     p.beta = (const float*)resolve(o.r[5], b); p.red = (double*)resolve(o.r[6], b);
                     p.dgamma = (float*)resolve(o.r[7], b); p.dbeta = (float*)resolve(o.r[8], b);
+                    p.add = resolve(o.r[9], b);
                     p.block_start = tot;
-                    if (type == OP_BN_BWD_REDUCE) p.nblocks = std::max(1, std::min(256, (p.M + 63) / 64));
+                    if (type != OP_BN_BWD_APPLY) p.nblocks = std::max(1, std::min(256, (p.M + 63) / 64));
                     else p.nblocks = elem_blocks((size_t)p.M * p.C / epv);
                     tot += p.nblocks;
                 }
                 g.total_blocks = tot;
-                err = type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
+                err = type == OP_BN_STATS ? launch_bn_stats(g, dt, s)
+                      : type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
             } break;
             case OP_POOL_FWD:
             case OP_POOL_BWD:
@@ -1054,7 +1314,8 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
         if (m.d.n_blocks < 1 || m.d.n_blocks > 64 || !m.d.blocks) { st = fail(LP_ERR_INVALID_ARG, "module %d: n_blocks %d or blocks NULL", k, m.d.n_blocks); break; }
         m.blocks.assign(m.d.blocks, m.d.blocks + m.d.n_blocks);
         m.d.blocks = nullptr;
-        st = build_module(net, k, ws);
+        if (m.d.order != LP_ORDER_POST && m.d.order != LP_ORDER_PRE) { st = fail(LP_ERR_INVALID_ARG, "module %d: unknown block order %d", k, m.d.order); break; }
+        st = m.d.order == LP_ORDER_PRE ? build_module_pre(net, k, ws) : build_module(net, k, ws);
         if (st == LP_OK && k > 0) {
             const ModulePlan& p = net->mods[k - 1];
             if (p.oN != m.d.N || p.oH != m.d.H || p.oW != m.d.W || p.oC != m.d.C)
@@ -1489,6 +1750,7 @@ lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, cons
     if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
     if (!net->ws) return fail(LP_ERR_WORKSPACE, "no workspace set");
     const ModulePlan& m = net->mods[k];
+    if (m.d.order != LP_ORDER_POST) return fail(LP_ERR_INVALID_ARG, "module %d: the saved-tensor ids describe the conv-BN-ReLU order only", k);
     if (which == 0) {
         if (!m.has_stem) return fail(LP_ERR_INVALID_ARG, "module %d has no stem", k);
         *ptr = net->ws + (m.d.stem == 2 ? m.ws_pool_out : m.ws_stem_act);

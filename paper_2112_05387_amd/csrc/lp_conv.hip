@@ -209,20 +209,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
                 const int row = wm * TM + i * MT + acc_row<MT>(r, lane);
                 const int ro = s_rowoff[row];
                 float v = acc[i][j][r];
-                // the batch statistics describe the values as stored (rounded to T)
-                const float vs = to_float(from_float<T>(v));
-                cs1[j] += vs;
-                cs2[j] += vs * vs;
                 if (ro >= 0 && col < P.Ncol) {
                     const size_t o = (size_t)ro + col;
                     if (add0) v += to_float(add0[o]);
                     if (add1) v += to_float(add1[o]);
-                    out[o] = from_float<T>(v);
+                    const T st = from_float<T>(v);
+                    out[o] = st;
+                    // the batch statistics describe the values as stored (addends included, rounded to T)
+                    const float vs = to_float(st);
+                    cs1[j] += vs;
+                    cs2[j] += vs * vs;
                 }
             }
         }
     if (P.stats) {
-        // rows beyond M hold zeros (their operand rows were zero), so they do not disturb the sums
         float* red = reinterpret_cast<float*>(&As[0][0]);      // [WGM][BN][2], operands are dead by now
 #pragma unroll
         for (int j = 0; j < FN; ++j) {

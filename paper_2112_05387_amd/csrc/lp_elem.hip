@@ -208,6 +208,63 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
     }
 }
 
+// red[c] += sum y, red[C+c] += sum y^2 over this workgroup's rows (batch statistics of a tensor no convolution
+// of this module produced: a module input in the pre-activation order)
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void bn_stats_kernel(const BnBwdGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    __shared__ float s_red[kElemBlock * EPV * 2];
+    const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
+    const int C = P.C, M = P.M, cv = C / EPV;
+    const int b = blockIdx.x - P.block_start;
+    const int rows_pb = (M + P.nblocks - 1) / P.nblocks;
+    const int row0 = b * rows_pb, row1 = min(M, row0 + rows_pb);
+    const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    for (int cbase = 0; cbase < cv; cbase += kElemBlock) {
+        const int ncv = min(cv - cbase, kElemBlock);
+        const int rl = kElemBlock / ncv;
+        const int tcv = threadIdx.x % ncv, trl = threadIdx.x / ncv;
+        float a1[EPV], a2[EPV];
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) { a1[e] = 0.f; a2[e] = 0.f; }
+        if (trl < rl) {
+            const int c0 = (cbase + tcv) * EPV;
+            int r = row0 + trl;
+            for (; r + 3 * rl < row1; r += 4 * rl) {
+                float yv[4][EPV];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) Vec<T>::load(y + (size_t)(r + u * rl) * C + c0, yv[u]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) { a1[e] += yv[u][e]; a2[e] += yv[u][e] * yv[u][e]; }
+            }
+            for (; r < row1; r += rl) {
+                float yv[EPV];
+                Vec<T>::load(y + (size_t)r * C + c0, yv);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) { a1[e] += yv[e]; a2[e] += yv[e] * yv[e]; }
+            }
+        }
+        __syncthreads();
+        if (trl < rl) {
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                s_red[((trl * ncv + tcv) * EPV + e) * 2] = a1[e];
+                s_red[((trl * ncv + tcv) * EPV + e) * 2 + 1] = a2[e];
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < ncv * EPV; i += kElemBlock) {
+            float s1 = 0.f, s2 = 0.f;
+            for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
+            const int c = cbase * EPV + i;
+            atomicAdd(&P.red[c], (double)s1);
+            atomicAdd(&P.red[C + c], (double)s2);
+        }
+    }
+}
+
 // dy = gamma*invstd*(g' - red0/M - yhat*red1/M)
 template <typename T>
 __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGroup g) {
@@ -270,6 +327,12 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGro
             float gg = gv[e];
             if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
             o[e] = k1[e] * gg - k2[e] * yv[e] + k3[e];
+        }
+        if (P.add) {
+            float av[EPV];
+            Vec<T>::load(reinterpret_cast<const T*>(P.add) + v * EPV, av);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) o[e] += av[e];
         }
         Vec<T>::store(dy + v * EPV, o);
     }
@@ -631,6 +694,11 @@ hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s) {
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     LP_DISPATCH_T(dtype, bn_bwd_reduce_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    return hipGetLastError();
+}
+hipError_t launch_bn_stats(const BnBwdGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, bn_stats_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
     return hipGetLastError();
 }
 hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s) {

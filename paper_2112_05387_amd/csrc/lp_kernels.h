@@ -85,7 +85,8 @@ struct BnApplyGroup {
 // Batch-norm backward.  g' = g * [gamma*yhat + beta > 0] when relu is set.
 // reduce: red[0..C) += sum g', red[C..2C) += sum g'*yhat.   apply: dy = gamma*invstd*(g' - red0/M - yhat*red1/M),
 // and the first workgroup of each problem writes dgamma = red1, dbeta = red0.
-struct BnBwdProb {
+struct BnBwdProb {       // add: optional addend of the apply pass with the layout of dy (identity skip of a pre-activation block)
+    const void* add;
     const void* g; const void* y; void* dy;
     const double* stats; const float* gamma; const float* beta;
     double* red; float* dgamma; float* dbeta;
@@ -159,6 +160,8 @@ hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s);
 hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s);
 hipError_t launch_auxvar(const AuxVarGroup& g, int dtype, hipStream_t s);
 hipError_t launch_sgd(const SgdGroup& g, hipStream_t s);
+// per-channel sum and sum of squares of a stored tensor [M, C] (fields y, red, M, C of BnBwdProb), added to red[2C]
+hipError_t launch_bn_stats(const BnBwdGroup& g, int dtype, hipStream_t s);
 constexpr int kSgdElemsPerBlock = 4096;
 hipError_t launch_maxpool_fwd(const PoolProb& p, int dtype, hipStream_t s);
 hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s);

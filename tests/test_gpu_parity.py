@@ -66,6 +66,32 @@ def test_wrn_layer_serial_reduced_batch():
     compare_step(wl.make_config("wrn28_10", batch=2, split=[12]))
 
 
+@pytest.mark.parametrize("dtype,serial", [("f32", False), ("bf16", False), ("f32", True)])
+def test_pre_activation_order(dtype, serial):
+    """BN-ReLU-conv blocks (Fig. 2), bare conv stem, BN-ReLU head: the mini network with K = 3 and as one module."""
+    from workloads import configs as cfg
+    net = cfg.with_order(gpu_mini_basic(dtype=dtype, serial=serial), "pre")
+    net.al, net.lam_sigma, net.rho = True, 0.05, 1.5
+    say("case mini_basic pre-activation", dtype, "K=1" if serial else "K=3")
+    compare_step(net, scale=0.5)
+
+
+def test_pre_activation_stemless_dx0():
+    """Pre-activation blocks without a stem (the statistics of the module input come from the stand-alone
+    reduction), dx[0] requested."""
+    from workloads import configs as cfg
+    net = wl.make_config("tiny")
+    cfg.with_order(net, "pre")
+    say("case tiny pre-activation f32")
+    compare_step(net, want_dx0=True)
+
+
+def test_wrn_pre_activation_reduced_batch():
+    from workloads import configs as cfg
+    say("case wrn28_10 pre-activation batch 2 bf16")
+    compare_step(cfg.with_order(wl.make_config("wrn28_10", batch=2), "pre"))
+
+
 def test_mini_wide_ragged_tiles():
     say("case mini_wide bf16")
     compare_step(gpu_mini_wide())
