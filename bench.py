@@ -168,6 +168,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run three plain 256 MiB device copies (a known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--lanes", default="default",
+                    help="default: the library's concurrent stream lanes; single: every module on one stream; or one "
+                         "digit 0..3 per module, e.g. 1200 (the result is then not the headline)")
     ap.add_argument("--order", choices=["post", "pre"], default="post",
                     help="block order: post = conv-BN-ReLU (the headline configuration), pre = BN-ReLU-conv (Fig. 2)")
     ap.add_argument("--speedup-terms", action="store_true",
@@ -193,21 +196,38 @@ def main():
         one_step(ls, net)
     torch.cuda.synchronize()
 
-    # timed region: EXACTLY --steps steps; every grouped launch is bracketed by hipEvents on the same stream
-    B.lp_profile_enable(ls.net, 1)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        one_step(ls, net)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = ev0.elapsed_time(ev1)
-    recs = B.lp_profile_fetch(ls.net)
-    B.lp_profile_enable(ls.net, 0)
+    if args.lanes != "default":
+        ls.set_stream_lanes(None if args.lanes == "single" else [int(c) for c in args.lanes])
+        for _ in range(args.warmup):
+            one_step(ls, net)
+
+    def timed_steps(profile):
+        # EXACTLY --steps steps; profile = 2: every grouped launch is bracketed by hipEvents and issued on one stream
+        B.lp_profile_enable(ls.net, profile)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(args.steps):
+            one_step(ls, net)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        recs = B.lp_profile_fetch(ls.net) if profile else []
+        B.lp_profile_enable(ls.net, 0)
+        return wall, ev0.elapsed_time(ev1), recs
+
+    # The timed region: the step as the library runs it (modules of different widths on concurrent stream lanes, no
+    # events between launches).  Kernels of different lanes overlap there, so a kernel's own duration is measured in a
+    # second pass over the same steps with every module on the caller's stream: full grouped launches, one after
+    # another, each bracketed by hipEvents (this is also what `--lanes single` times and what the rocprofv3
+    # summaries under profiles/ are taken with).
+    wall_ms, gpu_ms, _ = timed_steps(0)
     ms_per_step = wall_ms / args.steps
+    ls.set_stream_lanes(None)
+    one_step(ls, net)
+    iso_wall, gpu_iso, recs = timed_steps(1)
+    iso_ms_per_step = iso_wall / args.steps
 
     # per-kernel aggregation (kind, tile configuration)
     agg = {}
@@ -225,7 +245,8 @@ def main():
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
     roof.update({"traffic": None, "kernel": f"{B.KIND_NAMES[dk]} cfg{dcfg}", "launches_per_step": dom["launches"] / args.steps,
-                 "avg_launch_ms": dom["ms"] / dom["launches"], "share_of_gpu_time": dom["ms"] / max(gpu_ms, 1e-9)})
+                 "avg_launch_ms": dom["ms"] / dom["launches"], "share_of_gpu_time": dom["ms"] / max(gpu_iso, 1e-9),
+                 "measured": "launch durations from a second pass of the same steps with every module on one stream"})
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
@@ -242,7 +263,8 @@ def main():
             gb = a["bytes"] / (a["ms"] * 1e-3) / 1e9 if a["ms"] > 0 else 0.0
             print(f"  {B.KIND_NAMES[k]:24s} cfg{c} launches/step {a['launches'] / args.steps:6.1f}  ms/step {a['ms'] / args.steps:8.3f}"
                   f"  TFLOP/s {tf:8.1f}  GB/s(alg) {gb:8.1f}", file=sys.stderr)
-        print(f"  GPU time/step by events {gpu_ms / args.steps:.3f} ms, wall {ms_per_step:.3f} ms", file=sys.stderr)
+        print(f"  one stream: GPU time/step by events {gpu_iso / args.steps:.3f} ms; timed region ({args.lanes} lanes): "
+              f"{gpu_ms / args.steps:.3f} ms by events, wall {ms_per_step:.3f} ms", file=sys.stderr)
 
     out = {
         "metric": "module-parallel local-step samples/s (all K modules); conv TFLOP/s vs MFMA peak",
@@ -257,6 +279,8 @@ def main():
         "conv_frac_of_mfma_peak": (conv_flops / (conv_ms * 1e-3) / 1e12) / peak if conv_ms > 0 else None,
         "conv_tflop_per_step": cfg.conv_flops_step(net) / 1e12,
         "gpu_ms_per_step_events": gpu_ms / args.steps,
+        "stream_lanes": args.lanes, "ms_per_step_one_stream_with_events": iso_ms_per_step,
+        "step_conv_tflops": cfg.conv_flops_step(net) / (ms_per_step * 1e-3) / 1e12,
         "roofline": roof,
     }
     # the parameter update that follows a step (not part of `value`): momentum form, fp32 velocity, timed by events

@@ -118,6 +118,16 @@ lp_status lp_net_param_bytes(const struct lp_net* net, int aux, int k, size_t* p
 lp_status lp_net_num_tensors(const struct lp_net* net, int aux, int k, int* n);
 lp_status lp_net_tensor_info(const struct lp_net* net, int aux, int k, int i, lp_tensor_info* info);
 
+/* Stream lanes of lp_module_forward / lp_module_backward.  The modules of a step are independent (Sec. 4.1: each
+ * starts from its own auxiliary variable), so their kernel sequences may overlap: modules with lanes[k] = 0 are
+ * enqueued on the caller's stream, modules with lanes[k] = 1..3 on streams the net owns (created at the first call that
+ * needs them, default priority, destroyed with the net).  Modules of one lane are merged into grouped launches with
+ * each other only.  Every call forks from the caller's stream and joins it again before it returns (events, no host
+ * wait), so for the caller all work is ordered on `stream` as before; the pattern is legal under stream capture.
+ * lp_net_create picks a default (modules of equal output width share a lane); lanes == NULL puts every module on the
+ * caller's stream.  Host only.  Error: LP_ERR_INVALID_ARG (lane outside [0, 3]). */
+lp_status lp_net_set_stream_lanes(struct lp_net* net, const int* lanes);
+
 /* Workspace: saved activations, batch statistics, gradient scratch, re-laid-out filters.  The caller
  * allocates `bytes` of device memory (256-byte aligned) and lends it for the lifetime of the net. */
 lp_status lp_net_workspace_bytes(const struct lp_net* net, size_t* bytes);
@@ -225,11 +235,14 @@ lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, in
 lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel);
 
 /* Optional per-launch timing.  While enabled, every grouped kernel launch made by lp_auxnet_forward,
- * lp_module_forward and lp_module_backward is bracketed by two hipEvents on the caller's stream.
+ * lp_module_forward and lp_module_backward is bracketed by two hipEvents on the stream it is enqueued on.
+ * on = 1: launches of different stream lanes still overlap, so a record's duration includes the time its kernel
+ * shared the device; on = 2: the same launches (same grouping per lane) are all enqueued on the caller's stream, one
+ * after another, so that every record is the duration of its kernel alone.
  * lp_profile_fetch waits for the recorded launches, returns one record per launch in issue order and clears
  * the list (out == NULL: only the count).  kind: 0 clear, 1 filter re-layout, 2 conv forward/data-gradient,
  * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
- * apply, 10 conv weight-gradient.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
+ * apply, 10 conv weight-gradient, 11 batch statistics of a module input.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
  * every operand tensor moved once). */
 typedef struct { int kind, cfg, nprob; float ms; double flops, bytes; } lp_profile_rec;
 lp_status lp_profile_enable(struct lp_net* net, int on);

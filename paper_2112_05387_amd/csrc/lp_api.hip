@@ -159,8 +159,14 @@ struct lp_net {
     uint32_t fwd_done = 0;
     bool aux_fwd_done = false;
     std::vector<const void*> saved_x;
+    // optional second stream: modules in side_mask are issued there, concurrently with the others
+    std::vector<int> lane;                 // per module: 0 = the caller's stream, 1..3 = extra stream
+    hipStream_t extra_stream[4] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
     // optional per-launch timing (hipEvents around every grouped launch)
     bool prof = false;
+    int lanes_in_flight = 1;               // stream lanes of the call being enqueued (launch-time tile choice)
+    bool prof_serial = false;              // issue every stream lane on the caller's stream (launches timed in isolation)
     struct ProfRec { hipEvent_t a, b; int type, cfg, nprob; double flops, bytes; };
     std::vector<ProfRec> prof_recs;
     std::vector<hipEvent_t> prof_pool;
@@ -1107,10 +1113,13 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                         }
                         k64 = k64 && (c.Cin % 64 == 0);
                     }
+                    // alone on the device a launch wants at least 200 tiles; next to the launches of other stream lanes
+                    // the idle compute units are not lost, and the larger tile's better operand reuse wins
+                    const int T1 = net->lanes_in_flight > 1 ? 64 : 200, T2 = 200, T3 = 200;
                     if (cfg == FAST_256x320) {
-                        if (big < 200) cfg = mid < 200 ? FAST_128x160 : FAST_128x320;
+                        if (big < T1) cfg = mid < T2 ? FAST_128x160 : FAST_128x320;
                         if (k64) cfg = cfg == FAST_256x320 ? FAST64_256x320 : cfg == FAST_128x320 ? FAST64_128x320 : FAST64_128x160;
-                    } else if (big < 200) {
+                    } else if (big < T3) {
                         cfg = k64 ? FAST64_256x160 : FAST_256x160;
                     }
                 }
@@ -1209,7 +1218,8 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
     return err;
 }
 
-static lp_status run_programs(lp_net* net, const std::vector<const Program*>& progs, const Bindings& b, hipStream_t s) {
+// Order of the grouped launches of a set of independent programs (no launch happens here).
+static void plan_programs(const std::vector<const Program*>& progs, std::vector<std::vector<const Op*>>& plan) {
     const size_t np = progs.size();
     std::vector<size_t> step(np, 0);
     std::vector<std::vector<char>> issued(np);
@@ -1266,8 +1276,7 @@ static lp_status run_programs(lp_net* net, const std::vector<const Program*>& pr
             for (size_t j = 0; j < st.size(); ++j)
                 if (!issued[i][j] && st[j].key() == best_key) { ops.push_back(&st[j]); issued[i][j] = 1; }
         }
-        const hipError_t err = launch_group(net, ops, b, s);
-        if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+        plan.push_back(ops);
         for (size_t i = 0; i < np; ++i) {
             if (step[i] >= progs[i]->size()) continue;
             bool done = true;
@@ -1278,9 +1287,80 @@ static lp_status run_programs(lp_net* net, const std::vector<const Program*>& pr
             }
         }
     }
+}
+
+static lp_status run_programs(lp_net* net, const std::vector<const Program*>& progs, const Bindings& b, hipStream_t s,
+                              const std::vector<int>* lane = nullptr) {
+    // lane[i]: 0 = program i is issued on the caller's stream, j > 0 = on the net's j-th extra stream, concurrently.
+    // Programs of one lane are grouped with each other only.
+    constexpr int kLanes = 4;
+    std::vector<const Program*> set[kLanes];
+    for (size_t i = 0; i < progs.size(); ++i) set[lane ? std::min(std::max((*lane)[i], 0), kLanes - 1) : 0].push_back(progs[i]);
+    std::vector<std::vector<const Op*>> plan[kLanes];
+    int used = 0;
+    for (int l = 0; l < kLanes; ++l) if (!set[l].empty()) { plan_programs(set[l], plan[l]); ++used; }
+    hipError_t err = hipSuccess;
+    net->lanes_in_flight = std::max(used, 1);
+    if (used <= 1) {
+        for (int l = 0; l < kLanes; ++l)
+            for (auto& ops : plan[l]) {
+                err = launch_group(net, ops, b, s);
+                if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+            }
+        return LP_OK;
+    }
+    if (!net->ev_fork) {
+        if ((err = hipEventCreateWithFlags(&net->ev_fork, hipEventDisableTiming)) != hipSuccess)
+            return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
+        for (int l = 1; l < kLanes; ++l)
+            if ((err = hipStreamCreateWithFlags(&net->extra_stream[l], hipStreamNonBlocking)) != hipSuccess ||
+                (err = hipEventCreateWithFlags(&net->ev_join[l], hipEventDisableTiming)) != hipSuccess)
+                return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
+    }
+    if (net->prof && net->prof_serial) {
+        size_t pos[kLanes] = {0, 0, 0, 0};
+        for (bool more = true; more;) {
+            more = false;
+            for (int l = 0; l < kLanes; ++l)
+                if (pos[l] < plan[l].size()) {
+                    if ((err = launch_group(net, plan[l][pos[l]++], b, s)) != hipSuccess)
+                        return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+                    more = true;
+                }
+        }
+        return LP_OK;
+    }
+    hipStream_t st[kLanes];
+    st[0] = s;
+    for (int l = 1; l < kLanes; ++l) st[l] = net->extra_stream[l];
+    if ((err = hipEventRecord(net->ev_fork, s)) != hipSuccess) return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
+    for (int l = 1; l < kLanes; ++l)
+        if (!plan[l].empty() && (err = hipStreamWaitEvent(st[l], net->ev_fork, 0)) != hipSuccess)
+            return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
+    size_t pos[kLanes] = {0, 0, 0, 0};
+    for (bool more = true; more && err == hipSuccess;) {
+        more = false;
+        for (int l = 0; l < kLanes && err == hipSuccess; ++l)
+            if (pos[l] < plan[l].size()) { err = launch_group(net, plan[l][pos[l]++], b, st[l]); more = true; }
+    }
+    // join even after a failed launch: the caller's stream must not run ahead of what was enqueued on the others
+    for (int l = 1; l < kLanes; ++l) {
+        if (plan[l].empty()) continue;
+        hipError_t e2 = hipEventRecord(net->ev_join[l], st[l]);
+        if (e2 == hipSuccess) e2 = hipStreamWaitEvent(s, net->ev_join[l], 0);
+        if (err == hipSuccess) err = e2;
+    }
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
     return LP_OK;
 }
 
+// stream lane of every selected module, in the order the programs are collected
+static std::vector<int> lanes_of(const lp_net* net, uint32_t module_mask) {
+    std::vector<int> out;
+    for (int k = 0; k < net->K; ++k)
+        if ((module_mask >> k) & 1u) out.push_back(k < (int)net->lane.size() ? net->lane[k] : 0);
+    return out;
+}
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 }  // namespace
@@ -1332,12 +1412,31 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
     }
     if (st != LP_OK) { delete net; return st; }
     net->ws_bytes = ws.off;
+    // Default stream lanes: modules of the same output width run the same layer shapes and merge into full launches,
+    // so they share a lane; modules of different widths get lanes of their own (at most four), where the memory-bound
+    // passes of one overlap the matrix-bound passes of another and the launches fill each other's tails.
+    net->lane.assign(K, 0);
+    {
+        std::vector<int> widths;
+        for (int k = 0; k < K; ++k) {
+            const int w = net->mods[k].oC;
+            size_t i = 0;
+            while (i < widths.size() && widths[i] != w) ++i;
+            if (i == widths.size()) widths.push_back(w);
+            net->lane[k] = (int)std::min<size_t>(i, 3);
+        }
+    }
     *out = net;
     return LP_OK;
 }
 
 lp_status lp_net_destroy(struct lp_net* net) {
     if (net) {
+        if (net->ev_fork) (void)hipEventDestroy(net->ev_fork);
+        for (int l = 1; l < 4; ++l) {
+            if (net->extra_stream[l]) (void)hipStreamDestroy(net->extra_stream[l]);
+            if (net->ev_join[l]) (void)hipEventDestroy(net->ev_join[l]);
+        }
         for (auto& r : net->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (hipEvent_t e : net->prof_pool) (void)hipEventDestroy(e);
     }
@@ -1345,9 +1444,19 @@ lp_status lp_net_destroy(struct lp_net* net) {
     return LP_OK;
 }
 
+lp_status lp_net_set_stream_lanes(struct lp_net* net, const int* lanes) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!lanes) { net->lane.assign(net->K, 0); return LP_OK; }
+    for (int k = 0; k < net->K; ++k)
+        if (lanes[k] < 0 || lanes[k] > 3) return fail(LP_ERR_INVALID_ARG, "lanes[%d] = %d outside [0, 3]", k, lanes[k]);
+    net->lane.assign(lanes, lanes + net->K);
+    return LP_OK;
+}
+
 lp_status lp_profile_enable(struct lp_net* net, int on) {
     if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
     net->prof = on != 0;
+    net->prof_serial = on == 2;
     return LP_OK;
 }
 
@@ -1545,7 +1654,8 @@ lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_ma
         progs.push_back(&net->mods[k].fwd);
     }
     Bindings b; b.ws = net->ws; b.x = x; b.params = params; b.y = y; b.logits = logits;
-    st = run_programs(net, progs, b, (hipStream_t)stream);
+    const std::vector<int> lanes = lanes_of(net, module_mask);
+    st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
     if (st == LP_OK) {
         for (int k = 0; k < net->K; ++k)
             if ((module_mask >> k) & 1u) { net->saved_x[k] = x[k]; net->fwd_done |= (1u << k); }
@@ -1626,7 +1736,8 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
     }
     Bindings b; b.ws = net->ws; b.x = net->saved_x.data(); b.params = params; b.dparams = dparams; b.dy = dy; b.dx = dx;
     b.dlogits = dlogits;
-    st = run_programs(net, progs, b, (hipStream_t)stream);
+    const std::vector<int> lanes = lanes_of(net, module_mask);
+    st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
     if (st == LP_OK) net->fwd_done &= ~module_mask;
     return st;
 }

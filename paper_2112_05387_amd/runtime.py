@@ -61,6 +61,12 @@ class LocalStep:
         self.labels = torch.zeros((self.N,), dtype=torch.int32, device=self.dev)
         self.loss = torch.zeros((self.K,), dtype=torch.float32, device=self.dev)
 
+    def set_stream_lanes(self, lanes):
+        """lanes[k] in 0..3 (0 = the caller's stream) or None for a single stream."""
+        if lanes is not None:
+            assert len(lanes) == self.K
+        B.lp_net_set_stream_lanes(self.net, lanes)
+
     def close(self):
         if self.net is not None:
             torch.cuda.synchronize()

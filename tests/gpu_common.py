@@ -94,7 +94,7 @@ def _oracle_pieces(net, inp, scale, want_dx0, q):
     return o
 
 
-def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True):
+def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes="default"):
     """Parity of the whole local step on identical seeded inputs.
 
     fp32 mode: the oracle is the plain float64 definition, tolerance 1e-4 on every tensor.
@@ -156,6 +156,8 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True):
     ls = LocalStep(net)
     worst = {}
     try:
+        if lanes != "default":
+            ls.set_stream_lanes(lanes)
         load_step(ls, net, inp)
         if net.aux is not None and check_aux:
             ls.auxnet_forward()

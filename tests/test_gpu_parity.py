@@ -92,6 +92,16 @@ def test_wrn_pre_activation_reduced_batch():
     compare_step(cfg.with_order(wl.make_config("wrn28_10", batch=2), "pre"))
 
 
+@pytest.mark.parametrize("lanes", [None, [1, 2, 3], [0, 1, 1], [2, 0, 2]])
+def test_stream_lanes(lanes):
+    """The same step with every module on the caller's stream, every module on a stream of its own, and mixed
+    groupings: each must meet the parity bar (run twice in a row: the second pass re-forks from the joined stream)."""
+    net = gpu_mini_basic(dtype="bf16")
+    net.al, net.lam_sigma = True, 0.05
+    say("case stream lanes", lanes)
+    compare_step(net, lanes=lanes)
+
+
 def test_mini_wide_ragged_tiles():
     say("case mini_wide bf16")
     compare_step(gpu_mini_wide())
