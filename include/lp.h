@@ -124,8 +124,8 @@ lp_status lp_net_tensor_info(const struct lp_net* net, int aux, int k, int i, lp
  * needs them, default priority, destroyed with the net).  Modules of one lane are merged into grouped launches with
  * each other only.  Every call forks from the caller's stream and joins it again before it returns (events, no host
  * wait), so for the caller all work is ordered on `stream` as before; the pattern is legal under stream capture.
- * lp_net_create picks a default (modules of equal output width share a lane); lanes == NULL puts every module on the
- * caller's stream.  Host only.  Error: LP_ERR_INVALID_ARG (lane outside [0, 3]). */
+ * lp_net_create picks a default (K <= 4: a lane per module; otherwise modules of equal output width share a lane);
+ * lanes == NULL puts every module on the caller's stream.  Host only.  Error: LP_ERR_INVALID_ARG (lane outside [0, 3]). */
 lp_status lp_net_set_stream_lanes(struct lp_net* net, const int* lanes);
 
 /* Workspace: saved activations, batch statistics, gradient scratch, re-laid-out filters.  The caller

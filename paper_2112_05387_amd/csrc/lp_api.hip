@@ -195,6 +195,28 @@ static bool pick_fast_cfg(const lp_net* net, const ConvProb& c, int& cfg) {
     return true;
 }
 
+// the window kernel: 3x3 taps at offsets -1..1, stride 1, same-size input and output, tiles that are bands of whole
+// image rows (or whole images)
+static bool pick_win_cfg(const lp_net* net, const ConvProb& c, int& cfg) {
+    if (!conv_fast_ok(net, c)) return false;
+    if (c.ntr != 3 || c.nts != 3 || c.imul != 1 || c.omul != 1 || c.IH != c.OA || c.IW != c.OB || c.OH != c.OA || c.OW != c.OB)
+        return false;
+    for (int t = 0; t < 3; ++t)
+        if (std::abs(c.dh0 + c.dhs * t) > 1 || std::abs(c.dw0 + c.dws * t) > 1) return false;
+    const int BN = c.Ncol > 160 ? 320 : 160, BK = 64, BM = c.Ncol > 160 ? 256 : 512, NW = 8;
+    if (BM % c.OB != 0) return false;
+    const int TH = BM / c.OB;
+    if (c.OA % TH != 0 && TH % c.OA != 0) return false;
+    const int SH = std::min(TH, c.OA), NP = (TH / SH) * (SH + 2) * (c.OB + 2), RPS = 1024 / (BK * 2);
+    const int nslab = (NP + RPS - 1) / RPS;
+    if ((nslab + NW - 1) / NW > conv_win_max_slabs(BM, NW)) return false;
+    const size_t ring_end = (size_t)nslab * 1024 + (size_t)2 * BN * BK * 2;
+    if (std::max(ring_end, (size_t)NW * 32 * 336) + BM * sizeof(int) + (size_t)conv_win_max_slabs(BM, NW) * NW * 64 * 4 > 160 * 1024)
+        return false;
+    cfg = c.Ncol > 160 ? WIN64_256x320 : WIN64_512x160;
+    return true;
+}
+
 static int conv_cfg_for(int ncol, bool vec) {
     int cfg;
     if (ncol % 160 == 0) cfg = CFG_N160;
@@ -235,6 +257,7 @@ struct Builder {
         o.vec = (u.cin % epv()) == 0;
         o.cfg = conv_cfg_for(c.Ncol, o.vec);
         pick_fast_cfg(net, c, o.cfg);
+        pick_win_cfg(net, c, o.cfg);
         o.r[0] = in; o.r[1] = w; o.r[2] = out; o.r[5] = stats;
         return o;
     }
@@ -262,6 +285,7 @@ struct Builder {
                 o.vec = (u.cout % epv()) == 0;
                 o.cfg = conv_cfg_for(c.Ncol, o.vec);
                 pick_fast_cfg(net, c, o.cfg);
+                pick_win_cfg(net, c, o.cfg);
                 o.r[0] = dy; o.r[1] = wt; o.r[2] = dx; o.r[3] = add0; o.r[4] = add1;
                 step.push_back(o);
             }
@@ -1097,7 +1121,22 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             case OP_CONV: {
                 ConvGroup g; g.nprob = n; int tot = 0;
                 int cfg = ops[base]->cfg;
+                bool win = cfg >= WIN64_512x160;
                 const bool fast = cfg >= FAST_256x320;
+                if (win) {
+                    // The window kernel needs its eight-wave tiles (two waves per SIMD keep the matrix core fed) and
+                    // about one tile per compute unit; a launch with fewer tiles goes to the implicit-GEMM kernel,
+                    // whose smaller tile variants fill the chip.
+                    // (next to the launches of other stream lanes the idle compute units are not lost: keep it)
+                    const int TW = net->lanes_in_flight > 1 ? 0 : 200;
+                    long big = 0;
+                    for (int i = 0; i < n; ++i) {
+                        const ConvProb& c = ops[base + i]->conv;
+                        big += cfg == WIN64_256x320 ? (long)((c.M + 255) / 256) * ((c.Ncol + 319) / 320)
+                                                    : (long)((c.M + 511) / 512) * ((c.Ncol + 159) / 160);
+                    }
+                    if (big < TW) { cfg = cfg == WIN64_256x320 ? FAST_256x320 : FAST_512x160; win = false; }
+                }
                 if (cfg == FAST_256x320 || cfg == FAST_512x160) {
                     // Too few full-size tiles for the chip: the four-wave variants (and the two-wave one of the
                     // 320-wide family).  k-tiles of 64 channels where every problem allows them and the tile fits.
@@ -1124,7 +1163,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     }
                 }
                 if (used_cfg) *used_cfg = cfg;
-                const CfgInfo ci = fast ? conv_fast_cfg_info(cfg) : conv_cfg_info(cfg, dt);
+                const CfgInfo ci = win ? conv_win_cfg_info(cfg) : fast ? conv_fast_cfg_info(cfg) : conv_cfg_info(cfg, dt);
                 // longest tiles first: the blocks of a launch are dispatched in order
                 std::stable_sort(ops.begin() + base, ops.begin() + base + n,
                                  [](const Op* a, const Op* b2) { return a->conv.Kg > b2->conv.Kg; });
@@ -1137,7 +1176,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
-                err = fast ? launch_conv_fast(g, cfg, s) : launch_conv(g, dt, cfg, ops[base]->vec, s);
+                err = win ? launch_conv_win(g, cfg, s) : fast ? launch_conv_fast(g, cfg, s) : launch_conv(g, dt, cfg, ops[base]->vec, s);
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;
@@ -1412,11 +1451,13 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
     }
     if (st != LP_OK) { delete net; return st; }
     net->ws_bytes = ws.off;
-    // Default stream lanes: modules of the same output width run the same layer shapes and merge into full launches,
-    // so they share a lane; modules of different widths get lanes of their own (at most four), where the memory-bound
-    // passes of one overlap the matrix-bound passes of another and the launches fill each other's tails.
+    // Default stream lanes.  Up to four modules: a lane each, so that the memory-bound passes of one module overlap
+    // the matrix-bound passes of another and launches fill each other's tails.  More modules: those of the same
+    // output width run the same layer shapes and merge into full launches, so they share a lane (at most four lanes).
     net->lane.assign(K, 0);
-    {
+    if (K <= 4) {
+        for (int k = 0; k < K; ++k) net->lane[k] = k;
+    } else {
         std::vector<int> widths;
         for (int k = 0; k < K; ++k) {
             const int w = net->mods[k].oC;

@@ -139,14 +139,19 @@ enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160, CFG_COUNT,
                FAST_128x320 = 10, FAST_128x160 = 11,   // ... its four- and two-wave variants, chosen per launch
                FAST64_256x320 = 12, FAST64_128x320 = 13, FAST64_128x160 = 14,   // ... with k-tiles of 64 channels
                FAST_256x160 = 15, FAST64_256x160 = 16,  // four-wave variants of the 160-wide family
+               WIN64_512x160 = 21, WIN64_256x320 = 23,  // bf16 3x3 stride-1 kernel with the input window in LDS (lp_conv_win.hip)
                WGRAD_FAST = 8 };                       // bf16 wide-layer filter-gradient kernel (lp_wgrad_fast.hip)
 struct CfgInfo { int BM, BN, BK; };
 CfgInfo conv_cfg_info(int cfg, int dtype);
 CfgInfo wgrad_cfg_info(int cfg, int dtype);
 CfgInfo conv_fast_cfg_info(int cfg);
+CfgInfo conv_win_cfg_info(int cfg);
+// window slabs (1 KiB wave-loads) a wave of the window kernel can hold addresses for
+constexpr int conv_win_max_slabs(int BM, int NW) { return BM == 512 ? 10 : 7; }
 
 hipError_t launch_conv(const ConvGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
 hipError_t launch_conv_fast(const ConvGroup& g, int cfg, hipStream_t s);
+hipError_t launch_conv_win(const ConvGroup& g, int cfg, hipStream_t s);
 hipError_t launch_wgrad_fast(const WgradGroup& g, hipStream_t s);
 int wgrad_fast_blocks(const WgradProb& p);
 void fastdiv_make(unsigned d, unsigned* mul, unsigned* shift);
