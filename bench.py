@@ -192,14 +192,12 @@ def main():
         cfg.with_order(net, "pre")
     N = net.modules[0].N
     ls = build_state(net)
+    if args.lanes != "default":
+        ls.set_stream_lanes(None if args.lanes == "single" else [int(c) for c in args.lanes])
     for _ in range(args.warmup):
         one_step(ls, net)
     torch.cuda.synchronize()
 
-    if args.lanes != "default":
-        ls.set_stream_lanes(None if args.lanes == "single" else [int(c) for c in args.lanes])
-        for _ in range(args.warmup):
-            one_step(ls, net)
 
     def timed_steps(profile):
         # EXACTLY --steps steps; profile = 2: every grouped launch is bracketed by hipEvents and issued on one stream
@@ -222,11 +220,15 @@ def main():
     # second pass over the same steps with every module on the caller's stream: full grouped launches, one after
     # another, each bracketed by hipEvents (this is also what `--lanes single` times and what the rocprofv3
     # summaries under profiles/ are taken with).
-    wall_ms, gpu_ms, _ = timed_steps(0)
+    if args.lanes == "single":
+        wall_ms, gpu_ms, recs = timed_steps(1)           # one stream: the timed region itself carries the events
+        iso_wall, gpu_iso = wall_ms, gpu_ms
+    else:
+        wall_ms, gpu_ms, _ = timed_steps(0)
+        ls.set_stream_lanes(None)
+        one_step(ls, net)
+        iso_wall, gpu_iso, recs = timed_steps(1)
     ms_per_step = wall_ms / args.steps
-    ls.set_stream_lanes(None)
-    one_step(ls, net)
-    iso_wall, gpu_iso, recs = timed_steps(1)
     iso_ms_per_step = iso_wall / args.steps
 
     # per-kernel aggregation (kind, tile configuration)
