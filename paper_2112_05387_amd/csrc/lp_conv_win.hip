@@ -162,7 +162,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     const bool last_b = (wave + NW * (NSB - 1)) < NSBT;
     const int nk = 9 * nslabc;
     const bool b_hi = kvg >= CPR / 2;
-    int tr = 0, ts = 0, ci0 = 0, issued = 0;
+    // Order of the channel slabs: the sum over channels may run in any order.  With a half last slab, odd workgroups
+    // start with it, so that the two halves of the chip reach their slab boundaries (where every workgroup requests a
+    // whole window at once and waits for it) at different times.
+    const int ci_first = (half_last && (blockIdx.x & 1)) ? (nslabc - 1) * BK : 0;
+    const int ci_wrap = nslabc * BK;
+    int tr = 0, ts = 0, ci0 = ci_first, issued = 0;
     bool t_live = false;
     unsigned t_offb = 0;
     unsigned char* t_dst = s_b;
@@ -173,7 +178,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
         ++issued;
         if (++ts == 3) {
             ts = 0;
-            if (++tr == 3) { tr = 0; ci0 += BK; }
+            if (++tr == 3) { tr = 0; ci0 += BK; if (ci0 >= ci_wrap) ci0 = 0; }
         }
     };
     auto issue_b = [&](int j) {
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     __syncthreads();                     // row offsets and window addresses visible; nothing in flight yet
     if (nk > 0) {
         const int LT = last_b ? NSB : NSB - 1;                 // filter loads per tile of this wave
-        load_window(0);
+        load_window(ci_first);
 #pragma unroll
         for (int s = 0; s < STAGES; ++s) {
             tile_begin(s);
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
         load_a(0, 0);
 #pragma unroll
         for (int j = 0; j < FN; ++j) load_b(0, 0, j);
-        int st = 0, tap = 0, rci = 0;                          // ring stage, tap and channel slab of tile kt
+        int st = 0, tap = 0, rci = ci_first;                   // ring stage, tap and channel slab of tile kt
         t_live = false;
         for (int kt = 0; kt < nk; ++kt) {
             // a tile of the half slab has KS/2 k-steps: the first ones and, in the code of the last one below, k-step
@@ -284,6 +289,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
                 load_a(0, 0);
             } else if (more) {
                 rci += BK;
+                if (rci >= ci_wrap) rci = 0;
                 load_window(rci);                              // ahead of the filter tile: the window is the older request
             }
             tile_begin(st);                                    // filter tile kt+STAGES into the stage just freed
