@@ -87,7 +87,15 @@ typedef struct {
 
 /* One AuxNet block generating x_{j+1} from the mini-batch (Sec. 4.2, forward map of the auxiliary-variable
  * network, in its one-block form): conv3x3(cin -> cout, stride, pad 1) - BN(batch statistics) [- ReLU]. */
-typedef struct { int cin, cout, stride, relu; } lp_aux_desc;
+typedef struct {
+    int cin, cout, stride, relu;
+    int from_prev;   /* 0: the block reads the mini-batch x_0 (forward-unlocked form);  1: block j reads x_j, the output of
+                        block j-1 (x_{j+1} = AuxNet_j(x_j), the chained form of Algorithm 1's first loop; block 0 reads x_0
+                        either way).  cin and stride then refer to x_j.  lp_auxnet_forward runs chained blocks one after
+                        the other; lp_auxnet_distill_grad runs a chained block again from x_target[j-1], the corrected
+                        x_j, before it takes the gradient (Sec. 4.2: theta_j <- argmin |x_{j+1} - AuxNet_j(x_j; theta)|^2);
+                        lp_reauxnet_grad refuses chained blocks (LP_ERR_STATE). */
+} lp_aux_desc;
 
 typedef enum { LP_T_CONV = 0, LP_T_BN_GAMMA = 1, LP_T_BN_BETA = 2, LP_T_FC_W = 3, LP_T_FC_B = 4 } lp_tensor_kind;
 

@@ -33,7 +33,7 @@ class lp_module_desc(ctypes.Structure):
 
 
 class lp_aux_desc(ctypes.Structure):
-    _fields_ = [("cin", c_int), ("cout", c_int), ("stride", c_int), ("relu", c_int)]
+    _fields_ = [("cin", c_int), ("cout", c_int), ("stride", c_int), ("relu", c_int), ("from_prev", c_int)]
 
 
 class lp_tensor_info(ctypes.Structure):
@@ -136,7 +136,7 @@ def lp_net_create(modules, aux, dtype, bn_eps):
     if aux is not None:
         auxp = (lp_aux_desc * max(len(aux), 1))()
         for j, a in enumerate(aux):
-            auxp[j] = lp_aux_desc(a.cin, a.cout, a.stride, int(a.relu))
+            auxp[j] = lp_aux_desc(a.cin, a.cout, a.stride, int(a.relu), int(getattr(a, "from_prev", False)))
     out = c_void_p()
     dt = dtype if isinstance(dtype, int) else {"f32": LP_F32, "bf16": LP_BF16}[dtype]
     _check(lib().lp_net_create(K, mods, auxp, dt, float(bn_eps), ctypes.byref(out)))

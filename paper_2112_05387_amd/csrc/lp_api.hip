@@ -38,7 +38,7 @@ static lp_status fail(lp_status st, const char* fmt, ...) {
 namespace {
 
 enum Space { SP_NONE = 0, SP_WS, SP_X, SP_Y, SP_PARAM, SP_DPARAM, SP_DY, SP_DX, SP_LOGITS, SP_DLOGITS,
-             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG };
+             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG, SP_XTGT };
 struct Ref { int space = SP_NONE; int idx = 0; size_t off = 0; };
 static Ref mk(int sp, int idx, size_t off) { Ref r; r.space = sp; r.idx = idx; r.off = off; return r; }
 
@@ -56,6 +56,7 @@ struct Bindings {
     void* const* xout = nullptr;
     const void* image = nullptr;
     float* const* auxg = nullptr;
+    const void* const* xtgt = nullptr;     // corrected auxiliary variables (input of a chained AuxNet's distillation)
 };
 static void* resolve(const Ref& r, const Bindings& b) {
     switch (r.space) {
@@ -72,6 +73,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
         case SP_XOUT: return (char*)b.xout[r.idx] + r.off;
         case SP_IMAGE: return (char*)b.image + r.off;
         case SP_AUXG: return (char*)b.auxg[r.idx] + r.off;
+        case SP_XTGT: return (char*)b.xtgt[r.idx] + r.off;
         default: return nullptr;
     }
 }
@@ -143,6 +145,7 @@ struct AuxPlan {
     size_t param_bytes = 0, grad_bytes = 0;
     size_t ws_out = 0, ws_g = 0;           // recomputed AuxNet output and the gradient on it (distillation)
     Program fwd, bwd_a, bwd_b;             // distillation: before / after the loss kernel
+    bool chained = false;                  // input = the previous auxiliary variable instead of the mini-batch
 };
 
 }  // namespace
@@ -960,10 +963,11 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
 
 static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     AuxPlan& a = net->aux[j];
-    const ModulePlan& m0 = net->mods[0];
+    a.chained = a.d.from_prev != 0 && j > 0;
+    const ModulePlan& m0 = net->mods[a.chained ? j : 0];      // whose input tensor the AuxNet reads: x_j or the mini-batch x_0
     const ModulePlan& mt = net->mods[j + 1];
     const int epv = net->dtype == LP_BF16 ? 8 : 4;
-    if (a.d.cin != m0.d.C) return fail(LP_ERR_SHAPE, "aux %d: cin %d != image channels %d", j, a.d.cin, m0.d.C);
+    if (a.d.cin != m0.d.C) return fail(LP_ERR_SHAPE, "aux %d: cin %d != channels of its input (%d)", j, a.d.cin, m0.d.C);
     if (a.d.cout != mt.d.C || a.d.cout % epv) return fail(LP_ERR_SHAPE, "aux %d: cout %d != channels of x_%d (%d)", j, a.d.cout, j + 1, mt.d.C);
     if (a.d.stride < 1 || m0.d.H != mt.d.H * a.d.stride || m0.d.W != mt.d.W * a.d.stride)
         return fail(LP_ERR_SHAPE, "aux %d: stride %d does not map %dx%d to %dx%d", j, a.d.stride, m0.d.H, m0.d.W, mt.d.H, mt.d.W);
@@ -977,7 +981,8 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     Builder B{net};
     const Ref st = mk(SP_WS, 0, a.u.ws_stats), y = mk(SP_WS, 0, a.u.ws_y);
     a.fwd.push_back(Step{B.fill(st, sizeof(double) * 2 * a.u.cout)});
-    a.fwd.push_back(Step{B.conv_fwd(a.u, mk(SP_IMAGE, 0, 0), mk(SP_AUXP, j, a.tensors[a.u.t_w].offset), y, st)});
+    const Ref wflt = mk(SP_AUXP, j, a.tensors[a.u.t_w].offset);
+    a.fwd.push_back(Step{B.conv_fwd(a.u, a.chained ? mk(SP_XOUT, j - 1, 0) : mk(SP_IMAGE, 0, 0), wflt, y, st)});
     a.fwd.push_back(Step{B.bn_apply(a.u.N * a.u.Ho * a.u.Wo, a.u.cout, y, mk(SP_XOUT, j, 0), st,
                                     mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), mk(SP_AUXP, j, a.tensors[a.u.t_b].offset),
                                     a.d.relu != 0)});
@@ -989,12 +994,19 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     const int M = a.u.N * a.u.Ho * a.u.Wo;
     const Ref gam = mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), bet = mk(SP_AUXP, j, a.tensors[a.u.t_b].offset);
     const Ref red = mk(SP_WS, 0, a.u.ws_red), dyc = mk(SP_WS, 0, a.u.ws_dy), g = mk(SP_WS, 0, a.ws_g);
-    a.bwd_a.push_back(Step{B.fill(red, sizeof(double) * 2 * a.u.cout), B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)});
+    // A chained AuxNet is distilled at the CORRECTED input x_j (Sec. 4.2): its forward pass is run again from there.
+    const Ref din = a.chained ? mk(SP_XTGT, j - 1, 0) : mk(SP_IMAGE, 0, 0);
+    {
+        Step s0{B.fill(red, sizeof(double) * 2 * a.u.cout), B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)};
+        if (a.chained) s0.push_back(B.fill(st, sizeof(double) * 2 * a.u.cout));
+        a.bwd_a.push_back(s0);
+    }
+    if (a.chained) a.bwd_a.push_back(Step{B.conv_fwd(a.u, din, wflt, y, st)});
     a.bwd_a.push_back(Step{B.bn_apply(M, a.u.cout, y, mk(SP_WS, 0, a.ws_out), st, gam, bet, a.d.relu != 0)});
     const Ref dgam = mk(SP_AUXG, j, a.tensors[a.u.t_g].grad_offset), dbet = mk(SP_AUXG, j, a.tensors[a.u.t_b].grad_offset);
     a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
     a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
-    a.bwd_b.push_back(Step{B.wgrad(a.u, mk(SP_IMAGE, 0, 0), dyc, mk(SP_AUXG, j, a.tensors[a.u.t_w].grad_offset))});
+    a.bwd_b.push_back(Step{B.wgrad(a.u, din, dyc, mk(SP_AUXG, j, a.tensors[a.u.t_w].grad_offset))});
     return LP_OK;
 }
 
@@ -1594,7 +1606,11 @@ lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
         progs.push_back(&net->aux[j].fwd);
     }
     Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.xout = x_out;
-    st = run_programs(net, progs, b, (hipStream_t)stream);
+    bool any_chained = false;
+    for (const AuxPlan& a : net->aux) any_chained = any_chained || a.chained;
+    if (!any_chained) st = run_programs(net, progs, b, (hipStream_t)stream);
+    else   // x_{j+1} = AuxNet_j(x_j): one block after the other (the AuxNets are forward-locked, Sec. 4.2)
+        for (size_t j = 0; j < progs.size() && st == LP_OK; ++j) st = run_programs(net, {progs[j]}, b, (hipStream_t)stream);
     if (st == LP_OK) net->aux_fwd_done = true;
     return st;
 }
@@ -1619,6 +1635,8 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
         if (misaligned(aux_params[j]) || misaligned(x_target[j]) || misaligned(daux_params[j]))
             return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
         const AuxPlan& a = net->aux[j];
+        if (a.chained && (!x_target[j - 1] || misaligned(x_target[j - 1])))
+            return fail(LP_ERR_INVALID_ARG, "x_target[%d] (input of the chained AuxNet %d) is NULL or not 16-byte aligned", j - 1, j);
         pa.push_back(&a.bwd_a); pb.push_back(&a.bwd_b);
         mask |= 1u << j;
         LossProb& p = g.p[g.nprob];
@@ -1629,7 +1647,7 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
     }
     if (g.nprob) groups.push_back(g);
     if (!mask) return LP_OK;
-    Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.auxg = daux_params;
+    Bindings b; b.ws = net->ws; b.image = image; b.auxp = aux_params; b.auxg = daux_params; b.xtgt = x_target;
     st = run_programs(net, pa, b, s);
     if (st != LP_OK) return st;
     hipError_t err = launch_zero_selected(loss, mask, net->K - 1, s);
@@ -1660,6 +1678,7 @@ lp_status lp_reauxnet_grad(struct lp_net* net, void* stream, const void* image, 
         if (misaligned(aux_params[j]) || misaligned(y_prev[j]) || misaligned(dx[j + 1]) || misaligned(lam) || misaligned(daux_params[j]))
             return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
         AuxPlan& a = net->aux[j];
+        if (a.chained) return fail(LP_ERR_STATE, "aux %d reads the previous auxiliary variable: the recursive-AuxNet update is defined for AuxNets fed by the mini-batch", j);
         pa.push_back(&a.bwd_a); pb.push_back(&a.bwd_b);
         AuxVarProb& p = g.p[g.nprob];
         p.x = net->ws + a.ws_out; p.yprev = y_prev[j]; p.dx = dx[j + 1]; p.lam = lam; p.gout = net->ws + a.ws_g;

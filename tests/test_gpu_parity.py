@@ -326,6 +326,58 @@ def test_reauxnet_grad(dtype, al):
         ls.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chained_auxnet(dtype):
+    """AuxNet blocks that read the previous auxiliary variable (x_{j+1} = AuxNet_j(x_j)), ResNet-56 shapes at batch 8:
+    the forward chain, then the distillation gradients at corrected auxiliary variables (each block is run again from
+    its corrected input)."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err, store
+    from workloads import configs as cfg
+    net = cfg.chain_aux(wl.make_config("resnet56", batch=8))
+    net.dtype = dtype
+    scale = 0.5
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    q = None if dtype == "f32" else wl.round_bf16
+    say("case chained auxnet", dtype)
+    image = wl.make_image(net)
+    auxp = [wl.make_aux_params(net, j) for j in range(net.K - 1)]
+    ls = LocalStep(net)
+    try:
+        ls.set_x(0, image)
+        for j in range(net.K - 1):
+            ls.set_aux_params(j, auxp[j])
+        ls.auxnet_forward()
+        torch.cuda.synchronize()
+        errs = {}
+        x = image
+        for j in range(net.K - 1):              # every block against the oracle on the DEVICE's stored input
+            want = lpref.auxnet_forward(net.aux[j], x, auxp[j], net.bn_eps)
+            errs[f"x{j + 1}"] = rel_err(ls.to_host(ls.x[j + 1]), want)
+            x = ls.to_host(ls.x[j + 1])
+        corrected = [store(net, ls.to_host(ls.x[j + 1]) + wl.normal(47, f"corr{j}", ls.x[j + 1].shape, 0.5))
+                     for j in range(net.K - 1)]
+        for j in range(net.K - 1):
+            ls.x[j + 1].copy_(ls.to_dev(corrected[j]))
+        ls.auxnet_distill_grad(scale)
+        torch.cuda.synchronize()
+        for j in range(net.K - 1):
+            x_in = image if j == 0 else corrected[j - 1]
+            loss, grads = lpref.auxnet_distill_grad(net.aux[j], x_in, auxp[j], corrected[j], net.bn_eps, scale, q)
+            errs[f"aux{j}.loss"] = abs(float(ls.aux_loss[j].item()) - loss) / abs(loss)
+            for name, g, r in zip(("dW", "dgamma", "dbeta"), ls.get_aux_grads(j), grads):
+                errs[f"aux{j}.{name}"] = rel_err(g, r)
+        top = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+        say("    worst: " + ", ".join(f"{k}={v:.2e}" for k, v in top))
+        bad = {k: v for k, v in errs.items() if not v <= tol}
+        assert not bad, bad
+        with pytest.raises(Exception, match="recursive-AuxNet"):
+            ls.reauxnet_grad(1.0)
+    finally:
+        ls.close()
+
+
 def test_vanish_invariant_on_device():
     """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
     and dx of modules 0..K-2 are exactly zero."""

@@ -274,6 +274,32 @@ def test_auxnet_distill_grad_finite_differences(relu):
     assert loss0 == 0.0 and all(np.all(g == 0.0) for g in g0)
 
 
+def test_chained_auxnet_distill_finite_differences():
+    """A chained AuxNet block reads the previous auxiliary variable (here: 8 channels at 3x3) instead of the
+    mini-batch; its distillation gradient against central differences, the input held fixed."""
+    from workloads import configs as cfg
+    net = cfg.chain_aux(mini_basic(), relu=True)
+    a = net.aux[1]
+    assert a.from_prev and a.cin == net.modules[1].C and a.stride == 1
+    m = net.modules[1]
+    x_in = wl.normal(9, "chain_in", (m.N, m.H, m.W, m.C))
+    p = wl.make_aux_params(net, 1)
+    out = lpref.auxnet_forward(a, x_in, p, net.bn_eps)
+    target = out + wl.normal(9, "chain_target", out.shape, 0.3)
+    scale, h = 0.5, 1e-6
+    loss, grads = lpref.auxnet_distill_grad(a, x_in, p, target, net.bn_eps, scale)
+    f = lambda pp: scale * np.sum((lpref.auxnet_forward(a, x_in, pp, net.bn_eps) - target) ** 2)
+    assert abs(loss - f(p)) <= 1e-12 * abs(loss)
+    rng = np.random.default_rng(13)
+    for i in range(3):
+        d = rng.standard_normal(p[i].shape)
+        pp, pm = list(p), list(p)
+        pp[i], pm[i] = p[i] + h * d, p[i] - h * d
+        fd = (f(pp) - f(pm)) / (2 * h)
+        an = float(np.sum(grads[i] * d))
+        assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (i, fd, an)
+
+
 @pytest.mark.parametrize("order", ["post", "pre"])
 def test_module_forward_against_library_layers(order):
     """The forward pass of every module, re-composed from a library's float64 layers (conv2d, training-mode

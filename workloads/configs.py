@@ -52,6 +52,7 @@ class AuxDesc:
     cout: int
     stride: int
     relu: bool
+    from_prev: bool = False   # block j reads x_j (chained AuxNets, x_{j+1} = AuxNet_j(x_j)) instead of the mini-batch
 
 
 @dataclass
@@ -116,6 +117,13 @@ def with_order(net: NetDesc, order: str) -> NetDesc:
     """The same network with every module in the given block order (parameter tensors change with it)."""
     for m in net.modules:
         m.order = order
+    return net
+
+
+def chain_aux(net: NetDesc, relu: bool = False) -> NetDesc:
+    """AuxNet blocks that read the previous auxiliary variable: block j maps x_j (module j's input) to x_{j+1}."""
+    net.aux = [AuxDesc(cin=net.modules[j].C, cout=net.modules[j + 1].C, stride=net.modules[j].H // net.modules[j + 1].H,
+                       relu=relu, from_prev=True) for j in range(net.K - 1)]
     return net
 
 
