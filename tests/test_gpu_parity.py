@@ -378,6 +378,81 @@ def test_chained_auxnet(dtype):
         ls.close()
 
 
+def test_two_iterations_of_the_whole_method():
+    """Every entry point in sequence, twice: AuxNet forward -> module forward -> losses / terminal adjoints -> module
+    backward -> multiplier update -> correction of the auxiliary variables -> parameter update -> AuxNet distillation
+    gradient -> AuxNet parameter update, on the mini network in fp32, against the same sequence of oracle calls in
+    float64.  Checks what feeds what between the calls; the tolerance allows for the cancellation in the residuals
+    (see compare_step) accumulated over two iterations."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.helpers import rel_err
+    from workloads.configs import AuxDesc
+    net = gpu_mini_basic(dtype="f32")
+    net.al, net.rho = True, 1.5
+    net.aux = [AuxDesc(cin=3, cout=m.C, stride=net.modules[0].H // m.H, relu=False) for m in net.modules[1:]]
+    K, scale, eta, lr, mstep = net.K, 0.5, 0.05, 0.02, 0.1
+    say("case two iterations of the whole method")
+    image, labels = wl.make_image(net), wl.make_labels(net)
+    params = [wl.make_params(net, k) for k in range(K)]
+    auxp = [wl.make_aux_params(net, j) for j in range(K - 1)]
+    lams = [wl.normal(51, f"lam{k}", (net.modules[k + 1].N, net.modules[k + 1].H, net.modules[k + 1].W, net.modules[k + 1].C), 0.05)
+            for k in range(K - 1)]
+    f32 = lambda a: np.asarray(a, np.float32).astype(np.float64)
+    params = [[f32(t) for t in p] for p in params]; auxp = [[f32(t) for t in p] for p in auxp]; lams = [f32(l) for l in lams]
+    ls = LocalStep(net)
+    try:
+        for k in range(K):
+            ls.set_params(k, params[k])
+        for j in range(K - 1):
+            ls.set_aux_params(j, auxp[j])
+        ls.set_x(0, image)
+        ls.set_lams(lams)
+        ls.set_labels(labels)
+        for it in range(2):
+            # ---- device
+            ls.auxnet_forward()
+            ls.module_forward()
+            ls.local_loss_grad(net.rho, scale)
+            ls.module_backward()
+            ls.al_multiplier_update(mstep)
+            ls.aux_variable_update(net.rho, scale, eta)
+            ls.sgd_update(lr)
+            ls.auxnet_distill_grad(scale)
+            ls.sgd_update_aux(lr)
+            torch.cuda.synchronize()
+            # ---- oracle, the same sequence
+            xs = [image] + [lpref.auxnet_forward(net.aux[j], image, auxp[j], net.bn_eps) for j in range(K - 1)]
+            out = lpref.local_step(net, xs, params, labels, lams, scale)
+            new_lams = [lpref.multiplier_update(lams[k], out["y"][k], xs[k + 1], mstep) for k in range(K - 1)]
+            new_xs = [image] + [lpref.aux_variable_update(xs[k], out["y"][k - 1], out["dx"][k], new_lams[k - 1], net.rho, eta, scale)
+                                for k in range(1, K)]            # the multipliers were updated first, as on the device
+            params = [[lpref.sgd_update(w, g, lr)[0] for w, g in zip(params[k], out["dparams"][k])] for k in range(K)]
+            for j in range(K - 1):
+                _, g = lpref.auxnet_distill_grad(net.aux[j], image, auxp[j], new_xs[j + 1], net.bn_eps, scale)
+                auxp[j] = [lpref.sgd_update(w, gg, lr)[0] for w, gg in zip(auxp[j], g)]
+            lams = new_lams
+            errs = {}
+            for k in range(1, K):
+                errs[f"it{it}.x{k}"] = rel_err(ls.to_host(ls.x[k]), new_xs[k])
+            for k in range(K - 1):
+                errs[f"it{it}.lam{k}"] = rel_err(ls.to_host(ls.lam[k]), lams[k])
+            for k in range(K):
+                for i, info in enumerate(ls.tables[k]):
+                    got = ls.to_host(ls.params[k][info.offset:info.offset + 4 * int(info.numel)].view(torch.float32))
+                    errs[f"it{it}.m{k}.t{i}"] = rel_err(got.reshape(params[k][i].shape), params[k][i])
+            for j in range(K - 1):
+                for i, info in enumerate(ls.aux_tables[j]):
+                    got = ls.to_host(ls.aux_params[j][info.offset:info.offset + 4 * int(info.numel)].view(torch.float32))
+                    errs[f"it{it}.aux{j}.t{i}"] = rel_err(got.reshape(auxp[j][i].shape), auxp[j][i])
+            top = sorted(errs.items(), key=lambda kv: -kv[1])[:4]
+            say(f"    iteration {it}, worst: " + ", ".join(f"{k}={v:.2e}" for k, v in top))
+            bad = {k: v for k, v in errs.items() if not v <= 1e-4}
+            assert not bad, bad
+    finally:
+        ls.close()
+
+
 def test_vanish_invariant_on_device():
     """x_{k+1} := the device's own F_k(x_k), zero multipliers: losses, terminal adjoints, weight gradients
     and dx of modules 0..K-2 are exactly zero."""
