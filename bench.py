@@ -53,8 +53,20 @@ def build_state(net, seed_noise=True):
     return ls
 
 
+SEPARATE_CALLS = False
+
+
 def one_step(ls, net):
-    ls.step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
+    if not SEPARATE_CALLS:
+        ls.step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
+        return
+    if net.aux is not None:
+        ls.auxnet_forward()
+    ls.module_forward()
+    ls.local_loss_grad(net.rho, 1.0)
+    ls.module_backward()
+    if net.al and ls.lam is not None:
+        ls.al_multiplier_update(net.step)
 
 
 def speedup_terms(name, batch, reps):
@@ -171,12 +183,17 @@ def main():
     ap.add_argument("--lanes", default="default",
                     help="default: the library's concurrent stream lanes; single: every module on one stream; or one "
                          "digit 0..3 per module, e.g. 1200 (the result is then not the headline)")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="run the step as lp_module_forward / lp_local_loss_grad / lp_module_backward / "
+                         "lp_al_multiplier_update instead of the one lp_local_step call")
     ap.add_argument("--order", choices=["post", "pre"], default="post",
                     help="block order: post = conv-BN-ReLU (the headline configuration), pre = BN-ReLU-conv (Fig. 2)")
     ap.add_argument("--speedup-terms", action="store_true",
                     help="also time the terms of the paper's speed-up model (K = 1 network, single modules, interface "
                          "and AuxNet work) and add them to the JSON line")
     args = ap.parse_args()
+    global SEPARATE_CALLS
+    SEPARATE_CALLS = args.separate_calls
     if args.gpus != 1:
         print("bench.py: this build runs the local step of all K modules on ONE GPU; --gpus must be 1 "
               "(no multi-GPU figure is produced).", file=sys.stderr)

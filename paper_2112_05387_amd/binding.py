@@ -14,12 +14,12 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
-           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes",
+           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step",
            "lp_debug_im2col_offsets",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
-              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats"}
+              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats", 12: "loss", 13: "cross_entropy", 14: "multiplier_update"}
 
 
 class lp_block_desc(ctypes.Structure):
@@ -78,6 +78,8 @@ def lib():
                                          c_void_p, c_void_p, vpp, c_void_p]
         L.lp_module_backward.argtypes = [c_void_p, c_void_p, c_uint32, vpp, c_void_p, vpp, vpp, vpp]
         L.lp_al_multiplier_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, c_float]
+        L.lp_local_step.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, vpp, vpp, c_float, c_float, c_float, c_void_p,
+                                    c_void_p, vpp, c_void_p, c_void_p, vpp, vpp]
         L.lp_net_set_stream_lanes.argtypes = [c_void_p, POINTER(c_int)]
         L.lp_reauxnet_grad.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, vpp]
         L.lp_sgd_update.argtypes = [c_void_p, c_void_p, c_int, c_uint32, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
@@ -196,6 +198,13 @@ def lp_module_backward(net, stream, module_mask, dy, dlogits, params, dparams, d
 def lp_auxnet_distill_grad(net, stream, image, aux_params, x_target, loss_scale, loss, daux_params):
     _check(lib().lp_auxnet_distill_grad(net, stream, image, _ptr_array(aux_params), _ptr_array(x_target), float(loss_scale),
                                         loss, _ptr_array(daux_params)))
+
+
+def lp_local_step(net, stream, mask, x, params, y, x_next, lam, rho, scale, mult_step, labels, loss, dy, logits, dlogits,
+                  dparams, dx):
+    _check(lib().lp_local_step(net, stream, mask, _ptr_array(x), _ptr_array(params), _ptr_array(y), _ptr_array(x_next),
+                               None if lam is None else _ptr_array(lam), float(rho), float(scale), float(mult_step), labels,
+                               loss, _ptr_array(dy), logits, dlogits, _ptr_array(dparams), _ptr_array(dx)))
 
 
 def lp_net_set_stream_lanes(net, lanes):

@@ -38,7 +38,7 @@ static lp_status fail(lp_status st, const char* fmt, ...) {
 namespace {
 
 enum Space { SP_NONE = 0, SP_WS, SP_X, SP_Y, SP_PARAM, SP_DPARAM, SP_DY, SP_DX, SP_LOGITS, SP_DLOGITS,
-             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG, SP_XTGT };
+             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG, SP_XTGT, SP_XNEXT, SP_LAM, SP_LOSS, SP_LABELS };
 struct Ref { int space = SP_NONE; int idx = 0; size_t off = 0; };
 static Ref mk(int sp, int idx, size_t off) { Ref r; r.space = sp; r.idx = idx; r.off = off; return r; }
 
@@ -57,6 +57,12 @@ struct Bindings {
     const void* image = nullptr;
     float* const* auxg = nullptr;
     const void* const* xtgt = nullptr;     // corrected auxiliary variables (input of a chained AuxNet's distillation)
+    // the fused local step: interface tensors, multipliers, losses, labels and the scalars of its loss / multiplier kernels
+    const void* const* xnext = nullptr;
+    void* const* lam = nullptr;
+    float* loss = nullptr;
+    const int32_t* labels = nullptr;
+    float rho = 0.f, scale = 1.f, mstep = 0.f;
 };
 static void* resolve(const Ref& r, const Bindings& b) {
     switch (r.space) {
@@ -74,18 +80,24 @@ static void* resolve(const Ref& r, const Bindings& b) {
         case SP_IMAGE: return (char*)b.image + r.off;
         case SP_AUXG: return (char*)b.auxg[r.idx] + r.off;
         case SP_XTGT: return (char*)b.xtgt[r.idx] + r.off;
+        case SP_XNEXT: return (char*)b.xnext[r.idx] + r.off;
+        case SP_LAM: return (b.lam && b.lam[r.idx]) ? (char*)b.lam[r.idx] + r.off : nullptr;
+        case SP_LOSS: return (char*)b.loss + r.off;
+        case SP_LABELS: return (char*)b.labels + r.off;
         default: return nullptr;
     }
 }
 
 enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
-              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS };
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE, OP_MULT };
 
 struct Op {
     int type = 0, cfg = 0;
+    int phase = 0;                         // fused step: 0 forward, 1 loss, 2 backward, 3 multiplier update
     bool vec = true;
     Ref r[10];
     size_t fill_bytes = 0;
+    size_t numel = 0;                      // OP_LOSS, OP_MULT: elements of the interface tensor
     ConvProb conv;
     WgradProb wg;
     WtransProb wt;
@@ -137,6 +149,7 @@ struct ModulePlan {
     size_t ws_stats0 = 0, ws_stats_bytes = 0, ws_red0 = 0, ws_red_bytes = 0;
     size_t ws_G[2] = {0, 0}, ws_A = 0, ws_P = 0, ws_gpool = 0;
     Program fwd, bwd, bwd_dx0;             // bwd_dx0: variant that also produces dx for a stem-less module 0
+    Program step, step_dx0;                // forward, loss / terminal adjoint, backward, multiplier update in one list
 };
 struct AuxPlan {
     lp_aux_desc d;
@@ -961,6 +974,46 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
     return LP_OK;
 }
 
+// the whole local step of module k as one list: forward, loss and terminal adjoint, backward, multiplier update
+static void build_step_programs(lp_net* net, int k) {
+    ModulePlan& m = net->mods[k];
+    const bool last = (k == net->K - 1);
+    Step loss_step, mult_step;
+    if (last) {
+        Op o; o.type = OP_CE;
+        memset(&o.head, 0, sizeof(o.head));
+        o.head.N = m.oN; o.head.classes = m.d.n_classes;
+        o.r[0] = mk(SP_LOGITS, 0, 0); o.r[1] = mk(SP_LABELS, 0, 0); o.r[2] = mk(SP_LOSS, 0, sizeof(float) * k);
+        o.r[3] = mk(SP_DLOGITS, 0, 0);
+        loss_step.push_back(o);
+    } else {
+        const size_t numel = (size_t)m.oN * m.oH * m.oW * m.oC;
+        Op o; o.type = OP_LOSS; o.numel = numel;
+        o.r[0] = mk(SP_Y, k, 0); o.r[1] = mk(SP_XNEXT, k, 0); o.r[2] = mk(SP_LAM, k, 0); o.r[3] = mk(SP_DY, k, 0);
+        o.r[4] = mk(SP_LOSS, 0, sizeof(float) * k);
+        loss_step.push_back(o);
+        Op u; u.type = OP_MULT; u.numel = numel;
+        u.r[0] = mk(SP_LAM, k, 0); u.r[1] = mk(SP_Y, k, 0); u.r[2] = mk(SP_XNEXT, k, 0);
+        mult_step.push_back(u);
+    }
+    for (int variant = 0; variant < 2; ++variant) {
+        const Program& bw = variant == 0 ? m.bwd : m.bwd_dx0;
+        Program& out = variant == 0 ? m.step : m.step_dx0;
+        if (bw.empty()) continue;
+        out = m.fwd;
+        out.push_back(loss_step);
+        for (Op& o : out.back()) o.phase = 1;
+        for (const Step& st : bw) {
+            out.push_back(st);
+            for (Op& o : out.back()) o.phase = 2;
+        }
+        if (!mult_step.empty()) {
+            out.push_back(mult_step);
+            for (Op& o : out.back()) o.phase = 3;
+        }
+    }
+}
+
 static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     AuxPlan& a = net->aux[j];
     a.chained = a.d.from_prev != 0 && j > 0;
@@ -1043,6 +1096,8 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
         case OP_BN_BWD_REDUCE: bytes = (double)o.bnb.M * o.bnb.C * e * 2.0; break;
         case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * (o.r[9].space != SP_NONE ? 4.0 : 3.0); break;
         case OP_BN_STATS: bytes = (double)o.bnb.M * o.bnb.C * e; break;
+        case OP_LOSS: bytes = (double)o.numel * e * 4.0; break;
+        case OP_MULT: bytes = (double)o.numel * e * 4.0; break;
         case OP_POOL_FWD:
         case OP_POOL_BWD: bytes = ((double)o.pool.N * o.pool.H * o.pool.W + (double)o.pool.N * o.pool.Ho * o.pool.Wo) * o.pool.C * e; break;
         case OP_HEAD_FWD:
@@ -1241,6 +1296,38 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 err = type == OP_BN_STATS ? launch_bn_stats(g, dt, s)
                       : type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
             } break;
+            case OP_LOSS: {
+                LossGroup g; g.nprob = n; g.rho = b.rho; g.scale = b.scale; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    LossProb& p = g.p[i];
+                    p.y = resolve(o.r[0], b); p.xn = resolve(o.r[1], b); p.lam = resolve(o.r[2], b); p.dy = resolve(o.r[3], b);
+                    p.loss = (float*)resolve(o.r[4], b); p.numel = o.numel;
+                    p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
+                }
+                g.total_blocks = tot;
+                err = launch_loss(g, dt, s);
+            } break;
+            case OP_MULT: {
+                MultGroup g; g.nprob = 0; g.step = b.mstep; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    void* lam = resolve(o.r[0], b);
+                    if (!lam || b.mstep == 0.f) continue;          // penalty method, or no update asked for
+                    MultProb& p = g.p[g.nprob++];
+                    p.lam = lam; p.y = resolve(o.r[1], b); p.xn = resolve(o.r[2], b); p.numel = o.numel;
+                    p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
+                }
+                g.total_blocks = tot;
+                if (g.nprob) err = launch_mult(g, dt, s);
+            } break;
+            case OP_CE:
+                for (int i = 0; i < n && err == hipSuccess; ++i) {
+                    const Op& o = *ops[base + i];
+                    err = launch_ce((const float*)resolve(o.r[0], b), (const int32_t*)resolve(o.r[1], b), (float*)resolve(o.r[2], b),
+                                    (float*)resolve(o.r[3], b), o.head.N, o.head.classes, s);
+                }
+                break;
             case OP_POOL_FWD:
             case OP_POOL_BWD:
                 for (int i = 0; i < n && err == hipSuccess; ++i) {
@@ -1276,13 +1363,21 @@ static void plan_programs(const std::vector<const Program*>& progs, std::vector<
     std::vector<std::vector<char>> issued(np);
     for (size_t i = 0; i < np; ++i)
         if (!progs[i]->empty()) issued[i].assign((*progs[i])[0].size(), 0);
+    std::vector<char> off(np, 0);
     for (;;) {
+        // Programs of a fused step move through its phases together (a program that is ahead waits): the operations
+        // of one phase merge into grouped launches, those of different phases would not.
+        int min_phase = 1 << 30;
+        for (size_t i = 0; i < np; ++i)
+            if (step[i] < progs[i]->size()) min_phase = std::min(min_phase, (*progs[i])[step[i]][0].phase);
+        for (size_t i = 0; i < np; ++i)
+            off[i] = step[i] >= progs[i]->size() || (*progs[i])[step[i]][0].phase != min_phase;
         // candidate operations: everything not yet issued in the current step of every program
         int best_key = -1, best_cnt = 0;
         std::vector<std::pair<int, int>> keys;     // (key, count)
         bool any = false;
         for (size_t i = 0; i < np; ++i) {
-            if (step[i] >= progs[i]->size()) continue;
+            if (off[i]) continue;
             const Step& st = (*progs[i])[step[i]];
             for (size_t j = 0; j < st.size(); ++j) {
                 if (issued[i][j]) continue;
@@ -1301,7 +1396,7 @@ static void plan_programs(const std::vector<const Program*>& progs, std::vector<
         for (auto& kc : keys) only_wgrad = only_wgrad && (kc.first / 64 == OP_WGRAD);
         size_t lead = np, lead_left = 0;
         for (size_t i = 0; i < np; ++i) {
-            if (step[i] >= progs[i]->size()) continue;
+            if (off[i]) continue;
             const Step& st = (*progs[i])[step[i]];
             bool eligible = false;
             for (size_t j = 0; j < st.size(); ++j)
@@ -1322,14 +1417,14 @@ static void plan_programs(const std::vector<const Program*>& progs, std::vector<
         }
         std::vector<const Op*> ops;
         for (size_t i = 0; i < np; ++i) {
-            if (step[i] >= progs[i]->size()) continue;
+            if (off[i]) continue;
             const Step& st = (*progs[i])[step[i]];
             for (size_t j = 0; j < st.size(); ++j)
                 if (!issued[i][j] && st[j].key() == best_key) { ops.push_back(&st[j]); issued[i][j] = 1; }
         }
         plan.push_back(ops);
         for (size_t i = 0; i < np; ++i) {
-            if (step[i] >= progs[i]->size()) continue;
+            if (off[i]) continue;
             bool done = true;
             for (char c : issued[i]) done = done && c;
             if (done) {
@@ -1447,6 +1542,7 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
         m.d.blocks = nullptr;
         if (m.d.order != LP_ORDER_POST && m.d.order != LP_ORDER_PRE) { st = fail(LP_ERR_INVALID_ARG, "module %d: unknown block order %d", k, m.d.order); break; }
         st = m.d.order == LP_ORDER_PRE ? build_module_pre(net, k, ws) : build_module(net, k, ws);
+        if (st == LP_OK) build_step_programs(net, k);
         if (st == LP_OK && k > 0) {
             const ModulePlan& p = net->mods[k - 1];
             if (p.oN != m.d.N || p.oH != m.d.H || p.oW != m.d.W || p.oC != m.d.C)
@@ -1799,6 +1895,47 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
     const std::vector<int> lanes = lanes_of(net, module_mask);
     st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
     if (st == LP_OK) net->fwd_done &= ~module_mask;
+    return st;
+}
+
+lp_status lp_local_step(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* x,
+                        const void* const* params, void* const* y, const void* const* x_next, void* const* lam, float rho,
+                        float loss_scale, float mult_step, const int32_t* labels, float* loss, void* const* dy, float* logits,
+                        float* dlogits, float* const* dparams, void* const* dx) {
+    lp_status st = check_common(net, module_mask, true);
+    if (st != LP_OK) return st;
+    if (!x || !params || !dparams || !loss) return fail(LP_ERR_INVALID_ARG, "x, params, dparams or loss is NULL");
+    if (!(rho >= 0.f)) return fail(LP_ERR_INVALID_ARG, "rho must be non-negative");
+    std::vector<const Program*> progs;
+    for (int k = 0; k < net->K; ++k) {
+        if (!((module_mask >> k) & 1u)) continue;
+        const ModulePlan& m = net->mods[k];
+        if (!x[k] || !params[k] || !dparams[k]) return fail(LP_ERR_INVALID_ARG, "x[%d], params[%d] or dparams[%d] is NULL", k, k, k);
+        if (misaligned(x[k]) || misaligned(params[k]) || misaligned(dparams[k]))
+            return fail(LP_ERR_INVALID_ARG, "x[%d], params[%d] or dparams[%d] is not 16-byte aligned", k, k, k);
+        if (k < net->K - 1) {
+            if (!y || !x_next || !dy || !y[k] || !x_next[k] || !dy[k]) return fail(LP_ERR_INVALID_ARG, "y/x_next/dy[%d] is NULL", k);
+            if (misaligned(y[k]) || misaligned(x_next[k]) || misaligned(dy[k]) || (lam && lam[k] && misaligned(lam[k])))
+                return fail(LP_ERR_INVALID_ARG, "interface tensor %d is not 16-byte aligned", k);
+        } else if (!logits || !labels || !dlogits) return fail(LP_ERR_INVALID_ARG, "logits, labels or dlogits is NULL");
+        const bool needs_dx = !m.has_stem && k > 0;
+        const bool opt_dx = !m.has_stem && k == 0 && dx && dx[0];
+        if (needs_dx && (!dx || !dx[k])) return fail(LP_ERR_INVALID_ARG, "dx[%d] is NULL", k);
+        if ((needs_dx || opt_dx) && misaligned(dx[k])) return fail(LP_ERR_INVALID_ARG, "dx[%d] is not 16-byte aligned", k);
+        progs.push_back(opt_dx ? &m.step_dx0 : &m.step);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    // loss[k] = 0 for the selected modules, ahead of the fork (the loss kernels accumulate with atomics)
+    hipError_t err = launch_zero_selected(loss, module_mask, net->K, s);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    Bindings b; b.ws = net->ws; b.x = x; b.params = params; b.y = y; b.logits = logits;
+    b.dparams = dparams; b.dy = dy; b.dx = dx; b.dlogits = dlogits;
+    b.xnext = x_next; b.lam = lam; b.loss = loss; b.labels = labels; b.rho = rho; b.scale = loss_scale; b.mstep = mult_step;
+    const std::vector<int> lanes = lanes_of(net, module_mask);
+    st = run_programs(net, progs, b, s, &lanes);
+    if (st == LP_OK)
+        for (int k = 0; k < net->K; ++k)
+            if ((module_mask >> k) & 1u) { net->saved_x[k] = x[k]; net->fwd_done &= ~(1u << k); }
     return st;
 }
 

@@ -204,12 +204,19 @@ class LocalStep:
         B.lp_aux_variable_update(self.net, self._stream(), x, self._p(self.y), dx,
                                  None if self.lam is None else self._p(self.lam), rho, scale, eta)
 
+    def local_step(self, rho, scale=1.0, mult_step=0.0, mask=None, want_dx0=False):
+        """Forward, losses / terminal adjoints, backward and (mult_step != 0, multipliers set) the multiplier update of
+        the selected modules in one call: every stream lane runs through all phases on its own."""
+        dx = self._p(self.dx)
+        if not want_dx0:
+            dx[0] = None
+        B.lp_local_step(self.net, self._stream(), self._mask(mask), self._p(self.x), self._p(self.params), self._p(self.y),
+                        self._p(self.x[1:]), None if self.lam is None else self._p(self.lam), rho, scale, mult_step,
+                        self.labels.data_ptr(), self.loss.data_ptr(), self._p(self.dy), self.logits.data_ptr(),
+                        self.dlogits.data_ptr(), self._p(self.dparams), dx)
+
     def step(self, rho, scale=1.0, mult_step=None, with_aux=False):
         """One synchronous local step of all K modules."""
         if with_aux:
             self.auxnet_forward()
-        self.module_forward()
-        self.local_loss_grad(rho, scale)
-        self.module_backward()
-        if mult_step is not None and self.lam is not None:
-            self.al_multiplier_update(mult_step)
+        self.local_step(rho, scale, 0.0 if (mult_step is None or self.lam is None) else mult_step)

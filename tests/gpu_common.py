@@ -201,10 +201,8 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
                 worst[f"lam{k}"] = rel_err(ls.to_host(ls.lam[k]), want)
             ls.set_lams(inp["lams"])
         check(worst, "entry-point pass")
-        # ---- pass 2 (chained)
-        ls.module_forward()
-        ls.local_loss_grad(net.rho, scale)
-        ls.module_backward(want_dx0=want_dx0)
+        # ---- pass 2 (chained): the fused entry point, every stream lane through all phases on its own
+        ls.local_step(net.rho, scale, want_dx0=want_dx0)
         torch.cuda.synchronize()
         cw = {}
         for k in range(K):

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "lp.h")).read()
     declared = set(re.findall(r"\b(lp_[a-z0-9_]+)\s*\(", hdr))
     assert {"lp_module_forward", "lp_local_loss_grad", "lp_module_backward", "lp_auxnet_forward",
-            "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes"} <= declared
+            "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step"} <= declared
     L = B.lib()
     for name in declared:
         assert hasattr(L, name), f"{name} declared in lp.h but not exported"
@@ -141,6 +141,12 @@ def test_call_time_errors_without_touching_the_gpu():
         _expect(B.LP_ERR_INVALID_ARG, B.lp_sgd_update, h, None, 0, 1, [FAKE_PTR + 4, None], ptrs, None, None, 0.1, 0.0, 0.0)   # alignment
         _expect(B.LP_ERR_STATE, B.lp_sgd_update, h, None, 1, 1, ptrs, ptrs, None, None, 0.1, 0.0, 0.0)                  # no AuxNet
         _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_stream_lanes, h, [0, 7])
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_step, h, None, 3, ptrs, ptrs, ptrs[:1], ptrs[:1], None, 1.0, 1.0, 0.0, None,
+                FAKE_PTR, ptrs[:1], FAKE_PTR, FAKE_PTR, ptrs, ptrs)                                               # labels NULL
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_step, h, None, 0, ptrs, ptrs, ptrs[:1], ptrs[:1], None, 1.0, 1.0, 0.0, FAKE_PTR,
+                FAKE_PTR, ptrs[:1], FAKE_PTR, FAKE_PTR, ptrs, ptrs)                                               # empty mask
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_local_step, h, None, 3, ptrs, ptrs, ptrs[:1], ptrs[:1], None, -1.0, 1.0, 0.0, FAKE_PTR,
+                FAKE_PTR, ptrs[:1], FAKE_PTR, FAKE_PTR, ptrs, ptrs)                                               # rho < 0
         _expect(B.LP_ERR_INVALID_ARG, B.lp_net_tensor_info, h, 0, 0, 99)
         _expect(B.LP_ERR_INVALID_ARG, B.lp_net_param_bytes, h, 0, 5)
         _expect(B.LP_ERR_INVALID_ARG, B.lp_debug_saved_tensor, h, 0, 0)                                   # tiny has no stem

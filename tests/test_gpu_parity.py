@@ -378,7 +378,8 @@ def test_chained_auxnet(dtype):
         ls.close()
 
 
-def test_two_iterations_of_the_whole_method():
+@pytest.mark.parametrize("fused", [False, True])
+def test_two_iterations_of_the_whole_method(fused):
     """Every entry point in sequence, twice: AuxNet forward -> module forward -> losses / terminal adjoints -> module
     backward -> multiplier update -> correction of the auxiliary variables -> parameter update -> AuxNet distillation
     gradient -> AuxNet parameter update, on the mini network in fp32, against the same sequence of oracle calls in
@@ -412,10 +413,13 @@ def test_two_iterations_of_the_whole_method():
         for it in range(2):
             # ---- device
             ls.auxnet_forward()
-            ls.module_forward()
-            ls.local_loss_grad(net.rho, scale)
-            ls.module_backward()
-            ls.al_multiplier_update(mstep)
+            if fused:
+                ls.local_step(net.rho, scale, mult_step=mstep)
+            else:
+                ls.module_forward()
+                ls.local_loss_grad(net.rho, scale)
+                ls.module_backward()
+                ls.al_multiplier_update(mstep)
             ls.aux_variable_update(net.rho, scale, eta)
             ls.sgd_update(lr)
             ls.auxnet_distill_grad(scale)
