@@ -151,8 +151,14 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
     const int a_even = a_row_off + ((wc & 1) ? -a_sw : a_sw);      // pair parity of i = 0 is wc & 1
     const int a_odd = a_row_off + ((wc & 1) ? a_sw : -a_sw);
     const int b_row_off = WF_Y_BYTES + (lrow + tap_s) * WF_ROW + 8 * (lq & 3) + 160 * half;
-    auto tr_read = [&](const unsigned char* p) -> uint2 {
-        return __builtin_bit_cast(uint2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(lds_ptr_t)const_cast<unsigned char*>(p)));
+    // The transposing LDS read as inline assembly with explicit lgkmcnt waits below.  Through the compiler's builtin
+    // the read carries no memory operand, so the waitcnt pass cannot tell it from the in-flight direct-to-LDS loads
+    // and puts s_waitcnt vmcnt(0) in front of it: every k-step then waited for the loads of the stage two ahead.
+    auto tr_read = [&](const unsigned char* p) -> u32x2 {
+        u32x2 r;
+        const unsigned a = (unsigned)(uintptr_t)(lds_ptr_t)const_cast<unsigned char*>(p);
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r) : "v"(a));
+        return r;
     };
 
     f32x4 acc[5][5];
@@ -200,12 +206,15 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
                         km3 = ((bits & 64u) ? 0xffffu : 0u) | ((bits & 128u) ? 0xffff0000u : 0u);
                     }
                 }
-                u32x4 af[5];
+                // The compiler does not know that the results of these reads are pending: nothing may touch them before
+                // the s_waitcnt that covers them, and the empty asm behind that wait is where their values become
+                // usable (it orders every use after the wait).  LDS reads return in order.
+                u32x2 alo[5], ahi[5];
 #pragma unroll
                 for (int i = 0; i < 5; ++i) {
                     const unsigned char* pa = Ss + ((i & 1) ? a_odd : a_even) + 32 * i;
-                    const uint2 lo = tr_read(pa), hi = tr_read(pa + 4 * WF_ROW);
-                    af[i] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    alo[i] = tr_read(pa);
+                    ahi[i] = tr_read(pa + 4 * WF_ROW);
                 }
                 // window rows of this lane for h = 0 and h = 1; the pair swizzle follows the actual LDS row
                 const int wr0 = 32 * sub + lrow + tap_s, wr1 = wr0 + 4;
@@ -218,14 +227,27 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
                 const unsigned char* B1e = B1 + ((half & 1) ? -s1 : s1);
                 const unsigned char* B1o = B1 + ((half & 1) ? s1 : -s1);
                 // the X fragments one ahead of the MFMAs that use them (and no further: registers)
-                uint2 lo = tr_read(B0e), hi = tr_read(B1e);
+                u32x2 blo[5], bhi[5];
+                blo[0] = tr_read(B0e); bhi[0] = tr_read(B1e);
+                u32x4 af[5];
 #pragma unroll
                 for (int j = 0; j < 5; ++j) {
-                    const u32x4 bfj = {lo.x & km0, lo.y & km1, hi.x & km2, hi.y & km3};
                     if (j + 1 < 5) {
-                        lo = tr_read((((j + 1) & 1) ? B0o : B0e) + 32 * (j + 1));
-                        hi = tr_read((((j + 1) & 1) ? B1o : B1e) + 32 * (j + 1));
+                        blo[j + 1] = tr_read((((j + 1) & 1) ? B0o : B0e) + 32 * (j + 1));
+                        bhi[j + 1] = tr_read((((j + 1) & 1) ? B1o : B1e) + 32 * (j + 1));
+                        __builtin_amdgcn_s_waitcnt(0xc07f | (2 << 8));                 // lgkmcnt(2): all but the pair just issued
+                    } else {
+                        __builtin_amdgcn_s_waitcnt(0xc07f);                            // lgkmcnt(0)
                     }
+                    if (j == 0) {
+#pragma unroll
+                        for (int i = 0; i < 5; ++i) {
+                            asm volatile("" : "+v"(alo[i]), "+v"(ahi[i]));
+                            af[i] = u32x4{alo[i][0], alo[i][1], ahi[i][0], ahi[i][1]};
+                        }
+                    }
+                    asm volatile("" : "+v"(blo[j]), "+v"(bhi[j]));
+                    const u32x4 bfj = {blo[j][0] & km0, blo[j][1] & km1, bhi[j][0] & km2, bhi[j][1] & km3};
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < 5; ++i) Mma<bf16_t, 16>::run(af[i], bfj, acc[i][j]);
