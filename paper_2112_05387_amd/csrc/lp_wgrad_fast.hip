@@ -105,6 +105,10 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
     // (Everything is recomputed per stage rather than kept in registers: the accumulators need them.)
     const int nld = wave + WF_NW * (WF_LPW - 1) < WF_SLABS ? WF_LPW : WF_LPW - 1;
     const int Mtot = P.M;
+    // the division constants in scalar registers for good (left alone, the compiler re-reads them from the kernel
+    // arguments inside the loops and every re-read is a wait on the scalar cache)
+    unsigned mulW = P.mulW, shW = P.shW, mulH = P.mulH, shH = P.shH;
+    asm volatile("" : "+s"(mulW), "+s"(shW), "+s"(mulH), "+s"(shH));
     auto issue_loads = [&](int st, int kt) {
         const int mt = k_begin + kt * WF_BK;                 // first pixel of the stage (beyond k_end: all zeros)
         const bool live = mt < k_end;
@@ -124,8 +128,8 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
                 } else {
                     // window pixel p; zero unless it exists and its image row hp has hp-(r-1) inside the image
                     const int p = mt + row - 1 + (r - 1) * W;
-                    const unsigned t = fastdiv((unsigned)p, P.mulW, P.shW);
-                    const int hp = (int)t - (int)fastdiv(t, P.mulH, P.shH) * H;
+                    const unsigned t = fastdiv((unsigned)p, mulW, shW);
+                    const int hp = (int)t - (int)fastdiv(t, mulH, shH) * H;
                     ok = ok && row < WF_X_ROWS && (ci0 + ce < Cin) && p >= 0 && p < Mtot && (unsigned)(hp - (r - 1)) < (unsigned)H;
                     off = (unsigned)((p * Cin + ci0 + ce) * 2);
                 }
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(WF_NT) void conv_wgrad_fast_kernel(const WgradGroup
                 unsigned km0 = 0xffffffffu, km1 = 0xffffffffu, km2 = 0xffffffffu, km3 = 0xffffffffu;
                 if (tap_s != 1) {
                     const int k0 = k_begin + kt * WF_BK + sub * 32 + 8 * lg;
-                    const int ow0 = k0 - (int)fastdiv((unsigned)k0, P.mulW, P.shW) * W;
+                    const int ow0 = k0 - (int)fastdiv((unsigned)k0, mulW, shW) * W;
                     const int bad = tap_s == 0 ? 0 : W - 1;
                     int e = bad - ow0;                        // first of this lane's 8 elements in the bad column
                     if (e < 0) e += W;
