@@ -24,6 +24,20 @@ template <typename T> struct Vec {
             }
         }
     }
+    // the 16 bytes as loaded, and their conversion: kernels that want many loads in flight issue all load_raw first
+    __device__ static __forceinline__ u32x4 load_raw(const T* p) { return *reinterpret_cast<const u32x4*>(p); }
+    __device__ static __forceinline__ void unpack(const u32x4& v, float (&f)[N]) {
+        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = __uint_as_float(v[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f[2 * e] = __uint_as_float(v[e] << 16);
+                f[2 * e + 1] = __uint_as_float(v[e] & 0xffff0000u);
+            }
+        }
+    }
     __device__ static __forceinline__ void store(T* p, const float (&f)[N]) {
         u32x4 v;
         if constexpr (sizeof(T) == 4) {
@@ -95,17 +109,19 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
     const unsigned cstep = (unsigned)kElemBlock % (unsigned)cv;
     unsigned cidx = (unsigned)((base + threadIdx.x) % (size_t)cv);
     for (int i0 = threadIdx.x; i0 < kElemVecsPerBlock; i0 += U * kElemBlock) {
-        float f[U][EPV], sk[U][EPV];
+        // Unconditional loads (a vector beyond the end re-reads the last one and is dropped): behind a per-lane branch
+        // the compiler waits for each pair of loads before it issues the next.
+        u32x4 fraw[U], skraw[U];
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t v = base + i0 + u * kElemBlock;
             ok[u] = v < nvec;
-            if (ok[u]) {
-                Vec<T>::load(y + v * EPV, f[u]);
-                if (P.skip_mode) Vec<T>::load(skip + v * EPV, sk[u]);
-            }
+            const size_t vc = ok[u] ? v : nvec - 1;
+            fraw[u] = Vec<T>::load_raw(y + vc * EPV);
+            if (P.skip_mode) skraw[u] = Vec<T>::load_raw(skip + vc * EPV);
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c0 = (int)cidx * EPV;
@@ -113,15 +129,17 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
             if (cidx >= (unsigned)cv) cidx -= (unsigned)cv;
             if (!ok[u]) continue;
             const size_t v = base + i0 + u * kElemBlock;
-            float o[EPV];
+            float f[1][EPV], sk[1][EPV], o[EPV];
+            Vec<T>::unpack(fraw[u], f[0]);
+            if (P.skip_mode) Vec<T>::unpack(skraw[u], sk[0]);
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[u][e], s_sh[c0 + e]);
+            for (int e = 0; e < EPV; ++e) o[e] = fmaf(s_sc[c0 + e], f[0][e], s_sh[c0 + e]);
             if (P.skip_mode == 2) {
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) o[e] += fmaf(s_ssc[c0 + e], sk[u][e], s_ssh[c0 + e]);
+                for (int e = 0; e < EPV; ++e) o[e] += fmaf(s_ssc[c0 + e], sk[0][e], s_ssh[c0 + e]);
             } else if (P.skip_mode == 1) {
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) o[e] += sk[u][e];
+                for (int e = 0; e < EPV; ++e) o[e] += sk[0][e];
             }
             if (P.relu) {
 #pragma unroll
@@ -160,21 +178,27 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
             // four rows per trip: eight independent 16-byte loads in flight per thread
             int r = row0 + trl;
             for (; r + 3 * rl < row1; r += 4 * rl) {
-                float gv[4][EPV], yv[4][EPV];
+                // all eight loads first, as loaded (32 registers); converted one row at a time afterwards
+                u32x4 graw[4], yraw[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    Vec<T>::load(gp + (size_t)(r + u * rl) * C + c0, gv[u]);
-                    Vec<T>::load(y + (size_t)(r + u * rl) * C + c0, yv[u]);
+                    graw[u] = Vec<T>::load_raw(gp + (size_t)(r + u * rl) * C + c0);
+                    yraw[u] = Vec<T>::load_raw(y + (size_t)(r + u * rl) * C + c0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 4; ++u) {
+                    float gv[EPV], yv[EPV];
+                    Vec<T>::unpack(graw[u], gv);
+                    Vec<T>::unpack(yraw[u], yv);
 #pragma unroll
                     for (int e = 0; e < EPV; ++e) {
-                        float gg = gv[u][e];
-                        if (P.relu && !(fmaf(sc[e], yv[u][e], sh[e]) > 0.f)) gg = 0.f;
+                        float gg = gv[e];
+                        if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
                         a1[e] += gg;
-                        a2[e] += gg * ((yv[u][e] - mu[e]) * is[e]);
+                        a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
                     }
+                }
             }
             for (; r < row1; r += rl) {
                 float gv[EPV], yv[EPV];
