@@ -85,16 +85,25 @@ typedef struct {
     int order;                     /* lp_block_order */
 } lp_module_desc;
 
-/* One AuxNet block generating x_{j+1} from the mini-batch (Sec. 4.2, forward map of the auxiliary-variable
- * network, in its one-block form): conv3x3(cin -> cout, stride, pad 1) - BN(batch statistics) [- ReLU]. */
+/* AuxNet j, generating x_{j+1} (Sec. 4.2, forward map of the auxiliary-variable network): a stack of `depth` blocks
+ * conv3x3(pad 1) - BN(batch statistics) - ReLU, the ReLU of the last block being optional.  In its one-block form
+ * (depth 0 or 1) it is conv3x3(cin -> cout, stride) - BN [- ReLU].  With depth = d > 1 the blocks 0..d-2 in front
+ * of the last one have mid_cout[i] output channels and stride mid_stride[i] (each followed by ReLU); the last block
+ * maps mid_cout[d-2] -> cout with `stride`.  The product of the strides must map the input size to that of x_{j+1}.
+ * A stack that starts at the mini-batch and has one block per interface it passes (x_0 -> x_1 -> ... -> x_{j+1}
+ * shapes, parameters of its own) is the recursive AuxNet of Sec. 4.4. */
+#define LP_AUX_MAX_DEPTH 8
 typedef struct {
     int cin, cout, stride, relu;
-    int from_prev;   /* 0: the block reads the mini-batch x_0 (forward-unlocked form);  1: block j reads x_j, the output of
-                        block j-1 (x_{j+1} = AuxNet_j(x_j), the chained form of Algorithm 1's first loop; block 0 reads x_0
-                        either way).  cin and stride then refer to x_j.  lp_auxnet_forward runs chained blocks one after
-                        the other; lp_auxnet_distill_grad runs a chained block again from x_target[j-1], the corrected
+    int from_prev;   /* 0: the AuxNet reads the mini-batch x_0 (forward-unlocked form);  1: AuxNet j reads x_j, the output of
+                        AuxNet j-1 (x_{j+1} = AuxNet_j(x_j), the chained form of Algorithm 1's first loop; AuxNet 0 reads x_0
+                        either way).  cin and the strides then refer to x_j.  lp_auxnet_forward runs chained AuxNets one after
+                        the other; lp_auxnet_distill_grad runs a chained AuxNet again from x_target[j-1], the corrected
                         x_j, before it takes the gradient (Sec. 4.2: theta_j <- argmin |x_{j+1} - AuxNet_j(x_j; theta)|^2);
-                        lp_reauxnet_grad refuses chained blocks (LP_ERR_STATE). */
+                        lp_reauxnet_grad refuses chained AuxNets (LP_ERR_STATE). */
+    int depth;       /* number of blocks, 1..LP_AUX_MAX_DEPTH; 0 is read as 1 */
+    int mid_cout[LP_AUX_MAX_DEPTH - 1];     /* used when depth > 1: blocks 0..depth-2 */
+    int mid_stride[LP_AUX_MAX_DEPTH - 1];
 } lp_aux_desc;
 
 typedef enum { LP_T_CONV = 0, LP_T_BN_GAMMA = 1, LP_T_BN_BETA = 2, LP_T_FC_W = 3, LP_T_FC_B = 4 } lp_tensor_kind;
@@ -115,13 +124,14 @@ typedef struct {
 
 struct lp_net;
 
-/* Build the launch plan for K modules (and K-1 AuxNet blocks when aux != NULL).  Host only: no device
+/* Build the launch plan for K modules (and K-1 AuxNets when aux != NULL).  Host only: no device
  * memory is touched.  Descriptors are copied.  Errors: LP_ERR_INVALID_ARG, LP_ERR_SHAPE, LP_ERR_DTYPE. */
 lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* aux, int dtype, float bn_eps,
                         struct lp_net** out);
 lp_status lp_net_destroy(struct lp_net* net);
 
-/* Packed parameter layout of module k (aux = 0) or of AuxNet block k (aux = 1). */
+/* Packed parameter layout of module k (aux = 0) or of AuxNet k (aux = 1: filter, BN gamma, BN beta of every block of
+ * the stack in order; lp_tensor_info.slot is the block's index in the stack). */
 lp_status lp_net_param_bytes(const struct lp_net* net, int aux, int k, size_t* param_bytes, size_t* grad_bytes);
 lp_status lp_net_num_tensors(const struct lp_net* net, int aux, int k, int* n);
 lp_status lp_net_tensor_info(const struct lp_net* net, int aux, int k, int i, lp_tensor_info* info);
@@ -142,14 +152,15 @@ lp_status lp_net_workspace_bytes(const struct lp_net* net, size_t* bytes);
 lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes);
 
 /* x_{j+1} = AuxNet_j(image), j = 0..K-2  (Sec. 4.2; first loop of Algorithm 1, from-the-image form).
- * image: [N,H,W,C] of module 0.  aux_params[j]: packed parameters of AuxNet block j.  x_out[j]: x_{j+1}. */
+ * image: [N,H,W,C] of module 0.  aux_params[j]: packed parameters of AuxNet j.  x_out[j]: x_{j+1}. */
 lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
                             const void* const* aux_params, void* const* x_out);
 
 /* Gradient of the AuxNet distillation objective of Sec. 4.2 (theta_{k-1} <- argmin |x_k - AuxNet_{k-1}(x_0; theta)|^2,
  * one descent step per iteration; the step itself is the caller's).  For every j with daux_params[j] != NULL:
  *     loss[j] = loss_scale * sum (AuxNet_j(image) - x_target[j])^2,   daux_params[j] = d loss[j] / d theta_j,
- * back-propagated through [ReLU,] batch norm (batch statistics) and the convolution.  daux_params[j]: fp32
+ * back-propagated through [ReLU,] batch norm (batch statistics) and the convolution of every block of the stack.
+ * daux_params[j]: fp32
  * gradient buffer of AuxNet j (second size of lp_net_param_bytes(net, 1, j, ...), tensor table as the
  * parameters'), overwritten.  x_target[j]: K-1 device tensors shaped like x_{j+1}, storage type.  loss: K-1 device
  * floats, entries j overwritten.  Uses the pre-BN output and statistics lp_auxnet_forward saved in the workspace:
@@ -208,14 +219,14 @@ lp_status lp_al_multiplier_update(struct lp_net* net, void* stream, void* const*
  * generated from the mini-batch, x_k = ReAuxNet_k(x_0; xi_k), instead of being a free variable): the gradient of the
  * relaxed objective with respect to x_k,
  *     g_k = scale*(rho*(x_k - y_prev[k-1]) - lam_prev[k-1]) + dx[k],
- * pulled back through the AuxNet block ([ReLU,] BN with batch statistics, conv3x3) into daux_params[k-1]
+ * pulled back through every block of the AuxNet ([ReLU,] BN with batch statistics, conv3x3) into daux_params[k-1]
  * (overwritten; layout of lp_net_param_bytes(net, 1, k-1)).  x_k is the AuxNet output of the last lp_auxnet_forward
  * (recomputed from its saved activations: that call must have run with the same image and aux_params, else
  * LP_ERR_STATE); y_prev[k-1] = F_{k-1}(x_{k-1}) as written by lp_module_forward; dx[k] as written by
  * lp_module_backward for the step whose x_k was that AuxNet output (dx[0] is not read); lam_prev NULL or an entry
  * NULL: penalty method, as the paper states the rule.  daux_params[j] == NULL skips AuxNet j.  Depth of the
- * recursion: one block from the image, as the AuxNet descriptors define it.  The descent step is lp_sgd_update with
- * aux = 1.  Device memory, 16-byte aligned, activation dtype.
+ * recursion: the depth of the AuxNet descriptors (a stack of k blocks from the mini-batch for x_k is the paper's
+ * ReAuxNet_k).  The descent step is lp_sgd_update with aux = 1.  Device memory, 16-byte aligned, activation dtype.
  * Errors: LP_ERR_INVALID_ARG, LP_ERR_STATE, LP_ERR_WORKSPACE; LP_ERR_HIP if a launch fails. */
 lp_status lp_reauxnet_grad(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
                            const void* const* y_prev, const void* const* dx, const void* const* lam_prev, float rho,
@@ -224,7 +235,7 @@ lp_status lp_reauxnet_grad(struct lp_net* net, void* stream, const void* image, 
 /* Parameter update of Sec. 4.1 (W <- W - eta * dW for every tensor of a module, right after the module's adjoint
  * recursion).  The paper states plain gradient descent; the two usual extensions are off at 0:
  *     g' = dW + weight_decay * W;   v <- momentum * v + g'  (when momentum != 0);   W <- W - lr * (v or g').
- * aux = 0: modules (mask bit k, K sets), aux = 1: AuxNet blocks (K-1 sets).  params[k]: packed parameters, updated in
+ * aux = 0: modules (mask bit k, K sets), aux = 1: AuxNets (K-1 sets).  params[k]: packed parameters, updated in
  * place (bf16 tensors are re-rounded); dparams[k]: fp32 gradients; velocity[k]: fp32, layout of dparams[k], required
  * (and updated) when momentum != 0, zero it before the first step; master[k]: optional fp32 copy of the parameters with
  * the layout of dparams[k]: when given, the update is applied to it and params[k] receives the rounded result

@@ -33,7 +33,7 @@ import os
 
 import numpy as np
 
-from workloads.configs import ModuleDesc, AuxDesc, NetDesc, Block, block_convs
+from workloads.configs import ModuleDesc, AuxDesc, NetDesc, Block, block_convs, aux_blocks
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -458,26 +458,52 @@ def aux_variable_update(x, y_prev, dx, lam_prev, rho, eta, scale=1.0):
     return x - eta * (scale * g + _c64(dx))
 
 
+def _aux_stack_fwd(a: AuxDesc, x, params, eps, q):
+    """The AuxNet as the stack its descriptor lists: block i = conv3x3(stride_i, pad 1) -> BN(batch statistics)
+    [-> ReLU], parameters (filter, gamma, beta) at params[3i:3i+3]; blocks in front of the last end in ReLU and their
+    outputs are stored (rounded by q).  Returns the unrounded output of the last block and one cache per block."""
+    qq = q or _id
+    caches = []
+    blocks = aux_blocks(a)
+    h = _c64(x)
+    for i, (_, _, stride, relu) in enumerate(blocks):
+        h, c = _cbr_fwd(h, _c64(params[3 * i]), _c64(params[3 * i + 1]), _c64(params[3 * i + 2]), stride, 1, relu, eps, q)
+        caches.append(c)
+        if i + 1 < len(blocks):
+            h = qq(h)
+    return h, caches
+
+
+def _aux_stack_bwd(g, caches, q):
+    """Pull the gradient g on the AuxNet output back through the stack; returns the parameter gradients in the order
+    of the parameters."""
+    qq = q or _id
+    grads = [None] * len(caches)
+    for i in range(len(caches) - 1, -1, -1):
+        dx, grads[i] = _cbr_bwd(g, caches[i], need_dx=i > 0, q=q)
+        if i > 0:
+            g = qq(dx)
+    return [t for gr in grads for t in gr]
+
+
 def auxnet_forward(a: AuxDesc, image, params, eps=1e-5, q=None):
-    """x = [ReLU](BN(conv3x3_stride(image)))."""
-    out, _ = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]),
-                      a.stride, 1, a.relu, eps, q)
+    """x = AuxNet(image): every block of the stack is [ReLU](BN(conv3x3_stride(.)))."""
+    out, _ = _aux_stack_fwd(a, image, params, eps, q)
     return out if q is None else q(out)
 
 
 def auxnet_distill_grad(a: AuxDesc, image, params, target, eps=1e-5, scale=1.0, q=None):
     """Distillation objective of an AuxNet (Sec. 4.2: theta <- argmin |x_k - AuxNet(x_0; theta)|^2, one descent step
     per iteration; the step is the caller's):  loss = scale * sum (AuxNet(image) - target)^2  and its gradient with
-    respect to theta = (filter, gamma, beta), back-propagated through [ReLU,] BN (batch statistics) and the conv.
-    Returns (loss, [dW, dgamma, dbeta])."""
+    respect to theta = (filter, gamma, beta) of every block, back-propagated through [ReLU,] BN (batch statistics) and
+    the conv.  Returns (loss, [dW, dgamma, dbeta] per block, flat)."""
     qq = q or _id
-    out, cache = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]), a.stride, 1, a.relu, eps, q)
+    out, caches = _aux_stack_fwd(a, image, params, eps, q)
     out = qq(out)
     r = out - _c64(target)
     loss = scale * float(np.sum(r * r))
     g = qq(2.0 * scale * r)
-    _, grads = _cbr_bwd(g, cache, need_dx=False, q=q)
-    return loss, grads
+    return loss, _aux_stack_bwd(g, caches, q)
 
 
 def reauxnet_grad(a: AuxDesc, image, params, y_prev, dx, lam_prev, rho, scale=1.0, eps=1e-5, q=None):
@@ -487,18 +513,17 @@ def reauxnet_grad(a: AuxDesc, image, params, y_prev, dx, lam_prev, rho, scale=1.
         g = scale*(rho*(x_k - F_{k-1}(x_{k-1})) - lam_{k-1}) + dx_k,        x_k = ReAuxNet_k(x_0; xi_k),
     (interface term k-1 plus the local loss of module k, whose input gradient dx_k the module-local backward pass
     returns) pulled back through the AuxNet: d/d xi_k = g * dReAuxNet_k/d xi_k.  The paper states the rule for the
-    penalty method; lam_prev=None is that case, a multiplier enters as in the correction of x_k.  Depth one (a single
-    conv3x3 + BN [+ ReLU] block from the image), as the configurations define the AuxNet.
-    Returns [dW, dgamma, dbeta]."""
+    penalty method; lam_prev=None is that case, a multiplier enters as in the correction of x_k.  ReAuxNet_k is the
+    stack the descriptor lists (k blocks from the mini-batch in the paper's form).
+    Returns [dW, dgamma, dbeta] per block, flat."""
     qq = q or _id
-    out, cache = _cbr_fwd(_c64(image), _c64(params[0]), _c64(params[1]), _c64(params[2]), a.stride, 1, a.relu, eps, q)
+    out, caches = _aux_stack_fwd(a, image, params, eps, q)
     out = qq(out)
     g = rho * (out - _c64(y_prev))
     if lam_prev is not None:
         g = g - _c64(lam_prev)
     g = qq(scale * g + _c64(dx))
-    _, grads = _cbr_bwd(g, cache, need_dx=False, q=q)
-    return grads
+    return _aux_stack_bwd(g, caches, q)
 
 
 # ----------------------------------------------------------------------------- whole step / serial net

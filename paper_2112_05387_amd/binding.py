@@ -32,8 +32,13 @@ class lp_module_desc(ctypes.Structure):
                 ("order", c_int)]
 
 
+LP_AUX_MAX_DEPTH = 8
+
+
 class lp_aux_desc(ctypes.Structure):
-    _fields_ = [("cin", c_int), ("cout", c_int), ("stride", c_int), ("relu", c_int), ("from_prev", c_int)]
+    _fields_ = [("cin", c_int), ("cout", c_int), ("stride", c_int), ("relu", c_int), ("from_prev", c_int),
+                ("depth", c_int), ("mid_cout", c_int * (LP_AUX_MAX_DEPTH - 1)),
+                ("mid_stride", c_int * (LP_AUX_MAX_DEPTH - 1))]
 
 
 class lp_tensor_info(ctypes.Structure):
@@ -138,7 +143,14 @@ def lp_net_create(modules, aux, dtype, bn_eps):
     if aux is not None:
         auxp = (lp_aux_desc * max(len(aux), 1))()
         for j, a in enumerate(aux):
-            auxp[j] = lp_aux_desc(a.cin, a.cout, a.stride, int(a.relu), int(getattr(a, "from_prev", False)))
+            mid = tuple(getattr(a, "mid", ()))
+            if len(mid) > LP_AUX_MAX_DEPTH - 1:
+                raise ValueError(f"AuxNet {j}: {len(mid) + 1} blocks, at most {LP_AUX_MAX_DEPTH}")
+            d = lp_aux_desc(a.cin, a.cout, a.stride, int(a.relu), int(getattr(a, "from_prev", False)), len(mid) + 1)
+            for i, (co, sd) in enumerate(mid):
+                d.mid_cout[i] = co
+                d.mid_stride[i] = sd
+            auxp[j] = d
     out = c_void_p()
     dt = dtype if isinstance(dtype, int) else {"f32": LP_F32, "bf16": LP_BF16}[dtype]
     _check(lib().lp_net_create(K, mods, auxp, dt, float(bn_eps), ctypes.byref(out)))

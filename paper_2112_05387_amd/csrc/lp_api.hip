@@ -153,7 +153,9 @@ struct ModulePlan {
 };
 struct AuxPlan {
     lp_aux_desc d;
-    Unit u;
+    std::vector<Unit> pre;                 // the blocks in front of the last one (conv - BN - ReLU each)
+    Unit u;                                // the last block: its output is the auxiliary variable
+    std::vector<size_t> ws_act, ws_gact;   // output of pre[i] and the gradient with respect to it
     std::vector<lp_tensor_info> tensors;
     size_t param_bytes = 0, grad_bytes = 0;
     size_t ws_out = 0, ws_g = 0;           // recomputed AuxNet output and the gradient on it (distillation)
@@ -1020,46 +1022,100 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     const ModulePlan& m0 = net->mods[a.chained ? j : 0];      // whose input tensor the AuxNet reads: x_j or the mini-batch x_0
     const ModulePlan& mt = net->mods[j + 1];
     const int epv = net->dtype == LP_BF16 ? 8 : 4;
+    const int depth = a.d.depth > 0 ? a.d.depth : 1;
+    if (depth > LP_AUX_MAX_DEPTH) return fail(LP_ERR_INVALID_ARG, "aux %d: depth %d > %d", j, depth, LP_AUX_MAX_DEPTH);
     if (a.d.cin != m0.d.C) return fail(LP_ERR_SHAPE, "aux %d: cin %d != channels of its input (%d)", j, a.d.cin, m0.d.C);
     if (a.d.cout != mt.d.C || a.d.cout % epv) return fail(LP_ERR_SHAPE, "aux %d: cout %d != channels of x_%d (%d)", j, a.d.cout, j + 1, mt.d.C);
-    if (a.d.stride < 1 || m0.d.H != mt.d.H * a.d.stride || m0.d.W != mt.d.W * a.d.stride)
-        return fail(LP_ERR_SHAPE, "aux %d: stride %d does not map %dx%d to %dx%d", j, a.d.stride, m0.d.H, m0.d.W, mt.d.H, mt.d.W);
-    a.u = make_unit(3, a.d.cin, a.d.cout, a.d.stride, 1, m0.d.N, m0.d.H, m0.d.W, a.d.relu != 0);
+    // the stack: blocks 0..depth-2 end in ReLU, the last one maps to the shape of x_{j+1}
+    int c = a.d.cin, H = m0.d.H, W = m0.d.W;
+    for (int i = 0; i + 1 < depth; ++i) {
+        const int co = a.d.mid_cout[i], sd = a.d.mid_stride[i];
+        if (co < 1 || co % epv) return fail(LP_ERR_SHAPE, "aux %d: block %d has %d output channels (need a positive multiple of %d)", j, i, co, epv);
+        if (sd < 1 || H % sd || W % sd) return fail(LP_ERR_SHAPE, "aux %d: stride %d of block %d does not divide %dx%d", j, sd, i, H, W);
+        a.pre.push_back(make_unit(3, c, co, sd, 1, m0.d.N, H, W, true));
+        c = co; H = a.pre.back().Ho; W = a.pre.back().Wo;
+    }
+    if (a.d.stride < 1 || H != mt.d.H * a.d.stride || W != mt.d.W * a.d.stride)
+        return fail(LP_ERR_SHAPE, "aux %d: stride %d does not map %dx%d to %dx%d", j, a.d.stride, H, W, mt.d.H, mt.d.W);
+    a.u = make_unit(3, c, a.d.cout, a.d.stride, 1, m0.d.N, H, W, a.d.relu != 0);
     if (a.u.Ho != mt.d.H || a.u.Wo != mt.d.W) return fail(LP_ERR_SHAPE, "aux %d: output %dx%d != %dx%d", j, a.u.Ho, a.u.Wo, mt.d.H, mt.d.W);
     size_t poff = 0, goff = 0;
-    add_unit_tensors(a.tensors, poff, goff, a.u, -1, 0, net->dtype);
+    for (int i = 0; i + 1 < depth; ++i) add_unit_tensors(a.tensors, poff, goff, a.pre[i], -1, i, net->dtype);
+    add_unit_tensors(a.tensors, poff, goff, a.u, -1, depth - 1, net->dtype);
     a.param_bytes = poff; a.grad_bytes = goff;
-    a.u.ws_stats = ws.take(sizeof(double) * 2 * a.u.cout);
-    a.u.ws_y = ws.take(a.u.out_elems() * net->esz);
-    Builder B{net};
-    const Ref st = mk(SP_WS, 0, a.u.ws_stats), y = mk(SP_WS, 0, a.u.ws_y);
-    a.fwd.push_back(Step{B.fill(st, sizeof(double) * 2 * a.u.cout)});
-    const Ref wflt = mk(SP_AUXP, j, a.tensors[a.u.t_w].offset);
-    a.fwd.push_back(Step{B.conv_fwd(a.u, a.chained ? mk(SP_XOUT, j - 1, 0) : mk(SP_IMAGE, 0, 0), wflt, y, st)});
-    a.fwd.push_back(Step{B.bn_apply(a.u.N * a.u.Ho * a.u.Wo, a.u.cout, y, mk(SP_XOUT, j, 0), st,
-                                    mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), mk(SP_AUXP, j, a.tensors[a.u.t_b].offset),
-                                    a.d.relu != 0)});
-    // distillation gradient: recompute the output from the saved pre-BN tensor, (loss kernel), BN backward, filter gradient
-    a.u.ws_red = ws.take(sizeof(double) * 2 * a.u.cout);
-    a.u.ws_dy = ws.take(a.u.out_elems() * net->esz);
+    std::vector<Unit*> us;
+    for (Unit& p : a.pre) us.push_back(&p);
+    us.push_back(&a.u);
+    for (int i = 0; i < depth; ++i) {
+        Unit& u = *us[i];
+        u.ws_stats = ws.take(sizeof(double) * 2 * u.cout);
+        u.ws_red = ws.take(sizeof(double) * 2 * u.cout);
+        u.ws_y = ws.take(u.out_elems() * net->esz);
+        u.ws_dy = ws.take(u.out_elems() * net->esz);
+        if (i > 0) u.ws_wt = ws.take((size_t)u.cout * 9 * u.cin * net->esz);
+        if (i + 1 < depth) {
+            a.ws_act.push_back(ws.take(u.out_elems() * net->esz));
+            a.ws_gact.push_back(ws.take(u.out_elems() * net->esz));
+        }
+    }
     a.ws_out = ws.take(a.u.out_elems() * net->esz);
     a.ws_g = ws.take(a.u.out_elems() * net->esz);
-    const int M = a.u.N * a.u.Ho * a.u.Wo;
-    const Ref gam = mk(SP_AUXP, j, a.tensors[a.u.t_g].offset), bet = mk(SP_AUXP, j, a.tensors[a.u.t_b].offset);
-    const Ref red = mk(SP_WS, 0, a.u.ws_red), dyc = mk(SP_WS, 0, a.u.ws_dy), g = mk(SP_WS, 0, a.ws_g);
-    // A chained AuxNet is distilled at the CORRECTED input x_j (Sec. 4.2): its forward pass is run again from there.
+
+    Builder B{net};
+    auto W_ = [&](size_t off) { return mk(SP_WS, 0, off); };
+    auto P_ = [&](int t) { return mk(SP_AUXP, j, a.tensors[t].offset); };
+    auto G_ = [&](int t) { return mk(SP_AUXG, j, a.tensors[t].grad_offset); };
+    auto Mof = [](const Unit& u) { return u.N * u.Ho * u.Wo; };
+    // forward pass of the stack from `in`, the last block writing to `out`
+    auto forward = [&](Program& prog, Ref in, Ref out) {
+        for (int i = 0; i < depth; ++i) {
+            const Unit& u = *us[i];
+            const Ref dst = i + 1 < depth ? W_(a.ws_act[i]) : out;
+            prog.push_back(Step{B.conv_fwd(u, i == 0 ? in : W_(a.ws_act[i - 1]), P_(u.t_w), W_(u.ws_y), W_(u.ws_stats))});
+            prog.push_back(Step{B.bn_apply(Mof(u), u.cout, W_(u.ws_y), dst, W_(u.ws_stats), P_(u.t_g), P_(u.t_b), u.relu)});
+        }
+    };
+    auto fill_stats = [&](Step& s) {
+        for (int i = 0; i < depth; ++i) s.push_back(B.fill(W_(us[i]->ws_stats), sizeof(double) * 2 * us[i]->cout));
+    };
+    const Ref in0 = a.chained ? mk(SP_XOUT, j - 1, 0) : mk(SP_IMAGE, 0, 0);
+    {
+        Step s0;
+        fill_stats(s0);
+        a.fwd.push_back(s0);
+    }
+    forward(a.fwd, in0, mk(SP_XOUT, j, 0));
+
+    // Gradient through the stack.  First part (before the loss or correction kernel): the AuxNet output again, from the
+    // saved pre-BN tensor of the last block; a chained AuxNet is distilled at the CORRECTED input x_j (Sec. 4.2), so
+    // its whole forward pass is run again from there.
     const Ref din = a.chained ? mk(SP_XTGT, j - 1, 0) : mk(SP_IMAGE, 0, 0);
     {
-        Step s0{B.fill(red, sizeof(double) * 2 * a.u.cout), B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)};
-        if (a.chained) s0.push_back(B.fill(st, sizeof(double) * 2 * a.u.cout));
+        Step s0{B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)};
+        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(W_(us[i]->ws_red), sizeof(double) * 2 * us[i]->cout));
+        if (a.chained) fill_stats(s0);
+        for (int i = 1; i < depth; ++i) s0.push_back(B.wtrans(*us[i], P_(us[i]->t_w), W_(us[i]->ws_wt)));
         a.bwd_a.push_back(s0);
     }
-    if (a.chained) a.bwd_a.push_back(Step{B.conv_fwd(a.u, din, wflt, y, st)});
-    a.bwd_a.push_back(Step{B.bn_apply(M, a.u.cout, y, mk(SP_WS, 0, a.ws_out), st, gam, bet, a.d.relu != 0)});
-    const Ref dgam = mk(SP_AUXG, j, a.tensors[a.u.t_g].grad_offset), dbet = mk(SP_AUXG, j, a.tensors[a.u.t_b].grad_offset);
-    a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
-    a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, M, a.u.cout, g, y, dyc, st, gam, bet, red, dgam, dbet, a.d.relu != 0)});
-    a.bwd_b.push_back(Step{B.wgrad(a.u, din, dyc, mk(SP_AUXG, j, a.tensors[a.u.t_w].grad_offset))});
+    if (a.chained) forward(a.bwd_a, din, W_(a.ws_out));
+    else a.bwd_a.push_back(Step{B.bn_apply(Mof(a.u), a.u.cout, W_(a.u.ws_y), W_(a.ws_out), W_(a.u.ws_stats), P_(a.u.t_g), P_(a.u.t_b), a.u.relu)});
+    // Second part: from the gradient on the output, block by block towards the input; the filter gradients last.
+    Step wg_tail;
+    Ref gcur = W_(a.ws_g);
+    for (int i = depth - 1; i >= 0; --i) {
+        const Unit& u = *us[i];
+        const Ref y = W_(u.ws_y), dyc = W_(u.ws_dy), st = W_(u.ws_stats), red = W_(u.ws_red);
+        a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gcur, y, dyc, st, P_(u.t_g), P_(u.t_b), red, G_(u.t_g), G_(u.t_b), u.relu)});
+        a.bwd_b.push_back(Step{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gcur, y, dyc, st, P_(u.t_g), P_(u.t_b), red, G_(u.t_g), G_(u.t_b), u.relu)});
+        wg_tail.push_back(B.wgrad(u, i == 0 ? din : W_(a.ws_act[i - 1]), dyc, G_(u.t_w)));
+        if (i > 0) {
+            Step s;
+            B.conv_dgrad(u, dyc, W_(u.ws_wt), W_(a.ws_gact[i - 1]), Ref(), Ref(), s);
+            a.bwd_b.push_back(s);
+            gcur = W_(a.ws_gact[i - 1]);
+        }
+    }
+    a.bwd_b.push_back(wg_tail);
     return LP_OK;
 }
 

@@ -67,6 +67,47 @@ def test_tensor_table_matches_workload_specs(name):
         B.lp_net_destroy(h)
 
 
+@pytest.mark.parametrize("form", ["reaux", "deep", "chained_deep"])
+def test_aux_stack_tensor_table(form):
+    """AuxNets of several blocks: the parameter table lists filter, gamma, beta of every block in order, slot = index
+    of the block, and matches the shared tensor specs."""
+    from workloads import configs as cfg
+    net = wl.make_config("resnet56")
+    ws0 = None
+    h = B.lp_net_create(net.modules, net.aux, net.dtype, net.bn_eps)
+    try:
+        ws0 = B.lp_net_workspace_bytes(h)
+    finally:
+        B.lp_net_destroy(h)
+    if form == "reaux":
+        cfg.reaux(net)
+        assert [len(a.mid) for a in net.aux] == list(range(net.K - 1))
+        assert cfg.aux_blocks(net.aux[2]) == [(3, 16, 1, True), (16, 16, 1, True), (16, 32, 2, False)]
+    elif form == "deep":
+        cfg.deepen_aux(net, 2)
+    else:
+        cfg.deepen_aux(cfg.chain_aux(net), 1)
+    kinds = {"conv": B.LP_T_CONV, "bn_gamma": B.LP_T_BN_GAMMA, "bn_beta": B.LP_T_BN_BETA}
+    h = B.lp_net_create(net.modules, net.aux, net.dtype, net.bn_eps)
+    try:
+        for j, a in enumerate(net.aux):
+            specs = wl.aux_tensor_specs(a)
+            assert len(specs) == 3 * (len(a.mid) + 1) and B.lp_net_num_tensors(h, 1, j) == len(specs)
+            pb, gb = B.lp_net_param_bytes(h, 1, j)
+            end = gend = 0
+            for i, sp in enumerate(specs):
+                t = B.lp_net_tensor_info(h, 1, j, i)
+                assert t.kind == kinds[sp.kind] and t.block == -1 and t.slot == sp.slot == i // 3
+                assert tuple(t.dims[d] for d in range(t.ndim)) == tuple(sp.shape)
+                assert t.offset % 256 == 0 and t.offset >= end and t.grad_offset >= gend
+                end = t.offset + t.numel * (2 if t.dtype == B.LP_BF16 else 4)
+                gend = t.grad_offset + t.numel * 4
+            assert end <= pb and gend <= gb
+        assert B.lp_net_workspace_bytes(h) > ws0
+    finally:
+        B.lp_net_destroy(h)
+
+
 def _mod(blocks, N=2, H=8, W=8, C=8, stem=0, stem_cout=0, head=True, n_classes=4):
     return ModuleDesc(stem=stem, stem_cout=stem_cout, blocks=blocks, head=head, n_classes=n_classes, N=N, H=H, W=W, C=C)
 
@@ -100,6 +141,13 @@ def test_create_rejects_bad_descriptors():
     _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(3, 8, 1, False)], "f32", 1e-5)       # aux cin != image channels
     _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 16, 1, False)], "f32", 1e-5)      # aux cout
     _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 8, 2, False)], "f32", 1e-5)       # aux stride
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 8, 1, False, mid=((6, 1),))], "f32", 1e-5)   # width of a block in front: 6 % 4
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 8, 1, False, mid=((8, 2),))], "f32", 1e-5)   # strides do not multiply to 1
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, two, [AuxDesc(8, 8, 1, False, mid=((8, 3),))], "f32", 1e-5)   # 8 % 3
+    with pytest.raises(ValueError):
+        B.lp_net_create(two, [AuxDesc(8, 8, 1, False, mid=((8, 1),) * 8)], "f32", 1e-5)                    # nine blocks
+    h = B.lp_net_create(two, [AuxDesc(8, 8, 1, False, mid=((16, 1), (8, 1)))], "f32", 1e-5)
+    B.lp_net_destroy(h)
     h = B.lp_net_create(two, [AuxDesc(8, 8, 1, True)], "f32", 1e-5)
     B.lp_net_destroy(h)
 

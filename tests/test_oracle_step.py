@@ -300,6 +300,56 @@ def test_chained_auxnet_distill_finite_differences():
         assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (i, fd, an)
 
 
+def _three_block_aux():
+    """An AuxNet of three blocks from a 3-channel 8x8 mini-batch: 3 -> 4 (stride 2, ReLU) -> 8 (stride 1, ReLU) -> 8
+    (stride 2, the AuxNet's own ReLU flag off)."""
+    from workloads.configs import AuxDesc, NetDesc, aux_blocks, aux_tensor_specs
+    a = AuxDesc(cin=3, cout=8, stride=2, relu=False, mid=((4, 2), (8, 1)))
+    assert aux_blocks(a) == [(3, 4, 2, True), (4, 8, 1, True), (8, 8, 2, False)]
+    assert [sp.shape for sp in aux_tensor_specs(a)][::3] == [(4, 3, 3, 3), (8, 3, 3, 4), (8, 3, 3, 8)]
+    net = NetDesc(name="aux3", K=2, modules=[], aux=[a], dtype="f32", seed=21)
+    return net, a, wl.normal(21, "aux3_image", (2, 8, 8, 3)), wl.make_aux_params(net, 0)
+
+
+def test_deep_auxnet_against_library_layers():
+    """A three-block AuxNet re-composed from a library's float64 layers: pins the order of the blocks, the stride of
+    each, ReLU after the blocks in front of the last and none after the last, and which parameters each block uses."""
+    import torch
+    import torch.nn.functional as F
+    net, a, img, p = _three_block_aux()
+    t = lambda v: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float64))
+    h = t(img).permute(0, 3, 1, 2)
+    for i, (stride, relu) in enumerate([(2, True), (1, True), (2, False)]):
+        h = F.conv2d(h, t(p[3 * i]).permute(0, 3, 1, 2), stride=stride, padding=1)
+        h = F.batch_norm(h, None, None, t(p[3 * i + 1]), t(p[3 * i + 2]), True, 0.0, net.bn_eps)
+        h = F.relu(h) if relu else h
+    got = lpref.auxnet_forward(a, img, p, net.bn_eps)
+    assert got.shape == (2, 2, 2, 8) and np.any(got < 0)
+    np.testing.assert_allclose(got, h.permute(0, 2, 3, 1).numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_deep_auxnet_distill_finite_differences():
+    """Distillation gradient of the three-block AuxNet with respect to all nine parameter tensors against central
+    differences along random directions."""
+    net, a, img, p = _three_block_aux()
+    out = lpref.auxnet_forward(a, img, p, net.bn_eps)
+    target = out + wl.normal(22, "aux3_target", out.shape, 0.4)
+    scale, h = 0.3, 1e-6
+    loss, grads = lpref.auxnet_distill_grad(a, img, p, target, net.bn_eps, scale)
+    f = lambda pp: scale * np.sum((lpref.auxnet_forward(a, img, pp, net.bn_eps) - target) ** 2)
+    assert abs(loss - f(p)) <= 1e-12 * abs(loss) and len(grads) == 9
+    rng = np.random.default_rng(23)
+    for i in range(9):
+        assert grads[i].shape == p[i].shape
+        d = rng.standard_normal(p[i].shape)
+        pp, pm = list(p), list(p)
+        pp[i], pm[i] = p[i] + h * d, p[i] - h * d
+        fd = (f(pp) - f(pm)) / (2 * h)
+        an = float(np.sum(grads[i] * d))
+        assert abs(an) > 1e-6, i            # every block's parameters take part (BN's shift-invariance aside)
+        assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (i, fd, an)
+
+
 @pytest.mark.parametrize("order", ["post", "pre"])
 def test_module_forward_against_library_layers(order):
     """The forward pass of every module, re-composed from a library's float64 layers (conv2d, training-mode
@@ -349,16 +399,22 @@ def test_module_forward_against_library_layers(order):
         assert i + (2 if m.head else 0) == len(p)
 
 
-@pytest.mark.parametrize("al,relu", [(True, False), (False, True)])
-def test_reauxnet_grad_finite_differences(al, relu):
+@pytest.mark.parametrize("al,relu,stack", [(True, False, False), (False, True, False), (True, True, True), (False, False, True)])
+def test_reauxnet_grad_finite_differences(al, relu, stack):
     """With x_k = AuxNet(image; xi) substituted, the relaxed objective depends on xi through the interface term k-1
     and through the local loss of module k.  reauxnet_grad (fed with the oracle's dx_k at that x_k) must equal the
     central-difference gradient of that composite, for the middle module (interface loss below it) and for the
-    last one (cross-entropy below it)."""
+    last one (cross-entropy below it).  stack: x_k comes from k blocks of its own (the recursion of Sec. 4.4 at its
+    full depth), else from one block."""
+    from workloads import configs as cfg
     from workloads.configs import AuxDesc
     net = mini_basic()
     net.rho, net.al, net.lam_sigma = 1.4, al, 0.3
-    net.aux = [AuxDesc(cin=3, cout=m.C, stride=net.modules[0].H // m.H, relu=relu) for m in net.modules[1:]]
+    if stack:
+        cfg.reaux(net, relu)
+        assert [len(a.mid) for a in net.aux] == [0, 1] and net.aux[1].mid == ((8, 2),) and net.aux[1].stride == 1
+    else:
+        net.aux = [AuxDesc(cin=3, cout=m.C, stride=net.modules[0].H // m.H, relu=relu) for m in net.modules[1:]]
     inp = step_inputs(net, lpref)
     scale, h = 0.7, 1e-6
     rng = np.random.default_rng(17)
@@ -376,7 +432,8 @@ def test_reauxnet_grad_finite_differences(al, relu):
             return below + _local_loss(net, k, x, inp["params"][k], inp["xs"][k + 1] if k < net.K - 1 else None,
                                        inp["lams"][k] if (al and k < net.K - 1) else None, inp["labels"], scale)
 
-        for i in range(3):
+        assert len(grads) == len(theta) == 3 * (len(a.mid) + 1)
+        for i in range(len(theta)):
             assert grads[i].shape == theta[i].shape
             d = rng.standard_normal(theta[i].shape)
             tp, tm = list(theta), list(theta)

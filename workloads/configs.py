@@ -53,6 +53,18 @@ class AuxDesc:
     stride: int
     relu: bool
     from_prev: bool = False   # block j reads x_j (chained AuxNets, x_{j+1} = AuxNet_j(x_j)) instead of the mini-batch
+    mid: Tuple[Tuple[int, int], ...] = ()   # (cout, stride) of the conv3x3-BN-ReLU blocks in front of the last block
+
+
+def aux_blocks(a: "AuxDesc"):
+    """The stack of an AuxNet as (cin, cout, stride, relu) per block: the `mid` blocks end in ReLU, the last block maps
+    to `cout` with `stride` and the AuxNet's own ReLU flag."""
+    out, c = [], a.cin
+    for co, sd in a.mid:
+        out.append((c, co, sd, True))
+        c = co
+    out.append((c, a.cout, a.stride, bool(a.relu)))
+    return out
 
 
 @dataclass
@@ -124,6 +136,25 @@ def chain_aux(net: NetDesc, relu: bool = False) -> NetDesc:
     """AuxNet blocks that read the previous auxiliary variable: block j maps x_j (module j's input) to x_{j+1}."""
     net.aux = [AuxDesc(cin=net.modules[j].C, cout=net.modules[j + 1].C, stride=net.modules[j].H // net.modules[j + 1].H,
                        relu=relu, from_prev=True) for j in range(net.K - 1)]
+    return net
+
+
+def reaux(net: NetDesc, relu: bool = False) -> NetDesc:
+    """Recursive AuxNets (Sec. 4.4): x_{j+1} is generated from the mini-batch by a stack of j+1 blocks of its own, block
+    i of the stack mapping the shape of x_i to the shape of x_{i+1}."""
+    ms = net.modules
+    hop = lambda i: (ms[i + 1].C, ms[i].H // ms[i + 1].H)
+    net.aux = [AuxDesc(cin=ms[0].C, cout=ms[j + 1].C, stride=ms[j].H // ms[j + 1].H, relu=relu,
+                       mid=tuple(hop(i) for i in range(j))) for j in range(net.K - 1)]
+    return net
+
+
+def deepen_aux(net: NetDesc, extra: int = 1) -> NetDesc:
+    """Every AuxNet gets `extra` more blocks in front of its last one: the first block does the change of shape, the
+    others keep it (conv3x3 stride 1 at the width of the output)."""
+    for a in net.aux:
+        a.mid = ((a.cout, a.stride),) + ((a.cout, 1),) * (extra - 1)
+        a.stride = 1
     return net
 
 
@@ -236,9 +267,15 @@ def module_tensor_specs(m: ModuleDesc) -> List[TensorSpec]:
 
 
 def aux_tensor_specs(a: AuxDesc) -> List[TensorSpec]:
-    return [TensorSpec("aux.conv", "conv", (a.cout, 3, 3, a.cin), 9 * a.cin, -1, 0),
-            TensorSpec("aux.bn.gamma", "bn_gamma", (a.cout,), 0, -1, 0),
-            TensorSpec("aux.bn.beta", "bn_beta", (a.cout,), 0, -1, 0)]
+    """Filter, BN gamma, BN beta of every block of the stack, in order (slot = index of the block)."""
+    blocks = aux_blocks(a)
+    out = []
+    for i, (ci, co, _, _) in enumerate(blocks):
+        pre = "aux" if len(blocks) == 1 else f"aux.b{i}"
+        out += [TensorSpec(f"{pre}.conv", "conv", (co, 3, 3, ci), 9 * ci, -1, i),
+                TensorSpec(f"{pre}.bn.gamma", "bn_gamma", (co,), 0, -1, i),
+                TensorSpec(f"{pre}.bn.beta", "bn_beta", (co,), 0, -1, i)]
+    return out
 
 
 def module_conv_shapes(m: ModuleDesc):
