@@ -159,8 +159,6 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
     const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M, cv = C / EPV;
     const int b = blockIdx.x - P.block_start;
-    const int rows_pb = (M + P.nblocks - 1) / P.nblocks;
-    const int row0 = b * rows_pb, row1 = min(M, row0 + rows_pb);
     const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
     const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
     for (int cbase = 0; cbase < cv; cbase += kElemBlock) {
@@ -175,15 +173,19 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
             float sc[EPV], sh[EPV], mu[EPV], is[EPV];
 #pragma unroll
             for (int e = 0; e < EPV; ++e) bn_coeffs(P.stats, P.gamma, P.beta, c0 + e, C, M, g.eps, sc[e], sh[e], mu[e], is[e]);
-            // four rows per trip: eight independent 16-byte loads in flight per thread
-            int r = row0 + trl;
-            for (; r + 3 * rl < row1; r += 4 * rl) {
-                // all eight loads first, as loaded (32 registers); converted one row at a time afterwards
+            // Four rows per trip: eight independent 16-byte loads in flight per thread.  The trips of the blocks are
+            // interleaved (block b takes trips b, b + nblocks, ...), so that at any time the blocks together read one
+            // contiguous, moving window of the two tensors instead of nblocks distant streams.
+            const int rows_trip = 4 * rl;
+            for (int r0 = b * rows_trip; r0 < M; r0 += P.nblocks * rows_trip) {
+                // all eight loads first, as loaded (32 registers); converted one row at a time afterwards.  Rows past
+                // the end read the last row and count as zero.
                 u32x4 graw[4], yraw[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    graw[u] = Vec<T>::load_raw(gp + (size_t)(r + u * rl) * C + c0);
-                    yraw[u] = Vec<T>::load_raw(y + (size_t)(r + u * rl) * C + c0);
+                    const int r = min(r0 + trl + u * rl, M - 1);
+                    graw[u] = Vec<T>::load_raw(gp + (size_t)r * C + c0);
+                    yraw[u] = Vec<T>::load_raw(y + (size_t)r * C + c0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -191,25 +193,14 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
                     float gv[EPV], yv[EPV];
                     Vec<T>::unpack(graw[u], gv);
                     Vec<T>::unpack(yraw[u], yv);
+                    const bool in = r0 + trl + u * rl < M;
 #pragma unroll
                     for (int e = 0; e < EPV; ++e) {
-                        float gg = gv[e];
+                        float gg = in ? gv[e] : 0.f;
                         if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
                         a1[e] += gg;
                         a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
                     }
-                }
-            }
-            for (; r < row1; r += rl) {
-                float gv[EPV], yv[EPV];
-                Vec<T>::load(gp + (size_t)r * C + c0, gv);
-                Vec<T>::load(y + (size_t)r * C + c0, yv);
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    float gg = gv[e];
-                    if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
-                    a1[e] += gg;
-                    a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
                 }
             }
         }
