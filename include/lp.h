@@ -202,8 +202,9 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
  * lp_module_forward, lp_local_loss_grad, lp_module_backward and, when lam != NULL and mult_step != 0,
  * lp_al_multiplier_update(lam, y, x_next, mult_step), with the same arguments, results and conventions.  The
  * difference is the schedule: here every stream lane runs through all phases of its own modules without waiting for
- * the other lanes between the phases (the separate calls join all lanes at the end of each call).  The multiplier
- * lam[k] is read by the loss of module k and updated after that module's backward pass.
+ * the other lanes between the phases (the separate calls join all lanes at the end of each call), and the multiplier
+ * update rides on the loss kernel, which has y, x_next and lam at hand: it writes dy from the old lam[k] and then the
+ * new lam[k] (nothing else in the step reads it), bit for bit what the separate call writes.
  * Errors as the four calls'. */
 lp_status lp_local_step(struct lp_net* net, void* stream, uint32_t module_mask, const void* const* x,
                         const void* const* params, void* const* y, const void* const* x_next, void* const* lam, float rho,
@@ -275,7 +276,7 @@ lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, cons
  * the list (out == NULL: only the count).  kind: 0 clear, 1 filter re-layout, 2 conv forward/data-gradient,
  * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
  * apply, 10 conv weight-gradient, 11 batch statistics of a module input, 12 loss / terminal adjoint, 13 cross-entropy,
- * 14 multiplier update (12-14: launches of lp_local_step only).  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
+ * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12).  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
  * every operand tensor moved once). */
 typedef struct { int kind, cfg, nprob; float ms; double flops, bytes; } lp_profile_rec;
 lp_status lp_profile_enable(struct lp_net* net, int on);

@@ -89,7 +89,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
 }
 
 enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
-              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE, OP_MULT };
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE };
 
 struct Op {
     int type = 0, cfg = 0;
@@ -97,7 +97,7 @@ struct Op {
     bool vec = true;
     Ref r[10];
     size_t fill_bytes = 0;
-    size_t numel = 0;                      // OP_LOSS, OP_MULT: elements of the interface tensor
+    size_t numel = 0;                      // OP_LOSS: elements of the interface tensor
     ConvProb conv;
     WgradProb wg;
     WtransProb wt;
@@ -976,11 +976,11 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
     return LP_OK;
 }
 
-// the whole local step of module k as one list: forward, loss and terminal adjoint, backward, multiplier update
+// the whole local step of module k as one list: forward, loss and terminal adjoint (with the multiplier update), backward
 static void build_step_programs(lp_net* net, int k) {
     ModulePlan& m = net->mods[k];
     const bool last = (k == net->K - 1);
-    Step loss_step, mult_step;
+    Step loss_step;
     if (last) {
         Op o; o.type = OP_CE;
         memset(&o.head, 0, sizeof(o.head));
@@ -993,10 +993,7 @@ static void build_step_programs(lp_net* net, int k) {
         Op o; o.type = OP_LOSS; o.numel = numel;
         o.r[0] = mk(SP_Y, k, 0); o.r[1] = mk(SP_XNEXT, k, 0); o.r[2] = mk(SP_LAM, k, 0); o.r[3] = mk(SP_DY, k, 0);
         o.r[4] = mk(SP_LOSS, 0, sizeof(float) * k);
-        loss_step.push_back(o);
-        Op u; u.type = OP_MULT; u.numel = numel;
-        u.r[0] = mk(SP_LAM, k, 0); u.r[1] = mk(SP_Y, k, 0); u.r[2] = mk(SP_XNEXT, k, 0);
-        mult_step.push_back(u);
+        loss_step.push_back(o);     // with a multiplier step bound, the same kernel also writes lam + step*(y - x_next)
     }
     for (int variant = 0; variant < 2; ++variant) {
         const Program& bw = variant == 0 ? m.bwd : m.bwd_dx0;
@@ -1008,10 +1005,6 @@ static void build_step_programs(lp_net* net, int k) {
         for (const Step& st : bw) {
             out.push_back(st);
             for (Op& o : out.back()) o.phase = 2;
-        }
-        if (!mult_step.empty()) {
-            out.push_back(mult_step);
-            for (Op& o : out.back()) o.phase = 3;
         }
     }
 }
@@ -1153,7 +1146,6 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
         case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * (o.r[9].space != SP_NONE ? 4.0 : 3.0); break;
         case OP_BN_STATS: bytes = (double)o.bnb.M * o.bnb.C * e; break;
         case OP_LOSS: bytes = (double)o.numel * e * 4.0; break;
-        case OP_MULT: bytes = (double)o.numel * e * 4.0; break;
         case OP_POOL_FWD:
         case OP_POOL_BWD: bytes = ((double)o.pool.N * o.pool.H * o.pool.W + (double)o.pool.N * o.pool.Ho * o.pool.Wo) * o.pool.C * e; break;
         case OP_HEAD_FWD:
@@ -1353,29 +1345,18 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                       : type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
             } break;
             case OP_LOSS: {
-                LossGroup g; g.nprob = n; g.rho = b.rho; g.scale = b.scale; int tot = 0;
+                LossGroup g; g.nprob = n; g.rho = b.rho; g.scale = b.scale; g.step = b.mstep; int tot = 0;
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     LossProb& p = g.p[i];
                     p.y = resolve(o.r[0], b); p.xn = resolve(o.r[1], b); p.lam = resolve(o.r[2], b); p.dy = resolve(o.r[3], b);
+                    // the multiplier update rides on the pass that has y, x_next and lam in registers anyway
+                    p.lam_out = b.mstep != 0.f ? const_cast<void*>(p.lam) : nullptr;
                     p.loss = (float*)resolve(o.r[4], b); p.numel = o.numel;
                     p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
                 }
                 g.total_blocks = tot;
                 err = launch_loss(g, dt, s);
-            } break;
-            case OP_MULT: {
-                MultGroup g; g.nprob = 0; g.step = b.mstep; int tot = 0;
-                for (int i = 0; i < n; ++i) {
-                    const Op& o = *ops[base + i];
-                    void* lam = resolve(o.r[0], b);
-                    if (!lam || b.mstep == 0.f) continue;          // penalty method, or no update asked for
-                    MultProb& p = g.p[g.nprob++];
-                    p.lam = lam; p.y = resolve(o.r[1], b); p.xn = resolve(o.r[2], b); p.numel = o.numel;
-                    p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
-                }
-                g.total_blocks = tot;
-                if (g.nprob) err = launch_mult(g, dt, s);
             } break;
             case OP_CE:
                 for (int i = 0; i < n && err == hipSuccess; ++i) {
@@ -1779,7 +1760,7 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
     hipStream_t s = (hipStream_t)stream;
     std::vector<const Program*> pa, pb;
     uint32_t mask = 0;
-    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = 2.f; g.scale = loss_scale;   // rho/2 * r^2 with rho = 2: |r|^2
+    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = 2.f; g.scale = loss_scale; g.step = 0.f;   // rho/2 * r^2 with rho = 2: |r|^2
     std::vector<LossGroup> groups;
     for (int j = 0; j < net->K - 1; ++j) {
         if (!daux_params[j]) continue;
@@ -1792,7 +1773,7 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
         pa.push_back(&a.bwd_a); pb.push_back(&a.bwd_b);
         mask |= 1u << j;
         LossProb& p = g.p[g.nprob];
-        p.y = net->ws + a.ws_out; p.xn = x_target[j]; p.lam = nullptr; p.dy = net->ws + a.ws_g; p.loss = loss + j;
+        p.y = net->ws + a.ws_out; p.xn = x_target[j]; p.lam = nullptr; p.lam_out = nullptr; p.dy = net->ws + a.ws_g; p.loss = loss + j;
         p.numel = a.u.out_elems();
         p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
         if (++g.nprob == kMaxGroup) { groups.push_back(g); g.nprob = 0; g.total_blocks = 0; }
@@ -1885,7 +1866,7 @@ lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_m
     if (!loss) return fail(LP_ERR_INVALID_ARG, "loss is NULL");
     hipStream_t s = (hipStream_t)stream;
     const int epv = net->dtype == LP_BF16 ? 8 : 4;
-    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = rho; g.scale = loss_scale;
+    LossGroup g; g.nprob = 0; g.total_blocks = 0; g.rho = rho; g.scale = loss_scale; g.step = 0.f;
     bool want_ce = false;
     for (int k = 0; k < net->K; ++k) {
         if (!((module_mask >> k) & 1u)) continue;
@@ -1902,7 +1883,7 @@ lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_m
         if (!((module_mask >> k) & 1u)) continue;
         const ModulePlan& m = net->mods[k];
         LossProb& p = g.p[g.nprob];
-        p.y = y[k]; p.xn = x_next[k]; p.lam = (lam ? lam[k] : nullptr); p.dy = dy[k]; p.loss = loss + k;
+        p.y = y[k]; p.xn = x_next[k]; p.lam = (lam ? lam[k] : nullptr); p.lam_out = nullptr; p.dy = dy[k]; p.loss = loss + k;
         p.numel = (size_t)m.oN * m.oH * m.oW * m.oC;
         p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
         if (++g.nprob == kMaxGroup) {

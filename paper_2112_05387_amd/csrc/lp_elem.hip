@@ -387,7 +387,8 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
     const LossProb& P = g.p[find_problem(g, blockIdx.x)];
     const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
     const T* __restrict__ xn = reinterpret_cast<const T*>(P.xn);
-    const T* __restrict__ lam = reinterpret_cast<const T*>(P.lam);
+    const T* lam = reinterpret_cast<const T*>(P.lam);
+    T* lam_out = reinterpret_cast<T*>(P.lam_out);          // may alias lam: every vector is read before it is written
     T* __restrict__ dy = reinterpret_cast<T*>(P.dy);
     const size_t nvec = P.numel / EPV;
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
@@ -407,6 +408,11 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
             o[e] = g.scale * (g.rho * r + lm);
         }
         Vec<T>::store(dy + v * EPV, o);
+        if (lam && lam_out) {       // multiplier update of the same interface, from the same y - x_next
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) l[e] = fmaf(g.step, a[e] - b[e], l[e]);
+            Vec<T>::store(lam_out + v * EPV, l);
+        }
     }
     const float tot = block_sum(acc, s_tmp);
     if (threadIdx.x == 0 && tot != 0.f) atomicAdd(P.loss, g.scale * tot);

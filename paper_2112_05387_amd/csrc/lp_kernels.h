@@ -105,9 +105,10 @@ struct FillGroup { int nprob, total_blocks; FillProb p[kMaxGroup]; };
 // r = y - x_next;  dy = scale*(rho*r + lam);  loss += scale*(rho/2*sum r^2 + sum lam*r)
 struct LossProb {
     const void* y; const void* xn; const void* lam; void* dy; float* loss;
+    void* lam_out;           // != NULL: lam + step*(y - x_next) is written there (may be lam itself) after dy took the old lam
     size_t numel; int block_start, nblocks;
 };
-struct LossGroup { int nprob, total_blocks; float rho, scale; LossProb p[kMaxGroup]; };
+struct LossGroup { int nprob, total_blocks; float rho, scale, step; LossProb p[kMaxGroup]; };
 
 // lam += step*(y - x_next)
 struct MultProb { void* lam; const void* y; const void* xn; size_t numel; int block_start, nblocks; };
