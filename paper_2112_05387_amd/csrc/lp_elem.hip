@@ -636,31 +636,36 @@ __global__ void fc_bwd_w_kernel(const HeadProb P) {
     atomicAdd(&P.dw[i], s);
     if (c == 0) atomicAdd(&P.db[j], sb);
 }
-// dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW: one thread per (n, pixel lane of 8, 16-byte channel vector); it
-// computes its vector once and stores it to every eighth pixel
+// dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW
 template <typename T>
-__global__ void fc_bwd_x_kernel(const HeadProb P) {
-    constexpr int EPV = Vec<T>::N, PL = 8;
-    const int cv = P.C / EPV;
-    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (unsigned)(P.N * PL * cv)) return;
-    const int c0 = (int)(i % (unsigned)cv) * EPV;
-    const int pl = (int)(i / (unsigned)cv) % PL;
-    const int n = (int)(i / (unsigned)(PL * cv));
-    float s[EPV];
-#pragma unroll
-    for (int e = 0; e < EPV; ++e) s[e] = 0.f;
-    for (int j = 0; j < P.classes; ++j) {
-        const float d = P.dlogits[n * P.classes + j];
-        const float* __restrict__ wr = P.w + (size_t)j * P.C + c0;
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) s[e] += d * wr[e];
-    }
+__global__ __launch_bounds__(256) void fc_bwd_x_kernel(const HeadProb P) {
+    // One block per sample: d pooled[c] = sum_j dlogits[j] * w[j][c] once per channel (lanes along c: coalesced rows of
+    // w), then the block broadcasts it, divided by the number of pixels, to every pixel of the sample.
+    constexpr int EPV = Vec<T>::N;
+    extern __shared__ float s_dp[];      // C floats
+    const int n = blockIdx.x, C = P.C, cv = C / EPV, classes = P.classes;
     const float inv = 1.f / (float)P.HW;
+    const float* __restrict__ dl = P.dlogits + (size_t)n * classes;
+    for (int c = threadIdx.x; c < C; c += 256) {
+        float acc = 0.f;
+        int j = 0;
+        for (; j + 3 < classes; j += 4) {       // four rows of w in flight; summed in the order of the classes
+            const float w0 = P.w[(size_t)j * C + c], w1 = P.w[(size_t)(j + 1) * C + c];
+            const float w2 = P.w[(size_t)(j + 2) * C + c], w3 = P.w[(size_t)(j + 3) * C + c];
+            acc += dl[j] * w0; acc += dl[j + 1] * w1; acc += dl[j + 2] * w2; acc += dl[j + 3] * w3;
+        }
+        for (; j < classes; ++j) acc += dl[j] * P.w[(size_t)j * C + c];
+        s_dp[c] = acc * inv;
+    }
+    __syncthreads();
+    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * C;
+    for (int i = threadIdx.x; i < P.HW * cv; i += 256) {
+        const int p = i / cv, v = i - p * cv;
+        float o[EPV];
 #pragma unroll
-    for (int e = 0; e < EPV; ++e) s[e] *= inv;
-    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * P.C + c0;
-    for (int p = pl; p < P.HW; p += PL) Vec<T>::store(d + (size_t)p * P.C, s);
+        for (int e = 0; e < EPV; ++e) o[e] = s_dp[v * EPV + e];
+        Vec<T>::store(d + (size_t)p * C + v * EPV, o);
+    }
 }
 
 // softmax cross-entropy, mini-batch mean; one workgroup per sample
@@ -771,10 +776,10 @@ hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
-    const int epv = dtype == 1 ? 8 : 4;
     hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + 15) / 16), dim3(256), 0, s, p);
-    const size_t nthr = (size_t)p.N * 8 * (p.C / epv);
-    LP_DISPATCH_T(dtype, fc_bwd_x_kernel, dim3((unsigned)((nthr + 255) / 256)), dim3(256), s, p);
+    const size_t lds = (size_t)p.C * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL(fc_bwd_x_kernel<bf16_t>, dim3(p.N), dim3(256), lds, s, p);
+    else hipLaunchKernelGGL(fc_bwd_x_kernel<float>, dim3(p.N), dim3(256), lds, s, p);
     return hipGetLastError();
 }
 hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s) {
