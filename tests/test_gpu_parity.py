@@ -122,6 +122,42 @@ def test_wrn_reduced_batch():
     compare_step(wl.make_config("wrn28_10", batch=2))
 
 
+def _resnet50_at(side, batch):
+    """ResNet-50 (real depth and widths, 7x7 stride-2 stem + max-pool, 1000 classes) at another input resolution."""
+    from workloads import configs as cfg
+    ref = wl.make_config("resnet50", batch=batch)
+    blocks = [b for m in ref.modules for b in m.blocks]
+    m0 = ref.modules[0]
+    net = cfg._assemble(f"resnet50_{side}", cfg._split(blocks, [len(m.blocks) for m in ref.modules]), batch, side, side, m0.C,
+                        m0.stem, m0.stem_cout, ref.modules[-1].n_classes, seed=ref.seed)
+    net.dtype = ref.dtype
+    return net
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_resnet50_reduced_resolution(dtype):
+    """The ImageNet-shaped network (bottleneck blocks up to 2048 channels, 7x7 stride-2 stem + max-pool, 1000 classes)
+    at 64x64 and mini-batch 4: every tensor of the step, 1e-4 in fp32."""
+    say("case resnet50 at 64x64, batch 4", dtype)
+    net = _resnet50_at(64, 4)
+    net.dtype = dtype
+    compare_step(net)
+
+
+def test_resnet50_full_resolution_reduced_batch():
+    """The same network at 224x224, mini-batch 2, bf16 (the kernels at the real shapes: 112x112 stem output, 56x56 to
+    7x7 stages).  Forward outputs and losses are held to 2e-2.  The backward tensors of these 13-16-conv modules at two
+    samples per batch statistic are so sensitive to single roundings that the oracle's own spread (which the comparison
+    prints and allows for) is of order one for most of them.  fp32 at this size is not a case either: after a dozen
+    layers the device's fp32 forward differs from the float64 one by 2e-6, the 56x56 layers have 400k ReLU inputs each,
+    two of them within 1e-6 of zero, and one flipped mask element moves a filter gradient summed over 6272 pixels by
+    about 1e-2 of its norm (the oracle does the same when its stored tensors are perturbed by 1e-7; seen at 96x96
+    too, where the device's and the oracle's masks of one layer differ in exactly one element whose input is
+    2e-7); hence the strict comparison at 64x64 above."""
+    say("case resnet50 at 224x224, batch 2, bf16")
+    compare_step(wl.make_config("resnet50", batch=2))
+
+
 @pytest.mark.parametrize("dtype,al", [("f32", True), ("f32", False), ("bf16", True)])
 def test_aux_variable_update(dtype, al):
     """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) on seeded tensors, element by element
