@@ -102,6 +102,76 @@ def test_stream_lanes(lanes):
     compare_step(net, lanes=lanes)
 
 
+@pytest.mark.parametrize("mask,fused", [(0b101, True), (0b010, True), (0b110, False), (0b001, False)])
+def test_module_mask_subsets(mask, fused):
+    """A call with a module mask does exactly the selected modules: their outputs equal those of the all-modules call
+    (to fp32 summation order: the grouped launches hold other problems), and nothing that belongs to an unselected
+    module is written (outputs, adjoints, gradients, losses, multipliers keep a sentinel)."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.gpu_common import load_step
+    from tests.helpers import step_inputs
+    net = gpu_mini_basic(dtype="f32")
+    net.al, net.lam_sigma, net.rho = True, 0.05, 1.5
+    K, rho, scale, mstep = net.K, net.rho, 0.5, 0.1
+    say("case module mask", bin(mask), "one call" if fused else "four calls")
+    inp = step_inputs(net, lpref)
+
+    def run(ls, m):
+        if fused:
+            ls.local_step(rho, scale, mstep, mask=m)
+        else:
+            ls.module_forward(mask=m)
+            ls.local_loss_grad(rho, scale, mask=m)
+            ls.module_backward(mask=m)
+        torch.cuda.synchronize()
+
+    def state(ls):
+        out = {"loss": ls.loss.clone(), "logits": ls.logits.clone(), "dlogits": ls.dlogits.clone()}
+        for k in range(K):
+            out[f"dparams{k}"] = ls.dparams[k].clone()
+            out[f"dx{k}"] = ls.dx[k].clone()
+            if k < K - 1:
+                out[f"y{k}"] = ls.y[k].clone(); out[f"dy{k}"] = ls.dy[k].clone(); out[f"lam{k}"] = ls.lam[k].clone()
+        return out
+
+    owner = lambda name: K - 1 if name in ("logits", "dlogits") else int(name[-1])
+    ls = LocalStep(net)
+    try:
+        load_step(ls, net, inp)
+        run(ls, None)
+        full = state(ls)
+        # fresh multipliers, sentinels everywhere an entry point writes
+        ls.set_lams(inp["lams"])
+        lam0 = [l.clone() for l in ls.lam]
+        sentinel = 12345.0
+        for t in [ls.loss, ls.logits, ls.dlogits] + ls.dparams + ls.dx + ls.y + ls.dy:
+            t.fill_(sentinel)
+        run(ls, mask)
+        got = state(ls)
+        for name, t in got.items():
+            if name == "loss":
+                for k in range(K):
+                    if (mask >> k) & 1:
+                        assert abs(float(t[k]) - float(full["loss"][k])) <= 1e-5 * abs(float(full["loss"][k])), (name, k)
+                    else:
+                        assert float(t[k]) == sentinel, (name, k)
+                continue
+            k = owner(name)
+            sel = (mask >> k) & 1
+            if name.startswith("lam"):
+                want = full[name] if (sel and fused) else lam0[k]     # only the one call carries the multiplier update
+                assert torch.equal(t, want) if not (sel and fused) else torch.allclose(t, want, rtol=1e-5, atol=1e-6), name
+            elif name.startswith("dx") and (k == 0 or not sel):
+                assert bool((t == sentinel).all()), name              # dx[0] is not asked for; unselected modules
+            elif sel:
+                assert torch.allclose(t, full[name], rtol=1e-4, atol=1e-6), (name, float((t - full[name]).abs().max()))
+            else:
+                assert bool((t == sentinel).all()), name
+    finally:
+        ls.close()
+
+
 def test_mini_wide_ragged_tiles():
     say("case mini_wide bf16")
     compare_step(gpu_mini_wide())
