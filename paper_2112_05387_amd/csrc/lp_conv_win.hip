@@ -328,7 +328,48 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int prow = wm * TM + i * MT;              // first tile row of this pixel group
-        const int ro_w = s_rowoff[prow + lr];
+        // Addends (skip connections of the data-gradient) come in the way the result goes out: the 32 x 160 piece of the
+        // addend tensor is copied into the staging area with 16-byte accesses along the channels, and every lane then
+        // picks the elements of its accumulators from LDS.  Read straight from memory in the accumulator layout, a
+        // wave-load touched 32 rows for 16 bytes each, and the cache-line requests of the epilogue cost 10-15 us per launch.
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const bf16_t* __restrict__ ap = which == 0 ? add0 : add1;
+            if (!ap) continue;
+            constexpr int NLD = (MT + 2) / 3;           // rows per pixel lane
+            u32x4 araw[NLD];
+#pragma unroll
+            for (int t = 0; t < NLD; ++t) {             // all loads first, unconditional (a row that is not there reads element 0)
+                const int p = pl + 3 * t;
+                const int ro = s_rowoff[prow + (p < MT ? p : MT - 1)];
+                const bool ok = pl < 3 && p < MT && ro >= 0 && colg < P.Ncol;
+                araw[t] = *reinterpret_cast<const u32x4*>(ap + (ok ? (size_t)ro + colg : (size_t)0));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NLD; ++t) {
+                const int p = pl + 3 * t;
+                const int ro = s_rowoff[prow + (p < MT ? p : MT - 1)];
+                const bool ok = ro >= 0 && colg < P.Ncol;
+                u32x4 q = araw[t];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[e] = ok ? q[e] : 0u;
+                if (pl < 3 && p < MT) *reinterpret_cast<u32x4*>(E + p * EP_PITCH + cg * 16) = q;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);         // lgkmcnt(0): the piece is in LDS
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int c0 = j * MT + 8 * rg + 4 * lkc;
+                    const uint2 a = *reinterpret_cast<const uint2*>(E + lr * EP_PITCH + c0 * 2);
+                    acc[j][i][rg * 4 + 0] += __uint_as_float(a.x << 16); acc[j][i][rg * 4 + 1] += __uint_as_float(a.x & 0xffff0000u);
+                    acc[j][i][rg * 4 + 2] += __uint_as_float(a.y << 16); acc[j][i][rg * 4 + 3] += __uint_as_float(a.y & 0xffff0000u);
+                }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);         // read before the staging area is written again
+        }
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -337,22 +378,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
                 float v[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[j][i][rg * 4 + e];
-                if (add0 || add1) {
-                    const int col = n0 + wn * TN + c0;
-                    if (ro_w >= 0 && col < P.Ncol) {
-                        const size_t o = (size_t)ro_w + col;
-                        if (add0) {
-                            const uint2 a = *reinterpret_cast<const uint2*>(add0 + o);
-                            v[0] += __uint_as_float(a.x << 16); v[1] += __uint_as_float(a.x & 0xffff0000u);
-                            v[2] += __uint_as_float(a.y << 16); v[3] += __uint_as_float(a.y & 0xffff0000u);
-                        }
-                        if (add1) {
-                            const uint2 a = *reinterpret_cast<const uint2*>(add1 + o);
-                            v[0] += __uint_as_float(a.x << 16); v[1] += __uint_as_float(a.x & 0xffff0000u);
-                            v[2] += __uint_as_float(a.y << 16); v[3] += __uint_as_float(a.y & 0xffff0000u);
-                        }
-                    }
-                }
                 uint2 pk;
                 pk.x = pack_bf16x2(v[0], v[1]);
                 pk.y = pack_bf16x2(v[2], v[3]);
