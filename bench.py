@@ -56,6 +56,22 @@ def build_state(net, seed_noise=True):
 SEPARATE_CALLS = False
 
 
+def time_graph_replays(ls, net, steps):
+    """The same step captured once into a HIP graph (stream lanes included) and replayed `steps` times: wall time per
+    replay.  What it takes away is the host's launch work, which bounds the small networks."""
+    import torch
+    if SEPARATE_CALLS:
+        raise SystemExit("--graph captures the one-call step; it does not combine with --separate-calls")
+    g = ls.capture_step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def one_step(ls, net):
     if not SEPARATE_CALLS:
         ls.step(net.rho, 1.0, mult_step=(net.step if net.al else None), with_aux=(net.aux is not None))
@@ -183,6 +199,8 @@ def main():
     ap.add_argument("--lanes", default="default",
                     help="default: the library's concurrent stream lanes; single: every module on one stream; or one "
                          "digit 0..3 per module, e.g. 1200 (the result is then not the headline)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also capture the step into a HIP graph and time its replays (reported beside the eager step)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="run the step as lp_module_forward / lp_local_loss_grad / lp_module_backward / "
                          "lp_al_multiplier_update instead of the one lp_local_step call")
@@ -237,11 +255,16 @@ def main():
     # second pass over the same steps with every module on the caller's stream: full grouped launches, one after
     # another, each bracketed by hipEvents (this is also what `--lanes single` times and what the rocprofv3
     # summaries under profiles/ are taken with).
+    graph_ms = None
     if args.lanes == "single":
         wall_ms, gpu_ms, recs = timed_steps(1)           # one stream: the timed region itself carries the events
         iso_wall, gpu_iso = wall_ms, gpu_ms
+        if args.graph:
+            graph_ms = time_graph_replays(ls, net, args.steps)
     else:
         wall_ms, gpu_ms, _ = timed_steps(0)
+        if args.graph:
+            graph_ms = time_graph_replays(ls, net, args.steps)
         ls.set_stream_lanes(None)
         one_step(ls, net)
         iso_wall, gpu_iso, recs = timed_steps(1)
@@ -313,6 +336,9 @@ def main():
     torch.cuda.synchronize()
     sgd_ms = e0.elapsed_time(e1) / 10
     sgd_bytes = sum(int(t.numel) * ((4 if t.dtype == B.LP_BF16 else 8) + 12) for tab in ls.tables for t in tab)
+    if graph_ms is not None:
+        out["hip_graph"] = {"ms_per_step": graph_ms, "samples/s": N / (graph_ms * 1e-3),
+                            "note": "the step captured once (stream lanes included) and replayed; `value` is the eager step"}
     out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
     ls.close()
     if args.speedup_terms:

@@ -220,3 +220,21 @@ class LocalStep:
         if with_aux:
             self.auxnet_forward()
         self.local_step(rho, scale, 0.0 if (mult_step is None or self.lam is None) else mult_step)
+
+    def capture_step(self, rho, scale=1.0, mult_step=None, with_aux=False, warmup=2):
+        """The step as a HIP graph: `warmup` eager steps on a side stream (the library creates the streams and events of
+        its lanes and sets its kernel attributes on first use, which must not happen inside a capture), then one step
+        captured.  The library's fork / join of its stream lanes by events is a capture-legal pattern, it clears with
+        kernels (no memset nodes) and allocates nothing per call.  Returns the torch.cuda.CUDAGraph; every replay() is
+        one step on the buffers of this object (multipliers are updated in place, as in the eager step)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(warmup):
+                self.step(rho, scale, mult_step, with_aux)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            self.step(rho, scale, mult_step, with_aux)
+        return g

@@ -172,6 +172,56 @@ def test_module_mask_subsets(mask, fused):
         ls.close()
 
 
+@pytest.mark.parametrize("which", ["mini_basic", "wrn28_10"])
+def test_step_as_hip_graph_replays(which):
+    """The local step captured into a HIP graph (the stream lanes forked and joined by events inside the capture, the
+    multiplier update included): three replays, with eager work of the library and synchronisations between them, each
+    against the eager step from the same state.  mini_basic: three lanes, register-staged kernels; wrn28_10 at batch 2:
+    four lanes, the wide-layer kernels with their split-K atomics."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from tests.gpu_common import load_step
+    from tests.helpers import step_inputs
+    if which == "mini_basic":
+        net = gpu_mini_basic(dtype="bf16")
+        net.al, net.lam_sigma, net.rho = True, 0.05, 1.5
+    else:
+        net = wl.make_config("wrn28_10", batch=2)
+        net.aux = None
+    K, scale, mstep = net.K, 0.5, 0.1
+    say("case step as a HIP graph", which)
+    inp = step_inputs(net, lpref)
+    ls = LocalStep(net)
+    try:
+        load_step(ls, net, inp)
+
+        def snapshot():
+            torch.cuda.synchronize()
+            return ([g.clone() for g in ls.dparams] + [l.clone() for l in ls.lam] + [y.clone() for y in ls.y]
+                    + [ls.loss.clone(), ls.logits.clone()] + [d.clone() for d in ls.dx[1:]])
+
+        want = []
+        for _ in range(3):                       # eager: three steps in a row, multipliers carried along
+            ls.step(net.rho, scale, mstep)
+            want.append(snapshot())
+        ls.set_lams(inp["lams"])
+        g = ls.capture_step(net.rho, scale, mstep)
+        for l, src in zip(ls.lam, inp["lams"]):  # the warm-up steps moved the multipliers; the graph holds these very
+            l.copy_(ls.to_dev(src))              # tensors, so they are reset in place
+        for rep in range(3):
+            for t in ls.dparams + ls.y + [ls.loss, ls.logits]:
+                t.fill_(777.0)
+            torch.cuda.synchronize()
+            g.replay()
+            got = snapshot()
+            for i, (a, b) in enumerate(zip(got, want[rep])):
+                assert torch.allclose(a.float(), b.float(), rtol=2e-3, atol=1e-5), (rep, i, float((a.float() - b.float()).abs().max()))
+            ls.module_forward(mask=0b001)        # eager work between the replays (it rewrites y[0] with the same values)
+            torch.cuda.synchronize()
+    finally:
+        ls.close()
+
+
 def test_mini_wide_ragged_tiles():
     say("case mini_wide bf16")
     compare_step(gpu_mini_wide())
