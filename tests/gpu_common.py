@@ -46,6 +46,17 @@ def gpu_mini_wide(batch=3):
     return net
 
 
+def gpu_mini_wide_strided(batch=5, side=(12, 20), widths=(136, 296)):
+    """bf16, a stride-2 block between two wide widths (the shape of the 160->320 and 320->640 layers of WRN-28-10):
+    ragged channel tiles, an output width that is not a power of two (10, or 5 with side (12, 10)) and a pixel count
+    that is no multiple of a k-tile (batch 5: 300 or 150 output pixels)."""
+    a, b = widths
+    blocks = [Block("basic", a, a, a, 1, False), Block("basic", a, b, b, 2, True), Block("basic", b, b, b, 1, False)]
+    net = cfg._assemble("gpu_mini_wide_strided", [blocks[:1], blocks[1:]], batch, side[0], side[1], 3, 1, a, 7, seed=29)
+    net.dtype = "bf16"
+    return net
+
+
 def load_step(ls, net, inp):
     for k in range(net.K):
         ls.set_params(k, inp["params"][k])

@@ -227,6 +227,15 @@ def test_mini_wide_ragged_tiles():
     compare_step(gpu_mini_wide())
 
 
+@pytest.mark.parametrize("side,widths", [((12, 20), (136, 296)), ((12, 10), (160, 320)), ((8, 8), (320, 640))])
+def test_mini_wide_stride_2(side, widths):
+    """A stride-2 3x3 layer between wide widths (the 160->320 and 320->640 layers of WRN-28-10 in small): its filter
+    gradient goes through the register-staged kernel (ragged 160-wide tiles, output widths 10, 5 and 4)."""
+    from tests.gpu_common import gpu_mini_wide_strided
+    say("case mini_wide stride 2", side, widths)
+    compare_step(gpu_mini_wide_strided(side=side, widths=widths))
+
+
 def test_resnet20_full_size():
     say("case resnet20 batch 128 fp32")
     compare_step(wl.make_config("resnet20"))
