@@ -642,19 +642,30 @@ __global__ __launch_bounds__(256) void fc_bwd_x_kernel(const HeadProb P) {
     // One block per sample: d pooled[c] = sum_j dlogits[j] * w[j][c] once per channel (lanes along c: coalesced rows of
     // w), then the block broadcasts it, divided by the number of pixels, to every pixel of the sample.
     constexpr int EPV = Vec<T>::N;
-    extern __shared__ float s_dp[];      // C floats
+    extern __shared__ float s_dp[];      // C floats, then the sample's `classes` logit gradients
     const int n = blockIdx.x, C = P.C, cv = C / EPV, classes = P.classes;
     const float inv = 1.f / (float)P.HW;
-    const float* __restrict__ dl = P.dlogits + (size_t)n * classes;
+    float* s_dl = s_dp + C;
+    for (int j = threadIdx.x; j < classes; j += 256) s_dl[j] = P.dlogits[(size_t)n * classes + j];
+    __syncthreads();
     for (int c = threadIdx.x; c < C; c += 256) {
         float acc = 0.f;
         int j = 0;
-        for (; j + 3 < classes; j += 4) {       // four rows of w in flight; summed in the order of the classes
-            const float w0 = P.w[(size_t)j * C + c], w1 = P.w[(size_t)(j + 1) * C + c];
-            const float w2 = P.w[(size_t)(j + 2) * C + c], w3 = P.w[(size_t)(j + 3) * C + c];
-            acc += dl[j] * w0; acc += dl[j + 1] * w1; acc += dl[j + 2] * w2; acc += dl[j + 3] * w3;
+        for (; j + 7 < classes; j += 8) {       // eight rows of w in flight; summed in the order of the classes
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) w[u] = P.w[(size_t)(j + u) * C + c];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += s_dl[j + u] * w[u];
         }
-        for (; j < classes; ++j) acc += dl[j] * P.w[(size_t)j * C + c];
+        {                                       // the last up to seven classes, loaded together as well
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 7; ++u) w[u] = P.w[(size_t)min(j + u, classes - 1) * C + c];
+#pragma unroll
+            for (int u = 0; u < 7; ++u)
+                if (j + u < classes) acc += s_dl[j + u] * w[u];
+        }
         s_dp[c] = acc * inv;
     }
     __syncthreads();
@@ -777,7 +788,7 @@ hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
 }
 hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
     hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + 15) / 16), dim3(256), 0, s, p);
-    const size_t lds = (size_t)p.C * sizeof(float);
+    const size_t lds = (size_t)(p.C + p.classes) * sizeof(float);
     if (dtype == 1) hipLaunchKernelGGL(fc_bwd_x_kernel<bf16_t>, dim3(p.N), dim3(256), lds, s, p);
     else hipLaunchKernelGGL(fc_bwd_x_kernel<float>, dim3(p.N), dim3(256), lds, s, p);
     return hipGetLastError();
