@@ -267,6 +267,52 @@ lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, in
  * the stem, 1 + 8*block + {0,1,2: pre-BN conv output of slot, 3: projection conv output, 4: block output}. */
 lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel);
 
+/* Unit-by-unit views of a module in the conv-BN-ReLU order, for layer-wise checks (debug; read-only descriptions,
+ * host only).  A unit is one convolution with the batch norm behind it.  Every tensor is named by a reference: the
+ * caller's tensor of the last call (x[idx], y[idx], dy[idx], dx[idx]) or a byte offset into the workspace.
+ *   forward:   in --conv--> y (pre-BN, stored) ; stats = per-channel [sum, sum of squares] of y (fp64 [2*cout]);
+ *              out = [ReLU]( BN(y) [+ skip | + BN(y of unit skip_unit)] ), written by the unit's BN-apply pass
+ *              (the projection unit has none: its BN is applied inside the pass of the block's last unit);
+ *   backward:  gout = gradient arriving at the unit's BN output; dy = gradient on y (BN backward, stored);
+ *              red = per-channel [sum g', sum g'*yhat] (fp64 [2*cout]); din = the unit's data-gradient
+ *              (+ din_add, the skip-path gradient added in its epilogue), present when has_dgrad.
+ * Gradient buffers are reused from block to block inside a backward pass unless the net was created after
+ * lp_debug_keep_gradients(1) (a per-thread switch read by lp_net_create: every gradient then has a buffer of its own;
+ * the workspace grows, kernels and launches are the same).  The views describe the backward program without dx[0]. */
+enum { LP_REF_NONE = 0, LP_REF_WORKSPACE = 1, LP_REF_X = 2, LP_REF_Y = 3, LP_REF_DY = 4, LP_REF_DX = 5 };
+typedef struct { int space; int idx; size_t off; } lp_debug_ref;
+typedef struct {
+    int block, slot;             /* block -1: stem; slot 0..2 main path, 3 projection */
+    int R, stride, pad, cin, cout, N, H, W, Ho, Wo;
+    int relu;                    /* ReLU behind this unit's BN */
+    int t_w, t_gamma, t_beta;    /* indices into the module's tensor table */
+    int skip_kind;               /* added inside this unit's BN-apply pass: 0 nothing, 1 the tensor `skip`, 2 BN(y) of unit skip_unit */
+    int skip_unit;
+    int has_dgrad;
+    lp_debug_ref in, y, stats, out, skip, gout, dy, red, din, din_add;
+} lp_debug_unit;
+typedef struct {                 /* what lies around the units: max-pool of stem 2, head of the last module */
+    int keep_gradients;
+    int oN, oH, oW, oC;          /* shape of F_k(x_k) */
+    int pH, pW, pC;              /* stem 2: shape of the pool input [N, pH, pW, pC] */
+    lp_debug_ref pool_in, pool_out, pool_arg, g_pool_out, g_pool_in;
+    lp_debug_ref feat, pooled, dfeat;   /* last module: F_k(x_k), its spatial mean [N, C] fp32, the gradient on F_k(x_k) */
+    int t_fc_w, t_fc_b;
+} lp_debug_module;
+lp_status lp_debug_keep_gradients(int on);
+lp_status lp_debug_unit_count(const struct lp_net* net, int k, int* n);
+lp_status lp_debug_unit_info(const struct lp_net* net, int k, int i, lp_debug_unit* info);
+lp_status lp_debug_module_info(const struct lp_net* net, int k, lp_debug_module* info);
+
+/* Host-only bounds check of the direct-to-LDS filter loads of the wide-layer convolution kernels (no GPU): forms, with
+ * the kernels' own address functions, every filter load of a forward layer with Ncol filters [R, R, Cin] for every
+ * column tile (width bn), wave (nw per workgroup), lane, round, tap and channel slab (bk channels; kernel 0: the
+ * implicit-GEMM kernel, Cin % bk == 0; kernel 1: the window kernel, bk = 64 with an optional last half slab), and
+ * returns the largest byte offset past the end of any load that is not marked out of range, and how many such loads
+ * there are.  Safe kernels keep *max_end <= Ncol*R*R*Cin*2.  Errors: LP_ERR_INVALID_ARG, LP_ERR_SHAPE. */
+lp_status lp_debug_filter_load_extent(int kernel, int bk, int bn, int nw, int Ncol, int Cin, int R, size_t* max_end,
+                                      size_t* n_live);
+
 /* Optional per-launch timing.  While enabled, every grouped kernel launch made by lp_auxnet_forward,
  * lp_module_forward and lp_module_backward is bracketed by two hipEvents on the stream it is enqueued on.
  * on = 1: launches of different stream lanes still overlap, so a record's duration includes the time its kernel

@@ -20,13 +20,18 @@ What follows what:
   auxnet_forward     - AuxNet forward map of Sec. 4.2 in its one-block, from-the-image form
   multiplier_update  - multiplier update rule of Sec. 4.1
 
-Storage rounding.  Every routine that composes layers takes `q`, a callable applied where the
-bf16 mode of the method stores a tensor (conv output before BN, activation after BN+ReLU, block
-output, every stored gradient); q=None (the default) is the plain float64 definition, and that is
-what the pins exercise.  With q = round-to-bf16 the oracle is the same sequence of definitions with
-each stored tensor rounded once, so that decisions taken from stored values (the ReLU mask, the
-pooling argmax) are taken in the precision the bf16 mode defines.  Batch statistics are those of the
-stored (rounded) convolution result.
+Storage rounding (a DIAGNOSTIC mode, not the definition).  Every routine that composes layers takes `q`, a
+callable applied where a low-precision implementation stores a tensor: going forward the convolution result
+before BN, the activation after BN+ReLU and the block output; going backward the gradient of each of those
+tensors, and the data-gradient of a projection branch before it is added.  Batch statistics are those of the
+tensor that is normalised, i.e. of the stored (rounded) convolution result: batch norm is defined on the tensor it
+receives, and that choice keeps its two identities (zero mean / unit variance of what it outputs, zero sums of the
+backward result) exact for the stored values.  q=None (the default) is the plain float64 definition: it is what every
+pin of the primitives and of the step exercises and what the unit-by-unit device tests compare against.  The
+placement of the roundings is pinned separately (tests/test_oracle_step.py::test_storage_rounding_placement:
+the same mode built from a library's layers and its reverse-mode differentiation).  The mode exists for end-to-end
+comparisons of a whole bf16 backward pass, where decisions taken from stored values (ReLU masks, pooling argmax)
+must be taken from values of the same precision on both sides.
 """
 import ctypes
 import os

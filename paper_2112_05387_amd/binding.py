@@ -15,7 +15,8 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step",
-           "lp_debug_im2col_offsets",
+           "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
+           "lp_debug_module_info", "lp_debug_filter_load_extent",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
@@ -44,6 +45,25 @@ class lp_aux_desc(ctypes.Structure):
 class lp_tensor_info(ctypes.Structure):
     _fields_ = [("kind", c_int), ("block", c_int), ("slot", c_int), ("dtype", c_int), ("ndim", c_int),
                 ("dims", c_int * 4), ("offset", c_size_t), ("grad_offset", c_size_t), ("numel", c_size_t)]
+
+
+LP_REF_NONE, LP_REF_WORKSPACE, LP_REF_X, LP_REF_Y, LP_REF_DY, LP_REF_DX = 0, 1, 2, 3, 4, 5
+
+
+class lp_debug_ref(ctypes.Structure):
+    _fields_ = [("space", c_int), ("idx", c_int), ("off", c_size_t)]
+
+
+class lp_debug_unit(ctypes.Structure):
+    _fields_ = [(n, c_int) for n in ("block", "slot", "R", "stride", "pad", "cin", "cout", "N", "H", "W", "Ho", "Wo", "relu",
+                                     "t_w", "t_gamma", "t_beta", "skip_kind", "skip_unit", "has_dgrad")] + \
+               [(n, lp_debug_ref) for n in ("in_", "y", "stats", "out", "skip", "gout", "dy", "red", "din", "din_add")]
+
+
+class lp_debug_module(ctypes.Structure):
+    _fields_ = [(n, c_int) for n in ("keep_gradients", "oN", "oH", "oW", "oC", "pH", "pW", "pC")] + \
+               [(n, lp_debug_ref) for n in ("pool_in", "pool_out", "pool_arg", "g_pool_out", "g_pool_in", "feat", "pooled", "dfeat")] + \
+               [("t_fc_w", c_int), ("t_fc_b", c_int)]
 
 
 class lp_profile_rec(ctypes.Structure):
@@ -91,6 +111,11 @@ def lib():
         L.lp_aux_variable_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
         L.lp_debug_im2col_offsets.argtypes = [c_void_p] + [c_int] * 7 + [c_void_p, c_void_p, c_void_p, c_int]
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
+        L.lp_debug_keep_gradients.argtypes = [c_int]
+        L.lp_debug_unit_count.argtypes = [c_void_p, c_int, POINTER(c_int)]
+        L.lp_debug_unit_info.argtypes = [c_void_p, c_int, c_int, POINTER(lp_debug_unit)]
+        L.lp_debug_module_info.argtypes = [c_void_p, c_int, POINTER(lp_debug_module)]
+        L.lp_debug_filter_load_extent.argtypes = [c_int] * 7 + [POINTER(c_size_t), POINTER(c_size_t)]
         L.lp_profile_enable.argtypes = [c_void_p, c_int]
         L.lp_profile_fetch.argtypes = [c_void_p, POINTER(lp_profile_rec), c_int, POINTER(c_int)]
         L.lp_last_error.restype = c_char_p
@@ -253,6 +278,34 @@ def lp_debug_saved_tensor(net, k, which):
     p, n = c_void_p(), c_size_t()
     _check(lib().lp_debug_saved_tensor(net, k, which, ctypes.byref(p), ctypes.byref(n)))
     return p.value, n.value
+
+
+def lp_debug_keep_gradients(on):
+    _check(lib().lp_debug_keep_gradients(int(on)))
+
+
+def lp_debug_unit_count(net, k):
+    n = c_int()
+    _check(lib().lp_debug_unit_count(net, k, ctypes.byref(n)))
+    return n.value
+
+
+def lp_debug_unit_info(net, k, i):
+    u = lp_debug_unit()
+    _check(lib().lp_debug_unit_info(net, k, i, ctypes.byref(u)))
+    return u
+
+
+def lp_debug_module_info(net, k):
+    m = lp_debug_module()
+    _check(lib().lp_debug_module_info(net, k, ctypes.byref(m)))
+    return m
+
+
+def lp_debug_filter_load_extent(kernel, bk, bn, nw, ncol, cin, r):
+    end, live = c_size_t(), c_size_t()
+    _check(lib().lp_debug_filter_load_extent(kernel, bk, bn, nw, ncol, cin, r, ctypes.byref(end), ctypes.byref(live)))
+    return end.value, live.value
 
 
 def lp_profile_enable(net, on):

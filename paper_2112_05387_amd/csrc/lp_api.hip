@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/lp.h"
+#include "lp_addr.h"
 #include "lp_kernels.h"
 
 using namespace lp;
@@ -21,6 +22,7 @@ using namespace lp;
 // errors
 // ----------------------------------------------------------------------------------------------------
 static thread_local std::string g_err;
+static thread_local bool g_keep_gradients = false;   // lp_debug_keep_gradients: nets created on this thread keep every gradient
 
 static lp_status fail(lp_status st, const char* fmt, ...) {
     char buf[512];
@@ -128,6 +130,12 @@ struct BlockPlan {
     Ref in, out;                           // block input / output tensors
     Ref gout;                              // pre-activation order: gradient with respect to the block output (kept for the filter gradients)
     size_t in_elems = 0, out_elems = 0;
+    // conv-BN-ReLU order, backward pass: where the gradient on the block input, on the activation behind main[j]
+    // (j < main.size()-1) and the projection's data-gradient go.  Normally buffers the blocks of a module share;
+    // with lp_debug_keep_gradients every block has its own, so that all of them can be read after the pass.
+    size_t ws_gin = 0, ws_gproj = 0;
+    std::vector<size_t> ws_gact;
+    Ref gin_ref, g_ref;                    // gradient on the block input / output as the backward program binds them
 };
 struct ModulePlan {
     lp_module_desc d;
@@ -181,6 +189,8 @@ struct lp_net {
     std::vector<int> lane;                 // per module: 0 = the caller's stream, 1..3 = extra stream
     hipStream_t extra_stream[4] = {nullptr, nullptr, nullptr, nullptr};
     hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool lanes_ready = false;              // every extra stream and event above exists
+    bool keep_gradients = false;           // debug layout: no gradient buffer is reused inside a backward pass
     // optional per-launch timing (hipEvents around every grouped launch)
     bool prof = false;
     int lanes_in_flight = 1;               // stream lanes of the call being enqueued (launch-time tile choice)
@@ -560,6 +570,14 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
     m.ws_G[0] = ws.take(maxG * esz); m.ws_G[1] = ws.take(maxG * esz);
     m.ws_A = ws.take(std::max<size_t>(maxA, 1) * esz);
     m.ws_P = ws.take(std::max<size_t>(maxP, 1) * esz);
+    for (size_t i = 0; i < m.bp.size(); ++i) {
+        BlockPlan& bp = m.bp[i];
+        const bool keep = net->keep_gradients;
+        bp.ws_gin = keep ? ws.take(bp.in_elems * esz) : m.ws_G[i & 1];
+        bp.ws_gproj = (keep && bp.has_proj) ? ws.take(bp.in_elems * esz) : m.ws_P;
+        for (size_t j = 0; j + 1 < bp.main.size(); ++j)
+            bp.ws_gact.push_back(keep ? ws.take(bp.main[j].out_elems() * esz) : m.ws_A);
+    }
     if (last) {
         m.ws_pooled = ws.take((size_t)N * C * 4);
         m.ws_dfeat = ws.take((size_t)N * H * W * C * esz);
@@ -649,7 +667,6 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             Bw.push_back(Step{o});
             g = mk(SP_WS, 0, m.ws_dfeat);
         } else g = mk(SP_DY, k, 0);
-        const Ref A = mk(SP_WS, 0, m.ws_A), Pp = mk(SP_WS, 0, m.ws_P);
         auto dyref = [&](const Unit& u) { return mk(SP_WS, 0, u.ws_dy); };
         // The filter gradients depend on nothing but a unit's input and its output gradient, and nothing depends on
         // them: they are collected and run as the last step, where the scheduler groups them into few large launches.
@@ -659,7 +676,9 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             const bool need_in_grad = (i > 0) || m.has_stem || want_dx_first;
             Ref gin;                                // where the gradient with respect to the block input goes
             if (i == 0 && !m.has_stem) gin = mk(SP_DX, k, 0);
-            else gin = mk(SP_WS, 0, m.ws_G[i & 1]);
+            else gin = mk(SP_WS, 0, bp.ws_gin);
+            const Ref Pp = mk(SP_WS, 0, bp.ws_gproj);
+            bp.gin_ref = gin; bp.g_ref = g;
             const int nm = (int)bp.main.size();
             Ref gcur = g;                           // gradient arriving at the BN output of unit j
             for (int j = nm - 1; j >= 0; --j) {
@@ -689,6 +708,7 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
                 }
                 // data-gradient of this unit
                 if (j > 0) {
+                    const Ref A = mk(SP_WS, 0, bp.ws_gact[j - 1]);
                     B.conv_dgrad(u, Dm, mk(SP_WS, 0, u.ws_wt), A, Ref(), Ref(), s3);
                     Bw.push_back(s3);
                     gcur = A;
@@ -1492,13 +1512,26 @@ static lp_status run_programs(lp_net* net, const std::vector<const Program*>& pr
             }
         return LP_OK;
     }
-    if (!net->ev_fork) {
-        if ((err = hipEventCreateWithFlags(&net->ev_fork, hipEventDisableTiming)) != hipSuccess)
+    if (!net->lanes_ready) {
+        // all handles into locals first: the net takes them only when every one exists, a partial set is destroyed
+        hipEvent_t fork = nullptr, join[kLanes] = {nullptr, nullptr, nullptr, nullptr};
+        hipStream_t extra[kLanes] = {nullptr, nullptr, nullptr, nullptr};
+        err = hipEventCreateWithFlags(&fork, hipEventDisableTiming);
+        for (int l = 1; l < kLanes && err == hipSuccess; ++l) {
+            err = hipStreamCreateWithFlags(&extra[l], hipStreamNonBlocking);
+            if (err == hipSuccess) err = hipEventCreateWithFlags(&join[l], hipEventDisableTiming);
+        }
+        if (err != hipSuccess) {
+            if (fork) (void)hipEventDestroy(fork);
+            for (int l = 1; l < kLanes; ++l) {
+                if (extra[l]) (void)hipStreamDestroy(extra[l]);
+                if (join[l]) (void)hipEventDestroy(join[l]);
+            }
             return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
-        for (int l = 1; l < kLanes; ++l)
-            if ((err = hipStreamCreateWithFlags(&net->extra_stream[l], hipStreamNonBlocking)) != hipSuccess ||
-                (err = hipEventCreateWithFlags(&net->ev_join[l], hipEventDisableTiming)) != hipSuccess)
-                return fail(LP_ERR_HIP, "extra streams: %s", hipGetErrorString(err));
+        }
+        net->ev_fork = fork;
+        for (int l = 1; l < kLanes; ++l) { net->extra_stream[l] = extra[l]; net->ev_join[l] = join[l]; }
+        net->lanes_ready = true;
     }
     if (net->prof && net->prof_serial) {
         size_t pos[kLanes] = {0, 0, 0, 0};
@@ -1566,6 +1599,7 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
     if (!(bn_eps > 0.f)) return fail(LP_ERR_INVALID_ARG, "bn_eps must be positive");
     lp_net* net = new lp_net();
     net->K = K; net->dtype = dtype; net->eps = bn_eps; net->esz = dtype == LP_BF16 ? 2 : 4;
+    net->keep_gradients = g_keep_gradients;
     net->mods.resize(K);
     net->saved_x.assign(K, nullptr);
     WsAlloc ws;
@@ -2090,6 +2124,159 @@ lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, in
     return LP_OK;
 }
 
+lp_status lp_debug_keep_gradients(int on) {
+    g_keep_gradients = on != 0;
+    return LP_OK;
+}
+
+static lp_debug_ref dref(const Ref& r) {
+    lp_debug_ref d; d.space = LP_REF_NONE; d.idx = r.idx; d.off = r.off;
+    switch (r.space) {
+        case SP_WS: d.space = LP_REF_WORKSPACE; break;
+        case SP_X: d.space = LP_REF_X; break;
+        case SP_Y: d.space = LP_REF_Y; break;
+        case SP_DY: d.space = LP_REF_DY; break;
+        case SP_DX: d.space = LP_REF_DX; break;
+        default: d.idx = 0; d.off = 0; break;
+    }
+    return d;
+}
+static lp_debug_ref dws(size_t off) { return dref(mk(SP_WS, 0, off)); }
+
+// the conv+BN units of module k in forward order: stem, then per block main[0..], projection
+static void collect_units(const ModulePlan& m, std::vector<lp_debug_unit>& out, int k) {
+    auto base = [&](const Unit& u, int block, int slot) {
+        lp_debug_unit d; memset(&d, 0, sizeof(d));
+        d.block = block; d.slot = slot; d.R = u.R; d.stride = u.stride; d.pad = u.pad; d.cin = u.cin; d.cout = u.cout;
+        d.N = u.N; d.H = u.H; d.W = u.W; d.Ho = u.Ho; d.Wo = u.Wo; d.relu = u.relu ? 1 : 0;
+        d.t_w = u.t_w; d.t_gamma = u.t_g; d.t_beta = u.t_b; d.skip_unit = -1;
+        d.y = dws(u.ws_y); d.stats = dws(u.ws_stats); d.dy = dws(u.ws_dy); d.red = dws(u.ws_red);
+        return d;
+    };
+    if (m.has_stem) {
+        lp_debug_unit d = base(m.stem, -1, 0);
+        d.in = dref(mk(SP_X, k, 0));
+        d.out = dws(m.ws_stem_act);
+        d.gout = m.d.stem == 2 ? dws(m.ws_gpool) : dref(m.bp[0].gin_ref);
+        out.push_back(d);
+    }
+    for (size_t i = 0; i < m.bp.size(); ++i) {
+        const BlockPlan& bp = m.bp[i];
+        const bool need_in_grad = (i > 0) || m.has_stem;       // the backward program without dx[0]
+        const int nm = (int)bp.main.size();
+        const int first = (int)out.size();
+        for (int j = 0; j < nm; ++j) {
+            lp_debug_unit d = base(bp.main[j], (int)i, j);
+            d.in = j == 0 ? dref(bp.in) : dws(bp.ws_act[j - 1]);
+            if (j + 1 < nm) {
+                d.out = dws(bp.ws_act[j]);
+                d.gout = dws(bp.ws_gact[j]);
+            } else {
+                d.out = dref(bp.out);
+                d.gout = dref(bp.g_ref);
+                if (bp.has_proj) { d.skip_kind = 2; d.skip_unit = first + nm; }
+                else { d.skip_kind = 1; d.skip = dref(bp.in); }
+            }
+            if (j > 0) { d.has_dgrad = 1; d.din = dws(bp.ws_gact[j - 1]); }
+            else if (need_in_grad) {
+                d.has_dgrad = 1; d.din = dref(bp.gin_ref);
+                d.din_add = bp.has_proj ? dws(bp.ws_gproj) : dref(bp.g_ref);
+            }
+            out.push_back(d);
+        }
+        if (bp.has_proj) {
+            lp_debug_unit d = base(bp.proj, (int)i, 3);
+            d.in = dref(bp.in);
+            d.gout = dref(bp.g_ref);
+            if (need_in_grad) { d.has_dgrad = 1; d.din = dws(bp.ws_gproj); }
+            out.push_back(d);
+        }
+    }
+}
+
+lp_status lp_debug_unit_count(const struct lp_net* net, int k, int* n) {
+    if (!net || !n) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
+    if (net->mods[k].d.order != LP_ORDER_POST) return fail(LP_ERR_INVALID_ARG, "module %d: unit views describe the conv-BN-ReLU order only", k);
+    std::vector<lp_debug_unit> u;
+    collect_units(net->mods[k], u, k);
+    *n = (int)u.size();
+    return LP_OK;
+}
+
+lp_status lp_debug_unit_info(const struct lp_net* net, int k, int i, lp_debug_unit* info) {
+    if (!net || !info) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
+    if (net->mods[k].d.order != LP_ORDER_POST) return fail(LP_ERR_INVALID_ARG, "module %d: unit views describe the conv-BN-ReLU order only", k);
+    std::vector<lp_debug_unit> u;
+    collect_units(net->mods[k], u, k);
+    if (i < 0 || i >= (int)u.size()) return fail(LP_ERR_INVALID_ARG, "unit %d out of range", i);
+    *info = u[i];
+    return LP_OK;
+}
+
+lp_status lp_debug_module_info(const struct lp_net* net, int k, lp_debug_module* info) {
+    if (!net || !info) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
+    const ModulePlan& m = net->mods[k];
+    if (m.d.order != LP_ORDER_POST) return fail(LP_ERR_INVALID_ARG, "module %d: unit views describe the conv-BN-ReLU order only", k);
+    memset(info, 0, sizeof(*info));
+    info->keep_gradients = net->keep_gradients ? 1 : 0;
+    info->oN = m.oN; info->oH = m.oH; info->oW = m.oW; info->oC = m.oC;
+    if (m.d.stem == 2) {
+        info->pool_in = dws(m.ws_stem_act); info->pool_out = dws(m.ws_pool_out); info->pool_arg = dws(m.ws_pool_arg);
+        info->g_pool_out = dref(m.bp[0].gin_ref); info->g_pool_in = dws(m.ws_gpool);
+        info->pH = m.pH; info->pW = m.pW; info->pC = m.d.stem_cout;
+    }
+    if (k == net->K - 1) {
+        info->feat = dws(m.ws_feat); info->pooled = dws(m.ws_pooled); info->dfeat = dws(m.ws_dfeat);
+        info->t_fc_w = m.t_fcw; info->t_fc_b = m.t_fcb;
+    }
+    return LP_OK;
+}
+
+lp_status lp_debug_filter_load_extent(int kernel, int bk, int bn, int nw, int Ncol, int Cin, int R, size_t* max_end,
+                                      size_t* n_live) {
+    if (!max_end || !n_live) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if ((kernel != 0 && kernel != 1) || (bk != 32 && bk != 64) || bn < 1 || nw < 1 || Ncol < 1 || Cin < 1 || R < 1)
+        return fail(LP_ERR_INVALID_ARG, "bad geometry");
+    if (kernel == 0 ? (Cin % bk != 0) : (bk != 64 || Cin % 32 != 0))
+        return fail(LP_ERR_SHAPE, "Cin = %d does not fit channel slabs of %d", Cin, bk);
+    // the filter loads exactly as conv_igemm_fast_kernel (kernel 0) and conv_win_kernel (kernel 1) form them
+    ConvProb P; memset(&P, 0, sizeof(P));
+    P.Ncol = Ncol; P.Cin = Cin; P.S = R; P.rs = 1; P.ss = 1; P.ldw = R * R * Cin;
+    const int rps = 1024 / (bk * 2), cpr = bk * 2 / 16;
+    const int nsbt = bn / rps, nsb = (nsbt + nw - 1) / nw;
+    const int nslabc = (Cin + bk - 1) / bk;
+    const bool half_last = (Cin % bk) != 0;
+    size_t worst = 0, live = 0;
+    for (int tile_n = 0; tile_n * bn < Ncol; ++tile_n)
+        for (int wave = 0; wave < nw; ++wave) {
+            const bool last_b = (wave + nw * (nsb - 1)) < nsbt;
+            for (int lane = 0; lane < 64; ++lane) {
+                const int kvg = addr::filter_kvg(bk, lane, wave);
+                const addr::FilterRows f = addr::filter_rows(tile_n * bn, rps, nw, wave, lane / cpr, kvg, P.ldw, Ncol);
+                const bool b_hi = kvg >= cpr / 2;
+                for (int j = 0; j < nsb; ++j) {
+                    if (!(j + 1 < nsb || last_b)) continue;
+                    for (int sc = 0; sc < nslabc; ++sc)
+                        for (int tr = 0; tr < R; ++tr)
+                            for (int ts = 0; ts < R; ++ts) {
+                                const int ci0 = sc * bk;
+                                const bool t_live = !(kernel == 1 && b_hi && half_last && ci0 + bk > Cin);
+                                const unsigned vo = addr::filter_voffset(f, j, t_live);
+                                if (vo == addr::kOOB) continue;
+                                const size_t end = (size_t)vo + addr::filter_soffset(f, addr::filter_tap_offset(P, tr, ts, ci0), j) + 16;
+                                worst = std::max(worst, end);
+                                ++live;
+                            }
+                }
+            }
+        }
+    *max_end = worst; *n_live = live;
+    return LP_OK;
+}
+
 lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel) {
     if (!net || !ptr || !numel) return fail(LP_ERR_INVALID_ARG, "NULL argument");
     if (k < 0 || k >= net->K) return fail(LP_ERR_INVALID_ARG, "module %d out of range", k);
@@ -2102,8 +2289,9 @@ lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, cons
         *numel = m.bp[0].in_elems;
         return LP_OK;
     }
+    if (which < 0) return fail(LP_ERR_INVALID_ARG, "tensor id %d is negative", which);
     const int bi = (which - 1) / 8, sub = (which - 1) % 8;
-    if (which < 0 || bi >= (int)m.bp.size()) return fail(LP_ERR_INVALID_ARG, "block %d out of range", bi);
+    if (bi >= (int)m.bp.size()) return fail(LP_ERR_INVALID_ARG, "block %d out of range", bi);
     const BlockPlan& bp = m.bp[bi];
     if (sub < 3) {
         if (sub >= (int)bp.main.size()) return fail(LP_ERR_INVALID_ARG, "conv slot %d out of range", sub);

@@ -25,6 +25,7 @@
 // inside one filter tap, so the tap geometry is wave-uniform), at most 32 taps, tensors < 2 GiB.
 #include <algorithm>
 
+#include "lp_addr.h"
 #include "lp_kernels.h"
 #include "lp_mma.h"
 
@@ -32,7 +33,7 @@ namespace lp {
 
 namespace {
 
-constexpr unsigned kOOB = 0x80000000u;      // byte offset beyond any buffer
+using addr::kOOB;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     // chunk l%CPR) and therefore fetches global chunk (l%CPR) ^ swizzle(row).  64-byte rows: swizzle(row) = (row>>2)&3;
     // 128-byte rows: (row>>1)&7, which inside a slab is 4*(s&1) + (l>>4), and s&1 = wave&1 for every slab of a wave.
     const int lrow = lane / CPR;
-    const int kvg = BK == 32 ? ((lane & 3) ^ ((lane >> 4) & 3)) : ((lane & 7) ^ (4 * (wave & 1) + (lane >> 4)));
+    const int kvg = addr::filter_kvg(BK, lane, wave);
     int a_base[NSA];
     unsigned a_mask[NSA];
 #pragma unroll
@@ -132,9 +133,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
             a_mask[i] = mk;
         }
     }
-    // filter rows at or beyond Ncol start at or beyond the end of the buffer: no explicit check needed
-    const unsigned b_base0 = (unsigned)(((n0 + RPS * wave + lrow) * P.ldw + kvg * 8) * 2);
-    const unsigned b_step = (unsigned)(RPS * NW * P.ldw * 2);
+    // filter rows at or beyond Ncol (ragged last column tile) are marked out of range per lane, in every round
+    const addr::FilterRows frows = addr::filter_rows(n0, RPS, NW, wave, lrow, kvg, P.ldw, P.Ncol);
     const bool last_b = (wave + NW * (NSB - 1)) < NSBT;          // does this wave own a slab in the last round?
 
     const int nk = ntr * nts * (Cin / BK);
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     unsigned char* t_dst = smem;
     auto tile_begin = [&](int st) {
         t_live = issued < nk;
-        t_offb = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
+        t_offb = addr::filter_tap_offset(P, tr, ts, ci0);
         t_offa = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
         t_bit = tr * nts + ts;
         t_dst = smem + st * STAGE_BYTES + wave * 1024;
@@ -168,9 +168,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         } else if (i < NSA + NSB) {
             const int j = i - NSA;
             if (j + 1 < NSB || last_b) {
-                const unsigned off = t_live ? b_base0 : kOOB;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(t_dst + A_BYTES + j * (NW * 1024)), 16,
-                                                         (int)off, (int)(t_offb + j * b_step), 0, 0);
+                                                         (int)addr::filter_voffset(frows, j, t_live),
+                                                         (int)addr::filter_soffset(frows, t_offb, j), 0, 0);
             }
         }
     };

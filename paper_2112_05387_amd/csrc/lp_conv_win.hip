@@ -24,6 +24,7 @@
 // Cin % 32 == 0 (channel slabs of 64, the last one may be half).
 #include <algorithm>
 
+#include "lp_addr.h"
 #include "lp_kernels.h"
 #include "lp_mma.h"
 
@@ -31,7 +32,7 @@ namespace lp {
 
 namespace {
 
-constexpr unsigned kOOB = 0x80000000u;      // byte offset beyond any buffer
+using addr::kOOB;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
@@ -156,9 +157,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
 
     // ---- filter tiles (as in the implicit-GEMM kernel) ----
     const int lrow = lane / CPR;
-    const int kvg = BK == 32 ? ((lane & 3) ^ ((lane >> 4) & 3)) : ((lane & 7) ^ (4 * (wave & 1) + (lane >> 4)));
-    const unsigned b_base0 = (unsigned)(((n0 + RPS * wave + lrow) * P.ldw + kvg * 8) * 2);
-    const unsigned b_step = (unsigned)(RPS * NW * P.ldw * 2);
+    const int kvg = addr::filter_kvg(BK, lane, wave);
+    const addr::FilterRows frows = addr::filter_rows(n0, RPS, NW, wave, lrow, kvg, P.ldw, P.Ncol);
     const bool last_b = (wave + NW * (NSB - 1)) < NSBT;
     const int nk = 9 * nslabc;
     const bool b_hi = kvg >= CPR / 2;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     unsigned char* t_dst = s_b;
     auto tile_begin = [&](int st) {
         t_live = issued < nk && !(b_hi && half_last && ci0 + BK > Cin);
-        t_offb = (unsigned)((((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci0) * 2);
+        t_offb = addr::filter_tap_offset(P, tr, ts, ci0);
         t_dst = s_b + st * B_BYTES + wave * 1024;
         ++issued;
         if (++ts == 3) {
@@ -183,9 +183,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     };
     auto issue_b = [&](int j) {
         if (j < NSB && (j + 1 < NSB || last_b)) {
-            const unsigned off = t_live ? b_base0 : kOOB;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(t_dst + j * (NW * 1024)), 16, (int)off,
-                                                     (int)(t_offb + j * b_step), 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(t_dst + j * (NW * 1024)), 16,
+                                                     (int)addr::filter_voffset(frows, j, t_live),
+                                                     (int)addr::filter_soffset(frows, t_offb, j), 0, 0);
         }
     };
 

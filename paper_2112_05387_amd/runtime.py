@@ -17,12 +17,18 @@ class LocalStep:
 
     `desc` is any object with the attributes of the C descriptors (modules, aux, dtype, bn_eps, K)."""
 
-    def __init__(self, desc):
+    def __init__(self, desc, keep_gradients=False):
+        """keep_gradients: debug layout of the workspace in which no gradient buffer is reused inside a backward pass
+        (for the unit-by-unit views of `units` / `fetch`)."""
         self.desc = desc
         self.K = len(desc.modules)
         self.dtype = desc.dtype
         self.tdtype = torch.bfloat16 if desc.dtype == "bf16" else torch.float32
-        self.net = B.lp_net_create(desc.modules, desc.aux, desc.dtype, desc.bn_eps)
+        B.lp_debug_keep_gradients(keep_gradients)
+        try:
+            self.net = B.lp_net_create(desc.modules, desc.aux, desc.dtype, desc.bn_eps)
+        finally:
+            B.lp_debug_keep_gradients(False)
         self.dev = _dev()
         self.ws_bytes = B.lp_net_workspace_bytes(self.net)
         self.ws = torch.empty(self.ws_bytes + 256, dtype=torch.uint8, device=self.dev)
@@ -134,6 +140,25 @@ class LocalStep:
         off = ptr - self.ws.data_ptr()
         esz = 2 if self.dtype == "bf16" else 4
         return self.to_host(self.ws[off:off + n * esz].view(self.tdtype).reshape(shape))
+
+    def units(self, k):
+        """The conv+BN units of module k (debug views, forward order)."""
+        return [B.lp_debug_unit_info(self.net, k, i) for i in range(B.lp_debug_unit_count(self.net, k))]
+
+    def fetch(self, ref, shape, kind="act"):
+        """Host copy (float64) of the tensor a debug reference names.  kind: "act" storage type, "f64", "f32", "u8"."""
+        n = int(np.prod(shape))
+        if ref.space == B.LP_REF_NONE:
+            return None
+        if ref.space == B.LP_REF_WORKSPACE:
+            tdt, esz = {"act": (self.tdtype, 2 if self.dtype == "bf16" else 4), "f64": (torch.float64, 8),
+                        "f32": (torch.float32, 4), "u8": (torch.uint8, 1)}[kind]
+            t = self.ws[ref.off:ref.off + n * esz].view(tdt).reshape(shape)
+            return t.cpu().numpy().astype(np.float64) if kind in ("f64", "u8") else self.to_host(t)
+        assert kind == "act" and ref.off == 0
+        src = {B.LP_REF_X: self.x, B.LP_REF_Y: self.y, B.LP_REF_DY: self.dy, B.LP_REF_DX: self.dx}[ref.space][ref.idx]
+        assert src.numel() == n
+        return self.to_host(src).reshape(shape)
 
     # ---- the five entry points ---------------------------------------------------------------------
     @staticmethod

@@ -205,3 +205,48 @@ def test_call_time_errors_without_touching_the_gpu():
 def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+@pytest.mark.parametrize("kernel,bk,bn,nw,ncol,cin,r", [
+    (0, 64, 320, 8, 296, 320, 3), (0, 64, 320, 4, 296, 64, 3), (0, 64, 160, 2, 136, 128, 3), (0, 32, 160, 8, 136, 160, 3),
+    (0, 32, 320, 8, 520, 32, 1), (0, 64, 320, 8, 2048, 512, 1), (0, 32, 160, 4, 128, 96, 3), (1, 64, 320, 8, 296, 160, 3),
+    (1, 64, 160, 8, 136, 136 - 8, 3), (1, 64, 320, 8, 640, 640, 3), (1, 64, 160, 8, 160, 160, 3)])
+def test_filter_loads_stay_inside_the_filter_buffer(kernel, bk, bn, nw, ncol, cin, r):
+    """Every direct-to-LDS filter load the wide-layer kernels form (their own address functions, enumerated on the
+    host over column tiles, waves, lanes, rounds, taps and channel slabs) either is marked out of range or ends inside
+    the filter tensor, ragged last column tile included (136 of 160, 296 = 160 + 136, 520 = 320 + 200 ...)."""
+    end, live = B.lp_debug_filter_load_extent(kernel, bk, bn, nw, ncol, cin, r)
+    size = ncol * r * r * cin * 2
+    assert live > 0
+    assert end <= size, f"a live load ends at byte {end} of a {size}-byte filter tensor"
+    # every 16-byte chunk of the tensor is fetched exactly once per pass over it
+    assert live * 16 == size
+
+
+def test_unit_views_describe_every_conv_of_a_module():
+    net = wl.make_config("wrn28_10", batch=4)
+    B.lp_debug_keep_gradients(1)
+    try:
+        h = B.lp_net_create(net.modules, net.aux, net.dtype, net.bn_eps)
+    finally:
+        B.lp_debug_keep_gradients(0)
+    try:
+        for k, m in enumerate(net.modules):
+            specs = wl.module_tensor_specs(m)
+            n = B.lp_debug_unit_count(h, k)
+            assert n == sum(1 for s in specs if s.kind == "conv")
+            refs = set()
+            for i in range(n):
+                u = B.lp_debug_unit_info(h, k, i)
+                assert specs[u.t_w].shape == (u.cout, u.R, u.R, u.cin)
+                assert specs[u.t_gamma].kind == "bn_gamma" and specs[u.t_beta].kind == "bn_beta"
+                assert u.y.space == B.LP_REF_WORKSPACE and u.dy.space == B.LP_REF_WORKSPACE
+                for r in (u.y, u.dy, u.stats, u.red) + ((u.din,) if u.has_dgrad and u.din.space == B.LP_REF_WORKSPACE else ()):
+                    assert (r.space, r.off) not in refs, "with kept gradients no buffer is shared between units"
+                    refs.add((r.space, r.off))
+                assert (u.skip_kind == 2) == (u.skip_unit >= 0)
+            assert B.lp_debug_module_info(h, k).keep_gradients == 1
+        with pytest.raises(B.LpError):
+            B.lp_debug_unit_info(h, 0, 99)
+    finally:
+        B.lp_net_destroy(h)

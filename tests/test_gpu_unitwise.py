@@ -1,0 +1,53 @@
+"""Backward (and forward) parity unit by unit at a fixed tolerance: see tests/gpu_unitwise.py for what is compared.
+
+Cases: small networks that cover every kernel family (general fp32 / bf16 kernels, 7x7 stem with max-pool, bottleneck
+blocks, stride-2 projections, ragged wide layers), then the configurations at their full sizes in the launch
+configuration the benchmark times: ResNet-20 (fp32, batch 128), ResNet-56 (bf16, K = 8, batch 128), WideResNet-28-10
+(bf16, batch 128: every one of its 25 conv+BN units, wide kernels at their full-size tiles) and the ImageNet-shaped
+ResNet-50 (bf16, 224 x 224, batch 64)."""
+import pytest
+
+import workloads as wl
+from tests.gpu_common import gpu_mini_basic, gpu_mini_bottleneck, gpu_mini_wide, gpu_mini_wide_strided
+from tests.gpu_unitwise import check_units
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_units_mini_basic(dtype):
+    check_units(gpu_mini_basic(batch=3, dtype=dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_units_mini_bottleneck(dtype):
+    check_units(gpu_mini_bottleneck(batch=2, dtype=dtype))
+
+
+def test_units_mini_wide():
+    check_units(gpu_mini_wide(batch=3))
+    check_units(gpu_mini_wide_strided(batch=5))
+
+
+def test_units_separate_calls():
+    check_units(gpu_mini_basic(batch=3, dtype="bf16"), fused=False)
+
+
+def test_units_wrn28_10_batch_8():
+    check_units(wl.make_config("wrn28_10", batch=8))
+
+
+def test_units_resnet20_full_size():
+    check_units(wl.make_config("resnet20"))
+
+
+def test_units_resnet56_full_size():
+    check_units(wl.make_config("resnet56"))
+
+
+def test_units_wrn28_10_full_size():
+    check_units(wl.make_config("wrn28_10"))
+
+
+def test_units_resnet50_full_size():
+    check_units(wl.make_config("resnet50"))

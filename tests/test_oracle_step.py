@@ -471,3 +471,93 @@ def test_sgd_update_closed_forms():
     after = _local_loss(net, k, inp["xs"][k], stepped, None, None, inp["labels"], 1.0)
     gn2 = sum(float(np.sum(g * g)) for g in out["dparams"][k])
     assert after < before and abs((before - after) - 1e-3 * gn2) <= 0.05 * 1e-3 * gn2
+
+
+@pytest.mark.parametrize("order", ["post", "pre"])
+def test_storage_rounding_placement(order):
+    """Where the diagnostic storage-rounding mode rounds (`q` of the composing routines).  The mode is defined as:
+    every STORED tensor is rounded once -- convolution results, activations, block outputs going forward; the gradient
+    of each of those tensors going backward, the data-gradient of a projection branch before it is added -- and
+    batch statistics are those of the stored tensor.  Here that definition is built a second time from a library's
+    float64 layers and its reverse-mode differentiation: a `store` node rounds the value in the forward direction and
+    the gradient in the backward direction, and one is placed on every stored tensor.  With a coarse rounding grid
+    (2^-5) a rounding that the oracle puts anywhere else (or leaves out) moves results by 1e-2; agreement is 1e-9."""
+    import torch
+    import torch.nn.functional as F
+    grid = 32.0
+    q = lambda a: np.round(np.asarray(a, dtype=np.float64) * grid) / grid
+    tq = lambda a: torch.round(a * grid) / grid
+
+    class Store(torch.autograd.Function):          # value and gradient are both stored (rounded)
+        @staticmethod
+        def forward(ctx, a):
+            return tq(a)
+
+        @staticmethod
+        def backward(ctx, g):
+            return tq(g)
+
+    class StoreGrad(torch.autograd.Function):      # only the gradient is stored (a branch reading an already stored tensor)
+        @staticmethod
+        def forward(ctx, a):
+            return a.clone()
+
+        @staticmethod
+        def backward(ctx, g):
+            return tq(g)
+
+    store, store_grad = Store.apply, StoreGrad.apply
+    net = (mini_basic_pre if order == "pre" else mini_basic)()
+    net.al, net.lam_sigma = True, 0.1
+    inp = step_inputs(net, lpref)
+    xs = [q(x) for x in inp["xs"]]
+    lams = [q(l) for l in inp["lams"]]
+    want = lpref.local_step(net, xs, inp["params"], inp["labels"], lams, 1.0, need_dx0=False, q=q)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))
+    filt = lambda w: w.permute(0, 3, 1, 2)
+    bn = lambda a, g, b: F.batch_norm(a, None, None, g, b, True, 0.0, net.bn_eps)
+    for k, m in enumerate(net.modules):
+        p = [t(a).requires_grad_(True) for a in inp["params"][k]]
+        x = t(xs[k]).requires_grad_(True)
+        a = store(x.permute(0, 3, 1, 2))           # x_k is a stored tensor: its gradient dx_k is stored
+        i = 0
+        if order == "pre":
+            if m.stem:
+                a = store(F.conv2d(a, filt(p[0]), padding=1)); i = 1
+            for b in m.blocks:
+                o1 = store(F.relu(bn(a, p[i], p[i + 1])))
+                y1 = store(F.conv2d(o1, filt(p[i + 2]), stride=b.stride, padding=1))
+                o2 = store(F.relu(bn(y1, p[i + 3], p[i + 4])))
+                z = F.conv2d(o2, filt(p[i + 5]), padding=1)
+                skip = store(F.conv2d(store_grad(o1), filt(p[i + 6]), stride=b.stride)) if b.proj else a
+                a = store(z + skip)
+                i += 7 if b.proj else 6
+            feat = a
+            if m.head:
+                a = store(F.relu(bn(a, p[i], p[i + 1]))); i += 2
+        else:
+            if m.stem:
+                a = store(F.relu(bn(store(F.conv2d(a, filt(p[0]), padding=1)), p[1], p[2]))); i = 3
+            for b in m.blocks:
+                y = store(F.relu(bn(store(F.conv2d(a, filt(p[i]), stride=b.stride, padding=1)), p[i + 1], p[i + 2])))
+                z = bn(store(F.conv2d(y, filt(p[i + 3]), padding=1)), p[i + 4], p[i + 5])
+                if b.proj:
+                    skip = bn(store(F.conv2d(store_grad(a), filt(p[i + 6]), stride=b.stride)), p[i + 7], p[i + 8])
+                else:
+                    skip = a
+                a = store(z + skip)
+                i += 9 if b.proj else 6
+            feat = a
+        if m.head:
+            logits = F.linear(F.adaptive_avg_pool2d(a, 1).flatten(1), p[i], p[i + 1])
+            np.testing.assert_allclose(want["logits"], logits.detach().numpy(), rtol=0, atol=1e-9)
+            logits.backward(t(want["dlogits"]))
+        else:
+            y_out = feat.permute(0, 2, 3, 1)
+            np.testing.assert_allclose(want["y"][k], y_out.detach().numpy(), rtol=0, atol=1e-9)
+            y_out.backward(t(want["dy"][k]))        # the stored terminal adjoint of the oracle's own run
+        for j, (g, w) in enumerate(zip(p, want["dparams"][k])):
+            np.testing.assert_allclose(w, g.grad.numpy(), rtol=0, atol=1e-9 * max(1.0, float(np.max(np.abs(w)))),
+                                       err_msg=f"module {k} tensor {j}")
+        if want["dx"][k] is not None:
+            np.testing.assert_allclose(want["dx"][k], x.grad.numpy(), rtol=0, atol=1e-9)
