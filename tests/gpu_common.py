@@ -105,7 +105,7 @@ def _oracle_pieces(net, inp, scale, want_dx0, q):
     return o
 
 
-def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes="default"):
+def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes="default", max_uncovered=None):
     """End-to-end parity of the whole local step on identical seeded inputs (the bar for the backward pass of the
     bf16 kernels is the unit-by-unit test of tests/gpu_unitwise.py; this is the whole-network check beside it).
 
@@ -113,11 +113,13 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
 
     bf16 mode: forward outputs, losses and terminal adjoints are compared with the plain float64 definition (2e-2).
     A backward pass through several layers takes decisions from stored bf16 values (ReLU masks), so end to end it is
-    compared with the oracle's diagnostic storage-rounding mode.  For networks of at most three residual blocks the
-    tolerance is the flat 2e-2.  Deeper ones are chaotic in bf16 (a 1e-6 difference in front of a rounding flips a
-    mask bit and two valid evaluations drift apart): there the oracle measures its own spread (two runs with a 1e-6
-    relative perturbation in front of every rounding) and a tensor whose spread exceeds the tolerance is reported
-    as NOT COVERED by this test instead of being compared (its kernels are covered unit by unit).
+    compared with the oracle's diagnostic storage-rounding mode at the same flat 2e-2.  Such a pass is chaotic where
+    it is deep or where a gradient sums few pixels (a 1e-6 difference in front of a rounding flips a mask bit, and one
+    flipped bit moves a filter gradient summed over M pixels by about 1/sqrt(M) of its norm): the oracle therefore
+    measures its own spread (two more runs with a 1e-6 relative perturbation in front of every rounding), and a
+    tensor that misses the tolerance while the oracle's own spread reaches a third of it is reported as NOT COVERED
+    by this test -- it is never passed at a wider tolerance (its kernels are covered unit by unit).  max_uncovered,
+    when given, bounds the number of such tensors.
 
     Pass 1 (entry point by entry point): the loss/terminal-adjoint call and the backward call are each fed the
     ORACLE's value of their input (rounded to the storage type) on both sides.
@@ -133,12 +135,11 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
     inp = step_inputs(net, lpref)
     specs = [wl.module_tensor_specs(m) for m in net.modules]
     bf16 = net.dtype == "bf16"
-    deep = sum(len(m.blocks) for m in net.modules) > 3
     q = wl.round_bf16 if bf16 else None
     plain_fwd = [lpref.module_forward(net.modules[k], inp["xs"][k], inp["params"][k], net.bn_eps) for k in range(K)] if bf16 else None
     o = _oracle_pieces(net, inp, scale, want_dx0, q)
     spread = {}
-    if bf16 and deep:
+    if bf16:
         for trial in range(2):          # two perturbed evaluations; the spread of a tensor is the larger deviation
             o2 = _oracle_pieces(net, inp, scale, want_dx0, _PerturbedRounding(net.seed + 7919 * trial))
             for k in range(K):
@@ -153,18 +154,21 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
         bad, uncovered = {}, {}
         for name, v in errs.items():
             sp = spread.get(name.replace("fused.", ""), 0.0)
+            if v <= tol:
+                continue
             if 3.0 * sp > tol:
-                uncovered[name] = (v, sp)           # chaotic in bf16 end to end: reported, not judged
-            elif not (v <= tol):
+                uncovered[name] = (v, sp)           # chaotic in bf16 end to end: reported as not covered, never passed
+            else:
                 bad[name] = (v, tol)
         top = sorted(((k, v) for k, v in errs.items() if k not in uncovered), key=lambda kv: -kv[1])[:5]
         say(f"[{net.name} {net.dtype} N={net.modules[0].N}] {label}: {len(errs) - len(uncovered)} tensors within {tol:g}, worst: "
             + ", ".join(f"{k}={v:.2e}" for k, v in top))
         if uncovered:
             wt = sorted(uncovered.items(), key=lambda kv: -kv[1][0])[:4]
-            say(f"    NOT COVERED here ({len(uncovered)} backward tensors whose own bf16 spread in the oracle exceeds {tol / 3:.1e}; "
-                "unit-wise test covers their kernels), e.g. " + ", ".join(f"{k}: err {v:.1e} spread {s_:.1e}" for k, (v, s_) in wt))
+            say(f"    NOT COVERED here ({len(uncovered)} backward tensors beyond {tol:g} whose own bf16 spread in the oracle exceeds {tol / 3:.1e}; "
+                "the unit-wise test covers their kernels), e.g. " + ", ".join(f"{k}: err {v:.1e} spread {s_:.1e}" for k, (v, s_) in wt))
         assert not bad, f"{label}: beyond tolerance (error, allowed): {bad}"
+        assert max_uncovered is None or len(uncovered) <= max_uncovered, f"{label}: {len(uncovered)} tensors not covered"
 
     ls = LocalStep(net)
     worst = {}
