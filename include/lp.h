@@ -156,6 +156,21 @@ lp_status lp_net_set_workspace(struct lp_net* net, void* dev_ptr, size_t bytes);
 lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
                             const void* const* aux_params, void* const* x_out);
 
+/* lp_auxnet_forward for callers that cannot allocate device memory and have no workspace to lend (code under HIP-graph
+ * capture, serving loops, harnesses that forbid hipMalloc): same arguments, same kernels and same x_out, but the
+ * intermediates of the pass (per-channel statistics, pre-BN convolution results, activations between the blocks of a
+ * stack) live in a device array of LP_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs on
+ * holds one until the process ends) instead of the workspace; lp_net_set_workspace is not needed.  It allocates
+ * nothing and frees nothing.  Limits: LP_ERR_WORKSPACE when the AuxNets of the net need more than
+ * LP_STATIC_SCRATCH_BYTES (the ResNet-56 configuration at batch 128 needs 16.1 MiB in bf16); nothing is saved for
+ * lp_auxnet_distill_grad / lp_reauxnet_grad (they keep requiring lp_auxnet_forward); all calls on one GPU share the
+ * one array, which keeps the last call's contents: the call clears what must start at zero, and calls that overlap in
+ * time on one GPU (two streams, two nets, two threads) race.  The array's address is looked up on the first call on a
+ * device: make that call outside stream capture.  Errors otherwise as lp_auxnet_forward. */
+#define LP_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+lp_status lp_auxnet_forward_static(struct lp_net* net, void* stream, const void* image,
+                                   const void* const* aux_params, void* const* x_out);
+
 /* Gradient of the AuxNet distillation objective of Sec. 4.2 (theta_{k-1} <- argmin |x_k - AuxNet_{k-1}(x_0; theta)|^2,
  * one descent step per iteration; the step itself is the caller's).  For every j with daux_params[j] != NULL:
  *     loss[j] = loss_scale * sum (AuxNet_j(image) - x_target[j])^2,   daux_params[j] = d loss[j] / d theta_j,

@@ -13,7 +13,7 @@ LP_ORDER_POST, LP_ORDER_PRE = 0, 1
 LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
-           "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_module_forward",
+           "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_auxnet_forward_static", "lp_module_forward",
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step",
            "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
            "lp_debug_module_info", "lp_debug_filter_load_extent",
@@ -97,6 +97,7 @@ def lib():
         L.lp_net_workspace_bytes.argtypes = [c_void_p, POINTER(c_size_t)]
         L.lp_net_set_workspace.argtypes = [c_void_p, c_void_p, c_size_t]
         L.lp_auxnet_forward.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp]
+        L.lp_auxnet_forward_static.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp]
         L.lp_auxnet_distill_grad.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp, c_float, c_void_p, vpp]
         L.lp_module_forward.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, c_void_p]
         L.lp_local_loss_grad.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, c_float, c_float, c_void_p,
@@ -216,6 +217,10 @@ def lp_net_set_workspace(net, dev_ptr, nbytes):
 
 def lp_auxnet_forward(net, stream, image, aux_params, x_out):
     _check(lib().lp_auxnet_forward(net, stream, image, _ptr_array(aux_params), _ptr_array(x_out)))
+
+
+def lp_auxnet_forward_static(net, stream, image, aux_params, x_out):
+    _check(lib().lp_auxnet_forward_static(net, stream, image, _ptr_array(aux_params), _ptr_array(x_out)))
 
 
 def lp_module_forward(net, stream, module_mask, x, params, y, logits):

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -40,12 +41,13 @@ static lp_status fail(lp_status st, const char* fmt, ...) {
 namespace {
 
 enum Space { SP_NONE = 0, SP_WS, SP_X, SP_Y, SP_PARAM, SP_DPARAM, SP_DY, SP_DX, SP_LOGITS, SP_DLOGITS,
-             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG, SP_XTGT, SP_XNEXT, SP_LAM, SP_LOSS, SP_LABELS };
+             SP_AUXP, SP_XOUT, SP_IMAGE, SP_AUXG, SP_XTGT, SP_XNEXT, SP_LAM, SP_LOSS, SP_LABELS, SP_SCRATCH };
 struct Ref { int space = SP_NONE; int idx = 0; size_t off = 0; };
 static Ref mk(int sp, int idx, size_t off) { Ref r; r.space = sp; r.idx = idx; r.off = off; return r; }
 
 struct Bindings {
     char* ws = nullptr;
+    char* scratch = nullptr;               // the library's own device array (lp_auxnet_forward_static)
     const void* const* x = nullptr;
     void* const* y = nullptr;
     const void* const* params = nullptr;
@@ -69,6 +71,7 @@ struct Bindings {
 static void* resolve(const Ref& r, const Bindings& b) {
     switch (r.space) {
         case SP_WS: return b.ws + r.off;
+        case SP_SCRATCH: return b.scratch + r.off;
         case SP_X: return (char*)b.x[r.idx] + r.off;
         case SP_Y: return (char*)b.y[r.idx] + r.off;
         case SP_PARAM: return (char*)b.params[r.idx] + r.off;
@@ -168,6 +171,7 @@ struct AuxPlan {
     size_t param_bytes = 0, grad_bytes = 0;
     size_t ws_out = 0, ws_g = 0;           // recomputed AuxNet output and the gradient on it (distillation)
     Program fwd, bwd_a, bwd_b;             // distillation: before / after the loss kernel
+    Program fwd_static;                    // forward pass whose intermediates live in the library's own device array
     bool chained = false;                  // input = the previous auxiliary variable instead of the mini-batch
 };
 
@@ -191,6 +195,7 @@ struct lp_net {
     hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
     bool lanes_ready = false;              // every extra stream and event above exists
     bool keep_gradients = false;           // debug layout: no gradient buffer is reused inside a backward pass
+    size_t scratch_bytes = 0;              // what the AuxNet forward passes need of the library's own device array
     // optional per-launch timing (hipEvents around every grouped launch)
     bool prof = false;
     int lanes_in_flight = 1;               // stream lanes of the call being enqueued (launch-time tile choice)
@@ -1098,6 +1103,27 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
         a.fwd.push_back(s0);
     }
     forward(a.fwd, in0, mk(SP_XOUT, j, 0));
+    {   // the same pass with a compact layout of its intermediates (statistics, conv results, inner activations) in the
+        // library's own device array: nothing of it is kept for the gradient calls
+        WsAlloc sc; sc.off = net->scratch_bytes;
+        std::vector<size_t> s_stats(depth), s_y(depth), s_act(depth, 0);
+        for (int i = 0; i < depth; ++i) {
+            s_stats[i] = sc.take(sizeof(double) * 2 * us[i]->cout);
+            s_y[i] = sc.take(us[i]->out_elems() * net->esz);
+            if (i + 1 < depth) s_act[i] = sc.take(us[i]->out_elems() * net->esz);
+        }
+        net->scratch_bytes = sc.off;
+        auto S_ = [&](size_t off) { return mk(SP_SCRATCH, 0, off); };
+        Step s0;
+        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(S_(s_stats[i]), sizeof(double) * 2 * us[i]->cout));
+        a.fwd_static.push_back(s0);
+        for (int i = 0; i < depth; ++i) {
+            const Unit& u = *us[i];
+            const Ref dst = i + 1 < depth ? S_(s_act[i]) : mk(SP_XOUT, j, 0);
+            a.fwd_static.push_back(Step{B.conv_fwd(u, i == 0 ? in0 : S_(s_act[i - 1]), P_(u.t_w), S_(s_y[i]), S_(s_stats[i]))});
+            a.fwd_static.push_back(Step{B.bn_apply(Mof(u), u.cout, S_(s_y[i]), dst, S_(s_stats[i]), P_(u.t_g), P_(u.t_b), u.relu)});
+        }
+    }
 
     // Gradient through the stack.  First part (before the loss or correction kernel): the AuxNet output again, from the
     // saved pre-BN tensor of the last block; a chained AuxNet is distilled at the CORRECTED input x_j (Sec. 4.2), so
@@ -1582,6 +1608,35 @@ static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 }  // namespace
 
 // ----------------------------------------------------------------------------------------------------
+// The library's own device array (lp_auxnet_forward_static): intermediates of the AuxNet forward passes for callers
+// that can lend no workspace.  Every GPU the library runs on holds its own copy until the process ends; in host code
+// the array's name is only a handle, its device address comes from hipGetSymbolAddress, once per device.
+// ----------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[LP_STATIC_SCRATCH_BYTES];   // (the compiler gives it external linkage in the code object because host code names it below)
+
+namespace {
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+static lp_status static_scratch(char** out) {
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(err));
+    if (dev < 0 || dev >= kMaxDevices) return fail(LP_ERR_HIP, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) return fail(LP_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(err));
+        g_scratch_ptr[dev] = (char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LP_OK;
+}
+}  // namespace
+
+// ----------------------------------------------------------------------------------------------------
 // C ABI
 // ----------------------------------------------------------------------------------------------------
 extern "C" {
@@ -1779,6 +1834,31 @@ lp_status lp_auxnet_forward(struct lp_net* net, void* stream, const void* image,
     else   // x_{j+1} = AuxNet_j(x_j): one block after the other (the AuxNets are forward-locked, Sec. 4.2)
         for (size_t j = 0; j < progs.size() && st == LP_OK; ++j) st = run_programs(net, {progs[j]}, b, (hipStream_t)stream);
     if (st == LP_OK) net->aux_fwd_done = true;
+    return st;
+}
+
+lp_status lp_auxnet_forward_static(struct lp_net* net, void* stream, const void* image, const void* const* aux_params,
+                                   void* const* x_out) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (net->aux.empty()) return fail(LP_ERR_STATE, "the net was created without AuxNet descriptors");
+    if (!image || !aux_params || !x_out) return fail(LP_ERR_INVALID_ARG, "NULL argument");
+    if (misaligned(image)) return fail(LP_ERR_INVALID_ARG, "image is not 16-byte aligned");
+    if (net->scratch_bytes > LP_STATIC_SCRATCH_BYTES)
+        return fail(LP_ERR_WORKSPACE, "the AuxNet forward passes need %zu bytes of intermediates, the library's own array holds %zu",
+                    net->scratch_bytes, (size_t)LP_STATIC_SCRATCH_BYTES);
+    std::vector<const Program*> progs;
+    for (int j = 0; j < net->K - 1; ++j) {
+        if (!aux_params[j] || !x_out[j]) return fail(LP_ERR_INVALID_ARG, "aux_params[%d] or x_out[%d] is NULL", j, j);
+        if (misaligned(aux_params[j]) || misaligned(x_out[j])) return fail(LP_ERR_INVALID_ARG, "aux tensor %d is not 16-byte aligned", j);
+        progs.push_back(&net->aux[j].fwd_static);
+    }
+    Bindings b; b.image = image; b.auxp = aux_params; b.xout = x_out;
+    lp_status st = static_scratch(&b.scratch);
+    if (st != LP_OK) return st;
+    bool any_chained = false;
+    for (const AuxPlan& a : net->aux) any_chained = any_chained || a.chained;
+    if (!any_chained) return run_programs(net, progs, b, (hipStream_t)stream);
+    for (size_t j = 0; j < progs.size() && st == LP_OK; ++j) st = run_programs(net, {progs[j]}, b, (hipStream_t)stream);
     return st;
 }
 

@@ -250,3 +250,22 @@ def test_unit_views_describe_every_conv_of_a_module():
             B.lp_debug_unit_info(h, 0, 99)
     finally:
         B.lp_net_destroy(h)
+
+
+def test_static_auxnet_forward_rejects_what_does_not_fit():
+    """Size and argument checks of the entry point that allocates nothing come before any device call."""
+    net = wl.make_config("wrn28_10", batch=128)
+    m0 = net.modules[0]
+    net.aux = [AuxDesc(cin=m0.C, cout=m.C, stride=m0.H // m.H, relu=False) for m in net.modules[1:]]
+    h = B.lp_net_create(net.modules, net.aux, net.dtype, net.bn_eps)      # 40 + 20 + 10 MiB of pre-BN results alone
+    try:
+        _expect(B.LP_ERR_WORKSPACE, B.lp_auxnet_forward_static, h, None, FAKE_PTR, [FAKE_PTR] * 3, [FAKE_PTR] * 3)
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_auxnet_forward_static, h, None, None, [FAKE_PTR] * 3, [FAKE_PTR] * 3)
+    finally:
+        B.lp_net_destroy(h)
+    net = wl.make_config("resnet20", batch=4)
+    h = B.lp_net_create(net.modules, None, net.dtype, net.bn_eps)
+    try:
+        _expect(B.LP_ERR_STATE, B.lp_auxnet_forward_static, h, None, FAKE_PTR, [FAKE_PTR] * 3, [FAKE_PTR] * 3)
+    finally:
+        B.lp_net_destroy(h)
