@@ -148,19 +148,20 @@ def speedup_terms(name, batch, reps):
             "note": "every term measured on ONE GPU; the K devices of the model are not run"}
 
 
-def cpu_baseline(net_name, target_seconds=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same
-    network at a reduced mini-batch (the network, K and every layer shape are the configuration's)."""
+def cpu_baseline(net_name, target_seconds=60.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same network, at
+    the configuration's own mini-batch when the plain loops finish it within about a minute on the host's cores (the
+    headline configuration does), else at a reduced one (the network, K and every layer shape are the configuration's)."""
     import workloads as wl
     from oracle import lpref
-    from tests.helpers import step_inputs
     from workloads import configs as cfg
     full = wl.make_config(net_name)
     # the plain double loops reach roughly 4 GFLOP/s per thread on the GPU box's host; size the sample from that
     per_sample = cfg.conv_flops_step(full) / full.modules[0].N
     guess_rate = 4.0e9 * lpref.num_threads()
     batch = int(max(1, min(full.modules[0].N, target_seconds * guess_rate / per_sample)))
-    batch = max(batch, 1)
+    if batch * 10 >= full.modules[0].N * 9:
+        batch = full.modules[0].N
     net = wl.make_config(net_name, batch=batch)
     params = [wl.make_params(net, k) for k in range(net.K)]
     image, labels = wl.make_image(net), wl.make_labels(net)
@@ -180,7 +181,8 @@ def cpu_baseline(net_name, target_seconds=20.0):
     dt = time.perf_counter() - t0
     return {"value": batch / dt, "unit": "samples/s", "cores": lpref.num_threads(), "kind": "oracle",
             "sample": f"one local step of {net_name} (all K={net.K} modules, every layer at its real width) at "
-                      f"mini-batch {batch} instead of {full.modules[0].N}, float64 plain loops, {dt:.1f} s"}
+                      + (f"the configuration's mini-batch {batch}" if batch == full.modules[0].N else
+                         f"mini-batch {batch} instead of {full.modules[0].N}") + f", float64 plain loops, {dt:.1f} s"}
 
 
 def main():
@@ -235,7 +237,8 @@ def main():
 
 
     def timed_steps(profile):
-        # EXACTLY --steps steps; profile = 2: every grouped launch is bracketed by hipEvents and issued on one stream
+        # EXACTLY --steps steps; profile 1: every grouped launch is bracketed by hipEvents on its own stream; profile 2:
+        # the launches of all stream lanes are issued one after another on the caller's stream (durations alone)
         B.lp_profile_enable(ls.net, profile)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
@@ -250,11 +253,10 @@ def main():
         B.lp_profile_enable(ls.net, 0)
         return wall, ev0.elapsed_time(ev1), recs
 
-    # The timed region: the step as the library runs it (modules of different widths on concurrent stream lanes, no
-    # events between launches).  Kernels of different lanes overlap there, so a kernel's own duration is measured in a
-    # second pass over the same steps with every module on the caller's stream: full grouped launches, one after
-    # another, each bracketed by hipEvents (this is also what `--lanes single` times and what the rocprofv3
-    # summaries under profiles/ are taken with).
+    # The timed region: the step as the library runs it (modules on concurrent stream lanes, no events between launches).
+    # Kernels of different lanes overlap there, so a kernel's own duration is measured in a second pass over the same
+    # steps: the SAME launches (same grouping per lane, same tile variants as in the timed region), enqueued one after
+    # another on the caller's stream, each bracketed by hipEvents on that stream (lp_profile_enable(net, 2)).
     graph_ms = None
     if args.lanes == "single":
         wall_ms, gpu_ms, recs = timed_steps(1)           # one stream: the timed region itself carries the events
@@ -265,9 +267,8 @@ def main():
         wall_ms, gpu_ms, _ = timed_steps(0)
         if args.graph:
             graph_ms = time_graph_replays(ls, net, args.steps)
-        ls.set_stream_lanes(None)
         one_step(ls, net)
-        iso_wall, gpu_iso, recs = timed_steps(1)
+        iso_wall, gpu_iso, recs = timed_steps(2)
     ms_per_step = wall_ms / args.steps
     iso_ms_per_step = iso_wall / args.steps
 
@@ -288,7 +289,8 @@ def main():
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
     roof.update({"traffic": None, "kernel": f"{B.KIND_NAMES[dk]} cfg{dcfg}", "launches_per_step": dom["launches"] / args.steps,
                  "avg_launch_ms": dom["ms"] / dom["launches"], "share_of_gpu_time": dom["ms"] / max(gpu_iso, 1e-9),
-                 "measured": "launch durations from a second pass of the same steps with every module on one stream"})
+                 "measured": "hipEvents around every launch in a second pass over the same steps: the launches of the timed "
+                             "region (same grouping per stream lane, same tile variants), one after another on one stream"})
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:

@@ -100,7 +100,7 @@ struct Op {
     int type = 0, cfg = 0;
     int phase = 0;                         // fused step: 0 forward, 1 loss, 2 backward, 3 multiplier update
     bool vec = true;
-    Ref r[10];
+    Ref r[14];
     size_t fill_bytes = 0;
     size_t numel = 0;                      // OP_LOSS: elements of the interface tensor
     ConvProb conv;
@@ -1025,8 +1025,22 @@ static void build_step_programs(lp_net* net, int k) {
         Program& out = variant == 0 ? m.step : m.step_dx0;
         if (bw.empty()) continue;
         out = m.fwd;
-        out.push_back(loss_step);
-        for (Op& o : out.back()) o.phase = 1;
+        // The pass that writes F_k(x_k) (the BN apply + skip of the last block, conv-BN-ReLU order) also evaluates the
+        // local loss and the terminal adjoint on the value it stores: F_k(x_k) is not read again.  Where the module
+        // output is written by something else (the convolution epilogue of the pre-activation order) the loss keeps
+        // its own pass.
+        Op* last_apply = nullptr;
+        if (!last && !out.empty() && out.back().size() == 1 && out.back()[0].type == OP_BN_APPLY &&
+            out.back()[0].r[1].space == SP_Y)
+            last_apply = &out.back()[0];
+        if (last_apply) {
+            last_apply->cfg = 1;
+            last_apply->r[9] = mk(SP_XNEXT, k, 0); last_apply->r[10] = mk(SP_LAM, k, 0);
+            last_apply->r[11] = mk(SP_DY, k, 0); last_apply->r[12] = mk(SP_LOSS, 0, sizeof(float) * k);
+        } else {
+            out.push_back(loss_step);
+            for (Op& o : out.back()) o.phase = 1;
+        }
         for (const Step& st : bw) {
             out.push_back(st);
             for (Op& o : out.back()) o.phase = 2;
@@ -1187,7 +1201,8 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
         } break;
         case OP_WTRANS: bytes = 2.0 * o.wt.Cout * o.wt.RS * o.wt.Cin * e; break;
         case OP_FILL: bytes = (double)o.fill_bytes; break;
-        case OP_BN_APPLY: bytes = (double)o.bna.M * o.bna.C * e * (o.bna.skip_mode ? 3.0 : 2.0); break;
+        case OP_BN_APPLY:      // fused with the loss / terminal adjoint: + x_next, lam, dy (the multiplier written back: + 1)
+            bytes = (double)o.bna.M * o.bna.C * e * ((o.bna.skip_mode ? 3.0 : 2.0) + (o.cfg == 1 ? 3.0 : 0.0)); break;
         case OP_BN_BWD_REDUCE: bytes = (double)o.bnb.M * o.bnb.C * e * 2.0; break;
         case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * (o.r[9].space != SP_NONE ? 4.0 : 3.0); break;
         case OP_BN_STATS: bytes = (double)o.bnb.M * o.bnb.C * e; break;
@@ -1355,6 +1370,8 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
             } break;
             case OP_BN_APPLY: {
                 BnApplyGroup g; g.nprob = n; g.eps = net->eps; g.cmax = 0; int tot = 0;
+                const bool fused_loss = ops[base]->cfg == 1;
+                g.rho = b.rho; g.scale = b.scale; g.step = b.mstep;
                 for (int i = 0; i < n; ++i) g.cmax = std::max(g.cmax, ops[base + i]->bna.C);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
@@ -1363,10 +1380,16 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.gamma = (const float*)resolve(o.r[3], b); p.beta = (const float*)resolve(o.r[4], b);
                     p.skip = resolve(o.r[5], b); p.sstats = (const double*)resolve(o.r[6], b);
                     p.sgamma = (const float*)resolve(o.r[7], b); p.sbeta = (const float*)resolve(o.r[8], b);
+                    p.xn = nullptr; p.lam = nullptr; p.dy = nullptr; p.lam_out = nullptr; p.loss = nullptr;
+                    if (fused_loss) {      // the local loss and terminal adjoint (and the multiplier update) ride on this pass
+                        p.xn = resolve(o.r[9], b); p.lam = resolve(o.r[10], b); p.dy = resolve(o.r[11], b);
+                        p.loss = (float*)resolve(o.r[12], b);
+                        p.lam_out = b.mstep != 0.f ? const_cast<void*>(p.lam) : nullptr;
+                    }
                     p.block_start = tot; p.nblocks = elem_blocks((size_t)p.M * p.C / epv); tot += p.nblocks;
                 }
                 g.total_blocks = tot;
-                err = launch_bn_apply(g, dt, s);
+                err = launch_bn_apply(g, dt, fused_loss, s);
             } break;
             case OP_BN_STATS:
             case OP_BN_BWD_REDUCE:

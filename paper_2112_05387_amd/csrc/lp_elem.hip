@@ -74,7 +74,11 @@ template <typename G> __device__ __forceinline__ int find_problem(const G& g, in
 constexpr int kMaxC = 2048;
 
 // ------------------------------------------------------------------------------------------------
-template <typename T>
+__device__ __forceinline__ float block_sum(float v, float* s_tmp);
+
+// FUSE: the pass also evaluates the local loss and terminal adjoint of the interface tensor it writes (exactly the
+// arithmetic of loss_kernel, on the value as stored, vector by vector in the same order)
+template <typename T, bool FUSE>
 __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup g) {
     constexpr int EPV = Vec<T>::N;
     // per-channel coefficients: 4 arrays of g.cmax floats (sized by the launch: the LDS footprint limits occupancy)
@@ -108,10 +112,15 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
     // avoids a 64-bit remainder per vector
     const unsigned cstep = (unsigned)kElemBlock % (unsigned)cv;
     unsigned cidx = (unsigned)((base + threadIdx.x) % (size_t)cv);
+    const T* __restrict__ xn = reinterpret_cast<const T*>(P.xn);
+    const T* lam = reinterpret_cast<const T*>(P.lam);
+    T* lam_out = reinterpret_cast<T*>(P.lam_out);          // may alias lam: every vector is read before it is written
+    T* __restrict__ dyp = reinterpret_cast<T*>(P.dy);
+    float lacc = 0.f;
     for (int i0 = threadIdx.x; i0 < kElemVecsPerBlock; i0 += U * kElemBlock) {
         // Unconditional loads (a vector beyond the end re-reads the last one and is dropped): behind a per-lane branch
         // the compiler waits for each pair of loads before it issues the next.
-        u32x4 fraw[U], skraw[U];
+        u32x4 fraw[U], skraw[U], xnraw[FUSE ? U : 1], lmraw[FUSE ? U : 1];
         bool ok[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -120,6 +129,10 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
             const size_t vc = ok[u] ? v : nvec - 1;
             fraw[u] = Vec<T>::load_raw(y + vc * EPV);
             if (P.skip_mode) skraw[u] = Vec<T>::load_raw(skip + vc * EPV);
+            if constexpr (FUSE) {
+                xnraw[u] = Vec<T>::load_raw(xn + vc * EPV);
+                if (lam) lmraw[u] = Vec<T>::load_raw(lam + vc * EPV);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -146,7 +159,37 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
                 for (int e = 0; e < EPV; ++e) o[e] = fmaxf(o[e], 0.f);
             }
             Vec<T>::store(out + v * EPV, o);
+            if constexpr (FUSE) {
+                if constexpr (sizeof(T) == 2) {             // the loss is defined on F_k(x_k) as stored
+#pragma unroll
+                    for (int e = 0; e < EPV; e += 2) {
+                        const unsigned pk = pack_bf16x2(o[e], o[e + 1]);
+                        o[e] = __uint_as_float(pk << 16); o[e + 1] = __uint_as_float(pk & 0xffff0000u);
+                    }
+                }
+                float b[EPV], l[EPV], d[EPV];
+                Vec<T>::unpack(xnraw[u], b);
+                if (lam) Vec<T>::unpack(lmraw[u], l);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const float r = o[e] - b[e];
+                    const float lm = lam ? l[e] : 0.f;
+                    lacc += 0.5f * g.rho * r * r + lm * r;
+                    d[e] = g.scale * (g.rho * r + lm);
+                }
+                Vec<T>::store(dyp + v * EPV, d);
+                if (lam && lam_out) {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) l[e] = fmaf(g.step, o[e] - b[e], l[e]);
+                    Vec<T>::store(lam_out + v * EPV, l);
+                }
+            }
         }
+    }
+    if constexpr (FUSE) {
+        __shared__ float s_tmp[kElemBlock / 64];
+        const float tot = block_sum(lacc, s_tmp);
+        if (threadIdx.x == 0 && tot != 0.f) atomicAdd(P.loss, g.scale * tot);
     }
 }
 
@@ -721,11 +764,17 @@ __global__ void zero_selected_kernel(float* v, uint32_t mask, int n) {
         else hipLaunchKernelGGL(KERNEL<float>, grid, block, 0, stream, __VA_ARGS__);             \
     } while (0)
 
-hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s) {
+hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     const size_t lds = (size_t)4 * g.cmax * sizeof(float);
-    if (dtype == 1) hipLaunchKernelGGL(bn_apply_kernel<bf16_t>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
-    else hipLaunchKernelGGL(bn_apply_kernel<float>, dim3(g.total_blocks), dim3(kElemBlock), lds, s, g);
+    const dim3 grid(g.total_blocks), block(kElemBlock);
+    if (dtype == 1) {
+        if (fused_loss) hipLaunchKernelGGL((bn_apply_kernel<bf16_t, true>), grid, block, lds, s, g);
+        else hipLaunchKernelGGL((bn_apply_kernel<bf16_t, false>), grid, block, lds, s, g);
+    } else {
+        if (fused_loss) hipLaunchKernelGGL((bn_apply_kernel<float, true>), grid, block, lds, s, g);
+        else hipLaunchKernelGGL((bn_apply_kernel<float, false>), grid, block, lds, s, g);
+    }
     return hipGetLastError();
 }
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {

@@ -69,16 +69,21 @@ struct WtransGroup {
 
 // out = act( bn(y) [+ skip] ),  bn(y) = gamma*(y-mean)*invstd + beta from the summed statistics.
 // skip_mode 0: none, 1: plain tensor, 2: bn_s(skip) with its own statistics.
+// Fused form (the pass that writes a module's output F_k(x_k), inside lp_local_step): with dy != NULL the same pass
+// evaluates the local loss and terminal adjoint on the value it stores, as LossProb below describes (xn, lam, dy,
+// lam_out, loss), so that F_k(x_k) is not read again.
 struct BnApplyProb {
     const void* y; void* out;
     const double* stats; const float* gamma; const float* beta;
     const void* skip; const double* sstats; const float* sgamma; const float* sbeta;
+    const void* xn; const void* lam; void* dy; void* lam_out; float* loss;
     int M, C, relu, skip_mode;
     int block_start, nblocks;
 };
 struct BnApplyGroup {
     int nprob, total_blocks; float eps;
     int cmax;             // largest channel count of the group (sizes the coefficient arrays in LDS)
+    float rho, scale, step;   // fused form: penalty coefficient, loss scale, multiplier step
     BnApplyProb p[kMaxGroup];
 };
 
@@ -158,7 +163,7 @@ int wgrad_fast_blocks(const WgradProb& p);
 void fastdiv_make(unsigned d, unsigned* mul, unsigned* shift);
 hipError_t launch_wgrad(const WgradGroup& g, int dtype, int cfg, bool vec, hipStream_t s);
 hipError_t launch_wtrans(const WtransGroup& g, int dtype, hipStream_t s);
-hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, hipStream_t s);
+hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hipStream_t s);
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s);
 hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s);
 hipError_t launch_fill(const FillGroup& g, hipStream_t s);
