@@ -212,6 +212,24 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
                              const void* const* dy, const float* dlogits, const void* const* params,
                              float* const* dparams, void* const* dx);
 
+/* Deterministic reductions (for race hunting: run a step twice and compare bit for bit).  By default per-channel batch
+ * statistics, the sums of the batch-norm backward pass and the split filter gradients are accumulated with atomic adds,
+ * whose order varies from run to run (last-bit differences).  With on != 0 every such sum has a fixed order: the
+ * convolution epilogues emit no statistics and one workgroup per tensor sums the stored result instead; the
+ * batch-norm backward sums run in one workgroup per tensor; every filter-gradient tile is reduced over all pixels by
+ * one workgroup (no split); the head's weight gradient likewise.  Every activation, adjoint, gradient and multiplier
+ * of lp_module_forward / lp_local_loss_grad / lp_module_backward / lp_local_step / lp_al_multiplier_update is then
+ * bit-identical from run to run (the scalar losses, which are sums of per-workgroup atomics, keep their last-bit
+ * freedom).  Much slower; results equal the default mode's within rounding.  Host only. */
+lp_status lp_net_set_deterministic(struct lp_net* net, int on);
+
+/* Constraint violation of the interfaces (the quantity the convergence figures of Sec. 5 plot beside the loss):
+ * r2 = K-1 device floats or NULL.  While set, every lp_local_loss_grad / lp_local_step overwrites r2[k], for the
+ * selected modules k < K-1, with |F_k(x_k) - x_{k+1}|^2 = sum r^2 (unscaled; it comes out of the same pass and the same
+ * reduction as loss[k]).  The buffer is borrowed until it is reset or the net destroyed.  Host only.  Error:
+ * LP_ERR_INVALID_ARG. */
+lp_status lp_net_set_residual_output(struct lp_net* net, float* r2);
+
 /* The synchronous local step of the selected modules in ONE call (Sec. 4.1: forward, terminal condition of the
  * adjoint, backward recursion with the weight gradients, multiplier update, each module on its own): exactly
  * lp_module_forward, lp_local_loss_grad, lp_module_backward and, when lam != NULL and mult_step != 0,

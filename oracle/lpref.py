@@ -417,6 +417,12 @@ def local_loss_grad(y, x_next, lam, rho, scale=1.0):
     return scale * loss, scale * dy
 
 
+def residual_norm2(y, x_next):
+    """Constraint violation of an interface, |F_k(x_k) - x_{k+1}|^2 (the quantity Sec. 5 plots beside the loss)."""
+    r = _c64(y) - _c64(x_next)
+    return float(np.sum(r * r))
+
+
 def ce_loss_grad(logits, labels):
     """Mini-batch mean of softmax cross-entropy and its gradient w.r.t. the logits."""
     z = _c64(logits)

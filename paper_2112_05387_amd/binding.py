@@ -14,7 +14,7 @@ LP_T_CONV, LP_T_BN_GAMMA, LP_T_BN_BETA, LP_T_FC_W, LP_T_FC_B = 0, 1, 2, 3, 4
 
 EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_tensors", "lp_net_tensor_info",
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_auxnet_forward_static", "lp_module_forward",
-           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step",
+           "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step", "lp_net_set_residual_output", "lp_net_set_deterministic",
            "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
            "lp_debug_module_info", "lp_debug_filter_load_extent",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
@@ -107,6 +107,8 @@ def lib():
         L.lp_local_step.argtypes = [c_void_p, c_void_p, c_uint32, vpp, vpp, vpp, vpp, vpp, c_float, c_float, c_float, c_void_p,
                                     c_void_p, vpp, c_void_p, c_void_p, vpp, vpp]
         L.lp_net_set_stream_lanes.argtypes = [c_void_p, POINTER(c_int)]
+        L.lp_net_set_residual_output.argtypes = [c_void_p, c_void_p]
+        L.lp_net_set_deterministic.argtypes = [c_void_p, c_int]
         L.lp_reauxnet_grad.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, vpp]
         L.lp_sgd_update.argtypes = [c_void_p, c_void_p, c_int, c_uint32, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
         L.lp_aux_variable_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
@@ -252,6 +254,14 @@ def lp_local_step(net, stream, mask, x, params, y, x_next, lam, rho, scale, mult
 def lp_net_set_stream_lanes(net, lanes):
     arr = None if lanes is None else (c_int * len(lanes))(*[int(v) for v in lanes])
     _check(lib().lp_net_set_stream_lanes(net, arr))
+
+
+def lp_net_set_deterministic(net, on):
+    _check(lib().lp_net_set_deterministic(net, int(on)))
+
+
+def lp_net_set_residual_output(net, r2):
+    _check(lib().lp_net_set_residual_output(net, r2))
 
 
 def lp_reauxnet_grad(net, stream, image, aux_params, y_prev, dx, lam_prev, rho, scale, daux_params):

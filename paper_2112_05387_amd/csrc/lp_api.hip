@@ -195,6 +195,8 @@ struct lp_net {
     hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
     bool lanes_ready = false;              // every extra stream and event above exists
     bool keep_gradients = false;           // debug layout: no gradient buffer is reused inside a backward pass
+    bool deterministic = false;            // lp_net_set_deterministic: every reduction in a fixed order
+    float* r2 = nullptr;                   // optional device output [K-1]: |F_k(x_k) - x_{k+1}|^2 per interface (lp_net_set_residual_output)
     size_t scratch_bytes = 0;              // what the AuxNet forward passes need of the library's own device array
     // optional per-launch timing (hipEvents around every grouped launch)
     bool prof = false;
@@ -1343,21 +1345,35 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 // longest tiles first: the blocks of a launch are dispatched in order
                 std::stable_sort(ops.begin() + base, ops.begin() + base + n,
                                  [](const Op* a, const Op* b2) { return a->conv.Kg > b2->conv.Kg; });
+                BnBwdGroup sg; sg.nprob = 0; sg.total_blocks = 0; sg.eps = net->eps; sg.cmax = 0;
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     ConvProb& p = g.p[i]; p = o.conv;
                     p.in = resolve(o.r[0], b); p.wt = resolve(o.r[1], b); p.out = resolve(o.r[2], b);
                     p.add0 = resolve(o.r[3], b); p.add1 = resolve(o.r[4], b); p.stats = (double*)resolve(o.r[5], b);
+                    if (net->deterministic && p.stats) {
+                        // fixed summation order: no per-tile atomics from the epilogue; one workgroup per tensor sums
+                        // the stored result afterwards (a single addition per channel onto the cleared statistics)
+                        BnBwdProb& q = sg.p[sg.nprob]; memset(&q, 0, sizeof(q));
+                        q.y = p.out; q.red = p.stats; q.M = p.M; q.C = p.Ncol;
+                        q.block_start = sg.total_blocks; q.nblocks = 1; sg.total_blocks += 1;
+                        sg.cmax = std::max(sg.cmax, q.C); ++sg.nprob;
+                        p.stats = nullptr;
+                    }
                     p.tiles_m = (p.M + ci.BM - 1) / ci.BM; p.tiles_n = (p.Ncol + ci.BN - 1) / ci.BN;
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
                 err = win ? launch_conv_win(g, cfg, s) : fast ? launch_conv_fast(g, cfg, s) : launch_conv(g, dt, cfg, ops[base]->vec, s);
+                if (err == hipSuccess && sg.nprob) err = launch_bn_stats(sg, dt, s);
             } break;
             case OP_WGRAD: {
                 WgradGroup g; g.nprob = n; int tot = 0;
                 for (int i = 0; i < n; ++i) g.p[i] = ops[base + i]->wg;
-                if (ops[base]->cfg == WGRAD_FAST) plan_wgrad_fast_splits(g);
+                if (net->deterministic) {       // one block per output tile runs through all pixels: no partial sums to add
+                    const int bk = ops[base]->cfg == WGRAD_FAST ? 32 : wgrad_cfg_info(ops[base]->cfg, dt).BK;
+                    for (int i = 0; i < n; ++i) { g.p[i].ksplit = 1; g.p[i].kchunk = (g.p[i].M + bk - 1) / bk * bk; }
+                } else if (ops[base]->cfg == WGRAD_FAST) plan_wgrad_fast_splits(g);
                 for (int i = 0; i < n; ++i) {
                     const Op& o = *ops[base + i];
                     WgradProb& p = g.p[i];
@@ -1380,10 +1396,11 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.gamma = (const float*)resolve(o.r[3], b); p.beta = (const float*)resolve(o.r[4], b);
                     p.skip = resolve(o.r[5], b); p.sstats = (const double*)resolve(o.r[6], b);
                     p.sgamma = (const float*)resolve(o.r[7], b); p.sbeta = (const float*)resolve(o.r[8], b);
-                    p.xn = nullptr; p.lam = nullptr; p.dy = nullptr; p.lam_out = nullptr; p.loss = nullptr;
+                    p.xn = nullptr; p.lam = nullptr; p.dy = nullptr; p.lam_out = nullptr; p.loss = nullptr; p.r2 = nullptr;
                     if (fused_loss) {      // the local loss and terminal adjoint (and the multiplier update) ride on this pass
                         p.xn = resolve(o.r[9], b); p.lam = resolve(o.r[10], b); p.dy = resolve(o.r[11], b);
                         p.loss = (float*)resolve(o.r[12], b);
+                        p.r2 = net->r2 ? net->r2 + (p.loss - b.loss) : nullptr;      // loss + k  ->  r2 + k
                         p.lam_out = b.mstep != 0.f ? const_cast<void*>(p.lam) : nullptr;
                     }
                     p.block_start = tot; p.nblocks = elem_blocks((size_t)p.M * p.C / epv); tot += p.nblocks;
@@ -1405,7 +1422,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.dgamma = (float*)resolve(o.r[7], b); p.dbeta = (float*)resolve(o.r[8], b);
                     p.add = resolve(o.r[9], b);
                     p.block_start = tot;
-                    if (type != OP_BN_BWD_APPLY) p.nblocks = std::max(1, std::min(256, (p.M + 63) / 64));
+                    if (type != OP_BN_BWD_APPLY) p.nblocks = net->deterministic ? 1 : std::max(1, std::min(256, (p.M + 63) / 64));
                     else p.nblocks = elem_blocks((size_t)p.M * p.C / epv);
                     tot += p.nblocks;
                 }
@@ -1422,6 +1439,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     // the multiplier update rides on the pass that has y, x_next and lam in registers anyway
                     p.lam_out = b.mstep != 0.f ? const_cast<void*>(p.lam) : nullptr;
                     p.loss = (float*)resolve(o.r[4], b); p.numel = o.numel;
+                    p.r2 = net->r2 ? net->r2 + (p.loss - b.loss) : nullptr;
                     p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
                 }
                 g.total_blocks = tot;
@@ -1449,6 +1467,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 for (int i = 0; i < n && err == hipSuccess; ++i) {
                     const Op& o = *ops[base + i];
                     HeadProb p = o.head;
+                    p.slice = net->deterministic ? p.N : 0;
                     p.feat = resolve(o.r[0], b); p.pooled = (float*)resolve(o.r[1], b); p.w = (const float*)resolve(o.r[2], b);
                     p.b = (const float*)resolve(o.r[3], b); p.logits = (float*)resolve(o.r[4], b);
                     p.dlogits = (const float*)resolve(o.r[5], b); p.dw = (float*)resolve(o.r[6], b);
@@ -1751,6 +1770,19 @@ lp_status lp_net_set_stream_lanes(struct lp_net* net, const int* lanes) {
     return LP_OK;
 }
 
+lp_status lp_net_set_deterministic(struct lp_net* net, int on) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    net->deterministic = on != 0;
+    return LP_OK;
+}
+
+lp_status lp_net_set_residual_output(struct lp_net* net, float* r2) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (r2 && (reinterpret_cast<uintptr_t>(r2) & 3u)) return fail(LP_ERR_INVALID_ARG, "r2 is not 4-byte aligned");
+    net->r2 = r2;
+    return LP_OK;
+}
+
 lp_status lp_profile_enable(struct lp_net* net, int on) {
     if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
     net->prof = on != 0;
@@ -1911,6 +1943,7 @@ lp_status lp_auxnet_distill_grad(struct lp_net* net, void* stream, const void* i
         mask |= 1u << j;
         LossProb& p = g.p[g.nprob];
         p.y = net->ws + a.ws_out; p.xn = x_target[j]; p.lam = nullptr; p.lam_out = nullptr; p.dy = net->ws + a.ws_g; p.loss = loss + j;
+        p.r2 = nullptr;
         p.numel = a.u.out_elems();
         p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
         if (++g.nprob == kMaxGroup) { groups.push_back(g); g.nprob = 0; g.total_blocks = 0; }
@@ -2015,12 +2048,14 @@ lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_m
     if (want_ce && (!logits || !labels || !dlogits)) return fail(LP_ERR_INVALID_ARG, "logits, labels or dlogits is NULL");
     // loss[k] = 0 for the selected modules (the kernels below accumulate with atomics)
     hipError_t err = launch_zero_selected(loss, module_mask, net->K, s);
+    if (err == hipSuccess && net->r2 && net->K > 1) err = launch_zero_selected(net->r2, module_mask & ((1u << (net->K - 1)) - 1u), net->K - 1, s);
     if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
     for (int k = 0; k < net->K - 1; ++k) {
         if (!((module_mask >> k) & 1u)) continue;
         const ModulePlan& m = net->mods[k];
         LossProb& p = g.p[g.nprob];
         p.y = y[k]; p.xn = x_next[k]; p.lam = (lam ? lam[k] : nullptr); p.lam_out = nullptr; p.dy = dy[k]; p.loss = loss + k;
+        p.r2 = net->r2 ? net->r2 + k : nullptr;
         p.numel = (size_t)m.oN * m.oH * m.oW * m.oC;
         p.block_start = g.total_blocks; p.nblocks = elem_blocks(p.numel / epv); g.total_blocks += p.nblocks;
         if (++g.nprob == kMaxGroup) {
@@ -2101,6 +2136,7 @@ lp_status lp_local_step(struct lp_net* net, void* stream, uint32_t module_mask, 
     hipStream_t s = (hipStream_t)stream;
     // loss[k] = 0 for the selected modules, ahead of the fork (the loss kernels accumulate with atomics)
     hipError_t err = launch_zero_selected(loss, module_mask, net->K, s);
+    if (err == hipSuccess && net->r2 && net->K > 1) err = launch_zero_selected(net->r2, module_mask & ((1u << (net->K - 1)) - 1u), net->K - 1, s);
     if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
     Bindings b; b.ws = net->ws; b.x = x; b.params = params; b.y = y; b.logits = logits;
     b.dparams = dparams; b.dy = dy; b.dx = dx; b.dlogits = dlogits;

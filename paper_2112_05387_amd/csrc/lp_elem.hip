@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
     const T* lam = reinterpret_cast<const T*>(P.lam);
     T* lam_out = reinterpret_cast<T*>(P.lam_out);          // may alias lam: every vector is read before it is written
     T* __restrict__ dyp = reinterpret_cast<T*>(P.dy);
-    float lacc = 0.f;
+    float lacc = 0.f, racc = 0.f;
     for (int i0 = threadIdx.x; i0 < kElemVecsPerBlock; i0 += U * kElemBlock) {
         // Unconditional loads (a vector beyond the end re-reads the last one and is dropped): behind a per-lane branch
         // the compiler waits for each pair of loads before it issues the next.
@@ -175,6 +175,7 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
                     const float r = o[e] - b[e];
                     const float lm = lam ? l[e] : 0.f;
                     lacc += 0.5f * g.rho * r * r + lm * r;
+                    racc += r * r;
                     d[e] = g.scale * (g.rho * r + lm);
                 }
                 Vec<T>::store(dyp + v * EPV, d);
@@ -190,6 +191,10 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
         __shared__ float s_tmp[kElemBlock / 64];
         const float tot = block_sum(lacc, s_tmp);
         if (threadIdx.x == 0 && tot != 0.f) atomicAdd(P.loss, g.scale * tot);
+        if (P.r2) {
+            const float rt = block_sum(racc, s_tmp);
+            if (threadIdx.x == 0 && rt != 0.f) atomicAdd(P.r2, rt);
+        }
     }
 }
 
@@ -435,7 +440,7 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
     T* __restrict__ dy = reinterpret_cast<T*>(P.dy);
     const size_t nvec = P.numel / EPV;
     const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
-    float acc = 0.f;
+    float acc = 0.f, racc = 0.f;
     for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
         const size_t v = base + i;
         if (v >= nvec) break;
@@ -448,6 +453,7 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
             const float r = a[e] - b[e];
             const float lm = lam ? l[e] : 0.f;
             acc += 0.5f * g.rho * r * r + lm * r;
+            racc += r * r;
             o[e] = g.scale * (g.rho * r + lm);
         }
         Vec<T>::store(dy + v * EPV, o);
@@ -459,6 +465,10 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
     }
     const float tot = block_sum(acc, s_tmp);
     if (threadIdx.x == 0 && tot != 0.f) atomicAdd(P.loss, g.scale * tot);
+    if (P.r2) {
+        const float rt = block_sum(racc, s_tmp);
+        if (threadIdx.x == 0 && rt != 0.f) atomicAdd(P.r2, rt);
+    }
 }
 
 template <typename T>
@@ -668,7 +678,8 @@ __global__ void fc_bwd_w_kernel(const HeadProb P) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= P.classes * P.C) return;
     const int j = i / P.C, c = i % P.C;
-    const int n0 = blockIdx.y * 16, n1 = min(P.N, n0 + 16);
+    const int sl = P.slice > 0 ? P.slice : 16;
+    const int n0 = blockIdx.y * sl, n1 = min(P.N, n0 + sl);
     float s = 0.f, sb = 0.f;
 #pragma unroll 16
     for (int n = n0; n < n1; ++n) {
@@ -836,7 +847,8 @@ hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
-    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + 15) / 16), dim3(256), 0, s, p);
+    const int sl = p.slice > 0 ? p.slice : 16;
+    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + sl - 1) / sl), dim3(256), 0, s, p);
     const size_t lds = (size_t)(p.C + p.classes) * sizeof(float);
     if (dtype == 1) hipLaunchKernelGGL(fc_bwd_x_kernel<bf16_t>, dim3(p.N), dim3(256), lds, s, p);
     else hipLaunchKernelGGL(fc_bwd_x_kernel<float>, dim3(p.N), dim3(256), lds, s, p);

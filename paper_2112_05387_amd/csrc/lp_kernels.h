@@ -76,7 +76,7 @@ struct BnApplyProb {
     const void* y; void* out;
     const double* stats; const float* gamma; const float* beta;
     const void* skip; const double* sstats; const float* sgamma; const float* sbeta;
-    const void* xn; const void* lam; void* dy; void* lam_out; float* loss;
+    const void* xn; const void* lam; void* dy; void* lam_out; float* loss; float* r2;
     int M, C, relu, skip_mode;
     int block_start, nblocks;
 };
@@ -110,6 +110,7 @@ struct FillGroup { int nprob, total_blocks; FillProb p[kMaxGroup]; };
 // r = y - x_next;  dy = scale*(rho*r + lam);  loss += scale*(rho/2*sum r^2 + sum lam*r)
 struct LossProb {
     const void* y; const void* xn; const void* lam; void* dy; float* loss;
+    float* r2;               // != NULL: += sum r^2 (the constraint violation |F_k(x_k) - x_{k+1}|^2 of the interface)
     void* lam_out;           // != NULL: lam + step*(y - x_next) is written there (may be lam itself) after dy took the old lam
     size_t numel; int block_start, nblocks;
 };
@@ -136,6 +137,7 @@ struct HeadProb {        // global average pool + linear
     const void* feat; float* pooled; const float* w; const float* b; float* logits;
     const float* dlogits; float* dw; float* db; void* dfeat;
     int N, HW, C, classes;
+    int slice;               // samples per workgroup row of the head's weight gradient (0: 16; N: one partial sum per element)
 };
 
 // ---- launchers (host side; return hipError_t of the launch) ----------------------------------------

@@ -66,6 +66,8 @@ class LocalStep:
         self.dlogits = torch.zeros_like(self.logits)
         self.labels = torch.zeros((self.N,), dtype=torch.int32, device=self.dev)
         self.loss = torch.zeros((self.K,), dtype=torch.float32, device=self.dev)
+        self.r2 = torch.zeros((max(self.K - 1, 1),), dtype=torch.float32, device=self.dev)    # |F_k(x_k) - x_{k+1}|^2
+        B.lp_net_set_residual_output(self.net, self.r2.data_ptr())
 
     def set_stream_lanes(self, lanes):
         """lanes[k] in 0..3 (0 = the caller's stream) or None for a single stream."""

@@ -198,6 +198,8 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
         for k in range(K - 1):
             worst[f"dy{k}"] = rel_err(ls.to_host(ls.dy[k]), lg[k][1])
             worst[f"loss{k}"] = abs(float(ls.loss[k].item()) - lg[k][0]) / max(abs(lg[k][0]), 1e-30)
+            r2 = lpref.residual_norm2(o["y_in"][k], inp["xs"][k + 1])
+            worst[f"r2_{k}"] = abs(float(ls.r2[k].item()) - r2) / max(r2, 1e-30)
         worst[f"loss{K - 1}"] = abs(float(ls.loss[K - 1].item()) - o["ce_loss"]) / abs(o["ce_loss"])
         worst["dlogits"] = rel_err(ls.to_host(ls.dlogits), o["dz"])
         for k in range(K - 1):
@@ -231,6 +233,8 @@ def compare_step(net, scale=1.0, want_dx0=False, tol=None, check_aux=True, lanes
                 loss, dy = lpref.local_loss_grad(y_dev, inp["xs"][k + 1], None if inp["lams"] is None else inp["lams"][k], net.rho, scale)
                 cw[f"fused.dy{k}"] = rel_err(dy_dev, dy)
                 cw[f"fused.loss{k}"] = abs(float(ls.loss[k].item()) - loss) / max(abs(loss), 1e-30)
+                r2 = lpref.residual_norm2(y_dev, inp["xs"][k + 1])
+                cw[f"fused.r2_{k}"] = abs(float(ls.r2[k].item()) - r2) / max(r2, 1e-30)
                 dp, dx = lpref.module_backward(net.modules[k], fwd[k][2], dy=dy_dev, need_dx=need_dx, q=q)
             else:
                 z_dev, dz_dev = ls.to_host(ls.logits), ls.to_host(ls.dlogits)

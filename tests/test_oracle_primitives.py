@@ -281,3 +281,13 @@ def test_maxpool_first_max_and_adjoint():
     e = rng.standard_normal(x.shape)
     fd = (np.sum(lpref.maxpool_fwd(x + h * e)[0] * g) - np.sum(lpref.maxpool_fwd(x - h * e)[0] * g)) / (2 * h)
     assert abs(fd - np.sum(dx * e)) < 1e-6
+
+
+def test_residual_norm_hand_example_and_penalty_relation():
+    """|r|^2 by hand (3-4-12 -> 169), and its relation to the penalty term: with no multiplier loss = rho/2 * |r|^2."""
+    y = np.array([[[[3.0, 1.0]], [[5.0, -2.0]]]])
+    x = np.array([[[[0.0, 1.0]], [[1.0, 10.0]]]])
+    assert lpref.residual_norm2(y, x) == 169.0
+    loss, _ = lpref.local_loss_grad(y, x, None, rho=0.5, scale=2.0)
+    assert abs(loss - 2.0 * 0.25 * 169.0) < 1e-12
+    assert lpref.residual_norm2(x, x) == 0.0
