@@ -291,3 +291,18 @@ def test_residual_norm_hand_example_and_penalty_relation():
     loss, _ = lpref.local_loss_grad(y, x, None, rho=0.5, scale=2.0)
     assert abs(loss - 2.0 * 0.25 * 169.0) < 1e-12
     assert lpref.residual_norm2(x, x) == 0.0
+
+
+def test_c_routines_under_address_and_undefined_behaviour_sanitizers():
+    """The C part of the oracle, compiled with -fsanitize=address,undefined into a self-check executable that runs
+    every routine over small ragged shapes (see oracle/lpref_selfcheck.c): no out-of-bounds access, no undefined
+    behaviour, and the self-check's own comparisons hold."""
+    import os
+    import subprocess
+    from oracle.build import build_selfcheck
+    exe = build_selfcheck()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1", OMP_NUM_THREADS="4")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "0 failure(s)" in r.stdout
+    assert "ERROR" not in r.stderr and "runtime error" not in r.stderr, r.stderr
