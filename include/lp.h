@@ -296,6 +296,27 @@ lp_status lp_aux_variable_update(struct lp_net* net, void* stream, void* const* 
 lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, int S, int stride, int pad,
                                   const int64_t* m, const int64_t* q, int64_t* out, int count);
 
+/* The addresses the convolution kernels form, for bit-exact checks against the index function of the convolution's
+ * definition.  The library builds the same problem descriptor it builds for a layer (mode 0: forward convolution
+ * [N,H,W,Cin] -> Cout, R x R, stride, pad; mode 1: its data-gradient, parity class `parity` = ph*stride + pw of the
+ * output pixels, a GEMM over dY [N,Ho,Wo,Cout] and the re-laid-out filter [Cin][R][R][Cout]) and evaluates, on the
+ * device, the address functions the chosen kernel runs (kernel 0: the general implicit-GEMM kernel; 1: the wide-layer
+ * implicit-GEMM kernel with k-tiles of bk = 32 or 64 channels; 2: the window kernel), one sample per thread:
+ *   in_off[i]  element offset of the activation operand fetched for GEMM element (m[i], q[i]), q = (tr*nts + ts)*C + c
+ *              in the descriptor's own tap numbering, -1 where the kernel substitutes zero padding (the lane/chunk
+ *              swizzles of the direct-to-LDS loads are resolved; -2 would report a broken chunk permutation or a
+ *              fragment read outside the window);
+ *   w_off[i]   element offset of the filter element (row col[i]) that multiplies it;
+ *   out_off[i] element offset of output (m[i], column 0).
+ * lp_debug_conv_geometry (host only) returns what is needed to draw samples and to decode the tap numbering:
+ * geom[12] = {M, Ncol, C, ntr, nts, r0, rs, s0, ss, ldw, BM, bk} (filter tap of (tr, ts): (r0 + rs*tr, s0 + ss*ts)).
+ * Errors: LP_ERR_INVALID_ARG; LP_ERR_SHAPE when the kernel does not take the layer; LP_ERR_HIP. */
+lp_status lp_debug_conv_geometry(int kernel, int mode, int parity, int N, int H, int W, int Cin, int Cout, int R, int stride,
+                                 int pad, int bk, int* geom);
+lp_status lp_debug_conv_offsets(void* stream, int kernel, int mode, int parity, int N, int H, int W, int Cin, int Cout, int R,
+                                int stride, int pad, int bk, const int64_t* m, const int64_t* q, const int64_t* col,
+                                int64_t* in_off, int64_t* w_off, int64_t* out_off, int count);
+
 /* Read-only view of a saved activation after lp_module_forward (for layer-wise checks): which = 0 output of
  * the stem, 1 + 8*block + {0,1,2: pre-BN conv output of slot, 3: projection conv output, 4: block output}. */
 lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, const void** ptr, size_t* numel);

@@ -16,7 +16,7 @@ EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_auxnet_forward_static", "lp_module_forward",
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step", "lp_net_set_residual_output", "lp_net_set_deterministic",
            "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
-           "lp_debug_module_info", "lp_debug_filter_load_extent",
+           "lp_debug_module_info", "lp_debug_filter_load_extent", "lp_debug_conv_geometry", "lp_debug_conv_offsets",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
@@ -114,6 +114,8 @@ def lib():
         L.lp_aux_variable_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
         L.lp_debug_im2col_offsets.argtypes = [c_void_p] + [c_int] * 7 + [c_void_p, c_void_p, c_void_p, c_int]
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
+        L.lp_debug_conv_geometry.argtypes = [c_int] * 12 + [POINTER(c_int)]
+        L.lp_debug_conv_offsets.argtypes = [c_void_p] + [c_int] * 12 + [c_void_p] * 6 + [c_int]
         L.lp_debug_keep_gradients.argtypes = [c_int]
         L.lp_debug_unit_count.argtypes = [c_void_p, c_int, POINTER(c_int)]
         L.lp_debug_unit_info.argtypes = [c_void_p, c_int, c_int, POINTER(lp_debug_unit)]
@@ -293,6 +295,18 @@ def lp_debug_saved_tensor(net, k, which):
     p, n = c_void_p(), c_size_t()
     _check(lib().lp_debug_saved_tensor(net, k, which, ctypes.byref(p), ctypes.byref(n)))
     return p.value, n.value
+
+
+def lp_debug_conv_geometry(kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk):
+    g = (c_int * 12)()
+    _check(lib().lp_debug_conv_geometry(kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk, g))
+    return dict(zip(("M", "Ncol", "C", "ntr", "nts", "r0", "rs", "s0", "ss", "ldw", "BM", "bk"), list(g)))
+
+
+def lp_debug_conv_offsets(stream, kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk, m, q, col, in_off, w_off,
+                          out_off, count):
+    _check(lib().lp_debug_conv_offsets(stream, kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk, m, q, col,
+                                       in_off, w_off, out_off, count))
 
 
 def lp_debug_keep_gradients(on):

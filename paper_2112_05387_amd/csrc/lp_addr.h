@@ -47,5 +47,85 @@ LP_HD int filter_kvg(int bk, int lane, int wave) {
     return bk == 32 ? ((lane & 3) ^ ((lane >> 4) & 3)) : ((lane & 7) ^ (4 * (wave & 1) + (lane >> 4)));
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------
+// Activation (A operand) addresses.  GEMM row m is output pixel (n, a, b) of the row grid [N][OA][OB]; tap (tr, ts)
+// reads input pixel (a*imul + dh0 + dhs*tr, b*imul + dw0 + dws*ts) of image n, zero outside the image.
+// ---------------------------------------------------------------------------------------------------------------
+struct RowGeom { int pix, ih0, iw0; };      // n*IH*IW, and the input coordinate tap (0, 0) reads
+LP_HD RowGeom row_geom(const ConvProb& P, int m) {
+    const int per = P.OA * P.OB;
+    const int n = m / per, rem = m - n * per;
+    const int a = rem / P.OB, b = rem - a * P.OB;
+    RowGeom g;
+    g.pix = n * P.IH * P.IW; g.ih0 = a * P.imul + P.dh0; g.iw0 = b * P.imul + P.dw0;
+    return g;
+}
+LP_HD bool tap_inside(const ConvProb& P, const RowGeom& g, int tr, int ts, int& ih, int& iw) {
+    ih = g.ih0 + P.dhs * tr; iw = g.iw0 + P.dws * ts;
+    return (unsigned)ih < (unsigned)P.IH && (unsigned)iw < (unsigned)P.IW;
+}
+// general kernel: element offset of channel ci of input pixel (ih, iw)
+LP_HD size_t elem_offset(const ConvProb& P, const RowGeom& g, int ih, int iw, int ci) {
+    return (size_t)(g.pix + ih * P.IW + iw) * P.Cin + ci;
+}
+// output element offset of GEMM row m, column 0 (shared by every forward / data-gradient kernel)
+LP_HD int out_row_offset(const ConvProb& P, int m) {
+    const int per = P.OA * P.OB;
+    const int n = m / per, rem = m - n * per;
+    const int a = rem / P.OB, b = rem - a * P.OB;
+    return ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
+}
+
+// implicit-GEMM wide-layer kernel: per-lane byte offset of (row m, tap (0,0), chunk kvg), the bit mask of the taps that
+// fall inside the image, and the wave-uniform byte offset of (tap, channel slab); a load is base + tap offset when
+// the tap's bit is set, kOOB otherwise
+LP_HD int fast_row_base(const ConvProb& P, const RowGeom& g, int kvg) {
+    return ((g.pix + g.ih0 * P.IW + g.iw0) * P.Cin + kvg * 8) * 2;
+}
+LP_HD unsigned fast_row_mask(const ConvProb& P, const RowGeom& g) {
+    unsigned mk = 0u;
+    for (int tr = 0; tr < P.ntr; ++tr)
+        for (int ts = 0; ts < P.nts; ++ts) {
+            int ih, iw;
+            if (tap_inside(P, g, tr, ts, ih, iw)) mk |= 1u << (tr * P.nts + ts);
+        }
+    return mk;
+}
+LP_HD int fast_tap_offset(const ConvProb& P, int tr, int ts, int ci0) {
+    return ((P.dhs * tr * P.IW + P.dws * ts) * P.Cin + ci0) * 2;
+}
+
+// window kernel: the tile's window is nseg segments (one per image, or one band of an image) of (SH + 2) x (W + 2)
+// pixels; window pixel wp of the tile that starts at GEMM row m0 is fetched from the byte offset below (chunk lc of
+// the 64-channel slab that starts at channel 0; kOOB-like 0xffffffff: padding; bit 31: upper half of a slab)
+struct WinGeom { int H, W, per, TH, SH, nseg, WW, SEGP, NP; };
+LP_HD WinGeom win_geom(const ConvProb& P, int BM) {
+    WinGeom w;
+    w.H = P.OA; w.W = P.OB; w.per = w.H * w.W;
+    w.TH = BM / w.W; w.SH = w.TH < w.H ? w.TH : w.H; w.nseg = w.TH / w.SH;
+    w.WW = w.W + 2; w.SEGP = (w.SH + 2) * w.WW; w.NP = w.nseg * w.SEGP;
+    return w;
+}
+LP_HD unsigned win_slot_offset(const ConvProb& P, const WinGeom& w, int m0, int wp, int lc, int cpr) {
+    if (wp >= w.NP) return 0xffffffffu;
+    const int nimg = P.M / w.per;
+    const int sg = wp / w.SEGP, rem = wp - sg * w.SEGP;
+    const int wr = rem / w.WW, wc = rem - wr * w.WW;
+    const int gr = m0 / w.W + sg * w.SH;                 // first image row of the segment, counted over all images
+    const int n = gr / w.H, h0 = gr - n * w.H;
+    const int ih = h0 + wr - 1, iw = wc - 1;
+    if (!(n < nimg && (unsigned)ih < (unsigned)w.H && (unsigned)iw < (unsigned)w.W)) return 0xffffffffu;
+    unsigned ab = (unsigned)((((n * w.H + ih) * w.W + iw) * P.Cin + lc * 8) * 2);
+    if (lc >= cpr / 2) ab |= 0x80000000u;                // upper half: absent from a half slab
+    return ab;
+}
+// window row (in pixels) that output pixel p of the tile reads at tap (tr, ts)
+LP_HD int win_frag_row(const ConvProb& P, const WinGeom& w, int p, int tr, int ts) {
+    const int hh_all = p / w.W, x = p - hh_all * w.W;
+    const int sg = hh_all / w.SH, hh = hh_all - sg * w.SH;
+    return sg * w.SEGP + hh * w.WW + x + (1 + P.dh0 + P.dhs * tr) * w.WW + (1 + P.dw0 + P.dws * ts);
+}
+
 }  // namespace addr
 }  // namespace lp

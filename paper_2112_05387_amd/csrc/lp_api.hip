@@ -2258,7 +2258,67 @@ lp_status lp_debug_im2col_offsets(void* stream, int H, int W, int Cin, int R, in
                                   const int64_t* m, const int64_t* q, int64_t* out, int count) {
     if (!m || !q || !out || count < 0) return fail(LP_ERR_INVALID_ARG, "NULL argument or negative count");
     if (H < 1 || W < 1 || Cin < 1 || R < 1 || S < 1 || stride < 1 || pad < 0) return fail(LP_ERR_INVALID_ARG, "bad geometry");
-    const hipError_t err = launch_im2col_offsets(H, W, Cin, R, S, stride, pad, m, q, out, count, (hipStream_t)stream);
+    if (R != S) return fail(LP_ERR_INVALID_ARG, "square filters only");
+    lp_net tmp; tmp.dtype = LP_F32;
+    Builder B{&tmp};
+    const Unit u = make_unit(R, Cin, 8, stride, pad, 1, H, W, false);           // the row index alone fixes the image
+    const Op o = B.conv_fwd(u, Ref(), Ref(), Ref(), Ref());
+    const hipError_t err = launch_im2col_offsets(o.conv, m, q, out, count, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    return LP_OK;
+}
+
+// the descriptor the library builds for a forward convolution or one parity class of its data-gradient, and the tile
+// shape of the kernel asked for
+static lp_status debug_conv_prob(int kernel, int mode, int parity, int N, int H, int W, int Cin, int Cout, int R, int stride,
+                                 int pad, ConvProb& P, int& BM, int& bk, int& nw) {
+    if (kernel < 0 || kernel > 2 || (mode != 0 && mode != 1)) return fail(LP_ERR_INVALID_ARG, "kernel %d / mode %d", kernel, mode);
+    if (N < 1 || H < 1 || W < 1 || Cin < 1 || Cout < 1 || R < 1 || stride < 1 || pad < 0) return fail(LP_ERR_INVALID_ARG, "bad geometry");
+    if (parity < 0 || parity >= stride * stride) return fail(LP_ERR_INVALID_ARG, "parity class %d of a stride-%d data-gradient", parity, stride);
+    lp_net tmp; tmp.dtype = LP_BF16;
+    Builder B{&tmp};
+    Unit u = make_unit(R, Cin, Cout, stride, pad, N, H, W, false);
+    Op o;
+    if (mode == 0) o = B.conv_fwd(u, Ref(), Ref(), Ref(), Ref());
+    else {
+        if (H % stride || W % stride) return fail(LP_ERR_SHAPE, "%dx%d not divisible by the stride", H, W);
+        Step st;
+        B.conv_dgrad(u, Ref(), Ref(), Ref(), Ref(), Ref(), st);
+        o = st[parity];
+    }
+    P = o.conv;
+    BM = 128; bk = bk == 64 ? 64 : 32; nw = 8;
+    int cfg = 0;
+    if (kernel == 1) {
+        if (!pick_fast_cfg(&tmp, P, cfg)) return fail(LP_ERR_SHAPE, "the implicit-GEMM wide-layer kernel does not take this layer");
+        if (P.Cin % bk) return fail(LP_ERR_SHAPE, "k-tiles of %d channels do not divide %d", bk, P.Cin);
+        BM = cfg == FAST_256x320 ? 256 : 512;
+    } else if (kernel == 2) {
+        if (!pick_win_cfg(&tmp, P, cfg)) return fail(LP_ERR_SHAPE, "the window kernel does not take this layer");
+        BM = cfg == WIN64_256x320 ? 256 : 512; bk = 64;
+    }
+    return LP_OK;
+}
+
+lp_status lp_debug_conv_geometry(int kernel, int mode, int parity, int N, int H, int W, int Cin, int Cout, int R, int stride,
+                                 int pad, int bk, int* geom) {
+    if (!geom) return fail(LP_ERR_INVALID_ARG, "geom is NULL");
+    ConvProb P; int BM, nw;
+    const lp_status st = debug_conv_prob(kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, P, BM, bk, nw);
+    if (st != LP_OK) return st;
+    const int g[12] = {P.M, P.Ncol, P.Cin, P.ntr, P.nts, P.r0, P.rs, P.s0, P.ss, P.ldw, BM, bk};
+    memcpy(geom, g, sizeof(g));
+    return LP_OK;
+}
+
+lp_status lp_debug_conv_offsets(void* stream, int kernel, int mode, int parity, int N, int H, int W, int Cin, int Cout, int R,
+                                int stride, int pad, int bk, const int64_t* m, const int64_t* q, const int64_t* col,
+                                int64_t* in_off, int64_t* w_off, int64_t* out_off, int count) {
+    if (!m || !q || !col || !in_off || !w_off || !out_off || count < 0) return fail(LP_ERR_INVALID_ARG, "NULL argument or negative count");
+    ConvProb P; int BM, nw;
+    const lp_status st = debug_conv_prob(kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, P, BM, bk, nw);
+    if (st != LP_OK) return st;
+    const hipError_t err = launch_conv_offsets(P, kernel, BM, bk, nw, m, q, col, in_off, w_off, out_off, count, (hipStream_t)stream);
     if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
     return LP_OK;
 }

@@ -6,6 +6,7 @@
 // update (Sec. 4.1) and the convolutions inside F of the feature-flow equation; a dense contraction, so
 // they run on the matrix cores: operands are staged through LDS as [row][k] tiles (k contiguous, padded
 // pitch), read as 16-byte MFMA fragments, accumulated in fp32.
+#include "lp_addr.h"
 #include "lp_kernels.h"
 #include "lp_mma.h"
 
@@ -50,33 +51,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     // ---- per-row output offsets (also used by the epilogue) ---------------------------------------
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
-        int off = -1;
-        if (m < M) {
-            const int per = P.OA * P.OB;
-            const int n = m / per, rem = m - n * per;
-            const int a = rem / P.OB, b = rem - a * P.OB;
-            off = ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
-        }
-        s_rowoff[r] = off;
+        s_rowoff[r] = m < M ? addr::out_row_offset(P, m) : -1;
     }
 
     // ---- per-thread gather state ---------------------------------------------------------------
     const int kv = tid % VPR;                // this thread's 16-byte k-chunk inside a k-tile
-    int a_pix[A_PER_T], a_ih[A_PER_T], a_iw[A_PER_T];
+    addr::RowGeom a_g[A_PER_T];
 #pragma unroll
     for (int i = 0; i < A_PER_T; ++i) {
         const int v = tid + i * NT;
         const int row = v / VPR;
         const int m = m0 + row;
-        a_pix[i] = 0; a_ih[i] = -(1 << 28); a_iw[i] = 0;
-        if (v < A_VECS && m < M) {
-            const int per = P.OA * P.OB;
-            const int n = m / per, rem = m - n * per;
-            const int a = rem / P.OB, b = rem - a * P.OB;
-            a_pix[i] = n * IH * IW;
-            a_ih[i] = a * P.imul + P.dh0;
-            a_iw[i] = b * P.imul + P.dw0;
-        }
+        a_g[i].pix = 0; a_g[i].ih0 = -(1 << 28); a_g[i].iw0 = 0;       // a row that is not there: every tap outside
+        if (v < A_VECS && m < M) a_g[i] = addr::row_geom(P, m);
     }
     int b_off[B_PER_T];
 #pragma unroll
@@ -99,14 +86,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     auto load_tile = [&](int k0) {
         if constexpr (VEC) {
             const bool kok = tr < ntr;
-            const int dh = P.dhs * tr, dw = P.dws * ts;
             const int wk = ((P.r0 + P.rs * tr) * P.S + (P.s0 + P.ss * ts)) * Cin + ci;
 #pragma unroll
             for (int i = 0; i < A_PER_T; ++i) {
-                const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+                int ih, iw;
                 u32x4 v = {0u, 0u, 0u, 0u};
-                if (kok && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
-                    v = *reinterpret_cast<const u32x4*>(in + ((size_t)(a_pix[i] + ih * IW + iw) * Cin + ci));
+                if (addr::tap_inside(P, a_g[i], tr, ts, ih, iw) && kok)
+                    v = *reinterpret_cast<const u32x4*>(in + addr::elem_offset(P, a_g[i], ih, iw, ci));
                 a_reg[i] = v;
             }
 #pragma unroll
@@ -130,14 +116,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
                 const int tap = q / Cin, c = q - tap * Cin;
                 const int r = tap / nts, s = tap - r * nts;
                 const bool kok = q < P.Kg;
-                const int dh = P.dhs * r, dw = P.dws * s;
                 const int wk = ((P.r0 + P.rs * r) * P.S + (P.s0 + P.ss * s)) * Cin + c;
 #pragma unroll
                 for (int i = 0; i < A_PER_T; ++i) {
-                    const int ih = a_ih[i] + dh, iw = a_iw[i] + dw;
+                    int ih, iw;
                     T v = from_float<T>(0.f);
-                    if (kok && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
-                        v = in[(size_t)(a_pix[i] + ih * IW + iw) * Cin + c];
+                    if (addr::tap_inside(P, a_g[i], r, s, ih, iw) && kok)
+                        v = in[addr::elem_offset(P, a_g[i], ih, iw, c)];
                     av[i][e] = v;
                 }
 #pragma unroll
@@ -486,27 +471,66 @@ __global__ void wtrans_kernel(const WtransGroup g) {
 }
 
 // -------------------------------------------------------------------------------------------------
-// the im2col address function of the forward kernel, evaluated with the same integer arithmetic
+// debug kernels: the address functions the convolution kernels use (lp_addr.h), evaluated one sample per thread
 // -------------------------------------------------------------------------------------------------
-__global__ void im2col_offsets_kernel(int H, int W, int Cin, int R, int S, int stride, int pad,
-                                      const int64_t* __restrict__ ms, const int64_t* __restrict__ qs,
+__global__ void im2col_offsets_kernel(const ConvProb P, const int64_t* __restrict__ ms, const int64_t* __restrict__ qs,
                                       int64_t* __restrict__ out, int count) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
-    const int Ho = (H + 2 * pad - R) / stride + 1, Wo = (W + 2 * pad - S) / stride + 1;
-    // row decode as in conv_igemm_kernel (OA = Ho, OB = Wo, imul = stride, dh0 = dw0 = -pad, dhs = dws = 1)
     const int m = (int)ms[i], q = (int)qs[i];
-    const int per = Ho * Wo;
-    const int n = m / per, rem = m - n * per;
-    const int a = rem / Wo, b = rem - a * Wo;
-    const int a_pix = n * H * W, a_ih = a * stride - pad, a_iw = b * stride - pad;
-    const int tap = q / Cin, ci = q - tap * Cin;
-    const int tr = tap / S, ts = tap - tr * S;
-    const int ih = a_ih + tr, iw = a_iw + ts;
+    const int tap = q / P.Cin, ci = q - tap * P.Cin;
+    const int tr = tap / P.nts, ts = tap - tr * P.nts;
+    const addr::RowGeom rg = addr::row_geom(P, m);
+    int ih, iw;
     int64_t o = -1;
-    if (tr < R && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W)
-        o = (int64_t)((size_t)(a_pix + ih * W + iw) * Cin + ci);
+    if (tr < P.ntr && addr::tap_inside(P, rg, tr, ts, ih, iw)) o = (int64_t)addr::elem_offset(P, rg, ih, iw, ci);
     out[i] = o;
+}
+
+// kernel: 0 conv_igemm_kernel, 1 conv_igemm_fast_kernel (tile height BM, k-tiles of bk channels, nw waves),
+// 2 conv_win_kernel (tile height BM, 64-channel slabs).  For GEMM element (m, q = (tr*nts + ts)*Cin + ci) and
+// filter row `col`: in_off = element offset of the activation the kernel's loads fetch for it (-1: zero padding),
+// w_off = element offset of the filter element, out_off = element offset of output (m, column 0).
+__global__ void conv_offsets_kernel(const ConvProb P, int kernel, int BM, int bk, int nw, const int64_t* __restrict__ ms,
+                                    const int64_t* __restrict__ qs, const int64_t* __restrict__ cols,
+                                    int64_t* __restrict__ in_off, int64_t* __restrict__ w_off, int64_t* __restrict__ out_off,
+                                    int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const int m = (int)ms[i], q = (int)qs[i], col = (int)cols[i];
+    const int tap = q / P.Cin, ci = q - tap * P.Cin;
+    const int tr = tap / P.nts, ts = tap - tr * P.nts;
+    const addr::RowGeom rg = addr::row_geom(P, m);
+    int64_t o = -1;
+    if (kernel == 0) {
+        int ih, iw;
+        if (addr::tap_inside(P, rg, tr, ts, ih, iw)) o = (int64_t)addr::elem_offset(P, rg, ih, iw, ci);
+    } else if (kernel == 1) {
+        // the lane of the row's wave-load that fetches the 16-byte chunk holding channel ci of the slab
+        const int rps = 1024 / (bk * 2), cpr = bk * 2 / 16;
+        const int r = m % BM, slab = r / rps, lrow = r % rps, wave = slab % nw;
+        const int ci0 = ci - ci % bk, c8 = (ci % bk) / 8;
+        int found = 0, kvg = -1;
+        for (int x = 0; x < cpr; ++x) {
+            const int k = addr::filter_kvg(bk, lrow * cpr + x, wave);
+            if (k == c8) { ++found; kvg = k; }
+        }
+        if (found != 1) o = -2;                                  // the chunk permutation of a row is broken
+        else if ((addr::fast_row_mask(P, rg) >> (tr * P.nts + ts)) & 1u)
+            o = ((int64_t)addr::fast_row_base(P, rg, kvg) + addr::fast_tap_offset(P, tr, ts, ci0)) / 2 + ci % 8;
+    } else {
+        const addr::WinGeom wg = addr::win_geom(P, BM);
+        const int m0 = m / BM * BM;
+        const int wp = addr::win_frag_row(P, wg, m - m0, tr, ts);        // window pixel the fragment read addresses
+        const int ci0 = ci / 64 * 64, c8 = (ci % 64) / 8;
+        const unsigned ab = addr::win_slot_offset(P, wg, m0, wp, c8, 8);
+        if (wp < 0 || wp >= wg.NP) o = -2;                               // a fragment read outside the window
+        else if (ab != 0xffffffffu) o = ((int64_t)(ab & 0x7fffffffu) + ci0 * 2) / 2 + ci % 8;
+    }
+    in_off[i] = o;
+    const int ci0w = ci - ci % bk;
+    w_off[i] = (int64_t)col * P.ldw + addr::filter_tap_offset(P, tr, ts, ci0w) / 2 + (ci - ci0w);
+    out_off[i] = addr::out_row_offset(P, m);
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -590,11 +614,16 @@ hipError_t launch_wtrans(const WtransGroup& g, int dtype, hipStream_t s) {
     else hipLaunchKernelGGL(wtrans_kernel<float>, dim3(g.total_blocks), dim3(256), 0, s, g);
     return hipGetLastError();
 }
-hipError_t launch_im2col_offsets(int H, int W, int Cin, int R, int S, int stride, int pad,
-                                 const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s) {
+hipError_t launch_im2col_offsets(const ConvProb& p, const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s) {
     if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(im2col_offsets_kernel, dim3((count + 255) / 256), dim3(256), 0, s, H, W, Cin, R, S, stride, pad,
-                       m, q, out, count);
+    hipLaunchKernelGGL(im2col_offsets_kernel, dim3((count + 255) / 256), dim3(256), 0, s, p, m, q, out, count);
+    return hipGetLastError();
+}
+hipError_t launch_conv_offsets(const ConvProb& p, int kernel, int BM, int bk, int nw, const int64_t* m, const int64_t* q,
+                               const int64_t* col, int64_t* in_off, int64_t* w_off, int64_t* out_off, int count, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(conv_offsets_kernel, dim3((count + 255) / 256), dim3(256), 0, s, p, kernel, BM, bk, nw, m, q, col,
+                       in_off, w_off, out_off, count);
     return hipGetLastError();
 }
 

@@ -96,13 +96,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
 
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
-        int off = -1;
-        if (m < M) {
-            const int n = m / per, rem = m - n * per;
-            const int a = rem / P.OB, b = rem - a * P.OB;
-            off = ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
-        }
-        s_rowoff[r] = off;
+        s_rowoff[r] = m < M ? addr::out_row_offset(P, m) : -1;
     }
 
     const __amdgpu_buffer_rsrc_t rsrc_a = make_rsrc(P.in, (unsigned)((size_t)(M / per) * IH * IW * Cin * 2));
@@ -120,17 +114,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
         const int m = m0 + RPS * (wave + NW * i) + lrow;
         a_base[i] = 0; a_mask[i] = 0u;
         if (m < M) {
-            const int n = m / per, rem = m - n * per;
-            const int a = rem / P.OB, b = rem - a * P.OB;
-            const int ih0 = a * P.imul + P.dh0, iw0 = b * P.imul + P.dw0;
-            a_base[i] = (((n * IH + ih0) * IW + iw0) * Cin + kvg * 8) * 2;
-            unsigned mk = 0u;
-            for (int tr = 0; tr < ntr; ++tr)
-                for (int ts = 0; ts < nts; ++ts) {
-                    const int ih = ih0 + P.dhs * tr, iw = iw0 + P.dws * ts;
-                    if ((unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW) mk |= 1u << (tr * nts + ts);
-                }
-            a_mask[i] = mk;
+            const addr::RowGeom rg = addr::row_geom(P, m);
+            a_base[i] = addr::fast_row_base(P, rg, kvg);
+            a_mask[i] = addr::fast_row_mask(P, rg);
         }
     }
     // filter rows at or beyond Ncol (ragged last column tile) are marked out of range per lane, in every round
@@ -151,7 +137,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
     auto tile_begin = [&](int st) {
         t_live = issued < nk;
         t_offb = addr::filter_tap_offset(P, tr, ts, ci0);
-        t_offa = ((P.dhs * tr * IW + P.dws * ts) * Cin + ci0) * 2;
+        t_offa = addr::fast_tap_offset(P, tr, ts, ci0);
         t_bit = tr * nts + ts;
         t_dst = smem + st * STAGE_BYTES + wave * 1024;
         ++issued;

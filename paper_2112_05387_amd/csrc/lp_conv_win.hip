@@ -88,11 +88,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     const int t = blockIdx.x - P.tile_start;
     const int tile_n = t % P.tiles_n, tile_m = t / P.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int M = P.M, Cin = P.Cin, H = P.OA, W = P.OB;
-    const int per = H * W;
+    const int M = P.M, Cin = P.Cin;
     // tile = TH image rows: nseg segments of SH rows, each inside one image; window of a segment: (SH+2) x (W+2) pixels
-    const int TH = BM / W, SH = TH < H ? TH : H, nseg = TH / SH;
-    const int WW = W + 2, SEGP = (SH + 2) * WW, NP = nseg * SEGP;
+    const addr::WinGeom wg = addr::win_geom(P, BM);
+    const int per = wg.per, WW = wg.WW, NP = wg.NP;
     const int nslab = (NP + RPS - 1) / RPS;
     const int win_bytes = nslab * 1024;
     unsigned char* s_b = smem + win_bytes;
@@ -102,13 +101,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
 
     for (int r = tid; r < BM; r += NT) {
         const int m = m0 + r;
-        int off = -1;
-        if (m < M) {
-            const int n = m / per, rem = m - n * per;
-            const int a = rem / P.OB, b = rem - a * P.OB;
-            off = ((n * P.OH + a * P.omul + P.ooh) * P.OW + b * P.omul + P.oow) * P.Ncol;
-        }
-        s_rowoff[r] = off;
+        s_rowoff[r] = m < M ? addr::out_row_offset(P, m) : -1;
     }
 
     const int nimg = M / per;
@@ -117,26 +110,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
 
     // ---- window loads: slab sl = wave + NW*i holds window pixels RPS*sl .. RPS*sl + RPS-1; lane l writes LDS slot
     // (pixel RPS*sl + l/CPR, chunk l%CPR) and fetches global chunk (l%CPR) ^ swizzle(pixel)
-    const int R0 = m0 / W;                            // first image row of the tile, counted over all images
     // (kept in LDS: they are needed once per channel slab, and the registers are needed for the accumulators)
 #pragma unroll 1
     for (int i = 0; i < NSWMAX; ++i) {
         const int wp = (wave + NW * i) * RPS + lane / CPR;
-        unsigned ab = 0xffffffffu;                       // no pixel behind this slot
-        if (wp < NP) {
-            const int sg = wp / SEGP, rem = wp - sg * SEGP;
-            const int wr = rem / WW, wc = rem - wr * WW;
-            const int gr = R0 + sg * SH;
-            const int n = gr / H, h0 = gr - n * H;
-            const int ih = h0 + wr - 1, iw = wc - 1;
-            if (n < nimg && (unsigned)ih < (unsigned)H && (unsigned)iw < (unsigned)W) {
-                const int f = BK == 64 ? ((wp >> 1) & 7) : ((wp >> 2) & 3);
-                const int lc = (lane % CPR) ^ f;             // logical 8-channel chunk of the slab this lane fetches
-                ab = (unsigned)((((n * H + ih) * W + iw) * Cin + lc * 8) * 2);
-                if (lc >= CPR / 2) ab |= 0x80000000u;        // upper half: absent from a half slab
-            }
-        }
-        s_abase[i * NT] = ab;
+        const int f = BK == 64 ? ((wp >> 1) & 7) : ((wp >> 2) & 3);
+        const int lc = (lane % CPR) ^ f;                 // logical 8-channel chunk of the slab this lane fetches
+        s_abase[i * NT] = addr::win_slot_offset(P, wg, m0, wp, lc, CPR);     // 0xffffffff: no pixel behind this slot
     }
     // channel slabs: Cin / BK full ones and, when Cin is an odd multiple of BK/2, a last half slab whose upper
     // chunks are out of range (zeros) and whose upper k-steps are skipped
@@ -197,10 +177,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_win_kernel(const ConvGrou
     int a_row[FM];
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-        const int p = wm * TM + i * MT + lr;
-        const int hh_all = p / W, w = p - hh_all * W;
-        const int sg = hh_all / SH, hh = hh_all - sg * SH;
-        a_row[i] = (sg * SEGP + hh * WW + w + (1 + P.dh0) * WW + (1 + P.dw0)) * ROWB;       // tap (0, 0)
+        a_row[i] = addr::win_frag_row(P, wg, wm * TM + i * MT + lr, 0, 0) * ROWB;             // tap (0, 0)
     }
     const int swb4 = (BK == 32 ? ((lr >> 2) & 3) : ((lr >> 1) & 7)) << 4;
     const int b_rd = (wn * TN + lr) * ROWB;

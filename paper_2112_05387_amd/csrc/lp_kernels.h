@@ -183,8 +183,9 @@ hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s);
 hipError_t launch_ce(const float* logits, const int32_t* labels, float* loss, float* dlogits,
                      int N, int classes, hipStream_t s);
 hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s);
-hipError_t launch_im2col_offsets(int H, int W, int Cin, int R, int S, int stride, int pad,
-                                 const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s);
+hipError_t launch_im2col_offsets(const ConvProb& p, const int64_t* m, const int64_t* q, int64_t* out, int count, hipStream_t s);
+hipError_t launch_conv_offsets(const ConvProb& p, int kernel, int BM, int bk, int nw, const int64_t* m, const int64_t* q,
+                               const int64_t* col, int64_t* in_off, int64_t* w_off, int64_t* out_off, int count, hipStream_t s);
 
 constexpr int kElemBlock = 256;          // threads per workgroup of the elementwise kernels
 constexpr int kElemVecsPerBlock = 2048;  // 16-byte vectors handled by one workgroup

@@ -735,3 +735,81 @@ def test_deterministic_mode_is_bit_identical(which):
     # network amplifies last-bit differences of the statistics through flipped roundings, as between any two valid runs)
     judged = {k: v for k, v in worst.items() if net.dtype == "f32" or k.startswith(("y", "logits", "dlogits", "dy", "lam"))}
     assert all(v <= tol for v in judged.values()), judged
+
+
+ADDRESS_CASES = [
+    # kernel, mode, (N, H, W, Cin, Cout, R, stride, pad), bk
+    (0, 0, (3, 9, 7, 8, 16, 3, 1, 1), 32), (0, 0, (2, 10, 8, 8, 8, 3, 2, 1), 32), (0, 0, (2, 20, 16, 3, 8, 7, 2, 3), 32),
+    (0, 1, (2, 9, 7, 8, 16, 3, 1, 1), 32), (0, 1, (2, 10, 8, 8, 16, 3, 2, 1), 32), (0, 1, (2, 8, 8, 16, 8, 1, 2, 0), 32),
+    (1, 0, (4, 32, 32, 160, 160, 3, 1, 1), 32), (1, 0, (4, 16, 16, 320, 320, 3, 1, 1), 64), (1, 0, (4, 32, 32, 160, 320, 3, 2, 1), 32),
+    (1, 0, (4, 32, 32, 160, 320, 1, 2, 0), 32), (1, 1, (4, 16, 16, 320, 320, 3, 1, 1), 64), (1, 1, (4, 32, 32, 160, 320, 3, 2, 1), 64),
+    (1, 1, (4, 16, 16, 320, 640, 1, 2, 0), 64), (1, 0, (3, 6, 10, 160, 296, 3, 1, 1), 32),
+    (2, 0, (4, 32, 32, 160, 160, 3, 1, 1), 64), (2, 1, (4, 32, 32, 160, 160, 3, 1, 1), 64), (2, 0, (8, 16, 16, 320, 320, 3, 1, 1), 64),
+    (2, 1, (8, 16, 16, 320, 320, 3, 1, 1), 64), (2, 0, (16, 8, 8, 640, 640, 3, 1, 1), 64), (2, 1, (16, 8, 8, 640, 640, 3, 1, 1), 64),
+    (2, 0, (4, 32, 32, 160, 320, 3, 1, 1), 64), (2, 1, (4, 32, 32, 320, 160, 3, 1, 1), 64),
+]
+
+
+@pytest.mark.parametrize("kernel,mode,shape,bk", ADDRESS_CASES)
+def test_conv_addresses_bit_exact(kernel, mode, shape, bk):
+    """The integer work of the convolution kernels that run (general, wide-layer implicit GEMM, window): for sampled
+    GEMM elements the activation offset, the filter offset and the output offset that the kernels' own address
+    functions produce on the device -- lane / chunk swizzles of the direct-to-LDS loads resolved -- equal, bit for bit,
+    what the oracle's index function of the convolution's definition gives.  Forward: directly.  Data-gradient (all
+    parity classes of a strided layer): dX[n,hi,wi,ci] takes dY[n,ho,wo,co] * W[co,r,s,ci] exactly for the (ho,wo)
+    whose forward window reads (hi,wi) at tap (r,s) -- found by brute force with the same index function."""
+    import torch
+    from paper_2112_05387_amd import binding as B
+    N, H, W, Cin, Cout, R, stride, pad = shape
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    n_samples = 1500 if mode == 0 else 400
+    for parity in range(1 if mode == 0 else stride * stride):
+        g = B.lp_debug_conv_geometry(kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk)
+        if g["ntr"] == 0:
+            continue
+        say(f"case addresses kernel {kernel} {'dgrad' if mode else 'fwd'} {shape} parity {parity}: M={g['M']} taps {g['ntr']}x{g['nts']} BM={g['BM']}")
+        ms = wl.uniform_int(5, f"addr_m{parity}", (n_samples,), g["M"]).astype(np.int64)
+        qs = wl.uniform_int(5, f"addr_q{parity}", (n_samples,), g["ntr"] * g["nts"] * g["C"]).astype(np.int64)
+        cols = wl.uniform_int(5, f"addr_c{parity}", (n_samples,), g["Ncol"]).astype(np.int64)
+        # corners: first / last rows and columns of the GEMM, first / last tap and channel
+        ms[:4] = [0, g["M"] - 1, 0, g["M"] - 1]
+        qs[:4] = [0, g["ntr"] * g["nts"] * g["C"] - 1, g["ntr"] * g["nts"] * g["C"] - 1, 0]
+        cols[:4] = [0, g["Ncol"] - 1, 0, g["Ncol"] - 1]
+        t = lambda a: torch.from_numpy(a).to(dev)
+        dm, dq, dc = t(ms), t(qs), t(cols)
+        outs = [torch.empty(n_samples, dtype=torch.int64, device=dev) for _ in range(3)]
+        B.lp_debug_conv_offsets(stream, kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk, dm.data_ptr(), dq.data_ptr(),
+                                dc.data_ptr(), outs[0].data_ptr(), outs[1].data_ptr(), outs[2].data_ptr(), n_samples)
+        torch.cuda.synchronize()
+        in_off, w_off, out_off = (o.cpu().numpy() for o in outs)
+        want_in, want_w, want_out = np.empty_like(in_off), np.empty_like(w_off), np.empty_like(out_off)
+        for i in range(n_samples):
+            m, q, col = int(ms[i]), int(qs[i]), int(cols[i])
+            tap, c = divmod(q, g["C"])
+            tr, ts = divmod(tap, g["nts"])
+            r, s = g["r0"] + g["rs"] * tr, g["s0"] + g["ss"] * ts           # the filter tap the kernel multiplies with
+            if mode == 0:
+                assert (r, s) == (tr, ts)
+                want_in[i] = lpref.im2col_index(m, (r * R + s) * Cin + c, H, W, Cin, R, R, stride, pad)
+                want_w[i] = (col * R * R + r * R + s) * Cin + c             # W[co=col][r][s][ci=c]
+                want_out[i] = m * Cout
+            else:
+                # output pixel of this GEMM row: from the device's own output offset (dX is [N,H,W,Cin], column = ci)
+                pix = int(out_off[i]) // Cin
+                assert int(out_off[i]) % Cin == 0
+                n, rem = divmod(pix, H * W)
+                hi, wi = divmod(rem, W)
+                assert (hi % stride, wi % stride) == divmod(parity, stride)
+                want_out[i] = out_off[i]
+                want_w[i] = ((col * R + r) * R + s) * Cout + c              # re-laid-out filter [ci=col][r][s][co=c]
+                target = ((n * H + hi) * W + wi) * Cin + col
+                hit = [(ho, wo) for ho in range(Ho) for wo in range(Wo)
+                       if lpref.im2col_index((n * Ho + ho) * Wo + wo, (r * R + s) * Cin + col, H, W, Cin, R, R, stride, pad) == target]
+                assert len(hit) <= 1
+                want_in[i] = ((n * Ho + hit[0][0]) * Wo + hit[0][1]) * Cout + c if hit else -1
+        np.testing.assert_array_equal(in_off, want_in)
+        np.testing.assert_array_equal(w_off, want_w)
+        np.testing.assert_array_equal(out_off, want_out)
+        assert mode == 1 or pad == 0 or (want_in < 0).any(), "the sample never touched the padding"
