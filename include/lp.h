@@ -217,7 +217,7 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
  * whose order varies from run to run (last-bit differences).  With on != 0 every such sum has a fixed order: the
  * convolution epilogues emit no statistics and one workgroup per tensor sums the stored result instead; the
  * batch-norm backward sums run in one workgroup per tensor; every filter-gradient tile is reduced over all pixels by
- * one workgroup (no split); the head's weight gradient likewise.  Every activation, adjoint, gradient and multiplier
+ * one workgroup (no split).  Every activation, adjoint, gradient and multiplier
  * of lp_module_forward / lp_local_loss_grad / lp_module_backward / lp_local_step / lp_al_multiplier_update is then
  * bit-identical from run to run (the scalar losses, which are sums of per-workgroup atomics, keep their last-bit
  * freedom).  Much slower; results equal the default mode's within rounding.  Host only. */

@@ -1467,7 +1467,6 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 for (int i = 0; i < n && err == hipSuccess; ++i) {
                     const Op& o = *ops[base + i];
                     HeadProb p = o.head;
-                    p.slice = net->deterministic ? p.N : 0;
                     p.feat = resolve(o.r[0], b); p.pooled = (float*)resolve(o.r[1], b); p.w = (const float*)resolve(o.r[2], b);
                     p.b = (const float*)resolve(o.r[3], b); p.logits = (float*)resolve(o.r[4], b);
                     p.dlogits = (const float*)resolve(o.r[5], b); p.dw = (float*)resolve(o.r[6], b);

@@ -573,45 +573,62 @@ __global__ __launch_bounds__(kElemBlock) void auxvar_kernel(const AuxVarGroup g)
 }
 
 // ------------------------------------------------------------------------------------------------
-// max pooling (first maximum in row-major window order wins)
+// max pooling (first maximum in row-major window order wins); one thread per pixel and 16-byte channel vector
 template <typename T>
-__global__ void maxpool_fwd_kernel(const PoolProb P) {
-    const size_t total = (size_t)P.N * P.Ho * P.Wo * P.C;
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const PoolProb P) {
+    constexpr int EPV = Vec<T>::N;
+    const int cv = P.C / EPV;
+    const size_t total = (size_t)P.N * P.Ho * P.Wo * cv;
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const T* __restrict__ x = reinterpret_cast<const T*>(P.x);
-    const int c = (int)(i % P.C);
-    size_t r = i / P.C;
-    const int wo = (int)(r % P.Wo); r /= P.Wo;
-    const int ho = (int)(r % P.Ho);
-    const int n = (int)(r / P.Ho);
-    float best = 0.f; int bi = -1;
+    const int c0 = (int)(i % cv) * EPV;
+    unsigned r = (unsigned)(i / cv);
+    const int wo = (int)(r % (unsigned)P.Wo); r /= (unsigned)P.Wo;
+    const int ho = (int)(r % (unsigned)P.Ho);
+    const int n = (int)(r / (unsigned)P.Ho);
+    float best[EPV];
+    int bi[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) { best[e] = 0.f; bi[e] = -1; }
     for (int a = 0; a < P.R; ++a) {
         const int hi = ho * P.stride - P.pad + a;
         if (hi < 0 || hi >= P.H) continue;
         for (int b = 0; b < P.R; ++b) {
             const int wi = wo * P.stride - P.pad + b;
             if (wi < 0 || wi >= P.W) continue;
-            const float v = to_float(x[((size_t)(n * P.H + hi) * P.W + wi) * P.C + c]);
-            if (bi < 0 || v > best) { best = v; bi = a * P.R + b; }
+            float v[EPV];
+            Vec<T>::load(x + ((size_t)(n * P.H + hi) * P.W + wi) * P.C + c0, v);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = a * P.R + b; }
         }
     }
-    reinterpret_cast<T*>(P.y)[i] = from_float<T>(best);
-    P.arg[i] = (uint8_t)bi;
+    const size_t o = (size_t)(i / cv) * P.C + c0;
+    Vec<T>::store(reinterpret_cast<T*>(P.y) + o, best);
+    uint8_t arg[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) arg[e] = (uint8_t)bi[e];
+    if constexpr (EPV == 8) *reinterpret_cast<uint2*>(P.arg + o) = *reinterpret_cast<const uint2*>(arg);
+    else *reinterpret_cast<unsigned*>(P.arg + o) = *reinterpret_cast<const unsigned*>(arg);
 }
 
 template <typename T>
-__global__ void maxpool_bwd_kernel(const PoolProb P) {
-    const size_t total = (size_t)P.N * P.H * P.W * P.C;
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const PoolProb P) {
+    constexpr int EPV = Vec<T>::N;
+    const int cv = P.C / EPV;
+    const size_t total = (size_t)P.N * P.H * P.W * cv;
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= total) return;
     const T* __restrict__ dy = reinterpret_cast<const T*>(P.dy);
-    const int c = (int)(i % P.C);
-    size_t r = i / P.C;
-    const int wi = (int)(r % P.W); r /= P.W;
-    const int hi = (int)(r % P.H);
-    const int n = (int)(r / P.H);
-    float acc = 0.f;
+    const int c0 = (int)(i % cv) * EPV;
+    unsigned r = (unsigned)(i / cv);
+    const int wi = (int)(r % (unsigned)P.W); r /= (unsigned)P.W;
+    const int hi = (int)(r % (unsigned)P.H);
+    const int n = (int)(r / (unsigned)P.H);
+    float acc[EPV];
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
     // windows (ho, wo) that contain (hi, wi): ho*stride - pad + a = hi
     for (int a = 0; a < P.R; ++a) {
         const int th = hi + P.pad - a;
@@ -623,11 +640,19 @@ __global__ void maxpool_bwd_kernel(const PoolProb P) {
             if (tw < 0 || tw % P.stride) continue;
             const int wo = tw / P.stride;
             if (wo >= P.Wo) continue;
-            const size_t o = ((size_t)(n * P.Ho + ho) * P.Wo + wo) * P.C + c;
-            if (P.arg[o] == (uint8_t)(a * P.R + b)) acc += to_float(dy[o]);
+            const size_t o = ((size_t)(n * P.Ho + ho) * P.Wo + wo) * P.C + c0;
+            float g[EPV];
+            Vec<T>::load(dy + o, g);
+            uint8_t arg[EPV];
+            if constexpr (EPV == 8) *reinterpret_cast<uint2*>(arg) = *reinterpret_cast<const uint2*>(P.arg + o);
+            else *reinterpret_cast<unsigned*>(arg) = *reinterpret_cast<const unsigned*>(P.arg + o);
+            const uint8_t me = (uint8_t)(a * P.R + b);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e)
+                if (arg[e] == me) acc[e] += g[e];
         }
     }
-    reinterpret_cast<T*>(P.dx)[i] = from_float<T>(acc);
+    Vec<T>::store(reinterpret_cast<T*>(P.dx) + (size_t)(i / cv) * P.C + c0, acc);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -672,60 +697,55 @@ __global__ void fc_fwd_kernel(const HeadProb P) {          // one wave per (n, c
     for (int sh = 32; sh > 0; sh >>= 1) s += __shfl_xor(s, sh, 64);
     if (lane == 0) P.logits[o] = s + P.b[j];
 }
-// dW[j,c] += sum_n dz[n,j]*pooled[n,c]; db[j] += sum_n dz[n,j].  blockIdx.y takes a slice of 16 samples; the
-// gradient buffer was cleared at the start of the backward pass.
+// dW[j,c] = sum_n dz[n,j]*pooled[n,c]; db[j] = sum_n dz[n,j]: one thread per element, the samples in order (no
+// partial sums to combine: pooled and dz stay in cache, the whole pass reads 2*N values per thread)
 __global__ void fc_bwd_w_kernel(const HeadProb P) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= P.classes * P.C) return;
     const int j = i / P.C, c = i % P.C;
-    const int sl = P.slice > 0 ? P.slice : 16;
-    const int n0 = blockIdx.y * sl, n1 = min(P.N, n0 + sl);
     float s = 0.f, sb = 0.f;
-#pragma unroll 16
-    for (int n = n0; n < n1; ++n) {
+#pragma unroll 8
+    for (int n = 0; n < P.N; ++n) {
         const float d = P.dlogits[n * P.classes + j];
         s += d * P.pooled[n * P.C + c];
         sb += d;
     }
-    atomicAdd(&P.dw[i], s);
-    if (c == 0) atomicAdd(&P.db[j], sb);
+    P.dw[i] = s;
+    if (c == 0) P.db[j] = sb;
 }
 // dfeat[n,p,c] = (sum_j dz[n,j]*W[j,c]) / HW
 template <typename T>
 __global__ __launch_bounds__(256) void fc_bwd_x_kernel(const HeadProb P) {
-    // One block per sample: d pooled[c] = sum_j dlogits[j] * w[j][c] once per channel (lanes along c: coalesced rows of
-    // w), then the block broadcasts it, divided by the number of pixels, to every pixel of the sample.
+    // One block per sample and chunk of 256 channels: d pooled[c] = sum_j dlogits[j] * w[j][c] (lanes along c: coalesced
+    // rows of w, summed in the order of the classes), then the block broadcasts it, divided by the number of pixels, to
+    // every pixel of the sample with 16-byte stores.
     constexpr int EPV = Vec<T>::N;
-    extern __shared__ float s_dp[];      // C floats, then the sample's `classes` logit gradients
-    const int n = blockIdx.x, C = P.C, cv = C / EPV, classes = P.classes;
+    extern __shared__ float s_dp[];      // 256 floats, then the sample's `classes` logit gradients
+    const int n = blockIdx.x, cbase = blockIdx.y * 256, C = P.C, classes = P.classes;
+    const int nc = min(256, C - cbase);
     const float inv = 1.f / (float)P.HW;
-    float* s_dl = s_dp + C;
+    float* s_dl = s_dp + 256;
     for (int j = threadIdx.x; j < classes; j += 256) s_dl[j] = P.dlogits[(size_t)n * classes + j];
     __syncthreads();
-    for (int c = threadIdx.x; c < C; c += 256) {
+    if ((int)threadIdx.x < nc) {
+        const int c = cbase + threadIdx.x;
         float acc = 0.f;
         int j = 0;
-        for (; j + 7 < classes; j += 8) {       // eight rows of w in flight; summed in the order of the classes
+        for (; j + 7 < classes; j += 8) {       // eight rows of w in flight
             float w[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) w[u] = P.w[(size_t)(j + u) * C + c];
 #pragma unroll
             for (int u = 0; u < 8; ++u) acc += s_dl[j + u] * w[u];
         }
-        {                                       // the last up to seven classes, loaded together as well
-            float w[8];
-#pragma unroll
-            for (int u = 0; u < 7; ++u) w[u] = P.w[(size_t)min(j + u, classes - 1) * C + c];
-#pragma unroll
-            for (int u = 0; u < 7; ++u)
-                if (j + u < classes) acc += s_dl[j + u] * w[u];
-        }
-        s_dp[c] = acc * inv;
+        for (; j < classes; ++j) acc += s_dl[j] * P.w[(size_t)j * C + c];
+        s_dp[threadIdx.x] = acc * inv;
     }
     __syncthreads();
-    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * C;
-    for (int i = threadIdx.x; i < P.HW * cv; i += 256) {
-        const int p = i / cv, v = i - p * cv;
+    T* __restrict__ d = reinterpret_cast<T*>(P.dfeat) + (size_t)n * P.HW * C + cbase;
+    const int cvn = nc / EPV;
+    for (int i = threadIdx.x; i < P.HW * cvn; i += 256) {
+        const int p = i / cvn, v = i - p * cvn;
         float o[EPV];
 #pragma unroll
         for (int e = 0; e < EPV; ++e) o[e] = s_dp[v * EPV + e];
@@ -831,12 +851,12 @@ hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_maxpool_fwd(const PoolProb& p, int dtype, hipStream_t s) {
-    const size_t total = (size_t)p.N * p.Ho * p.Wo * p.C;
+    const size_t total = (size_t)p.N * p.Ho * p.Wo * (p.C / (dtype == 1 ? 8 : 4));
     LP_DISPATCH_T(dtype, maxpool_fwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, p);
     return hipGetLastError();
 }
 hipError_t launch_maxpool_bwd(const PoolProb& p, int dtype, hipStream_t s) {
-    const size_t total = (size_t)p.N * p.H * p.W * p.C;
+    const size_t total = (size_t)p.N * p.H * p.W * (p.C / (dtype == 1 ? 8 : 4));
     LP_DISPATCH_T(dtype, maxpool_bwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), s, p);
     return hipGetLastError();
 }
@@ -847,11 +867,11 @@ hipError_t launch_head_fwd(const HeadProb& p, int dtype, hipStream_t s) {
     return hipGetLastError();
 }
 hipError_t launch_head_bwd(const HeadProb& p, int dtype, hipStream_t s) {
-    const int sl = p.slice > 0 ? p.slice : 16;
-    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256, (p.N + sl - 1) / sl), dim3(256), 0, s, p);
-    const size_t lds = (size_t)(p.C + p.classes) * sizeof(float);
-    if (dtype == 1) hipLaunchKernelGGL(fc_bwd_x_kernel<bf16_t>, dim3(p.N), dim3(256), lds, s, p);
-    else hipLaunchKernelGGL(fc_bwd_x_kernel<float>, dim3(p.N), dim3(256), lds, s, p);
+    hipLaunchKernelGGL(fc_bwd_w_kernel, dim3((p.classes * p.C + 255) / 256), dim3(256), 0, s, p);
+    const size_t lds = (size_t)(256 + p.classes) * sizeof(float);
+    const dim3 grid(p.N, (p.C + 255) / 256);
+    if (dtype == 1) hipLaunchKernelGGL(fc_bwd_x_kernel<bf16_t>, grid, dim3(256), lds, s, p);
+    else hipLaunchKernelGGL(fc_bwd_x_kernel<float>, grid, dim3(256), lds, s, p);
     return hipGetLastError();
 }
 hipError_t launch_zero_selected(float* v, uint32_t mask, int n, hipStream_t s) {

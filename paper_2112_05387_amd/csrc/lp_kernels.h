@@ -137,7 +137,6 @@ struct HeadProb {        // global average pool + linear
     const void* feat; float* pooled; const float* w; const float* b; float* logits;
     const float* dlogits; float* dw; float* db; void* dfeat;
     int N, HW, C, classes;
-    int slice;               // samples per workgroup row of the head's weight gradient (0: 16; N: one partial sum per element)
 };
 
 // ---- launchers (host side; return hipError_t of the launch) ----------------------------------------
