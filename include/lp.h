@@ -63,13 +63,18 @@ typedef enum { LP_ORDER_POST = 0, LP_ORDER_PRE = 1 } lp_block_order;
 /* Residual block X_{m+1} = skip(X_m) + F(X_m, W_m)  (Sec. 2.1 and the feature flow of Sec. 4.1).
  * basic:      F = conv3x3(stride) - BN - ReLU - conv3x3 - BN
  * bottleneck: F = conv1x1 - BN - ReLU - conv3x3(stride) - BN - ReLU - conv1x1 - BN   (inner width `width`)
- * skip = identity, or conv1x1(stride) - BN when `proj` is set.  There is no ReLU after the sum. */
+ * skip = identity, or conv1x1(stride) - BN when `proj` is set.  As the feature-flow equation writes it there is no
+ * ReLU after the sum.  Two options of the conv-BN-ReLU order (zero keeps the form above; LP_ORDER_PRE refuses them):
+ * proj_plain: the projection is the bare conv1x1(stride), without BN (its parameter set is the filter alone);
+ * post_relu: X_{m+1} = ReLU(skip(X_m) + F(X_m, W_m)), the classic post-activation block. */
 typedef struct {
     int kind;      /* lp_block_kind */
     int cin, cout;
     int width;     /* bottleneck inner width; ignored for basic blocks */
     int stride;    /* 1 or 2 */
     int proj;      /* required when stride != 1 or cin != cout */
+    int proj_plain;
+    int post_relu;
 } lp_block_desc;
 
 /* Module k: [input layer S] + blocks + [output layer T]  (S and T belong to the first and last worker,
@@ -207,7 +212,9 @@ lp_status lp_local_loss_grad(struct lp_net* net, void* stream, uint32_t module_m
  * terminal adjoint dy[k] (k < K-1) or dlogits (k = K-1).  dparams[k]: fp32 gradient buffer of module k
  * (overwritten).  dx[k]: gradient with respect to x_k, written for k >= 1, and for k = 0 only when module 0
  * has no stem and dx[0] != NULL.  Requires lp_module_forward of the same modules since the last backward:
- * otherwise LP_ERR_STATE. */
+ * otherwise LP_ERR_STATE.  Like x[k] and params[k], the y[k] given to that forward call is read again here when the
+ * last block of module k has post_relu (the ReLU behind the sum is masked from the stored output): it must still hold
+ * F_k(x_k). */
 lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_mask,
                              const void* const* dy, const float* dlogits, const void* const* params,
                              float* const* dparams, void* const* dx);
@@ -325,7 +332,8 @@ lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, cons
  * host only).  A unit is one convolution with the batch norm behind it.  Every tensor is named by a reference: the
  * caller's tensor of the last call (x[idx], y[idx], dy[idx], dx[idx]) or a byte offset into the workspace.
  *   forward:   in --conv--> y (pre-BN, stored) ; stats = per-channel [sum, sum of squares] of y (fp64 [2*cout]);
- *              out = [ReLU]( BN(y) [+ skip | + BN(y of unit skip_unit)] ), written by the unit's BN-apply pass
+ *              out = [ReLU]( BN(y) [+ skip | + BN(y of unit skip_unit) | + y of a plain unit skip_unit] ), written by
+ *              the unit's BN-apply pass (ReLU: the unit's own `relu`, or `post_relu` on the last unit of a block)
  *              (the projection unit has none: its BN is applied inside the pass of the block's last unit);
  *   backward:  gout = gradient arriving at the unit's BN output; dy = gradient on y (BN backward, stored);
  *              red = per-channel [sum g', sum g'*yhat] (fp64 [2*cout]); din = the unit's data-gradient
@@ -343,7 +351,10 @@ typedef struct {
     int skip_kind;               /* added inside this unit's BN-apply pass: 0 nothing, 1 the tensor `skip`, 2 BN(y) of unit skip_unit */
     int skip_unit;
     int has_dgrad;
-    lp_debug_ref in, y, stats, out, skip, gout, dy, red, din, din_add;
+    int plain;                   /* a bare projection: no BN (no stats / red / parameters of one; out = none, dy = gout) */
+    int post_relu;               /* the block output is ReLU(sum): `out` carries it, and `gout` is the arriving gradient
+                                    `graw` already masked by out > 0 (a pass of its own at the start of the block's backward) */
+    lp_debug_ref in, y, stats, out, skip, gout, dy, red, din, din_add, graw;
 } lp_debug_unit;
 typedef struct {                 /* what lies around the units: max-pool of stem 2, head of the last module */
     int keep_gradients;
@@ -376,7 +387,7 @@ lp_status lp_debug_filter_load_extent(int kernel, int bk, int bn, int nw, int Nc
  * the list (out == NULL: only the count).  kind: 0 clear, 1 filter re-layout, 2 conv forward/data-gradient,
  * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
  * apply, 10 conv weight-gradient, 11 batch statistics of a module input, 12 loss / terminal adjoint, 13 cross-entropy,
- * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12).  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
+ * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12), 15 gradient mask of a ReLU behind a residual sum.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
  * every operand tensor moved once). */
 typedef struct { int kind, cfg, nprob; float ms; double flops, bytes; } lp_profile_rec;
 lp_status lp_profile_enable(struct lp_net* net, int on);

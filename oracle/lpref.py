@@ -194,7 +194,10 @@ def _cbr_bwd(da, cache, need_dx=True, q=None):
 
 # ----------------------------------------------------------------------------- residual block
 def block_forward(x, p, b: Block, eps, q=None):
-    """X_{m+1} = skip(X_m) + F(X_m, W_m); F = conv-BN-ReLU ... conv-BN (no ReLU after the add)."""
+    """X_{m+1} = skip(X_m) + F(X_m, W_m); F = conv-BN-ReLU ... conv-BN.  As the feature-flow equation of Sec. 4.1 writes
+    it there is no ReLU after the sum; b.post_relu is the variant with one, X_{m+1} = ReLU(skip + F) (the classic
+    post-activation block).  skip = X_m, or BN(conv1x1_stride(X_m)), or the bare conv1x1_stride(X_m) when b.proj_bn
+    is off."""
     qq = q or _id
     convs = block_convs(b)
     main = [c for c in convs if c[0] != 3]
@@ -206,17 +209,25 @@ def block_forward(x, p, b: Block, eps, q=None):
             a = qq(a)                      # activation between two convolutions is stored
         caches.append(c)
         i += 3
-    if b.proj:
+    if b.proj and b.proj_bn:
         _, r, ci, co, st, pad = convs[-1]
         s, pc = _cbr_fwd(x, p[i], p[i + 1], p[i + 2], st, pad, relu=False, eps=eps, q=q)
+    elif b.proj:
+        _, r, ci, co, st, pad = convs[-1]
+        s = qq(conv_fwd(x, p[i], st, pad))                 # the bare projection's result is stored
+        pc = ("plain", x, p[i], st, pad)
     else:
         s, pc = x, None
-    return qq(s + a), (caches, pc)         # the block output is stored
+    pre = s + a
+    out = np.maximum(pre, 0.0) if b.post_relu else pre
+    return qq(out), (caches, pc, pre if b.post_relu else None)         # the block output is stored
 
 
 def block_backward(dout, cache, need_dx=True, q=None):
     qq = q or _id
-    caches, pc = cache
+    caches, pc, pre = cache
+    if pre is not None:
+        dout = dout * (pre > 0.0)          # ReLU behind the sum (its gradient is 0 at exactly 0)
     grads = []
     da = dout
     for j in range(len(caches) - 1, -1, -1):
@@ -225,7 +236,12 @@ def block_backward(dout, cache, need_dx=True, q=None):
             da = qq(da)                    # gradient of a stored activation is stored
         grads = g + grads
     dx = da
-    if pc is not None:
+    if pc is not None and isinstance(pc[0], str):          # bare projection: no BN between the sum and the conv1x1
+        _, px, pw, pst, ppad = pc
+        grads = grads + [conv_wgrad(px, dout, pw.shape, pst, ppad)]
+        if need_dx:
+            dx = qq(dx + qq(conv_dgrad(dout, pw, px.shape, pst, ppad)))
+    elif pc is not None:
         dxp, g = _cbr_bwd(dout, pc, need_dx=need_dx, q=q)
         grads = grads + g
         if need_dx:
@@ -358,7 +374,7 @@ def module_forward(m: ModuleDesc, x, params, eps=1e-5, q=None):
         cache["stem"] = (c, (idx, pre_shape))
         i = 3
     for b in m.blocks:
-        n = 3 * len(block_convs(b))
+        n = 3 * len(block_convs(b)) - (2 if (b.proj and not b.proj_bn) else 0)
         a, c = block_forward(a, p[i:i + n], b, eps, q)
         cache["blocks"].append(c)
         i += n

@@ -20,11 +20,13 @@ EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
-              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats", 12: "loss", 13: "cross_entropy", 14: "multiplier_update"}
+              6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats", 12: "loss", 13: "cross_entropy", 14: "multiplier_update",
+              15: "relu_mask"}
 
 
 class lp_block_desc(ctypes.Structure):
-    _fields_ = [("kind", c_int), ("cin", c_int), ("cout", c_int), ("width", c_int), ("stride", c_int), ("proj", c_int)]
+    _fields_ = [("kind", c_int), ("cin", c_int), ("cout", c_int), ("width", c_int), ("stride", c_int), ("proj", c_int),
+                ("proj_plain", c_int), ("post_relu", c_int)]
 
 
 class lp_module_desc(ctypes.Structure):
@@ -56,8 +58,8 @@ class lp_debug_ref(ctypes.Structure):
 
 class lp_debug_unit(ctypes.Structure):
     _fields_ = [(n, c_int) for n in ("block", "slot", "R", "stride", "pad", "cin", "cout", "N", "H", "W", "Ho", "Wo", "relu",
-                                     "t_w", "t_gamma", "t_beta", "skip_kind", "skip_unit", "has_dgrad")] + \
-               [(n, lp_debug_ref) for n in ("in_", "y", "stats", "out", "skip", "gout", "dy", "red", "din", "din_add")]
+                                     "t_w", "t_gamma", "t_beta", "skip_kind", "skip_unit", "has_dgrad", "plain", "post_relu")] + \
+               [(n, lp_debug_ref) for n in ("in_", "y", "stats", "out", "skip", "gout", "dy", "red", "din", "din_add", "graw")]
 
 
 class lp_debug_module(ctypes.Structure):
@@ -165,7 +167,8 @@ def lp_net_create(modules, aux, dtype, bn_eps):
         blks = (lp_block_desc * max(nb, 1))()
         for i, b in enumerate(m.blocks):
             kind = b.kind if isinstance(b.kind, int) else {"basic": 0, "bottleneck": 1}[b.kind]
-            blks[i] = lp_block_desc(kind, b.cin, b.cout, b.width, b.stride, int(b.proj))
+            blks[i] = lp_block_desc(kind, b.cin, b.cout, b.width, b.stride, int(b.proj),
+                                    int(not getattr(b, "proj_bn", True)), int(getattr(b, "post_relu", False)))
         keep.append(blks)
         mods[k] = lp_module_desc(int(m.stem), int(m.stem_cout), nb, blks, int(m.head), int(m.n_classes), m.N, m.H, m.W, m.C,
                                  {"post": LP_ORDER_POST, "pre": LP_ORDER_PRE}[getattr(m, "order", "post")])

@@ -94,7 +94,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
 }
 
 enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
-              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE };
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE, OP_MULT_UNUSED, OP_RELU_MASK };
 
 struct Op {
     int type = 0, cfg = 0;
@@ -128,6 +128,9 @@ struct Unit {
 struct BlockPlan {
     std::vector<Unit> main;                // 2 (basic) or 3 (bottleneck)
     bool has_proj = false;
+    bool proj_plain = false, post_relu = false;   // options of the conv-BN-ReLU order: bare conv1x1 projection, ReLU behind the sum
+    size_t ws_gmask = 0;                   // post_relu: the arriving gradient masked by (block output > 0)
+    Ref graw_ref;                          // ... and the unmasked one
     Unit proj;
     std::vector<size_t> ws_act;            // activations between main convs
     Ref in, out;                           // block input / output tensors
@@ -189,6 +192,7 @@ struct lp_net {
     uint32_t fwd_done = 0;
     bool aux_fwd_done = false;
     std::vector<const void*> saved_x;
+    std::vector<void*> saved_y;            // y[k] of the last forward call (a ReLU behind the last block's sum is masked from it)
     // optional second stream: modules in side_mask are issued there, concurrently with the others
     std::vector<int> lane;                 // per module: 0 = the caller's stream, 1..3 = extra stream
     hipStream_t extra_stream[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -494,10 +498,15 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             bp.main.push_back(make_unit(1, b.width, b.cout, 1, 0, N, H / b.stride, W / b.stride, false));
         }
         for (size_t j = 0; j < bp.main.size(); ++j) add_unit_tensors(m.tensors, poff, goff, bp.main[j], i, (int)j, dt);
+        bp.post_relu = b.post_relu != 0;
         if (b.proj) {
             bp.has_proj = true;
+            bp.proj_plain = b.proj_plain != 0;
             bp.proj = make_unit(1, b.cin, b.cout, b.stride, 0, N, H, W, false);
-            add_unit_tensors(m.tensors, poff, goff, bp.proj, i, 3, dt);
+            if (bp.proj_plain) {
+                bp.proj.t_w = (int)m.tensors.size();
+                add_tensor(m.tensors, poff, goff, LP_T_CONV, i, 3, dt, {b.cout, 1, 1, b.cin});
+            } else add_unit_tensors(m.tensors, poff, goff, bp.proj, i, 3, dt);
         }
         bp.in_elems = (size_t)N * H * W * C;
         H /= b.stride; W /= b.stride; C = b.cout;
@@ -585,6 +594,12 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
         for (size_t j = 0; j + 1 < bp.main.size(); ++j)
             bp.ws_gact.push_back(keep ? ws.take(bp.main[j].out_elems() * esz) : m.ws_A);
     }
+    {   // ReLU behind the sum: one buffer for the masked gradient (per block when every gradient is kept)
+        size_t maxO = 0, shared = 0;
+        for (auto& bp : m.bp) if (bp.post_relu) maxO = std::max(maxO, bp.out_elems);
+        if (maxO && !net->keep_gradients) shared = ws.take(maxO * esz);
+        for (auto& bp : m.bp) if (bp.post_relu) bp.ws_gmask = net->keep_gradients ? ws.take(bp.out_elems * esz) : shared;
+    }
     if (last) {
         m.ws_pooled = ws.take((size_t)N * C * 4);
         m.ws_dfeat = ws.take((size_t)N * H * W * C * esz);
@@ -621,18 +636,20 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
         for (size_t j = 0; j < bp.main.size(); ++j) {
             const Unit& u = bp.main[j];
             Step s{B.conv_fwd(u, cur, wref(u), yref(u), stats(u))};
-            if (j == 0 && bp.has_proj) s.push_back(B.conv_fwd(bp.proj, bp.in, wref(bp.proj), yref(bp.proj), stats(bp.proj)));
+            if (j == 0 && bp.has_proj)
+                s.push_back(B.conv_fwd(bp.proj, bp.in, wref(bp.proj), yref(bp.proj), bp.proj_plain ? Ref() : stats(bp.proj)));
             F.push_back(s);
             if (j + 1 < bp.main.size()) {
                 Ref a = mk(SP_WS, 0, bp.ws_act[j]);
                 F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), a, stats(u), gref(u), bref(u), true)});
                 cur = a;
-            } else if (bp.has_proj) {
+            } else if (bp.has_proj && !bp.proj_plain) {
                 const Unit& p = bp.proj;
-                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), false, 2, yref(p),
+                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), bp.post_relu, 2, yref(p),
                                             stats(p), gref(p), bref(p))});
-            } else {
-                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), false, 1, bp.in)});
+            } else {      // identity skip, or the bare projection's result
+                F.push_back(Step{B.bn_apply(Mof(u), u.cout, yref(u), bp.out, stats(u), gref(u), bref(u), bp.post_relu, 1,
+                                            bp.has_proj ? yref(bp.proj) : bp.in)});
             }
         }
     }
@@ -685,18 +702,25 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
             if (i == 0 && !m.has_stem) gin = mk(SP_DX, k, 0);
             else gin = mk(SP_WS, 0, bp.ws_gin);
             const Ref Pp = mk(SP_WS, 0, bp.ws_gproj);
+            bp.graw_ref = g;
+            if (bp.post_relu) {                     // through the ReLU behind the sum: everything below sees the masked gradient
+                Op o; o.type = OP_RELU_MASK; o.numel = bp.out_elems;
+                o.r[0] = g; o.r[1] = bp.out; o.r[2] = mk(SP_WS, 0, bp.ws_gmask);
+                Bw.push_back(Step{o});
+                g = o.r[2];
+            }
             bp.gin_ref = gin; bp.g_ref = g;
             const int nm = (int)bp.main.size();
             Ref gcur = g;                           // gradient arriving at the BN output of unit j
             for (int j = nm - 1; j >= 0; --j) {
                 const Unit& u = bp.main[j];
                 const bool lastu = (j == nm - 1);
-                const Ref Dm = dyref(u), Dp = bp.has_proj ? dyref(bp.proj) : Ref();
+                const Ref Dm = dyref(u), Dp = !bp.has_proj ? Ref() : bp.proj_plain ? g : dyref(bp.proj);   // bare projection: no BN to go through
                 Step s1{B.bn_bwd(OP_BN_BWD_REDUCE, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
                                  grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), u.relu)};
                 Step s2{B.bn_bwd(OP_BN_BWD_APPLY, Mof(u), u.cout, gcur, yref(u), Dm, stats(u), gref(u), bref(u), redr(u),
                                  grad_ref(m, k, u.t_g), grad_ref(m, k, u.t_b), u.relu)};
-                if (lastu && bp.has_proj) {
+                if (lastu && bp.has_proj && !bp.proj_plain) {
                     const Unit& p = bp.proj;
                     s1.push_back(B.bn_bwd(OP_BN_BWD_REDUCE, Mof(p), p.cout, g, yref(p), Dp, stats(p), gref(p), bref(p), redr(p),
                                           grad_ref(m, k, p.t_g), grad_ref(m, k, p.t_b), false));
@@ -710,7 +734,10 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
                 const Ref uin = (j == 0) ? bp.in : mk(SP_WS, 0, bp.ws_act[j - 1]);
                 wg_tail.push_back(B.wgrad(u, uin, Dm, grad_ref(m, k, u.t_w)));
                 if (lastu && bp.has_proj) {
-                    wg_tail.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
+                    // a bare projection's gradient operand is the block-output gradient itself, whose buffer the next
+                    // block reuses: its filter gradient cannot wait for the tail and runs with this step
+                    if (bp.proj_plain) s3.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
+                    else wg_tail.push_back(B.wgrad(bp.proj, bp.in, Dp, grad_ref(m, k, bp.proj.t_w)));
                     if (need_in_grad) B.conv_dgrad(bp.proj, Dp, mk(SP_WS, 0, bp.proj.ws_wt), Pp, Ref(), Ref(), s3);
                 }
                 // data-gradient of this unit
@@ -790,6 +817,7 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
     for (int i = 0; i < d.n_blocks; ++i) {
         const lp_block_desc& b = m.blocks[i];
         if (b.kind != LP_BLOCK_BASIC) return fail(LP_ERR_SHAPE, "module %d block %d: the pre-activation order supports basic blocks", k, i);
+        if (b.proj_plain || b.post_relu) return fail(LP_ERR_SHAPE, "module %d block %d: proj_plain / post_relu are options of the conv-BN-ReLU order", k, i);
         if (b.cin != C) return fail(LP_ERR_SHAPE, "module %d block %d: cin %d does not match incoming %d channels", k, i, b.cin, C);
         if (b.stride != 1 && b.stride != 2) return fail(LP_ERR_SHAPE, "module %d block %d: stride %d (1 or 2)", k, i, b.stride);
         if (H % b.stride || W % b.stride) return fail(LP_ERR_SHAPE, "module %d block %d: %dx%d not divisible by stride", k, i, H, W);
@@ -1209,6 +1237,7 @@ static void op_work(const lp_net* net, const Op& o, double& flops, double& bytes
         case OP_BN_BWD_APPLY: bytes = (double)o.bnb.M * o.bnb.C * e * (o.r[9].space != SP_NONE ? 4.0 : 3.0); break;
         case OP_BN_STATS: bytes = (double)o.bnb.M * o.bnb.C * e; break;
         case OP_LOSS: bytes = (double)o.numel * e * 4.0; break;
+        case OP_RELU_MASK: bytes = (double)o.numel * e * 3.0; break;
         case OP_POOL_FWD:
         case OP_POOL_BWD: bytes = ((double)o.pool.N * o.pool.H * o.pool.W + (double)o.pool.N * o.pool.Ho * o.pool.Wo) * o.pool.C * e; break;
         case OP_HEAD_FWD:
@@ -1444,6 +1473,17 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 }
                 g.total_blocks = tot;
                 err = launch_loss(g, dt, s);
+            } break;
+            case OP_RELU_MASK: {
+                MaskGroup g; g.nprob = n; int tot = 0;
+                for (int i = 0; i < n; ++i) {
+                    const Op& o = *ops[base + i];
+                    MaskProb& p = g.p[i];
+                    p.g = resolve(o.r[0], b); p.out = resolve(o.r[1], b); p.gm = resolve(o.r[2], b); p.numel = o.numel;
+                    p.block_start = tot; p.nblocks = elem_blocks(o.numel / epv); tot += p.nblocks;
+                }
+                g.total_blocks = tot;
+                err = launch_relu_mask(g, dt, s);
             } break;
             case OP_CE:
                 for (int i = 0; i < n && err == hipSuccess; ++i) {
@@ -1698,6 +1738,7 @@ lp_status lp_net_create(int K, const lp_module_desc* mods, const lp_aux_desc* au
     net->keep_gradients = g_keep_gradients;
     net->mods.resize(K);
     net->saved_x.assign(K, nullptr);
+    net->saved_y.assign(K, nullptr);
     WsAlloc ws;
     lp_status st = LP_OK;
     for (int k = 0; k < K && st == LP_OK; ++k) {
@@ -2020,7 +2061,10 @@ lp_status lp_module_forward(struct lp_net* net, void* stream, uint32_t module_ma
     st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
     if (st == LP_OK) {
         for (int k = 0; k < net->K; ++k)
-            if ((module_mask >> k) & 1u) { net->saved_x[k] = x[k]; net->fwd_done |= (1u << k); }
+            if ((module_mask >> k) & 1u) {
+                net->saved_x[k] = x[k]; net->fwd_done |= (1u << k);
+                net->saved_y[k] = (k < net->K - 1) ? y[k] : nullptr;
+            }
     }
     return st;
 }
@@ -2099,7 +2143,7 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
         progs.push_back(opt_dx ? &m.bwd_dx0 : &m.bwd);
     }
     Bindings b; b.ws = net->ws; b.x = net->saved_x.data(); b.params = params; b.dparams = dparams; b.dy = dy; b.dx = dx;
-    b.dlogits = dlogits;
+    b.dlogits = dlogits; b.y = net->saved_y.data();
     const std::vector<int> lanes = lanes_of(net, module_mask);
     st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
     if (st == LP_OK) net->fwd_done &= ~module_mask;
@@ -2348,6 +2392,7 @@ static void collect_units(const ModulePlan& m, std::vector<lp_debug_unit>& out, 
         d.block = block; d.slot = slot; d.R = u.R; d.stride = u.stride; d.pad = u.pad; d.cin = u.cin; d.cout = u.cout;
         d.N = u.N; d.H = u.H; d.W = u.W; d.Ho = u.Ho; d.Wo = u.Wo; d.relu = u.relu ? 1 : 0;
         d.t_w = u.t_w; d.t_gamma = u.t_g; d.t_beta = u.t_b; d.skip_unit = -1;
+        d.graw.space = LP_REF_NONE;
         d.y = dws(u.ws_y); d.stats = dws(u.ws_stats); d.dy = dws(u.ws_dy); d.red = dws(u.ws_red);
         return d;
     };
@@ -2372,6 +2417,8 @@ static void collect_units(const ModulePlan& m, std::vector<lp_debug_unit>& out, 
             } else {
                 d.out = dref(bp.out);
                 d.gout = dref(bp.g_ref);
+                d.post_relu = bp.post_relu ? 1 : 0;
+                if (bp.post_relu) d.graw = dref(bp.graw_ref);
                 if (bp.has_proj) { d.skip_kind = 2; d.skip_unit = first + nm; }
                 else { d.skip_kind = 1; d.skip = dref(bp.in); }
             }
@@ -2386,6 +2433,7 @@ static void collect_units(const ModulePlan& m, std::vector<lp_debug_unit>& out, 
             lp_debug_unit d = base(bp.proj, (int)i, 3);
             d.in = dref(bp.in);
             d.gout = dref(bp.g_ref);
+            if (bp.proj_plain) { d.plain = 1; d.dy = dref(bp.g_ref); d.stats = d.red = dref(Ref()); }
             if (need_in_grad) { d.has_dgrad = 1; d.din = dws(bp.ws_gproj); }
             out.push_back(d);
         }

@@ -471,6 +471,28 @@ __global__ __launch_bounds__(kElemBlock) void loss_kernel(const LossGroup g) {
     }
 }
 
+// gradient through the ReLU behind a residual sum: gm = g where the stored block output is positive, else 0
+template <typename T>
+__global__ __launch_bounds__(kElemBlock) void relu_mask_kernel(const MaskGroup g) {
+    constexpr int EPV = Vec<T>::N;
+    const MaskProb& P = g.p[find_problem(g, blockIdx.x)];
+    const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
+    const T* __restrict__ out = reinterpret_cast<const T*>(P.out);
+    T* __restrict__ gm = reinterpret_cast<T*>(P.gm);
+    const size_t nvec = P.numel / EPV;
+    const size_t base = (size_t)(blockIdx.x - P.block_start) * kElemVecsPerBlock;
+    for (int i = threadIdx.x; i < kElemVecsPerBlock; i += kElemBlock) {
+        const size_t v = base + i;
+        if (v >= nvec) break;
+        float a[EPV], o[EPV];
+        Vec<T>::load(gp + v * EPV, a);
+        Vec<T>::load(out + v * EPV, o);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) a[e] = o[e] > 0.f ? a[e] : 0.f;
+        Vec<T>::store(gm + v * EPV, a);
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kElemBlock) void mult_kernel(const MultGroup g) {
     constexpr int EPV = Vec<T>::N;
@@ -828,6 +850,11 @@ hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s) {
 hipError_t launch_fill(const FillGroup& g, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     hipLaunchKernelGGL(fill_kernel, dim3(g.total_blocks), dim3(kElemBlock), 0, s, g);
+    return hipGetLastError();
+}
+hipError_t launch_relu_mask(const MaskGroup& g, int dtype, hipStream_t s) {
+    if (g.total_blocks <= 0) return hipSuccess;
+    LP_DISPATCH_T(dtype, relu_mask_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
     return hipGetLastError();
 }
 hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s) {

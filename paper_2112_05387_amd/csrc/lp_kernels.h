@@ -104,6 +104,10 @@ struct BnBwdGroup {
     BnBwdProb p[kMaxGroup];
 };
 
+// gm = g * [out > 0]: the gradient through a ReLU behind a residual sum, from the stored block output
+struct MaskProb { const void* g; const void* out; void* gm; size_t numel; int block_start, nblocks; };
+struct MaskGroup { int nprob, total_blocks; MaskProb p[kMaxGroup]; };
+
 struct FillProb { void* ptr; size_t bytes; int block_start; };
 struct FillGroup { int nprob, total_blocks; FillProb p[kMaxGroup]; };
 
@@ -168,6 +172,7 @@ hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hi
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s);
 hipError_t launch_bn_bwd_apply(const BnBwdGroup& g, int dtype, hipStream_t s);
 hipError_t launch_fill(const FillGroup& g, hipStream_t s);
+hipError_t launch_relu_mask(const MaskGroup& g, int dtype, hipStream_t s);
 hipError_t launch_loss(const LossGroup& g, int dtype, hipStream_t s);
 hipError_t launch_mult(const MultGroup& g, int dtype, hipStream_t s);
 hipError_t launch_auxvar(const AuxVarGroup& g, int dtype, hipStream_t s);

@@ -28,6 +28,17 @@ def gpu_mini_basic(batch=3, dtype="f32", serial=False):
     return net
 
 
+def gpu_mini_basic_flags(batch=3, dtype="f32"):
+    """gpu_mini_basic with ReLU behind the residual sum in three of its four blocks and a bare conv1x1 projection."""
+    net = gpu_mini_basic(batch, dtype)
+    net.name = "gpu_mini_basic_flags"
+    blocks = [b for m in net.modules for b in m.blocks]
+    for i in (0, 1, 3):
+        blocks[i].post_relu = True
+    blocks[1].proj_bn = False
+    return net
+
+
 def gpu_mini_bottleneck(batch=2, dtype="f32"):
     blocks = [Block("bottleneck", 8, 16, 8, 1, True), Block("bottleneck", 16, 32, 8, 2, True),
               Block("bottleneck", 32, 32, 8, 1, False)]

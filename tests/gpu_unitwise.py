@@ -85,11 +85,20 @@ def check_units(net, tol=None, fused=True, modules=None, note=""):
                 tag = f"m{k}.{'stem' if u.block < 0 else 'b%d' % u.block}.{'proj' if u.slot == 3 else 'c%d' % u.slot}"
                 in_shape, out_shape = (u.N, u.H, u.W, u.cin), (u.N, u.Ho, u.Wo, u.cout)
                 Mpix = u.N * u.Ho * u.Wo
-                w, gamma, beta = P[u.t_w], P[u.t_gamma], P[u.t_beta]
+                w = P[u.t_w]
                 x_in = ls.fetch(u.in_, in_shape)
                 y_dev = ls.fetch(u.y, out_shape)
                 # ---- forward: convolution
                 errs[f"{tag}.y"] = rel_err(y_dev, lpref.conv_fwd(x_in, w, u.stride, u.pad))
+                if u.plain:
+                    # a bare projection: no BN; the gradient on its result is the (masked) gradient on the block output
+                    g = ls.fetch(u.gout, out_shape)
+                    if u.has_dgrad:
+                        errs[f"{tag}.din"] = rel_err(ls.fetch(u.din, in_shape), lpref.conv_dgrad(g, w, in_shape, u.stride, u.pad))
+                    errs[f"{tag}.dW"] = rel_err(grads[u.t_w], lpref.conv_wgrad(x_in, g, w.shape, u.stride, u.pad))
+                    say(f"  {tag:16s} [{u.N}x{u.H}x{u.W}x{u.cin} -> {u.cout}, {u.R}x{u.R}/{u.stride}, no BN]")
+                    continue
+                gamma, beta = P[u.t_gamma], P[u.t_beta]
                 # ---- forward: batch statistics of the stored tensor
                 st = ls.fetch(u.stats, (2, u.cout), "f64")
                 mean_ref = y_dev.mean(axis=(0, 1, 2))
@@ -106,10 +115,14 @@ def check_units(net, tol=None, fused=True, modules=None, note=""):
                         pre = z + ls.fetch(u.skip, out_shape)
                     elif u.skip_kind == 2:
                         pu = units[u.skip_unit]
-                        zp, _ = lpref.bn_fwd(ls.fetch(pu.y, out_shape), P[pu.t_gamma], P[pu.t_beta], net.bn_eps)
+                        yp = ls.fetch(pu.y, out_shape)
+                        zp = yp if pu.plain else lpref.bn_fwd(yp, P[pu.t_gamma], P[pu.t_beta], net.bn_eps)[0]
                         pre = z + zp
-                    want = np.maximum(pre, 0.0) if u.relu else pre
-                    errs[f"{tag}.out"] = rel_err(ls.fetch(u.out, out_shape), want)
+                    want = np.maximum(pre, 0.0) if (u.relu or u.post_relu) else pre
+                    out_dev = ls.fetch(u.out, out_shape)
+                    errs[f"{tag}.out"] = rel_err(out_dev, want)
+                    if u.post_relu:          # the mask pass: the arriving gradient where the stored block output is positive
+                        errs[f"{tag}.gmask"] = rel_err(ls.fetch(u.gout, out_shape), ls.fetch(u.graw, out_shape) * (out_dev > 0.0))
                 # ---- backward: BN (through the unit's own ReLU)
                 g = ls.fetch(u.gout, out_shape)
                 amb = None

@@ -15,6 +15,18 @@ def mini_basic(batch=3, dtype="f32"):
     return net
 
 
+def mini_basic_flags(batch=3, dtype="f32"):
+    """mini_basic with the two block options of the conv-BN-ReLU order switched on: ReLU after the residual sum in
+    blocks 0, 1 and 3, and a bare conv1x1 projection (no BN) on the stride-2 block."""
+    net = mini_basic(batch, dtype)
+    net.name = "mini_basic_flags"
+    blocks = [b for m in net.modules for b in m.blocks]
+    for i in (0, 1, 3):
+        blocks[i].post_relu = True
+    blocks[1].proj_bn = False
+    return net
+
+
 def mini_basic_pre(batch=3, dtype="f32"):
     """mini_basic in the pre-activation order: bare conv stem, BN-ReLU-conv blocks, BN-ReLU in front of the head."""
     return cfg.with_order(mini_basic(batch, dtype), "pre")

@@ -269,3 +269,32 @@ def test_static_auxnet_forward_rejects_what_does_not_fit():
         _expect(B.LP_ERR_STATE, B.lp_auxnet_forward_static, h, None, FAKE_PTR, [FAKE_PTR] * 3, [FAKE_PTR] * 3)
     finally:
         B.lp_net_destroy(h)
+
+
+def test_block_options_tensor_table_and_refusals():
+    from tests.helpers import mini_basic_flags, mini_basic_pre
+    net = mini_basic_flags()
+    for m in net.modules:                   # channel counts of the CPU-sized net are too small for the device: widen
+        m.C = m.C * 2 if m.stem == 0 else m.C
+        m.stem_cout *= 2
+        for b in m.blocks:
+            b.cin, b.cout, b.width = b.cin * 2, b.cout * 2, b.width * 2
+    h = B.lp_net_create(net.modules, None, "f32", net.bn_eps)
+    try:
+        for k, m in enumerate(net.modules):
+            specs = wl.module_tensor_specs(m)
+            assert B.lp_net_num_tensors(h, 0, k) == len(specs)
+            for i, sp in enumerate(specs):
+                info = B.lp_net_tensor_info(h, 0, k, i)
+                assert tuple(info.dims[j] for j in range(info.ndim)) == tuple(sp.shape), (k, sp.name)
+        assert sum(1 for sp in wl.module_tensor_specs(net.modules[0]) if sp.name.startswith("block1.proj")) == 1
+    finally:
+        B.lp_net_destroy(h)
+    pre = mini_basic_pre()
+    for m in pre.modules:
+        m.C = m.C * 2 if m.stem == 0 else m.C
+        m.stem_cout *= 2
+        for b in m.blocks:
+            b.cin, b.cout, b.width = b.cin * 2, b.cout * 2, b.width * 2
+    pre.modules[1].blocks[0].post_relu = True
+    _expect(B.LP_ERR_SHAPE, B.lp_net_create, pre.modules, None, "f32", pre.bn_eps)

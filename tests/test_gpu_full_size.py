@@ -56,7 +56,7 @@ def test_wrn28_10_full_size():
             m = net.modules[k]
             say(f"full size: oracle forward of module {k}")
             y, logits, cache = lpref.module_forward(m, xs[k], params[k], net.bn_eps)
-            unit_caches, proj_cache = cache["blocks"][-1]
+            unit_caches, proj_cache, _ = cache["blocks"][-1]
             last = unit_caches[-1]
             if k < K - 1:
                 errs[f"y{k}"] = rel_err(dev_y[k], y)

@@ -48,6 +48,16 @@ def test_mini_basic_al(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_block_options(dtype):
+    """post_relu and proj_plain: the whole step end to end (entry-point pass and fused pass)."""
+    from tests.gpu_common import gpu_mini_basic_flags
+    net = gpu_mini_basic_flags(dtype=dtype)
+    net.al, net.lam_sigma = True, 0.05
+    say("case block options", dtype)
+    compare_step(net)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_mini_bottleneck(dtype):
     net = gpu_mini_bottleneck(dtype=dtype)
     say("case mini_bottleneck", dtype)

@@ -8,7 +8,7 @@ ResNet-50 (bf16, 224 x 224, batch 64)."""
 import pytest
 
 import workloads as wl
-from tests.gpu_common import gpu_mini_basic, gpu_mini_bottleneck, gpu_mini_wide, gpu_mini_wide_strided
+from tests.gpu_common import gpu_mini_basic, gpu_mini_basic_flags, gpu_mini_bottleneck, gpu_mini_wide, gpu_mini_wide_strided
 from tests.gpu_unitwise import check_units
 
 pytestmark = pytest.mark.gpu
@@ -22,6 +22,12 @@ def test_units_mini_basic(dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_units_mini_bottleneck(dtype):
     check_units(gpu_mini_bottleneck(batch=2, dtype=dtype))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_units_block_options(dtype):
+    """ReLU behind the residual sum and a bare conv1x1 projection (the two options of the conv-BN-ReLU order)."""
+    check_units(gpu_mini_basic_flags(batch=3, dtype=dtype))
 
 
 def test_units_mini_wide():

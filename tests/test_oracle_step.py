@@ -4,7 +4,7 @@ import pytest
 
 import workloads as wl
 from oracle import lpref
-from tests.helpers import mini_basic, mini_basic_pre, mini_bottleneck, step_inputs, rel_err
+from tests.helpers import mini_basic, mini_basic_flags, mini_basic_pre, mini_bottleneck, step_inputs, rel_err
 
 
 def _local_loss(net, k, x, params, x_next, lam, labels, scale):
@@ -15,7 +15,7 @@ def _local_loss(net, k, x, params, x_next, lam, labels, scale):
     return lpref.ce_loss_grad(logits, labels)[0]
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre, mini_basic_flags])
 def test_module_backward_finite_differences(mk):
     """Every parameter tensor and the module input: directional derivatives, one tensor at a time,
     plus single coordinates, against central differences of the local loss (float64)."""
@@ -53,7 +53,7 @@ def test_module_backward_finite_differences(mk):
         assert abs(fd - an) <= 2e-6 * max(1.0, abs(an)), (k, "dx", fd, an)
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre, mini_basic_flags])
 def test_vanish_invariant(mk):
     """x_{k+1} = F_k(x_k) and zero multipliers: every penalty term, its terminal adjoint, every weight
     gradient and every dx of modules 0..K-2 vanish exactly (the relaxed problem reduces to the original)."""
@@ -70,7 +70,7 @@ def test_vanish_invariant(mk):
     assert out["loss"][-1] > 0.0
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre, mini_basic_flags])
 def test_last_module_equals_end_to_end_and_serial_fd(mk):
     """With consistent auxiliary variables the last module's local gradients are those of end-to-end
     back-propagation; the end-to-end gradients themselves are pinned by finite differences of the
@@ -105,7 +105,7 @@ def test_last_module_equals_end_to_end_and_serial_fd(mk):
     assert abs(fd - float(np.sum(adj[0] * d))) <= 2e-6
 
 
-@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre])
+@pytest.mark.parametrize("mk", [mini_basic, mini_bottleneck, mini_basic_pre, mini_basic_flags])
 def test_multiplier_equal_to_adjoint_reproduces_end_to_end(mk):
     """Consistent auxiliary variables, arbitrary rho, multiplier on each interface := end-to-end adjoint
     there: every module's weight gradients and dx equal end-to-end back-propagation."""
@@ -350,14 +350,14 @@ def test_deep_auxnet_distill_finite_differences():
         assert abs(fd - an) <= 5e-6 * max(1.0, abs(an)), (i, fd, an)
 
 
-@pytest.mark.parametrize("order", ["post", "pre"])
+@pytest.mark.parametrize("order", ["post", "pre", "post_flags"])
 def test_module_forward_against_library_layers(order):
     """The forward pass of every module, re-composed from a library's float64 layers (conv2d, training-mode
     batch_norm, relu, adaptive average pool, linear) in NCHW: pins the sequencing of both block orders (where BN
     sits, what the projection reads, no ReLU after the sum, the head)."""
     import torch
     import torch.nn.functional as F
-    net = (mini_basic_pre if order == "pre" else mini_basic)()
+    net = {"pre": mini_basic_pre, "post": mini_basic, "post_flags": mini_basic_flags}[order]()
     inp = step_inputs(net, lpref)
     t = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64))
     act = lambda a: t(a).permute(0, 3, 1, 2)
@@ -387,9 +387,14 @@ def test_module_forward_against_library_layers(order):
             for b in m.blocks:
                 y = F.relu(bn(F.conv2d(a, filt(p[i]), stride=b.stride, padding=1), p[i + 1], p[i + 2]))
                 z = bn(F.conv2d(y, filt(p[i + 3]), padding=1), p[i + 4], p[i + 5])
-                skip = bn(F.conv2d(a, filt(p[i + 6]), stride=b.stride), p[i + 7], p[i + 8]) if b.proj else a
-                a = z + skip
-                i += 9 if b.proj else 6
+                if b.proj and b.proj_bn:
+                    skip = bn(F.conv2d(a, filt(p[i + 6]), stride=b.stride), p[i + 7], p[i + 8])
+                elif b.proj:
+                    skip = F.conv2d(a, filt(p[i + 6]), stride=b.stride)          # bare projection
+                else:
+                    skip = a
+                a = F.relu(z + skip) if b.post_relu else z + skip
+                i += 6 + ((3 if b.proj_bn else 1) if b.proj else 0)
             feat = a
         y, logits, _ = lpref.module_forward(m, inp["xs"][k], p, net.bn_eps)
         np.testing.assert_allclose(y, feat.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-11)
@@ -473,7 +478,7 @@ def test_sgd_update_closed_forms():
     assert after < before and abs((before - after) - 1e-3 * gn2) <= 0.05 * 1e-3 * gn2
 
 
-@pytest.mark.parametrize("order", ["post", "pre"])
+@pytest.mark.parametrize("order", ["post", "pre", "post_flags"])
 def test_storage_rounding_placement(order):
     """Where the diagnostic storage-rounding mode rounds (`q` of the composing routines).  The mode is defined as:
     every STORED tensor is rounded once -- convolution results, activations, block outputs going forward; the gradient
@@ -507,7 +512,7 @@ def test_storage_rounding_placement(order):
             return tq(g)
 
     store, store_grad = Store.apply, StoreGrad.apply
-    net = (mini_basic_pre if order == "pre" else mini_basic)()
+    net = {"pre": mini_basic_pre, "post": mini_basic, "post_flags": mini_basic_flags}[order]()
     net.al, net.lam_sigma = True, 0.1
     inp = step_inputs(net, lpref)
     xs = [q(x) for x in inp["xs"]]
@@ -541,12 +546,14 @@ def test_storage_rounding_placement(order):
             for b in m.blocks:
                 y = store(F.relu(bn(store(F.conv2d(a, filt(p[i]), stride=b.stride, padding=1)), p[i + 1], p[i + 2])))
                 z = bn(store(F.conv2d(y, filt(p[i + 3]), padding=1)), p[i + 4], p[i + 5])
-                if b.proj:
+                if b.proj and b.proj_bn:
                     skip = bn(store(F.conv2d(store_grad(a), filt(p[i + 6]), stride=b.stride)), p[i + 7], p[i + 8])
+                elif b.proj:
+                    skip = store(F.conv2d(store_grad(a), filt(p[i + 6]), stride=b.stride))
                 else:
                     skip = a
-                a = store(z + skip)
-                i += 9 if b.proj else 6
+                a = store(F.relu(z + skip) if b.post_relu else z + skip)
+                i += 6 + ((3 if b.proj_bn else 1) if b.proj else 0)
             feat = a
         if m.head:
             logits = F.linear(F.adaptive_avg_pool2d(a, 1).flatten(1), p[i], p[i + 1])

@@ -19,6 +19,8 @@ class Block:
     width: int         # bottleneck inner width (basic: == cout)
     stride: int        # stride of the block (basic: first 3x3; bottleneck: the 3x3)
     proj: bool         # 1x1 conv(stride)+BN on the skip path
+    proj_bn: bool = True       # False: the projection is the bare conv1x1(stride), no BN (conv-BN-ReLU order only)
+    post_relu: bool = False    # True: ReLU after the residual sum, X_{m+1} = ReLU(skip + F) (conv-BN-ReLU order only)
 
 
 @dataclass
@@ -256,6 +258,8 @@ def module_tensor_specs(m: ModuleDesc) -> List[TensorSpec]:
         for slot, r, ci, co, _, _ in block_convs(b):
             nm = f"block{i}." + ("proj" if slot == 3 else f"conv{slot + 1}")
             t.append(TensorSpec(nm, "conv", (co, r, r, ci), r * r * ci, i, slot))
+            if slot == 3 and not b.proj_bn:
+                continue                   # a bare projection has no BN parameters
             t.append(TensorSpec(nm + ".bn.gamma", "bn_gamma", (co,), 0, i, slot))
             t.append(TensorSpec(nm + ".bn.beta", "bn_beta", (co,), 0, i, slot))
     if m.head:
