@@ -148,6 +148,35 @@ def speedup_terms(name, batch, reps):
             "note": "every term measured on ONE GPU; the K devices of the model are not run"}
 
 
+def measure_peak():
+    """What the matrix cores of this device sustain under their own power management: MFMA-only and MFMA + LDS
+    operand reads (the convolution kernels' wave tile), one workgroup per CU and two, with the shader clock each ran at."""
+    import torch
+    from paper_2112_05387_amd import binding as B
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    out = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for mode, name in ((0, "mfma_only"), (1, "mfma_plus_lds_reads")):
+        for blocks in (256, 512):
+            iters = 4000
+            clk = torch.zeros(2 * blocks, dtype=torch.int64, device=dev)
+            B.lp_debug_mfma_peak(stream, mode, blocks, 200, clk.data_ptr(), sink.data_ptr())      # warm-up
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(3):
+                B.lp_debug_mfma_peak(stream, mode, blocks, iters, clk.data_ptr(), sink.data_ptr())
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 3
+            c = clk.cpu().numpy().reshape(blocks, 2).astype("float64")
+            ghz = float((c[:, 0] / c[:, 1]).mean()) * 0.1           # cycles per tick of the 100 MHz counter
+            flops = blocks * 8.0 * iters * 40 * 32768
+            out[f"{name}_{blocks}_workgroups"] = {"TFLOP/s": flops / (ms * 1e-3) / 1e12, "shader_clock_GHz": ghz, "ms": ms}
+    return out
+
+
 def cpu_baseline(net_name, target_seconds=60.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same network, at
     the configuration's own mini-batch when the plain loops finish it within about a minute on the host's cores (the
@@ -199,8 +228,10 @@ def main():
                     help="after the timed region run three plain 256 MiB device copies (a known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--lanes", default="default",
-                    help="default: the library's concurrent stream lanes; single: every module on one stream; or one "
-                         "digit 0..3 per module, e.g. 1200 (the result is then not the headline)")
+                    help="default: the library's concurrent stream lanes; single: every module on one stream; serial: the "
+                         "launches of the default lanes (same grouping, same tile variants) issued one after another on "
+                         "one stream, warm-up included (what the per-kernel rocprofv3 summaries are taken with); or one "
+                         "digit 0..3 per module, e.g. 1200 (in all these cases the result is not the headline)")
     ap.add_argument("--graph", action="store_true",
                     help="also capture the step into a HIP graph and time its replays (reported beside the eager step)")
     ap.add_argument("--separate-calls", action="store_true",
@@ -208,6 +239,9 @@ def main():
                          "lp_al_multiplier_update instead of the one lp_local_step call")
     ap.add_argument("--order", choices=["post", "pre"], default="post",
                     help="block order: post = conv-BN-ReLU (the headline configuration), pre = BN-ReLU-conv (Fig. 2)")
+    ap.add_argument("--measure-peak", action="store_true",
+                    help="also run the synthetic MFMA kernels (register operands only / with the kernels' LDS operand reads) "
+                         "and report what the matrix cores of this device sustain, with the shader clock they ran at")
     ap.add_argument("--speedup-terms", action="store_true",
                     help="also time the terms of the paper's speed-up model (K = 1 network, single modules, interface "
                          "and AuxNet work) and add them to the JSON line")
@@ -229,8 +263,10 @@ def main():
         cfg.with_order(net, "pre")
     N = net.modules[0].N
     ls = build_state(net)
-    if args.lanes != "default":
+    if args.lanes not in ("default", "serial"):
         ls.set_stream_lanes(None if args.lanes == "single" else [int(c) for c in args.lanes])
+    if args.lanes == "serial":
+        B.lp_profile_enable(ls.net, 2)
     for _ in range(args.warmup):
         one_step(ls, net)
     torch.cuda.synchronize()
@@ -258,7 +294,11 @@ def main():
     # steps: the SAME launches (same grouping per lane, same tile variants as in the timed region), enqueued one after
     # another on the caller's stream, each bracketed by hipEvents on that stream (lp_profile_enable(net, 2)).
     graph_ms = None
-    if args.lanes == "single":
+    if args.lanes == "serial":
+        B.lp_profile_fetch(ls.net)                       # drop the warm-up's records
+        wall_ms, gpu_ms, recs = timed_steps(2)
+        iso_wall, gpu_iso = wall_ms, gpu_ms
+    elif args.lanes == "single":
         wall_ms, gpu_ms, recs = timed_steps(1)           # one stream: the timed region itself carries the events
         iso_wall, gpu_iso = wall_ms, gpu_ms
         if args.graph:
@@ -343,6 +383,8 @@ def main():
                             "note": "the step captured once (stream lanes included) and replayed; `value` is the eager step"}
     out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
     ls.close()
+    if args.measure_peak:
+        out["measured_mfma_peak"] = measure_peak()
     if args.speedup_terms:
         out["speedup_model"] = speedup_terms(args.config, args.batch, max(3, args.steps // 2))
     if args.calibrate_copy:

@@ -378,6 +378,15 @@ lp_status lp_debug_module_info(const struct lp_net* net, int k, lp_debug_module*
 lp_status lp_debug_filter_load_extent(int kernel, int bk, int bn, int nw, int Ncol, int Cin, int R, size_t* max_end,
                                       size_t* n_live);
 
+/* What the matrix cores of this device sustain (measurement aid of bench.py --measure-peak; no operand of the
+ * library is touched).  Launches `blocks` workgroups of eight waves, each wave running `iters` times the 40
+ * v_mfma_f32_32x32x16_bf16 of one filter tap of the convolution kernels' wave tile (2 x 5 micro-tiles, four k-steps):
+ * mode 0 on register operands only, mode 1 with the seven operand fragments of every k-step read from LDS as the
+ * kernels read them.  Work: blocks * 8 * iters * 40 * 32768 flop.  clk (device, 2*blocks uint64, or NULL): per
+ * workgroup the shader-clock cycles and the ticks of the constant 100 MHz counter between its start and end.
+ * sink: one device float (never written in practice).  The caller times the launch. */
+lp_status lp_debug_mfma_peak(void* stream, int mode, int blocks, int iters, uint64_t* clk, float* sink);
+
 /* Optional per-launch timing.  While enabled, every grouped kernel launch made by lp_auxnet_forward,
  * lp_module_forward and lp_module_backward is bracketed by two hipEvents on the stream it is enqueued on.
  * on = 1: launches of different stream lanes still overlap, so a record's duration includes the time its kernel

@@ -16,7 +16,7 @@ EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_
            "lp_net_workspace_bytes", "lp_net_set_workspace", "lp_auxnet_forward", "lp_auxnet_forward_static", "lp_module_forward",
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step", "lp_net_set_residual_output", "lp_net_set_deterministic",
            "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
-           "lp_debug_module_info", "lp_debug_filter_load_extent", "lp_debug_conv_geometry", "lp_debug_conv_offsets",
+           "lp_debug_module_info", "lp_debug_filter_load_extent", "lp_debug_conv_geometry", "lp_debug_conv_offsets", "lp_debug_mfma_peak",
            "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
@@ -118,6 +118,7 @@ def lib():
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
         L.lp_debug_conv_geometry.argtypes = [c_int] * 12 + [POINTER(c_int)]
         L.lp_debug_conv_offsets.argtypes = [c_void_p] + [c_int] * 12 + [c_void_p] * 6 + [c_int]
+        L.lp_debug_mfma_peak.argtypes = [c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]
         L.lp_debug_keep_gradients.argtypes = [c_int]
         L.lp_debug_unit_count.argtypes = [c_void_p, c_int, POINTER(c_int)]
         L.lp_debug_unit_info.argtypes = [c_void_p, c_int, c_int, POINTER(lp_debug_unit)]
@@ -310,6 +311,10 @@ def lp_debug_conv_offsets(stream, kernel, mode, parity, N, H, W, Cin, Cout, R, s
                           out_off, count):
     _check(lib().lp_debug_conv_offsets(stream, kernel, mode, parity, N, H, W, Cin, Cout, R, stride, pad, bk, m, q, col,
                                        in_off, w_off, out_off, count))
+
+
+def lp_debug_mfma_peak(stream, mode, blocks, iters, clk, sink):
+    _check(lib().lp_debug_mfma_peak(stream, mode, blocks, iters, clk, sink))
 
 
 def lp_debug_keep_gradients(on):

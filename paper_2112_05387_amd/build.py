@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblp.so")
-SOURCES = ["lp_api.hip", "lp_conv.hip", "lp_conv_fast.hip", "lp_conv_win.hip", "lp_wgrad_fast.hip", "lp_elem.hip"]
+SOURCES = ["lp_api.hip", "lp_conv.hip", "lp_conv_fast.hip", "lp_conv_win.hip", "lp_wgrad_fast.hip", "lp_elem.hip", "lp_peak.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -2366,6 +2366,13 @@ lp_status lp_debug_conv_offsets(void* stream, int kernel, int mode, int parity, 
     return LP_OK;
 }
 
+lp_status lp_debug_mfma_peak(void* stream, int mode, int blocks, int iters, uint64_t* clk, float* sink) {
+    if ((mode != 0 && mode != 1) || blocks < 1 || iters < 1 || !sink) return fail(LP_ERR_INVALID_ARG, "bad argument");
+    const hipError_t err = launch_mfma_peak(mode, blocks, iters, (unsigned long long*)clk, sink, (hipStream_t)stream);
+    if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
+    return LP_OK;
+}
+
 lp_status lp_debug_keep_gradients(int on) {
     g_keep_gradients = on != 0;
     return LP_OK;

@@ -191,6 +191,8 @@ hipError_t launch_im2col_offsets(const ConvProb& p, const int64_t* m, const int6
 hipError_t launch_conv_offsets(const ConvProb& p, int kernel, int BM, int bk, int nw, const int64_t* m, const int64_t* q,
                                const int64_t* col, int64_t* in_off, int64_t* w_off, int64_t* out_off, int count, hipStream_t s);
 
+hipError_t launch_mfma_peak(int mode, int blocks, int iters, unsigned long long* clk, float* sink, hipStream_t s);
+
 constexpr int kElemBlock = 256;          // threads per workgroup of the elementwise kernels
 constexpr int kElemVecsPerBlock = 2048;  // 16-byte vectors handled by one workgroup
 
