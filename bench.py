@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}     # dense MFMA, MI355X data sheet
 PEAK_HBM_GBS = 8000.0
+N_CUS = 256
 
 
 def build_state(net, seed_noise=True):
@@ -315,8 +316,9 @@ def main():
     # per-kernel aggregation (kind, tile configuration)
     agg = {}
     for r in recs:
-        a = agg.setdefault((r["kind"], r["cfg"]), {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
-        a["ms"] += r["ms"]; a["flops"] += r["flops"]; a["bytes"] += r["bytes"]; a["launches"] += 1
+        a = agg.setdefault((r["kind"], r["cfg"]), {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0, "blocks": 0, "cu_ms": 0.0})
+        a["ms"] += r["ms"]; a["flops"] += r["flops"]; a["bytes"] += r["bytes"]; a["launches"] += 1; a["blocks"] += r["blocks"]
+        a["cu_ms"] += r["ms"] * min(1.0, r["blocks"] / N_CUS)
     conv_ms = sum(a["ms"] for (k, _), a in agg.items() if k in (2, 10))
     conv_flops = sum(a["flops"] for (k, _), a in agg.items() if k in (2, 10))
     (dk, dcfg), dom = max(agg.items(), key=lambda kv: kv[1]["ms"])
@@ -324,6 +326,11 @@ def main():
     if dk in (2, 10):
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak}
+        if dom["cu_ms"] > 0:
+            # a lane's launch is sized to share the chip with the other lanes: workgroups per launch, and the rate per
+            # compute unit it occupies (one workgroup per CU) against a CU's share of the peak
+            roof["workgroups_per_launch"] = dom["blocks"] / dom["launches"]
+            roof["frac_on_occupied_cus"] = dom["flops"] / (dom["cu_ms"] * 1e-3) / 1e12 / peak
     else:
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}

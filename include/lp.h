@@ -397,8 +397,9 @@ lp_status lp_debug_mfma_peak(void* stream, int mode, int blocks, int iters, uint
  * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
  * apply, 10 conv weight-gradient, 11 batch statistics of a module input, 12 loss / terminal adjoint, 13 cross-entropy,
  * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12), 15 gradient mask of a ReLU behind a residual sum.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
- * every operand tensor moved once). */
-typedef struct { int kind, cfg, nprob; float ms; double flops, bytes; } lp_profile_rec;
+ * every operand tensor moved once).  blocks: workgroups of the launch (conv kernels: one per output tile and split; 0: not
+ * recorded for this kind). */
+typedef struct { int kind, cfg, nprob, blocks; float ms; double flops, bytes; } lp_profile_rec;
 lp_status lp_profile_enable(struct lp_net* net, int on);
 lp_status lp_profile_fetch(struct lp_net* net, lp_profile_rec* out, int max_recs, int* n_out);
 

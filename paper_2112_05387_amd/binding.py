@@ -69,7 +69,7 @@ class lp_debug_module(ctypes.Structure):
 
 
 class lp_profile_rec(ctypes.Structure):
-    _fields_ = [("kind", c_int), ("cfg", c_int), ("nprob", c_int), ("ms", c_float), ("flops", ctypes.c_double),
+    _fields_ = [("kind", c_int), ("cfg", c_int), ("nprob", c_int), ("blocks", c_int), ("ms", c_float), ("flops", ctypes.c_double),
                 ("bytes", ctypes.c_double)]
 
 
@@ -356,4 +356,4 @@ def lp_profile_fetch(net):
         return []
     recs = (lp_profile_rec * n.value)()
     _check(lib().lp_profile_fetch(net, recs, n.value, ctypes.byref(n)))
-    return [dict(kind=r.kind, cfg=r.cfg, nprob=r.nprob, ms=r.ms, flops=r.flops, bytes=r.bytes) for r in recs]
+    return [dict(kind=r.kind, cfg=r.cfg, nprob=r.nprob, blocks=r.blocks, ms=r.ms, flops=r.flops, bytes=r.bytes) for r in recs]

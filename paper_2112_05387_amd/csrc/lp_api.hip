@@ -206,7 +206,7 @@ struct lp_net {
     bool prof = false;
     int lanes_in_flight = 1;               // stream lanes of the call being enqueued (launch-time tile choice)
     bool prof_serial = false;              // issue every stream lane on the caller's stream (launches timed in isolation)
-    struct ProfRec { hipEvent_t a, b; int type, cfg, nprob; double flops, bytes; };
+    struct ProfRec { hipEvent_t a, b; int type, cfg, nprob, blocks; double flops, bytes; };
     std::vector<ProfRec> prof_recs;
     std::vector<hipEvent_t> prof_pool;
 };
@@ -1275,22 +1275,22 @@ static void plan_wgrad_fast_splits(WgradGroup& g) {
 }
 
 static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s,
-                                    int* used_cfg);
+                                    int* used_cfg, int* used_blocks);
 
 static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const Bindings& b, hipStream_t s) {
     hipError_t err = hipSuccess;
     for (size_t base = 0; base < ops.size() && err == hipSuccess; base += kMaxGroup) {
         const int n = (int)std::min<size_t>(kMaxGroup, ops.size() - base);
-        if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s, nullptr); continue; }
+        if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s, nullptr, nullptr); continue; }
         lp_net::ProfRec r;
-        r.type = ops[base]->type; r.cfg = ops[base]->cfg; r.nprob = n; r.flops = 0; r.bytes = 0;
+        r.type = ops[base]->type; r.cfg = ops[base]->cfg; r.nprob = n; r.blocks = 0; r.flops = 0; r.bytes = 0;
         for (int i = 0; i < n; ++i) { double f, by; op_work(net, *ops[base + i], f, by); r.flops += f; r.bytes += by; }
         for (hipEvent_t* e : {&r.a, &r.b}) {
             if (!net->prof_pool.empty()) { *e = net->prof_pool.back(); net->prof_pool.pop_back(); }
             else if ((err = hipEventCreate(e)) != hipSuccess) return err;
         }
         if ((err = hipEventRecord(r.a, s)) != hipSuccess) return err;
-        err = launch_group_impl(net, ops, base, n, b, s, &r.cfg);
+        err = launch_group_impl(net, ops, base, n, b, s, &r.cfg, &r.blocks);
         if (err == hipSuccess) err = hipEventRecord(r.b, s);
         net->prof_recs.push_back(r);
     }
@@ -1298,7 +1298,7 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
 }
 
 static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, size_t base, int n, const Bindings& b, hipStream_t s,
-                                    int* used_cfg) {
+                                    int* used_cfg, int* used_blocks) {
     const int type = ops[base]->type, dt = net->dtype;
     const int epv = dt == LP_BF16 ? 8 : 4;
     hipError_t err = hipSuccess;
@@ -1393,6 +1393,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.tile_start = tot; tot += p.tiles_m * p.tiles_n;
                 }
                 g.total_tiles = tot;
+                if (used_blocks) *used_blocks = tot;
                 err = win ? launch_conv_win(g, cfg, s) : fast ? launch_conv_fast(g, cfg, s) : launch_conv(g, dt, cfg, ops[base]->vec, s);
                 if (err == hipSuccess && sg.nprob) err = launch_bn_stats(sg, dt, s);
             } break;
@@ -1411,6 +1412,7 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     tot += ops[base]->cfg == WGRAD_FAST ? wgrad_fast_blocks(p) : p.tiles_m * p.tiles_n * p.ksplit;
                 }
                 g.total_tiles = tot;
+                if (used_blocks) *used_blocks = tot;
                 err = ops[base]->cfg == WGRAD_FAST ? launch_wgrad_fast(g, s) : launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
             case OP_BN_APPLY: {
@@ -1842,7 +1844,7 @@ lp_status lp_profile_fetch(struct lp_net* net, lp_profile_rec* out, int max_recs
         float ms = 0.f;
         if (err == hipSuccess) err = hipEventElapsedTime(&ms, r.a, r.b);
         if (err != hipSuccess) return fail(LP_ERR_HIP, "event timing failed: %s", hipGetErrorString(err));
-        out[i].kind = r.type; out[i].cfg = r.cfg; out[i].nprob = r.nprob;
+        out[i].kind = r.type; out[i].cfg = r.cfg; out[i].nprob = r.nprob; out[i].blocks = r.blocks;
         out[i].ms = ms; out[i].flops = r.flops; out[i].bytes = r.bytes;
         net->prof_pool.push_back(r.a); net->prof_pool.push_back(r.b);
     }
