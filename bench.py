@@ -389,6 +389,26 @@ def main():
         out["hip_graph"] = {"ms_per_step": graph_ms, "samples/s": N / (graph_ms * 1e-3),
                             "note": "the step captured once (stream lanes included) and replayed; `value` is the eager step"}
     out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
+    # the same update inside the backward pass (epilogues of the filter-gradient kernels), lr = 0 so that the parameters
+    # stay what they are: K steps with it against K steps followed by the pass above
+    ls.set_fused_update(True, 0.0, 0.9, 5e-4, velocity=vel)
+    one_step(ls, net)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(ls, net)
+    torch.cuda.synchronize()
+    inside_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ls.set_fused_update(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(ls, net)
+        ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
+    torch.cuda.synchronize()
+    behind_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    out["step_with_update"] = {"inside_backward_ms": inside_ms, "as_a_pass_behind_the_step_ms": behind_ms,
+                               "note": "not part of `value` (the metric is the local step); same box, same run"}
     ls.close()
     if args.measure_peak:
         out["measured_mfma_peak"] = measure_peak()

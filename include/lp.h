@@ -286,6 +286,22 @@ lp_status lp_sgd_update(struct lp_net* net, void* stream, int aux, uint32_t mask
                         const float* const* dparams, float* const* velocity, float* const* master, float lr,
                         float momentum, float weight_decay);
 
+/* The same update INSIDE the backward pass (Sec. 4.1 states the update of W_{kn+m} right after the adjoint at that
+ * layer, inside the backward loop of Algorithm 1, not as a pass of its own).  While switched on, lp_module_backward
+ * and lp_local_step update params[k] of the selected modules in place (the const of their params argument
+ * notwithstanding): every convolution filter in the epilogue of its filter-gradient kernel -- the workgroup that adds
+ * the last partial sum of an output tile reads the finished gradient tile back and applies
+ *     g' = dW + weight_decay * W;   v <- momentum * v + g';   W <- W - lr * (v or g')
+ * to that tile -- and the small tensors (BN affine, head) in one grouped launch behind the module's last kernel.
+ * dparams[k] still receives the gradients.  velocity (K entries, required when momentum != 0; zero them before the
+ * first step) and master (K entries or NULL, entries may be NULL) as in lp_sgd_update; the pointers are kept by the
+ * net until the update is switched off (on = 0: the other arguments are ignored) or set again.  Results equal those of
+ * lp_module_backward followed by lp_sgd_update up to the order in which the partial sums were added; in the
+ * deterministic mode bit for bit.  Nothing else of a step may read params[k] while its backward pass runs.
+ * Errors: LP_ERR_INVALID_ARG. */
+lp_status lp_net_set_fused_update(struct lp_net* net, int on, float lr, float momentum, float weight_decay,
+                                  float* const* velocity, float* const* master);
+
 /* Correction of the auxiliary variables that follows the adjoint recursion in Sec. 4.1 (the update of lambda_k,
  * 1 <= k <= K-1): one gradient step of the relaxed objective with respect to x_k,
  *     x[k] <- x[k] - eta * ( scale*(rho*(x[k] - y_prev[k-1]) - lam_prev[k-1]) + dx[k] ),
@@ -396,7 +412,8 @@ lp_status lp_debug_mfma_peak(void* stream, int mode, int blocks, int iters, uint
  * the list (out == NULL: only the count).  kind: 0 clear, 1 filter re-layout, 2 conv forward/data-gradient,
  * 3 BN apply, 4 max-pool, 5 head, 6 head backward, 7 max-pool backward, 8 BN backward reduce, 9 BN backward
  * apply, 10 conv weight-gradient, 11 batch statistics of a module input, 12 loss / terminal adjoint, 13 cross-entropy,
- * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12), 15 gradient mask of a ReLU behind a residual sum.  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
+ * 14 multiplier update (12, 13: launches of lp_local_step only; 14: not recorded any more, lp_local_step folds it into 12), 15 gradient mask of a ReLU behind a residual sum,
+ * 16 update of the small tensors (lp_net_set_fused_update).  flops / bytes: algorithmic work of the launch (2*M*Ngemm*Kgemm per conv;
  * every operand tensor moved once).  blocks: workgroups of the launch (conv kernels: one per output tile and split; 0: not
  * recorded for this kind). */
 typedef struct { int kind, cfg, nprob, blocks; float ms; double flops, bytes; } lp_profile_rec;

@@ -17,11 +17,11 @@ EXPORTS = ["lp_net_create", "lp_net_destroy", "lp_net_param_bytes", "lp_net_num_
            "lp_local_loss_grad", "lp_module_backward", "lp_al_multiplier_update", "lp_aux_variable_update", "lp_auxnet_distill_grad", "lp_sgd_update", "lp_reauxnet_grad", "lp_net_set_stream_lanes", "lp_local_step", "lp_net_set_residual_output", "lp_net_set_deterministic",
            "lp_debug_im2col_offsets", "lp_debug_keep_gradients", "lp_debug_unit_count", "lp_debug_unit_info",
            "lp_debug_module_info", "lp_debug_filter_load_extent", "lp_debug_conv_geometry", "lp_debug_conv_offsets", "lp_debug_mfma_peak",
-           "lp_debug_saved_tensor", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
+           "lp_debug_saved_tensor", "lp_net_set_fused_update", "lp_profile_enable", "lp_profile_fetch", "lp_last_error", "lp_version"]
 
 KIND_NAMES = {0: "fill", 1: "filter_relayout", 2: "conv_igemm(fwd/dgrad)", 3: "bn_apply", 4: "maxpool_fwd", 5: "head_fwd",
               6: "head_bwd", 7: "maxpool_bwd", 8: "bn_bwd_reduce", 9: "bn_bwd_apply", 10: "conv_wgrad", 11: "bn_stats", 12: "loss", 13: "cross_entropy", 14: "multiplier_update",
-              15: "relu_mask"}
+              15: "relu_mask", 16: "sgd(small tensors)"}
 
 
 class lp_block_desc(ctypes.Structure):
@@ -113,6 +113,7 @@ def lib():
         L.lp_net_set_deterministic.argtypes = [c_void_p, c_int]
         L.lp_reauxnet_grad.argtypes = [c_void_p, c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, vpp]
         L.lp_sgd_update.argtypes = [c_void_p, c_void_p, c_int, c_uint32, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
+        L.lp_net_set_fused_update.argtypes = [c_void_p, c_int, c_float, c_float, c_float, vpp, vpp]
         L.lp_aux_variable_update.argtypes = [c_void_p, c_void_p, vpp, vpp, vpp, vpp, c_float, c_float, c_float]
         L.lp_debug_im2col_offsets.argtypes = [c_void_p] + [c_int] * 7 + [c_void_p, c_void_p, c_void_p, c_int]
         L.lp_debug_saved_tensor.argtypes = [c_void_p, c_int, c_int, POINTER(c_void_p), POINTER(c_size_t)]
@@ -280,6 +281,12 @@ def lp_sgd_update(net, stream, aux, mask, params, dparams, velocity, master, lr,
     _check(lib().lp_sgd_update(net, stream, int(aux), mask, _ptr_array(params), _ptr_array(dparams),
                                None if velocity is None else _ptr_array(velocity),
                                None if master is None else _ptr_array(master), float(lr), float(momentum), float(weight_decay)))
+
+
+def lp_net_set_fused_update(net, on, lr=0.0, momentum=0.0, weight_decay=0.0, velocity=None, master=None):
+    _check(lib().lp_net_set_fused_update(net, int(on), float(lr), float(momentum), float(weight_decay),
+                                         None if velocity is None else _ptr_array(velocity),
+                                         None if master is None else _ptr_array(master)))
 
 
 def lp_aux_variable_update(net, stream, x, y_prev, dx, lam_prev, rho, scale, eta):

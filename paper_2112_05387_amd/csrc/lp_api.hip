@@ -67,6 +67,9 @@ struct Bindings {
     float* loss = nullptr;
     const int32_t* labels = nullptr;
     float rho = 0.f, scale = 1.f, mstep = 0.f;
+    // parameter update inside the backward pass (lp_net_set_fused_update): per module, layout of dparams
+    float* const* vel = nullptr;
+    float* const* master = nullptr;
 };
 static void* resolve(const Ref& r, const Bindings& b) {
     switch (r.space) {
@@ -94,7 +97,7 @@ static void* resolve(const Ref& r, const Bindings& b) {
 }
 
 enum OpType { OP_FILL = 0, OP_WTRANS, OP_CONV, OP_BN_APPLY, OP_POOL_FWD, OP_HEAD_FWD, OP_HEAD_BWD, OP_POOL_BWD,
-              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE, OP_MULT_UNUSED, OP_RELU_MASK };
+              OP_BN_BWD_REDUCE, OP_BN_BWD_APPLY, OP_WGRAD, OP_BN_STATS, OP_LOSS, OP_CE, OP_MULT_UNUSED, OP_RELU_MASK, OP_SGD_REST };
 
 struct Op {
     int type = 0, cfg = 0;
@@ -161,6 +164,8 @@ struct ModulePlan {
     int t_hg = -1, t_hb = -1;              // pre-activation order: BN in front of the head
     size_t ws_hstats = 0, ws_hred = 0, ws_hf = 0, ws_ghead = 0, ws_gstem = 0;
     size_t ws_stats0 = 0, ws_stats_bytes = 0, ws_red0 = 0, ws_red_bytes = 0;
+    size_t ws_cnt0 = 0, ws_cnt_bytes = 0;  // completion tickets of the filter-gradient tiles (update in the epilogue)
+    std::vector<char> t_in_epilogue;       // per tensor: its update rides on a filter-gradient kernel
     size_t ws_G[2] = {0, 0}, ws_A = 0, ws_P = 0, ws_gpool = 0;
     Program fwd, bwd, bwd_dx0;             // bwd_dx0: variant that also produces dx for a stem-less module 0
     Program step, step_dx0;                // forward, loss / terminal adjoint, backward, multiplier update in one list
@@ -200,6 +205,10 @@ struct lp_net {
     bool lanes_ready = false;              // every extra stream and event above exists
     bool keep_gradients = false;           // debug layout: no gradient buffer is reused inside a backward pass
     bool deterministic = false;            // lp_net_set_deterministic: every reduction in a fixed order
+    // lp_net_set_fused_update: the parameter update runs inside lp_module_backward / lp_local_step
+    bool fused_update = false;
+    float fu_lr = 0.f, fu_momentum = 0.f, fu_wd = 0.f;
+    std::vector<float*> fu_vel, fu_master;
     float* r2 = nullptr;                   // optional device output [K-1]: |F_k(x_k) - x_{k+1}|^2 per interface (lp_net_set_residual_output)
     size_t scratch_bytes = 0;              // what the AuxNet forward passes need of the library's own device array
     // optional per-launch timing (hipEvents around every grouped launch)
@@ -442,6 +451,45 @@ struct WsAlloc {
     size_t off = 0;
     size_t take(size_t bytes) { const size_t o = off; off = align_up(off + std::max<size_t>(bytes, 16)); return o; }
 };
+
+// Parameter update inside the backward pass: every filter-gradient operation of module k that writes into dparams[k]
+// gets the filter it belongs to (r[4]) and a run of completion tickets in the workspace (r[3], one per output tile;
+// cleared by the step that clears the gradients); one last step updates the tensors no filter-gradient kernel owns
+// (BN affine, head).  The operations carry these references always; they are bound only while the update is switched on.
+static void attach_update(lp_net* net, int k, WsAlloc& ws) {
+    ModulePlan& m = net->mods[k];
+    m.t_in_epilogue.assign(m.tensors.size(), 0);
+    std::vector<size_t> cnt_off(m.tensors.size(), 0);
+    m.ws_cnt0 = ws.off;
+    bool first = true;
+    for (Program* P : {&m.bwd, &m.bwd_dx0}) {
+        for (Step& st : *P)
+            for (Op& o : st) {
+                if (o.type != OP_WGRAD || o.r[2].space != SP_DPARAM) continue;
+                int t = -1;
+                for (size_t i = 0; i < m.tensors.size(); ++i)
+                    if (m.tensors[i].kind == LP_T_CONV && m.tensors[i].grad_offset == o.r[2].off) t = (int)i;
+                if (t < 0) continue;
+                if (first) { cnt_off[t] = ws.take(sizeof(unsigned) * (size_t)o.wg.tiles_m * o.wg.tiles_n); m.t_in_epilogue[t] = 1; }
+                if (!m.t_in_epilogue[t]) continue;
+                o.r[3] = mk(SP_WS, 0, cnt_off[t]);
+                o.r[4] = mk(SP_PARAM, k, m.tensors[t].offset);
+            }
+        first = false;
+    }
+    m.ws_cnt_bytes = ws.off - m.ws_cnt0;
+    Builder B{net};
+    for (Program* P : {&m.bwd, &m.bwd_dx0}) {
+        if (P->empty()) continue;
+        for (Step& st : *P) {
+            bool clears_grads = false;
+            for (const Op& o : st) clears_grads = clears_grads || (o.type == OP_FILL && o.r[0].space == SP_DPARAM);
+            if (clears_grads) { if (m.ws_cnt_bytes) st.push_back(B.fill(mk(SP_WS, 0, m.ws_cnt0), m.ws_cnt_bytes)); break; }
+        }
+        Op o; o.type = OP_SGD_REST; o.r[0] = mk(SP_PARAM, k, 0);
+        P->push_back(Step{o});
+    }
+}
 
 // ---- build one module: units, tensors, workspace, programs ------------------------------------------------
 static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
@@ -781,6 +829,7 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
         }
         Bw.push_back(wg_tail);
     }
+    attach_update(net, k, ws);
     return LP_OK;
 }
 
@@ -1028,6 +1077,7 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
         if (m.has_stem) wg_tail.push_back(B.wgrad(m.stem, mk(SP_X, k, 0), W_(m.ws_gstem), grad_ref(m, k, m.stem.t_w)));
         Bw.push_back(wg_tail);
     }
+    attach_update(net, k, ws);
     return LP_OK;
 }
 
@@ -1408,10 +1458,18 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     const Op& o = *ops[base + i];
                     WgradProb& p = g.p[i];
                     p.x = resolve(o.r[0], b); p.dy = resolve(o.r[1], b); p.dw = (float*)resolve(o.r[2], b);
+                    p.w = nullptr; p.vel = nullptr; p.master = nullptr; p.cnt = nullptr;
+                    if (net->fused_update && o.r[4].space == SP_PARAM) {
+                        const int k = o.r[4].idx;
+                        p.w = resolve(o.r[4], b); p.cnt = (unsigned*)resolve(o.r[3], b);
+                        if (b.vel && b.vel[k]) p.vel = (float*)((char*)b.vel[k] + o.r[2].off);
+                        if (b.master && b.master[k]) p.master = (float*)((char*)b.master[k] + o.r[2].off);
+                    }
                     p.tile_start = tot;
                     tot += ops[base]->cfg == WGRAD_FAST ? wgrad_fast_blocks(p) : p.tiles_m * p.tiles_n * p.ksplit;
                 }
                 g.total_tiles = tot;
+                g.lr = net->fu_lr; g.momentum = net->fu_momentum; g.wd = net->fu_wd; g.lowp = dt == LP_BF16;
                 if (used_blocks) *used_blocks = tot;
                 err = ops[base]->cfg == WGRAD_FAST ? launch_wgrad_fast(g, s) : launch_wgrad(g, dt, ops[base]->cfg, ops[base]->vec, s);
             } break;
@@ -1460,6 +1518,28 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                 g.total_blocks = tot;
                 err = type == OP_BN_STATS ? launch_bn_stats(g, dt, s)
                       : type == OP_BN_BWD_REDUCE ? launch_bn_bwd_reduce(g, dt, s) : launch_bn_bwd_apply(g, dt, s);
+            } break;
+            case OP_SGD_REST: {
+                if (!net->fused_update) break;
+                SgdGroup g; g.nprob = 0; g.total_blocks = 0; g.lr = net->fu_lr; g.momentum = net->fu_momentum; g.wd = net->fu_wd;
+                for (int i = 0; i < n && err == hipSuccess; ++i) {
+                    const int k = ops[base + i]->r[0].idx;
+                    const ModulePlan& m = net->mods[k];
+                    for (size_t t = 0; t < m.tensors.size() && err == hipSuccess; ++t) {
+                        if (m.t_in_epilogue[t]) continue;
+                        const lp_tensor_info& ti = m.tensors[t];
+                        SgdProb& p = g.p[g.nprob];
+                        p.p = (char*)b.params[k] + ti.offset; p.lowp = ti.dtype == LP_BF16;
+                        p.g = (const float*)((const char*)b.dparams[k] + ti.grad_offset);
+                        p.v = (b.vel && b.vel[k]) ? (float*)((char*)b.vel[k] + ti.grad_offset) : nullptr;
+                        p.master = (b.master && b.master[k]) ? (float*)((char*)b.master[k] + ti.grad_offset) : nullptr;
+                        p.numel = ti.numel; p.block_start = g.total_blocks;
+                        p.nblocks = (int)((ti.numel + kSgdElemsPerBlock - 1) / kSgdElemsPerBlock);
+                        g.total_blocks += p.nblocks;
+                        if (++g.nprob == kMaxGroup) { err = launch_sgd(g, s); g.nprob = 0; g.total_blocks = 0; }
+                    }
+                }
+                if (g.nprob && err == hipSuccess) err = launch_sgd(g, s);
             } break;
             case OP_LOSS: {
                 LossGroup g; g.nprob = n; g.rho = b.rho; g.scale = b.scale; g.step = b.mstep; int tot = 0;
@@ -1818,6 +1898,26 @@ lp_status lp_net_set_deterministic(struct lp_net* net, int on) {
     return LP_OK;
 }
 
+lp_status lp_net_set_fused_update(struct lp_net* net, int on, float lr, float momentum, float weight_decay,
+                                  float* const* velocity, float* const* master) {
+    if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
+    if (!on) { net->fused_update = false; return LP_OK; }
+    if (momentum != 0.f && !velocity) return fail(LP_ERR_INVALID_ARG, "momentum != 0 needs velocity buffers");
+    std::vector<float*> vel(net->K, nullptr), mas(net->K, nullptr);
+    for (int k = 0; k < net->K; ++k) {
+        if (momentum != 0.f) {
+            if (!velocity[k]) return fail(LP_ERR_INVALID_ARG, "velocity[%d] is NULL", k);
+            vel[k] = velocity[k];
+        }
+        if (master) mas[k] = master[k];
+        if (misaligned(vel[k]) || misaligned(mas[k])) return fail(LP_ERR_INVALID_ARG, "parameter set %d: a buffer is not 16-byte aligned", k);
+    }
+    net->fu_vel = vel; net->fu_master = mas;
+    net->fu_lr = lr; net->fu_momentum = momentum; net->fu_wd = weight_decay;
+    net->fused_update = true;
+    return LP_OK;
+}
+
 lp_status lp_net_set_residual_output(struct lp_net* net, float* r2) {
     if (!net) return fail(LP_ERR_INVALID_ARG, "net is NULL");
     if (r2 && (reinterpret_cast<uintptr_t>(r2) & 3u)) return fail(LP_ERR_INVALID_ARG, "r2 is not 4-byte aligned");
@@ -2145,6 +2245,7 @@ lp_status lp_module_backward(struct lp_net* net, void* stream, uint32_t module_m
         progs.push_back(opt_dx ? &m.bwd_dx0 : &m.bwd);
     }
     Bindings b; b.ws = net->ws; b.x = net->saved_x.data(); b.params = params; b.dparams = dparams; b.dy = dy; b.dx = dx;
+    if (net->fused_update) { b.vel = net->fu_vel.data(); b.master = net->fu_master.data(); }
     b.dlogits = dlogits; b.y = net->saved_y.data();
     const std::vector<int> lanes = lanes_of(net, module_mask);
     st = run_programs(net, progs, b, (hipStream_t)stream, &lanes);
@@ -2185,6 +2286,7 @@ lp_status lp_local_step(struct lp_net* net, void* stream, uint32_t module_mask, 
     if (err != hipSuccess) return fail(LP_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(err));
     Bindings b; b.ws = net->ws; b.x = x; b.params = params; b.y = y; b.logits = logits;
     b.dparams = dparams; b.dy = dy; b.dx = dx; b.dlogits = dlogits;
+    if (net->fused_update) { b.vel = net->fu_vel.data(); b.master = net->fu_master.data(); }
     b.xnext = x_next; b.lam = lam; b.loss = loss; b.labels = labels; b.rho = rho; b.scale = loss_scale; b.mstep = mult_step;
     const std::vector<int> lanes = lanes_of(net, module_mask);
     st = run_programs(net, progs, b, s, &lanes);

@@ -200,18 +200,18 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
 
 // ------------------------------------------------------------------------------------------------
 // red[c] += sum g', red[C+c] += sum g'*yhat over this workgroup's rows
-template <typename T>
-__global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
+template <typename T, int NT>
+__global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
     constexpr int EPV = Vec<T>::N;
-    __shared__ float s_red[kElemBlock * EPV * 2];
+    __shared__ float s_red[NT * EPV * 2];
     const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M, cv = C / EPV;
     const int b = blockIdx.x - P.block_start;
     const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
     const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
-    for (int cbase = 0; cbase < cv; cbase += kElemBlock) {
-        const int ncv = min(cv - cbase, kElemBlock);     // channel vectors in this pass
-        const int rl = kElemBlock / ncv;                 // row lanes
+    for (int cbase = 0; cbase < cv; cbase += NT) {
+        const int ncv = min(cv - cbase, NT);     // channel vectors in this pass
+        const int rl = NT / ncv;                 // row lanes
         const int tcv = threadIdx.x % ncv, trl = threadIdx.x / ncv;
         float a1[EPV], a2[EPV];
 #pragma unroll
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_reduce_kernel(const BnBwdGr
             }
         }
         __syncthreads();
-        for (int i = threadIdx.x; i < ncv * EPV; i += kElemBlock) {
+        for (int i = threadIdx.x; i < ncv * EPV; i += NT) {
             float s1 = 0.f, s2 = 0.f;
             for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
             const int c = cbase * EPV + i;
@@ -832,7 +832,8 @@ hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hi
 }
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
-    LP_DISPATCH_T(dtype, bn_bwd_reduce_kernel, dim3(g.total_blocks), dim3(kElemBlock), s, g);
+    if (dtype == 1) hipLaunchKernelGGL((bn_bwd_reduce_kernel<bf16_t, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), 0, s, g);
+    else hipLaunchKernelGGL((bn_bwd_reduce_kernel<float, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), 0, s, g);
     return hipGetLastError();
 }
 hipError_t launch_bn_stats(const BnBwdGroup& g, int dtype, hipStream_t s) {

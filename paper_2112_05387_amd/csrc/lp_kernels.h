@@ -49,9 +49,17 @@ struct WgradProb {
     int ksplit, kchunk;
     int tiles_m, tiles_n, tile_start;
     unsigned mulW, shW, mulH, shH;   // fast division by IW and IH (wide-layer kernel)
+    // parameter update in the epilogue (w != NULL): the workgroup that adds the LAST partial sum of an output tile
+    // (ticket from cnt[tile], zero before the launch) reads the finished gradient tile back and updates the filter
+    void* w;                         // the filter itself, storage type of the activations, layout of dw
+    float* vel;                      // momentum buffer (NULL: none)
+    float* master;                   // fp32 copy of the filter (NULL: w is read)
+    unsigned* cnt;                   // tiles_m * tiles_n tickets
 };
 struct WgradGroup {
     int nprob, total_tiles;
+    float lr, momentum, wd;          // of the update in the epilogue
+    int lowp;                        // the filters are bf16
     WgradProb p[kMaxGroup];
 };
 
@@ -194,6 +202,7 @@ hipError_t launch_conv_offsets(const ConvProb& p, int kernel, int BM, int bk, in
 hipError_t launch_mfma_peak(int mode, int blocks, int iters, unsigned long long* clk, float* sink, hipStream_t s);
 
 constexpr int kElemBlock = 256;          // threads per workgroup of the elementwise kernels
+constexpr int kBnReduceBlock = 512;      // threads per workgroup of the BN backward reduction (measured: 256 -7 %, 1024 -20 %)
 constexpr int kElemVecsPerBlock = 2048;  // 16-byte vectors handled by one workgroup
 
 }  // namespace lp

@@ -109,4 +109,84 @@ __device__ __forceinline__ void mma_ktile(const T* __restrict__ As, const T* __r
     }
 }
 
+// Parameter update of a finished gradient tile by one workgroup of NT threads (epilogues of the filter-gradient
+// kernels):  g' = dW + wd * W;  v <- momentum * v + g';  W <- W - lr * (v or g')  -- the arithmetic of the parameter-update
+// kernel, element by element.  The tile is `nrows` runs of `ncols` consecutive elements; run q starts at element
+// row_start(q) of the filter / gradient / velocity / master tensors (all in the filter's [Cout][R][S][Cin] order).
+// Runs whose start and length are multiples of four go as 16-byte vectors (8 bytes of a bf16 filter), U vectors per
+// thread in flight: all loads of a trip first, then the arithmetic, then the stores.
+struct SgdCoef { float lr, momentum, wd; bool lowp; };
+
+// The gradient was accumulated by device-scope atomics of workgroups on other XCDs, i.e. at the memory side, past the
+// L2 of this XCD, which may still hold the line as the clearing kernel left it: read it at device scope as well.
+__device__ __forceinline__ float load_agent(const float* p) {
+    return __hip_atomic_load(const_cast<float*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ float sgd_step(float& v, float w, float grad, bool has_v, const SgdCoef& c) {
+    float d = fmaf(c.wd, w, grad);
+    if (has_v) { d = fmaf(c.momentum, v, d); v = d; }
+    return fmaf(-c.lr, d, w);
+}
+
+template <int NT, int U, typename RowStart>
+__device__ __forceinline__ void sgd_update_tile(void* __restrict__ w, float* __restrict__ vel, float* __restrict__ master,
+                                                const float* __restrict__ dw, int nrows, int ncols, bool vec4, RowStart row_start,
+                                                const SgdCoef& c, int tid) {
+    unsigned short* wl = reinterpret_cast<unsigned short*>(w);
+    float* wf = reinterpret_cast<float*>(w);
+    if (vec4) {
+        const int vpr = ncols >> 2, nvec = nrows * vpr;
+        for (int v0 = tid; v0 < nvec; v0 += NT * U) {
+            size_t idx[U]; bool ok[U];
+            f32x4 gr[U], x[U], vv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int v = v0 + u * NT;
+                ok[u] = v < nvec;
+                const int q = ok[u] ? v / vpr : 0, cv = ok[u] ? v - q * vpr : 0;
+                idx[u] = row_start(q) + 4 * (size_t)cv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) gr[u][e] = load_agent(dw + idx[u] + e);
+                if (master) x[u] = *reinterpret_cast<const f32x4*>(master + idx[u]);
+                else if (c.lowp) {
+                    const u32x2 r = *reinterpret_cast<const u32x2*>(wl + idx[u]);
+                    x[u][0] = __uint_as_float(r[0] << 16); x[u][1] = __uint_as_float(r[0] & 0xffff0000u);
+                    x[u][2] = __uint_as_float(r[1] << 16); x[u][3] = __uint_as_float(r[1] & 0xffff0000u);
+                } else x[u] = *reinterpret_cast<const f32x4*>(wf + idx[u]);
+                if (vel) vv[u] = *reinterpret_cast<const f32x4*>(vel + idx[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (!ok[u]) continue;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float ve = vel ? vv[u][e] : 0.f;
+                    x[u][e] = sgd_step(ve, x[u][e], gr[u][e], vel != nullptr, c);
+                    vv[u][e] = ve;
+                }
+                if (vel) *reinterpret_cast<f32x4*>(vel + idx[u]) = vv[u];
+                if (master) *reinterpret_cast<f32x4*>(master + idx[u]) = x[u];
+                if (c.lowp) {
+                    u32x2 r; r[0] = pack_bf16x2(x[u][0], x[u][1]); r[1] = pack_bf16x2(x[u][2], x[u][3]);
+                    *reinterpret_cast<u32x2*>(wl + idx[u]) = r;
+                } else *reinterpret_cast<f32x4*>(wf + idx[u]) = x[u];
+            }
+        }
+    } else {
+        const int n = nrows * ncols;
+        for (int i = tid; i < n; i += NT) {
+            const int q = i / ncols;
+            const size_t id = row_start(q) + (size_t)(i - q * ncols);
+            float x = master ? master[id] : (c.lowp ? bf16_bits_to_float(wl[id]) : wf[id]);
+            float ve = vel ? vel[id] : 0.f;
+            x = sgd_step(ve, x, load_agent(dw + id), vel != nullptr, c);
+            if (vel) vel[id] = ve;
+            if (master) master[id] = x;
+            if (c.lowp) wl[id] = float_to_bf16_bits(x);
+            else wf[id] = x;
+        }
+    }
+}
+
 }  // namespace lp

@@ -224,6 +224,14 @@ class LocalStep:
                         None if velocity is None else self._p(velocity), None if master is None else self._p(master),
                         lr, momentum, weight_decay)
 
+    def set_fused_update(self, on, lr=0.0, momentum=0.0, weight_decay=0.0, velocity=None, master=None):
+        """Parameter update inside the backward pass (in the epilogues of the filter-gradient kernels); `velocity` and
+        `master` are lists of K device tensors laid out like the gradients and must stay alive while it is on."""
+        self._fused_keep = (velocity, master)
+        B.lp_net_set_fused_update(self.net, on, lr, momentum, weight_decay,
+                                  None if velocity is None else self._p(velocity),
+                                  None if master is None else self._p(master))
+
     def aux_variable_update(self, rho, scale, eta):
         """x_k <- x_k - eta*(scale*(rho*(x_k - y_{k-1}) - lam_{k-1}) + dx_k) for k = 1..K-1 (in place)."""
         x = [None] + [t.data_ptr() for t in self.x[1:]]

@@ -189,6 +189,11 @@ def test_call_time_errors_without_touching_the_gpu():
         _expect(B.LP_ERR_INVALID_ARG, B.lp_sgd_update, h, None, 0, 1, [FAKE_PTR + 4, None], ptrs, None, None, 0.1, 0.0, 0.0)   # alignment
         _expect(B.LP_ERR_STATE, B.lp_sgd_update, h, None, 1, 1, ptrs, ptrs, None, None, 0.1, 0.0, 0.0)                  # no AuxNet
         _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_stream_lanes, h, [0, 7])
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_fused_update, h, 1, 0.1, 0.9, 0.0, None, None)          # momentum, no velocity
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_fused_update, h, 1, 0.1, 0.9, 0.0, [FAKE_PTR, None], None)   # velocity[1]
+        _expect(B.LP_ERR_INVALID_ARG, B.lp_net_set_fused_update, h, 1, 0.1, 0.0, 0.0, None, [FAKE_PTR + 4, None])   # alignment
+        B.lp_net_set_fused_update(h, 1, 0.1, 0.9, 5e-4, ptrs, [FAKE_PTR, None])
+        B.lp_net_set_fused_update(h, 0)
         _expect(B.LP_ERR_INVALID_ARG, B.lp_local_step, h, None, 3, ptrs, ptrs, ptrs[:1], ptrs[:1], None, 1.0, 1.0, 0.0, None,
                 FAKE_PTR, ptrs[:1], FAKE_PTR, FAKE_PTR, ptrs, ptrs)                                               # labels NULL
         _expect(B.LP_ERR_INVALID_ARG, B.lp_local_step, h, None, 0, ptrs, ptrs, ptrs[:1], ptrs[:1], None, 1.0, 1.0, 0.0, FAKE_PTR,

@@ -823,3 +823,145 @@ def test_conv_addresses_bit_exact(kernel, mode, shape, bk):
         np.testing.assert_array_equal(w_off, want_w)
         np.testing.assert_array_equal(out_off, want_out)
         assert mode == 1 or pad == 0 or (want_in < 0).any(), "the sample never touched the padding"
+
+
+def _read_params(ls, k):
+    """Stored parameters of module k as float64 arrays (bf16 tensors widened exactly)."""
+    import torch
+    from paper_2112_05387_amd import binding as B
+    out = []
+    for info in ls.tables[k]:
+        n = int(info.numel)
+        shape = tuple(info.dims[i] for i in range(info.ndim))
+        if info.dtype == B.LP_BF16:
+            t = ls.params[k][info.offset:info.offset + 2 * n].view(torch.bfloat16)
+        else:
+            t = ls.params[k][info.offset:info.offset + 4 * n].view(torch.float32)
+        out.append(ls.to_host(t).reshape(shape).astype(np.float64))
+    return out
+
+
+def _read_like_grads(ls, buf, k):
+    return [ls.to_host(buf[k][info.grad_offset // 4:info.grad_offset // 4 + int(info.numel)])
+            .reshape(tuple(info.dims[i] for i in range(info.ndim))).astype(np.float64) for info in ls.tables[k]]
+
+
+@pytest.mark.parametrize("case,momentum,wd,use_master,fused_call", [
+    ("basic_f32", 0.9, 5e-4, False, True), ("basic_bf16", 0.9, 5e-4, True, True), ("basic_bf16", 0.0, 0.0, False, False),
+    ("bottleneck_bf16", 0.9, 0.0, False, True), ("wide", 0.9, 5e-4, True, True), ("wide", 0.5, 0.0, False, False),
+    ("wide_strided", 0.9, 5e-4, False, True), ("wrn_batch_8", 0.9, 5e-4, True, True)])
+def test_update_inside_backward(case, momentum, wd, use_master, fused_call):
+    """The parameter update in the epilogues of the filter-gradient kernels (Sec. 4.1: W is updated right after the
+    adjoint at its layer): two local steps in a row with the update switched on.  After each step the oracle's update
+    rule, fed the parameters / velocity the device held before the step and the gradients the device wrote in that
+    step, gives the expected parameters, velocity and master copy of EVERY tensor (filters: updated by the workgroup
+    that completed a gradient tile; BN affine and head: by the small grouped launch behind the module)."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from paper_2112_05387_amd import binding as B
+    from tests.gpu_common import gpu_mini_wide_strided
+    from tests.gpu_unitwise import seeded_step_inputs
+    net = {"basic_f32": lambda: gpu_mini_basic(batch=3, dtype="f32"), "basic_bf16": lambda: gpu_mini_basic(batch=3, dtype="bf16"),
+           "bottleneck_bf16": lambda: gpu_mini_bottleneck(batch=2, dtype="bf16"), "wide": lambda: gpu_mini_wide(batch=3),
+           "wide_strided": lambda: gpu_mini_wide_strided(batch=5), "wrn_batch_8": lambda: wl.make_config("wrn28_10", batch=8)}[case]()
+    lr = 1.0        # large on purpose: every tensor's update must stand far above the comparison tolerance
+    say("case update inside backward", case, momentum, wd, "master" if use_master else "", "one call" if fused_call else "separate calls")
+    params, image, labels, xs, lams = seeded_step_inputs(net)
+    ls = LocalStep(net)
+    try:
+        for k in range(net.K):
+            ls.set_params(k, params[k])
+            ls.set_x(k, xs[k])
+        ls.set_lams(lams)
+        ls.set_labels(labels)
+        vel = [torch.zeros_like(d) for d in ls.dparams] if momentum else None
+        master = None
+        if use_master:
+            master = [torch.zeros_like(d) for d in ls.dparams]
+            for k in range(net.K):
+                for info, w in zip(ls.tables[k], params[k]):
+                    o = info.grad_offset // 4
+                    master[k][o:o + int(info.numel)].copy_(torch.from_numpy(np.asarray(w, np.float32).reshape(-1)))
+        ls.set_fused_update(True, lr, momentum, wd, velocity=vel, master=master)
+        worst = {"param": 0.0, "velocity": 0.0, "master": 0.0}
+        smallest = 1e30
+        for it in range(2):
+            before_w = [(_read_like_grads(ls, master, k) if use_master else _read_params(ls, k)) for k in range(net.K)]
+            before_v = [(_read_like_grads(ls, vel, k) if momentum else None) for k in range(net.K)]
+            if fused_call:
+                ls.local_step(net.rho, 1.0)
+            else:
+                ls.module_forward()
+                ls.local_loss_grad(net.rho, 1.0)
+                ls.module_backward()
+            torch.cuda.synchronize()
+            for k in range(net.K):
+                grads = ls.get_grads(k)
+                after_w = _read_params(ls, k)
+                after_v = _read_like_grads(ls, vel, k) if momentum else None
+                after_m = _read_like_grads(ls, master, k) if use_master else None
+                for i, info in enumerate(ls.tables[k]):
+                    w_new, v_new = lpref.sgd_update(before_w[k][i], grads[i].astype(np.float64), lr,
+                                                    before_v[k][i] if momentum else None, momentum, wd)
+                    tol = 4e-3 if info.dtype == B.LP_BF16 else 1e-6        # bf16 parameters: one rounding of the stored value
+                    e = rel_err(after_w[i], w_new)
+                    assert e <= tol, (case, it, k, i, "parameter", e)
+                    worst["param"] = max(worst["param"], e)
+                    # the step must be large against the tolerance, or a missing update would pass
+                    step_size = float(np.max(np.abs(w_new - before_w[k][i])) / np.max(np.abs(w_new)))
+                    assert step_size >= 5 * tol, (case, it, k, i, "update too small for the check to mean anything", step_size)
+                    smallest = min(smallest, step_size)
+                    if momentum:
+                        e = rel_err(after_v[i], v_new)
+                        assert e <= 1e-6, (case, it, k, i, "velocity", e)
+                        worst["velocity"] = max(worst["velocity"], e)
+                    if use_master:
+                        e = rel_err(after_m[i], w_new)
+                        assert e <= 1e-6, (case, it, k, i, "master", e)
+                        worst["master"] = max(worst["master"], e)
+        say(f"    update inside backward, {case}: worst parameter {worst['param']:.2e}, velocity {worst['velocity']:.2e}, master {worst['master']:.2e}; "
+            f"smallest update of a tensor {smallest:.1e} of its magnitude")
+    finally:
+        ls.close()
+
+
+def test_update_inside_backward_deterministic_bit_identical():
+    """In the deterministic mode (unsplit filter gradients) the update inside the backward pass equals the step followed
+    by lp_sgd_update bit for bit: parameters, velocity and master copy."""
+    import torch
+    from paper_2112_05387_amd import LocalStep
+    from paper_2112_05387_amd import binding as B
+    from tests.gpu_unitwise import seeded_step_inputs
+    net = gpu_mini_wide(batch=3)
+    lr, momentum, wd = 0.05, 0.9, 5e-4
+    params, image, labels, xs, lams = seeded_step_inputs(net)
+    res = []
+    for inside in (False, True):
+        ls = LocalStep(net)
+        try:
+            B.lp_net_set_deterministic(ls.net, 1)
+            for k in range(net.K):
+                ls.set_params(k, params[k])
+                ls.set_x(k, xs[k])
+            ls.set_lams(lams)
+            ls.set_labels(labels)
+            vel = [torch.zeros_like(d) for d in ls.dparams]
+            master = [torch.zeros_like(d) for d in ls.dparams]
+            for k in range(net.K):
+                for info, w in zip(ls.tables[k], params[k]):
+                    o = info.grad_offset // 4
+                    master[k][o:o + int(info.numel)].copy_(torch.from_numpy(np.asarray(w, np.float32).reshape(-1)))
+            if inside:
+                ls.set_fused_update(True, lr, momentum, wd, velocity=vel, master=master)
+            for it in range(2):
+                ls.local_step(net.rho, 1.0)
+                if not inside:
+                    ls.sgd_update(lr, momentum, wd, velocity=vel, master=master)
+            torch.cuda.synchronize()
+            res.append(([p.cpu().clone() for p in ls.params], [v.cpu().clone() for v in vel], [m.cpu().clone() for m in master]))
+        finally:
+            ls.close()
+    for name, a, b in zip(("parameters", "velocity", "master"), res[0], res[1]):
+        for k in range(net.K):
+            assert torch.equal(a[k], b[k]), (name, k)
+    say("    update inside backward, deterministic mode: bit-identical to step + lp_sgd_update over two steps")
