@@ -323,10 +323,13 @@ def main():
     conv_flops = sum(a["flops"] for (k, _), a in agg.items() if k in (2, 10))
     (dk, dcfg), dom = max(agg.items(), key=lambda kv: kv[1]["ms"])
     peak = PEAK_TFLOPS[net.dtype]
-    if dk in (2, 10):
+    # a convolution whose algorithmic intensity lies under the ridge of its dtype (peak flop/s over peak bytes/s: 312 flop/B
+    # in bf16, 20 in fp32) is bounded by HBM, like the elementwise passes: the 16- and 32-channel layers of ResNet-20 / -56
+    ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if dk in (2, 10) and dom["flops"] >= ridge * dom["bytes"]:
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak}
-        if dom["cu_ms"] > 0:
+        if dom["cu_ms"] > 0 and dcfg >= 8:       # the direct-to-LDS kernels: one workgroup per compute unit
             # a lane's launch is sized to share the chip with the other lanes: workgroups per launch, and the rate per
             # compute unit it occupies (one workgroup per CU) against a CU's share of the peak
             roof["workgroups_per_launch"] = dom["blocks"] / dom["launches"]
