@@ -1331,6 +1331,7 @@ static hipError_t launch_group(lp_net* net, std::vector<const Op*>& ops, const B
     hipError_t err = hipSuccess;
     for (size_t base = 0; base < ops.size() && err == hipSuccess; base += kMaxGroup) {
         const int n = (int)std::min<size_t>(kMaxGroup, ops.size() - base);
+        if (ops[base]->type == OP_SGD_REST && !net->fused_update) continue;      // nothing to launch, nothing to record
         if (!net->prof) { err = launch_group_impl(net, ops, base, n, b, s, nullptr, nullptr); continue; }
         lp_net::ProfRec r;
         r.type = ops[base]->type; r.cfg = ops[base]->cfg; r.nprob = n; r.blocks = 0; r.flops = 0; r.bytes = 0;

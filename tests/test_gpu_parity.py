@@ -757,6 +757,7 @@ ADDRESS_CASES = [
     (2, 0, (4, 32, 32, 160, 160, 3, 1, 1), 64), (2, 1, (4, 32, 32, 160, 160, 3, 1, 1), 64), (2, 0, (8, 16, 16, 320, 320, 3, 1, 1), 64),
     (2, 1, (8, 16, 16, 320, 320, 3, 1, 1), 64), (2, 0, (16, 8, 8, 640, 640, 3, 1, 1), 64), (2, 1, (16, 8, 8, 640, 640, 3, 1, 1), 64),
     (2, 0, (4, 32, 32, 160, 320, 3, 1, 1), 64), (2, 1, (4, 32, 32, 320, 160, 3, 1, 1), 64),
+    (2, 0, (4, 32, 32, 32, 160, 3, 1, 1), 64),      # one (half) slab of 32 channels
 ]
 
 
