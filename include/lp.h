@@ -347,17 +347,19 @@ lp_status lp_debug_saved_tensor(const struct lp_net* net, int k, int which, cons
 /* Unit-by-unit views of a module in the conv-BN-ReLU order, for layer-wise checks (debug; read-only descriptions,
  * host only).  A unit is one convolution with the batch norm behind it.  Every tensor is named by a reference: the
  * caller's tensor of the last call (x[idx], y[idx], dy[idx], dx[idx]) or a byte offset into the workspace.
- *   forward:   in --conv--> y (pre-BN, stored) ; stats = per-channel [sum, sum of squares] of y (fp64 [2*cout]);
+ *   forward:   in --conv--> y (pre-BN, stored) ; stats = per-channel [sum, sum of squares] of y, kept as LP_STAT_STRIPES
+ *              partial sums that add up to it (fp64 [LP_STAT_STRIPES][2*cout]);
  *              out = [ReLU]( BN(y) [+ skip | + BN(y of unit skip_unit) | + y of a plain unit skip_unit] ), written by
  *              the unit's BN-apply pass (ReLU: the unit's own `relu`, or `post_relu` on the last unit of a block)
  *              (the projection unit has none: its BN is applied inside the pass of the block's last unit);
  *   backward:  gout = gradient arriving at the unit's BN output; dy = gradient on y (BN backward, stored);
- *              red = per-channel [sum g', sum g'*yhat] (fp64 [2*cout]); din = the unit's data-gradient
+ *              red = per-channel [sum g', sum g'*yhat] (fp64 [LP_STAT_STRIPES][2*cout], partial sums as above); din = the unit's data-gradient
  *              (+ din_add, the skip-path gradient added in its epilogue), present when has_dgrad.
  * Gradient buffers are reused from block to block inside a backward pass unless the net was created after
  * lp_debug_keep_gradients(1) (a per-thread switch read by lp_net_create: every gradient then has a buffer of its own;
  * the workspace grows, kernels and launches are the same).  The views describe the backward program without dx[0]. */
 enum { LP_REF_NONE = 0, LP_REF_WORKSPACE = 1, LP_REF_X = 2, LP_REF_Y = 3, LP_REF_DY = 4, LP_REF_DX = 5 };
+#define LP_STAT_STRIPES 8
 typedef struct { int space; int idx; size_t off; } lp_debug_ref;
 typedef struct {
     int block, slot;             /* block -1: stem; slot 0..2 main path, 3 projection */

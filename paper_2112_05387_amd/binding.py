@@ -36,6 +36,7 @@ class lp_module_desc(ctypes.Structure):
 
 
 LP_AUX_MAX_DEPTH = 8
+LP_STAT_STRIPES = 8          # per-channel sums are kept as this many partial sums (debug views)
 
 
 class lp_aux_desc(ctypes.Structure):

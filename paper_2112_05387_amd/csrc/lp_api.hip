@@ -222,6 +222,8 @@ struct lp_net {
 
 namespace {
 
+static_assert(kStatStripes == LP_STAT_STRIPES, "the header documents the layout of the per-channel sums");
+
 static size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // the wide-layer bf16 kernel applies when a k-tile of 32 channels lies inside one tap and offsets fit 31 bits
@@ -586,10 +588,10 @@ static lp_status build_module(lp_net* net, int k, WsAlloc& ws) {
         if (bp.has_proj) units.push_back(&bp.proj);
     }
     m.ws_stats0 = ws.off;
-    for (Unit* u : units) u->ws_stats = ws.take(sizeof(double) * 2 * u->cout);
+    for (Unit* u : units) u->ws_stats = ws.take(stat_bytes(u->cout));
     m.ws_stats_bytes = ws.off - m.ws_stats0;
     m.ws_red0 = ws.off;
-    for (Unit* u : units) u->ws_red = ws.take(sizeof(double) * 2 * u->cout);
+    for (Unit* u : units) u->ws_red = ws.take(stat_bytes(u->cout));
     m.ws_red_bytes = ws.off - m.ws_red0;
     size_t maxD = 0, maxA = 0, maxG = 0, maxP = 0;
     for (Unit* u : units) {
@@ -919,12 +921,12 @@ static lp_status build_module_pre(lp_net* net, int k, WsAlloc& ws) {
     const bool first_block_dx_optional = (k == 0 && !m.has_stem);
     const size_t nb = m.bp.size();
     m.ws_stats0 = ws.off;
-    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_stats = ws.take(sizeof(double) * 2 * u.cin);
-    if (last) m.ws_hstats = ws.take(sizeof(double) * 2 * C);
+    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_stats = ws.take(stat_bytes(u.cin));
+    if (last) m.ws_hstats = ws.take(stat_bytes(C));
     m.ws_stats_bytes = ws.off - m.ws_stats0;
     m.ws_red0 = ws.off;
-    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_red = ws.take(sizeof(double) * 2 * u.cin);
-    if (last) m.ws_hred = ws.take(sizeof(double) * 2 * C);
+    for (auto& bp : m.bp) for (auto& u : bp.main) u.ws_red = ws.take(stat_bytes(u.cin));
+    if (last) m.ws_hred = ws.take(stat_bytes(C));
     m.ws_red_bytes = ws.off - m.ws_red0;
     if (m.has_stem) {
         m.ws_stem_act = ws.take(m.stem.out_elems() * esz);      // the bare stem output = input of the first block
@@ -1160,8 +1162,8 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     us.push_back(&a.u);
     for (int i = 0; i < depth; ++i) {
         Unit& u = *us[i];
-        u.ws_stats = ws.take(sizeof(double) * 2 * u.cout);
-        u.ws_red = ws.take(sizeof(double) * 2 * u.cout);
+        u.ws_stats = ws.take(stat_bytes(u.cout));
+        u.ws_red = ws.take(stat_bytes(u.cout));
         u.ws_y = ws.take(u.out_elems() * net->esz);
         u.ws_dy = ws.take(u.out_elems() * net->esz);
         if (i > 0) u.ws_wt = ws.take((size_t)u.cout * 9 * u.cin * net->esz);
@@ -1188,7 +1190,7 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
         }
     };
     auto fill_stats = [&](Step& s) {
-        for (int i = 0; i < depth; ++i) s.push_back(B.fill(W_(us[i]->ws_stats), sizeof(double) * 2 * us[i]->cout));
+        for (int i = 0; i < depth; ++i) s.push_back(B.fill(W_(us[i]->ws_stats), stat_bytes(us[i]->cout)));
     };
     const Ref in0 = a.chained ? mk(SP_XOUT, j - 1, 0) : mk(SP_IMAGE, 0, 0);
     {
@@ -1202,14 +1204,14 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
         WsAlloc sc; sc.off = net->scratch_bytes;
         std::vector<size_t> s_stats(depth), s_y(depth), s_act(depth, 0);
         for (int i = 0; i < depth; ++i) {
-            s_stats[i] = sc.take(sizeof(double) * 2 * us[i]->cout);
+            s_stats[i] = sc.take(stat_bytes(us[i]->cout));
             s_y[i] = sc.take(us[i]->out_elems() * net->esz);
             if (i + 1 < depth) s_act[i] = sc.take(us[i]->out_elems() * net->esz);
         }
         net->scratch_bytes = sc.off;
         auto S_ = [&](size_t off) { return mk(SP_SCRATCH, 0, off); };
         Step s0;
-        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(S_(s_stats[i]), sizeof(double) * 2 * us[i]->cout));
+        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(S_(s_stats[i]), stat_bytes(us[i]->cout)));
         a.fwd_static.push_back(s0);
         for (int i = 0; i < depth; ++i) {
             const Unit& u = *us[i];
@@ -1225,7 +1227,7 @@ static lp_status build_aux(lp_net* net, int j, WsAlloc& ws) {
     const Ref din = a.chained ? mk(SP_XTGT, j - 1, 0) : mk(SP_IMAGE, 0, 0);
     {
         Step s0{B.fill(mk(SP_AUXG, j, 0), a.grad_bytes)};
-        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(W_(us[i]->ws_red), sizeof(double) * 2 * us[i]->cout));
+        for (int i = 0; i < depth; ++i) s0.push_back(B.fill(W_(us[i]->ws_red), stat_bytes(us[i]->cout)));
         if (a.chained) fill_stats(s0);
         for (int i = 1; i < depth; ++i) s0.push_back(B.wtrans(*us[i], P_(us[i]->t_w), W_(us[i]->ws_wt)));
         a.bwd_a.push_back(s0);

@@ -28,8 +28,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     static_assert(TM % MT == 0 && TN % MT == 0, "wave tile must be whole micro-tiles");
     typedef typename AccT<MT>::type acc_t;
 
-    __shared__ __attribute__((aligned(16))) T As[2][BM * PITCH];
-    __shared__ __attribute__((aligned(16))) T Bs[2][BN * PITCH];
+    // both operands' double buffers in one array: the epilogue stages the result tile over it
+    __shared__ __attribute__((aligned(16))) T s_ab[2 * (BM + BN) * PITCH];
+    T* const As0 = s_ab;                               // As[buf] = As0 + buf * BM * PITCH
+    T* const Bs0 = s_ab + 2 * BM * PITCH;              // Bs[buf] = Bs0 + buf * BN * PITCH
     __shared__ int s_rowoff[BM];
 
     // ---- which problem, which tile ------------------------------------------------------------
@@ -143,13 +145,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
         for (int i = 0; i < A_PER_T; ++i) {
             const int v = tid + i * NT;
             if (A_VECS % NT == 0 || v < A_VECS)
-                *reinterpret_cast<u32x4*>(&As[buf][(v / VPR) * PITCH + kv * EPV]) = a_reg[i];
+                *reinterpret_cast<u32x4*>(As0 + buf * (BM * PITCH) + (v / VPR) * PITCH + kv * EPV) = a_reg[i];
         }
 #pragma unroll
         for (int i = 0; i < B_PER_T; ++i) {
             const int v = tid + i * NT;
             if (B_VECS % NT == 0 || v < B_VECS)
-                *reinterpret_cast<u32x4*>(&Bs[buf][(v / VPR) * PITCH + kv * EPV]) = b_reg[i];
+                *reinterpret_cast<u32x4*>(Bs0 + buf * (BN * PITCH) + (v / VPR) * PITCH + kv * EPV) = b_reg[i];
         }
     };
 
@@ -171,12 +173,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         if (kt + 1 < nk) load_tile((kt + 1) * BK);
-        mma_ktile<T, MT, FM, FN, BK, PITCH>(As[cur], Bs[cur], wm * TM, wn * TN, lane, acc);
+        mma_ktile<T, MT, FM, FN, BK, PITCH>(As0 + cur * (BM * PITCH), Bs0 + cur * (BN * PITCH), wm * TM, wn * TN, lane, acc);
         if (kt + 1 < nk) store_tile(cur ^ 1);
         __syncthreads();
     }
 
     // ---- epilogue: [+ addends] -> store; per-column sum / sum of squares -------------------------------
+    // Every wave passes its result through a private LDS slice, one micro-tile row (MT pixels x TN channels) at a time:
+    // the accumulators go in as they lie in the registers (a lane holds single elements of 4 or 16 pixels), and come out
+    // as 16-byte vectors along the channels, so that addends are loaded and results stored with one 16-byte access per
+    // lane instead of one 2- or 4-byte access per element (each of which the compiler followed by a full wait: the
+    // addend loads of a data-gradient ran one after another).  The rounded values go back into the slice, where each lane
+    // picks up its own elements again for the batch statistics, which describe the values as stored.
     T* __restrict__ out = reinterpret_cast<T*>(P.out);
     const T* __restrict__ add0 = reinterpret_cast<const T*>(P.add0);
     const T* __restrict__ add1 = reinterpret_cast<const T*>(P.add1);
@@ -184,31 +192,116 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     float cs1[FN], cs2[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) { cs1[j] = 0.f; cs2[j] = 0.f; }
+    constexpr int SP = TN + 4;                          // floats per slice row (16-byte aligned, staggers the banks)
+    constexpr int G = TN / EPV;                         // output vectors per row
+    constexpr int ITEMS = MT * G, IPL = (ITEMS + 63) / 64;
+    static_assert(TN % EPV == 0, "wave tile columns must be whole vectors");
+    static_assert((size_t)WGM * WGN * MT * SP * sizeof(float) <= sizeof(s_ab), "result slices must fit the operand buffers");
+    float* const slice = reinterpret_cast<float*>(s_ab) + wave * (MT * SP);
+    if (P.Ncol % EPV == 0) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < FM; ++i) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = n0 + wn * TN + j * MT + lc;
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int r = 0; r < AccT<MT>::N; ++r) {
-                const int row = wm * TM + i * MT + acc_row<MT>(r, lane);
-                const int ro = s_rowoff[row];
-                float v = acc[i][j][r];
-                if (ro >= 0 && col < P.Ncol) {
-                    const size_t o = (size_t)ro + col;
-                    if (add0) v += to_float(add0[o]);
-                    if (add1) v += to_float(add1[o]);
-                    const T st = from_float<T>(v);
-                    out[o] = st;
-                    // the batch statistics describe the values as stored (addends included, rounded to T)
-                    const float vs = to_float(st);
-                    cs1[j] += vs;
-                    cs2[j] += vs * vs;
+                for (int r = 0; r < AccT<MT>::N; ++r) slice[acc_row<MT>(r, lane) * SP + j * MT + lc] = acc[i][j][r];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // all addend loads of this row first (a vector that does not exist reads element 0 and is dropped)
+            u32x4 a0[IPL], a1[IPL];
+            size_t off[IPL];
+            bool ok[IPL];
+#pragma unroll
+            for (int t = 0; t < IPL; ++t) {
+                const int item = lane + 64 * t;
+                const int row = item / G, grp = item - row * G;
+                const int ro = (ITEMS % 64 == 0 || item < ITEMS) ? s_rowoff[wm * TM + i * MT + row] : -1;
+                const int col = n0 + wn * TN + grp * EPV;
+                ok[t] = ro >= 0 && col < P.Ncol;
+                off[t] = ok[t] ? (size_t)ro + col : (size_t)0;
+                if (add0) a0[t] = *reinterpret_cast<const u32x4*>(add0 + off[t]);
+                if (add1) a1[t] = *reinterpret_cast<const u32x4*>(add1 + off[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < IPL; ++t) {
+                if (!ok[t]) continue;
+                const int item = lane + 64 * t;
+                const int row = item / G, grp = item - row * G;
+                float* sp = slice + row * SP + grp * EPV;
+                float v[EPV];
+#pragma unroll
+                for (int e = 0; e < EPV; e += 4) {
+                    const f32x4 q = *reinterpret_cast<const f32x4*>(sp + e);
+                    v[e] = q[0]; v[e + 1] = q[1]; v[e + 2] = q[2]; v[e + 3] = q[3];
+                }
+                u32x4 st;
+                if constexpr (sizeof(T) == 4) {
+                    if (add0) { const f32x4 a = __builtin_bit_cast(f32x4, a0[t]); v[0] += a[0]; v[1] += a[1]; v[2] += a[2]; v[3] += a[3]; }
+                    if (add1) { const f32x4 a = __builtin_bit_cast(f32x4, a1[t]); v[0] += a[0]; v[1] += a[1]; v[2] += a[2]; v[3] += a[3]; }
+                    st = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (add0) { v[2 * e] += __uint_as_float(a0[t][e] << 16); v[2 * e + 1] += __uint_as_float(a0[t][e] & 0xffff0000u); }
+                        if (add1) { v[2 * e] += __uint_as_float(a1[t][e] << 16); v[2 * e + 1] += __uint_as_float(a1[t][e] & 0xffff0000u); }
+                        st[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+                        v[2 * e] = __uint_as_float(st[e] << 16); v[2 * e + 1] = __uint_as_float(st[e] & 0xffff0000u);
+                    }
+                }
+                *reinterpret_cast<u32x4*>(out + off[t]) = st;
+#pragma unroll
+                for (int e = 0; e < EPV; e += 4) *reinterpret_cast<f32x4*>(sp + e) = f32x4{v[e], v[e + 1], v[e + 2], v[e + 3]};
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (P.stats) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int col = n0 + wn * TN + j * MT + lc;
+#pragma unroll
+                    for (int r = 0; r < AccT<MT>::N; ++r) {
+                        const int prow = acc_row<MT>(r, lane);
+                        if (s_rowoff[wm * TM + i * MT + prow] >= 0 && col < P.Ncol) {
+                            const float vs = slice[prow * SP + j * MT + lc];
+                            cs1[j] += vs;
+                            cs2[j] += vs * vs;
+                        }
+                    }
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
+    } else {
+        // output channel counts that are no multiple of a vector: element by element
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn * TN + j * MT + lc;
+#pragma unroll
+                for (int r = 0; r < AccT<MT>::N; ++r) {
+                    const int row = wm * TM + i * MT + acc_row<MT>(r, lane);
+                    const int ro = s_rowoff[row];
+                    float v = acc[i][j][r];
+                    if (ro >= 0 && col < P.Ncol) {
+                        const size_t o = (size_t)ro + col;
+                        if (add0) v += to_float(add0[o]);
+                        if (add1) v += to_float(add1[o]);
+                        const T st = from_float<T>(v);
+                        out[o] = st;
+                        const float vs = to_float(st);
+                        cs1[j] += vs;
+                        cs2[j] += vs * vs;
+                    }
+                }
+            }
+    }
+    __syncthreads();                                    // the slices are done with before the statistics reuse the buffer
     if (P.stats) {
-        float* red = reinterpret_cast<float*>(&As[0][0]);      // [WGM][BN][2], operands are dead by now
+        float* red = reinterpret_cast<float*>(s_ab);           // [WGM][BN][2], operands and slices are dead by now
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             float s1 = cs1[j], s2 = cs2[j];
@@ -230,8 +323,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
                 float s1 = 0.f, s2 = 0.f;
 #pragma unroll
                 for (int w = 0; w < WGM; ++w) { s1 += red[(w * BN + c) * 2]; s2 += red[(w * BN + c) * 2 + 1]; }
-                atomicAdd(&P.stats[col], (double)s1);
-                atomicAdd(&P.stats[P.Ncol + col], (double)s2);
+                double* st = P.stats + (size_t)(blockIdx.x % stat_stripes(P.Ncol)) * 2 * P.Ncol;      // this workgroup's stripe
+                atomicAdd(&st[col], (double)s1);
+                atomicAdd(&st[P.Ncol + col], (double)s2);
             }
         }
     }

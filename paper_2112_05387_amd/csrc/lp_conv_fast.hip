@@ -366,8 +366,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void conv_igemm_fast_kernel(const C
                         const int idx = ((((w * WGN + wn_c) * 3 + q) * TN) + cc) * 2;
                         a1 += red[idx]; a2 += red[idx + 1];
                     }
-                atomicAdd(&P.stats[col], (double)a1);
-                atomicAdd(&P.stats[P.Ncol + col], (double)a2);
+                double* st = P.stats + (size_t)(blockIdx.x % stat_stripes(P.Ncol)) * 2 * P.Ncol;      // this workgroup's stripe
+                atomicAdd(&st[col], (double)a1);
+                atomicAdd(&st[P.Ncol + col], (double)a2);
             }
         }
     }

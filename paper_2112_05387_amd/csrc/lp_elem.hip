@@ -55,8 +55,11 @@ template <typename T> struct Vec {
 __device__ __forceinline__ void bn_coeffs(const double* stats, const float* gamma, const float* beta, int c, int C,
                                           int M, float eps, float& sc, float& sh, float& mean, float& invstd) {
     const double inv_m = 1.0 / (double)M;          // the same for every channel: the compiler hoists it out of loops
-    const double mu = stats[c] * inv_m;
-    double var = stats[C + c] * inv_m - mu * mu;
+    double s1 = 0.0, s2 = 0.0;
+    const int ns = stat_stripes(C);
+    for (int st = 0; st < ns; ++st) { s1 += stats[st * 2 * C + c]; s2 += stats[st * 2 * C + C + c]; }
+    const double mu = s1 * inv_m;
+    double var = s2 * inv_m - mu * mu;
     if (var < 0.0) var = 0.0;
     mean = (float)mu;
     invstd = rsqrtf((float)var + eps);
@@ -204,11 +207,24 @@ template <typename T, int NT>
 __global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
     constexpr int EPV = Vec<T>::N;
     __shared__ float s_red[NT * EPV * 2];
+    // per-channel coefficients, computed once per workgroup (4 arrays of g.cmax floats, sized by the launch)
+    extern __shared__ __attribute__((aligned(16))) float s_coef[];
+    const int cm = 4 * (g.cmax >> 2);
+    float* s_sc = s_coef;
+    float* s_sh = s_coef + cm;
+    float* s_mu = s_coef + 2 * cm;
+    float* s_is = s_coef + 3 * cm;
     const BnBwdProb& P = g.p[find_problem(g, blockIdx.x)];
     const int C = P.C, M = P.M, cv = C / EPV;
     const int b = blockIdx.x - P.block_start;
     const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
     const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    for (int c = threadIdx.x; c < C; c += NT) {
+        float sc, sh, mu, is;
+        bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
+        s_sc[c] = sc; s_sh[c] = sh; s_mu[c] = mu; s_is[c] = is;
+    }
+    __syncthreads();
     for (int cbase = 0; cbase < cv; cbase += NT) {
         const int ncv = min(cv - cbase, NT);     // channel vectors in this pass
         const int rl = NT / ncv;                 // row lanes
@@ -220,7 +236,7 @@ __global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
             const int c0 = (cbase + tcv) * EPV;
             float sc[EPV], sh[EPV], mu[EPV], is[EPV];
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) bn_coeffs(P.stats, P.gamma, P.beta, c0 + e, C, M, g.eps, sc[e], sh[e], mu[e], is[e]);
+            for (int e = 0; e < EPV; ++e) { sc[e] = s_sc[c0 + e]; sh[e] = s_sh[c0 + e]; mu[e] = s_mu[c0 + e]; is[e] = s_is[c0 + e]; }
             // Four rows per trip: eight independent 16-byte loads in flight per thread.  The trips of the blocks are
             // interleaved (block b takes trips b, b + nblocks, ...), so that at any time the blocks together read one
             // contiguous, moving window of the two tensors instead of nblocks distant streams.
@@ -265,8 +281,9 @@ __global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
             float s1 = 0.f, s2 = 0.f;
             for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
             const int c = cbase * EPV + i;
-            atomicAdd(&P.red[c], (double)s1);
-            atomicAdd(&P.red[C + c], (double)s2);
+            double* red = P.red + (size_t)(blockIdx.x % stat_stripes(C)) * 2 * C;
+            atomicAdd(&red[c], (double)s1);
+            atomicAdd(&red[C + c], (double)s2);
         }
     }
 }
@@ -322,8 +339,9 @@ __global__ __launch_bounds__(kElemBlock) void bn_stats_kernel(const BnBwdGroup g
             float s1 = 0.f, s2 = 0.f;
             for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
             const int c = cbase * EPV + i;
-            atomicAdd(&P.red[c], (double)s1);
-            atomicAdd(&P.red[C + c], (double)s2);
+            double* red = P.red + (size_t)(blockIdx.x % stat_stripes(C)) * 2 * C;
+            atomicAdd(&red[c], (double)s1);
+            atomicAdd(&red[C + c], (double)s2);
         }
     }
 }
@@ -347,14 +365,16 @@ __global__ __launch_bounds__(kElemBlock) void bn_bwd_apply_kernel(const BnBwdGro
         float sc, sh, mu, is;
         bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
         const double inv_m = 1.0 / (double)M;
-        const float r0 = (float)(P.red[c] * inv_m), r1 = (float)(P.red[C + c] * inv_m);
+        double rs0 = 0.0, rs1 = 0.0;
+        for (int st = 0; st < stat_stripes(C); ++st) { rs0 += P.red[st * 2 * C + c]; rs1 += P.red[st * 2 * C + C + c]; }
+        const float r0 = (float)(rs0 * inv_m), r1 = (float)(rs1 * inv_m);
         const float k1 = P.gamma[c] * is;
         const float k2 = k1 * is * r1;
         s_sc[c] = sc; s_sh[c] = sh;
         s_k1[c] = k1; s_k2[c] = k2; s_k3[c] = k2 * mu - k1 * r0;
         if (first) {
-            P.dgamma[c] = (float)P.red[C + c];
-            P.dbeta[c] = (float)P.red[c];
+            P.dgamma[c] = (float)rs1;
+            P.dbeta[c] = (float)rs0;
         }
     }
     __syncthreads();
@@ -832,8 +852,9 @@ hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hi
 }
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
-    if (dtype == 1) hipLaunchKernelGGL((bn_bwd_reduce_kernel<bf16_t, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), 0, s, g);
-    else hipLaunchKernelGGL((bn_bwd_reduce_kernel<float, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), 0, s, g);
+    const size_t lds = (size_t)4 * g.cmax * sizeof(float);
+    if (dtype == 1) hipLaunchKernelGGL((bn_bwd_reduce_kernel<bf16_t, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), lds, s, g);
+    else hipLaunchKernelGGL((bn_bwd_reduce_kernel<float, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), lds, s, g);
     return hipGetLastError();
 }
 hipError_t launch_bn_stats(const BnBwdGroup& g, int dtype, hipStream_t s) {

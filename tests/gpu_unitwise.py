@@ -100,7 +100,7 @@ def check_units(net, tol=None, fused=True, modules=None, note=""):
                     continue
                 gamma, beta = P[u.t_gamma], P[u.t_beta]
                 # ---- forward: batch statistics of the stored tensor
-                st = ls.fetch(u.stats, (2, u.cout), "f64")
+                st = ls.fetch(u.stats, (B.LP_STAT_STRIPES, 2, u.cout), "f64").sum(axis=0)      # kept as partial sums
                 mean_ref = y_dev.mean(axis=(0, 1, 2))
                 var_ref = ((y_dev - mean_ref) ** 2).mean(axis=(0, 1, 2))
                 mean_dev = st[0] / Mpix
