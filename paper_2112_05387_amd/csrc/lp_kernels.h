@@ -153,7 +153,9 @@ struct HeadProb {        // global average pool + linear
 
 // ---- launchers (host side; return hipError_t of the launch) ----------------------------------------
 // tile configuration ids of the implicit-GEMM kernels
-enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160, CFG_COUNT,
+enum ConvCfg { CFG_N16 = 0, CFG_N32, CFG_N64, CFG_N128, CFG_N160,
+               CFG_N64S,                               // 64 x 64 tiles with twice the k-tile: 33..64 output channels, few pixels (forward / data-gradient only)
+               CFG_COUNT,
                FAST_256x320 = 8, FAST_512x160 = 9,     // bf16 wide-layer kernel (lp_conv_fast.hip)
                FAST_128x320 = 10, FAST_128x160 = 11,   // ... its four- and two-wave variants, chosen per launch
                FAST64_256x320 = 12, FAST64_128x320 = 13, FAST64_128x160 = 14,   // ... with k-tiles of 64 channels
