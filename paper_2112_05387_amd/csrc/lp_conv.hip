@@ -695,7 +695,7 @@ hipError_t wgrad_dispatch(const WgradGroup& g, int cfg, hipStream_t s) {
         case CFG_N16: return wgrad_launch_bk<T, 16, 128, 2 * CfgK<T>::BK, 1, 4, 16, VEC>(g, s);
         case CFG_N32: return wgrad_launch_bk<T, 32, 128, 2 * CfgK<T>::BK, 1, 4, 16, VEC>(g, s);
         case CFG_N64: return wgrad_launch_bk<T, 64, 128, 2 * CfgK<T>::BK, 2, 2, 32, VEC>(g, s);
-        case CFG_N128: if constexpr (VEC) return wgrad_launch<T, 128, 128, 2, 2, 32, true>(g, s); else break;
+        case CFG_N128: if constexpr (VEC) return wgrad_launch_bk<T, 128, 128, 2 * CfgK<T>::BK, 2, 2, 32, true>(g, s); else break;
         case CFG_N160: if constexpr (VEC) return wgrad_launch<T, 160, 160, 2, 2, 16, true>(g, s); else break;
         default: break;
     }
@@ -720,8 +720,8 @@ CfgInfo wgrad_cfg_info(int cfg, int dtype) {
         case CFG_N16: return {16, 128, 2 * bk};
         case CFG_N32: return {32, 128, 2 * bk};
         case CFG_N64: return {64, 128, 2 * bk};
-        case CFG_N128: return {128, 128, bk};
-        default: return {160, 160, bk};
+        case CFG_N128: return {128, 128, 2 * bk};
+        default: return {160, 160, bk};      // (doubled k-tiles cost this one its second workgroup per CU: slower)
     }
 }
 
