@@ -223,6 +223,9 @@ def main():
     ap.add_argument("--config", default="wrn28_10")
     ap.add_argument("--batch", type=int, default=None, help="override the mini-batch (the result is then not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="skip what follows the timed steps (parameter-update timings): for rocprofv3 runs, whose summaries\n"
+                         "then hold the kernels of the warm-up and timed steps alone")
     ap.add_argument("--kernel-table", action="store_true", help="print the per-kernel breakdown to stderr")
     ap.add_argument("--dump-launches", action="store_true", help="print every launch of the last timed step to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -377,41 +380,42 @@ def main():
         "step_conv_tflops": cfg.conv_flops_step(net) / (ms_per_step * 1e-3) / 1e12,
         "roofline": roof,
     }
-    # the parameter update that follows a step (not part of `value`): momentum form, fp32 velocity, timed by events
-    vel = [torch.zeros_like(d) for d in ls.dparams]
-    ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
+    if not args.steps_only:
+        # the parameter update that follows a step (not part of `value`): momentum form, fp32 velocity, timed by events
+        vel = [torch.zeros_like(d) for d in ls.dparams]
         ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
-    e1.record()
-    torch.cuda.synchronize()
-    sgd_ms = e0.elapsed_time(e1) / 10
-    sgd_bytes = sum(int(t.numel) * ((4 if t.dtype == B.LP_BF16 else 8) + 12) for tab in ls.tables for t in tab)
-    if graph_ms is not None:
-        out["hip_graph"] = {"ms_per_step": graph_ms, "samples/s": N / (graph_ms * 1e-3),
-                            "note": "the step captured once (stream lanes included) and replayed; `value` is the eager step"}
-    out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
-    # the same update inside the backward pass (epilogues of the filter-gradient kernels), lr = 0 so that the parameters
-    # stay what they are: K steps with it against K steps followed by the pass above
-    ls.set_fused_update(True, 0.0, 0.9, 5e-4, velocity=vel)
-    one_step(ls, net)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
+        e1.record()
+        torch.cuda.synchronize()
+        sgd_ms = e0.elapsed_time(e1) / 10
+        sgd_bytes = sum(int(t.numel) * ((4 if t.dtype == B.LP_BF16 else 8) + 12) for tab in ls.tables for t in tab)
+        if graph_ms is not None:
+            out["hip_graph"] = {"ms_per_step": graph_ms, "samples/s": N / (graph_ms * 1e-3),
+                                "note": "the step captured once (stream lanes included) and replayed; `value` is the eager step"}
+        out["sgd_update"] = {"ms": sgd_ms, "GB/s(alg)": sgd_bytes / (sgd_ms * 1e-3) / 1e9, "form": "momentum 0.9, weight decay 5e-4"}
+        # the same update inside the backward pass (epilogues of the filter-gradient kernels), lr = 0 so that the parameters
+        # stay what they are: K steps with it against K steps followed by the pass above
+        ls.set_fused_update(True, 0.0, 0.9, 5e-4, velocity=vel)
         one_step(ls, net)
-    torch.cuda.synchronize()
-    inside_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ls.set_fused_update(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step(ls, net)
-        ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
-    torch.cuda.synchronize()
-    behind_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    out["step_with_update"] = {"inside_backward_ms": inside_ms, "as_a_pass_behind_the_step_ms": behind_ms,
-                               "note": "not part of `value` (the metric is the local step); same box, same run"}
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(ls, net)
+        torch.cuda.synchronize()
+        inside_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        ls.set_fused_update(False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(ls, net)
+            ls.sgd_update(0.0, 0.9, 5e-4, velocity=vel)
+        torch.cuda.synchronize()
+        behind_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["step_with_update"] = {"inside_backward_ms": inside_ms, "as_a_pass_behind_the_step_ms": behind_ms,
+                                   "note": "not part of `value` (the metric is the local step); same box, same run"}
     ls.close()
     if args.measure_peak:
         out["measured_mfma_peak"] = measure_peak()
