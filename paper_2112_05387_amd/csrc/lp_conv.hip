@@ -28,10 +28,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     static_assert(TM % MT == 0 && TN % MT == 0, "wave tile must be whole micro-tiles");
     typedef typename AccT<MT>::type acc_t;
 
-    // both operands' double buffers in one array: the epilogue stages the result tile over it
-    __shared__ __attribute__((aligned(16))) T s_ab[2 * (BM + BN) * PITCH];
-    T* const As0 = s_ab;                               // As[buf] = As0 + buf * BM * PITCH
-    T* const Bs0 = s_ab + 2 * BM * PITCH;              // Bs[buf] = Bs0 + buf * BN * PITCH
+    // both operands' buffers in one array: the epilogue stages the result tile over it
+    // Narrow tiles (16 / 32 output channels) keep ONE operand buffer: their 256 rows of pixels are what fills the LDS, a
+    // layer has 512 of them per 32 x 32 x 128 tensor, and with one buffer five workgroups fit a CU instead of three, so
+    // that a launch is one generation of workgroups (measured: -15 % on the 16-channel layers; the second barrier per
+    // k-tile costs nothing there, the kernel being bound by its chain of latencies, not by the k-loop).
+    constexpr int NBUF = (BN <= 32) ? 1 : 2;
+    __shared__ __attribute__((aligned(16))) T s_ab[NBUF * (BM + BN) * PITCH];
+    T* const As0 = s_ab;
+    T* const Bs0 = s_ab + NBUF * BM * PITCH;
     __shared__ int s_rowoff[BM];
 
     // ---- which problem, which tile ------------------------------------------------------------
@@ -171,10 +176,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_igemm_kernel(const ConvGro
     store_tile(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+        const int cur = NBUF == 2 ? (kt & 1) : 0;
         if (kt + 1 < nk) load_tile((kt + 1) * BK);
         mma_ktile<T, MT, FM, FN, BK, PITCH>(As0 + cur * (BM * PITCH), Bs0 + cur * (BN * PITCH), wm * TM, wn * TN, lane, acc);
-        if (kt + 1 < nk) store_tile(cur ^ 1);
+        if (NBUF == 1) __syncthreads();
+        if (kt + 1 < nk) store_tile(NBUF == 2 ? (cur ^ 1) : 0);
         __syncthreads();
     }
 
@@ -352,8 +358,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_wgrad_kernel(const WgradGr
     static_assert(TM % MT == 0 && TN % MT == 0, "wave tile must be whole micro-tiles");
     typedef typename AccT<MT>::type acc_t;
 
-    __shared__ __attribute__((aligned(16))) T As[2][BM * PITCH];
-    __shared__ __attribute__((aligned(16))) T Bs[2][BN * PITCH];
+    constexpr int NBUF = (BM <= 64) ? 1 : 2;             // narrow filters: one operand buffer, twice the workgroups per CU (as in the forward kernel)
+    __shared__ __attribute__((aligned(16))) T As[NBUF][BM * PITCH];
+    __shared__ __attribute__((aligned(16))) T Bs[NBUF][BN * PITCH];
 
     const int tid = threadIdx.x;
     int pi = 0;
@@ -495,10 +502,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void conv_wgrad_kernel(const WgradGr
     }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+        const int cur = NBUF == 2 ? (kt & 1) : 0;
         if (kt + 1 < nk) load_tile(k_begin + (kt + 1) * BK);
         mma_ktile<T, MT, FM, FN, BK, PITCH>(As[cur], Bs[cur], wm * TM, wn * TN, lane, acc);
-        if (kt + 1 < nk) store_tile(cur ^ 1);
+        if (NBUF == 1) __syncthreads();
+        if (kt + 1 < nk) store_tile(NBUF == 2 ? (cur ^ 1) : 0);
         __syncthreads();
     }
 
