@@ -202,7 +202,12 @@ __global__ __launch_bounds__(kElemBlock) void bn_apply_kernel(const BnApplyGroup
 }
 
 // ------------------------------------------------------------------------------------------------
-// red[c] += sum g', red[C+c] += sum g'*yhat over this workgroup's rows
+// red[c] += sum g', red[C+c] += sum g'*yhat over this workgroup's rows.
+// C / EPV <= NT channel vectors (C <= 2048): thread t owns channel vector t % cv and is row lane t / cv.  A trip is
+// four rows per row lane, i.e. eight independent 16-byte loads per thread.  The trips of the blocks are interleaved
+// (block b takes trips b, b + nblocks, ...), so that at any time the blocks together read one contiguous, moving window
+// of the two tensors instead of nblocks distant streams.  The first trip is requested before the coefficient prologue
+// (it does not depend on it) and every further trip before the previous one is consumed.
 template <typename T, int NT>
 __global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
     constexpr int EPV = Vec<T>::N;
@@ -219,72 +224,79 @@ __global__ __launch_bounds__(NT) void bn_bwd_reduce_kernel(const BnBwdGroup g) {
     const int b = blockIdx.x - P.block_start;
     const T* __restrict__ gp = reinterpret_cast<const T*>(P.g);
     const T* __restrict__ y = reinterpret_cast<const T*>(P.y);
+    const int rl = NT / cv;                      // row lanes
+    const int tcv = threadIdx.x % cv, trl = threadIdx.x / cv;
+    const bool active = trl < rl;
+    const int c0 = tcv * EPV;
+    const int rows_trip = 4 * rl, stride = P.nblocks * rows_trip;
+    // a trip as loaded (32 registers); rows past the end read the last row and count as zero when consumed
+    auto request = [&](u32x4 (&graw)[4], u32x4 (&yraw)[4], int r0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = min(r0 + trl + u * rl, M - 1);
+            graw[u] = Vec<T>::load_raw(gp + (size_t)r * C + c0);
+            yraw[u] = Vec<T>::load_raw(y + (size_t)r * C + c0);
+        }
+    };
+    u32x4 ga[4], ya[4], gb[4], yb[4];
+    int r0 = b * rows_trip;
+    if (active && r0 < M) request(ga, ya, r0);
     for (int c = threadIdx.x; c < C; c += NT) {
         float sc, sh, mu, is;
         bn_coeffs(P.stats, P.gamma, P.beta, c, C, M, g.eps, sc, sh, mu, is);
         s_sc[c] = sc; s_sh[c] = sh; s_mu[c] = mu; s_is[c] = is;
     }
     __syncthreads();
-    for (int cbase = 0; cbase < cv; cbase += NT) {
-        const int ncv = min(cv - cbase, NT);     // channel vectors in this pass
-        const int rl = NT / ncv;                 // row lanes
-        const int tcv = threadIdx.x % ncv, trl = threadIdx.x / ncv;
-        float a1[EPV], a2[EPV];
+    float a1[EPV], a2[EPV];
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) { a1[e] = 0.f; a2[e] = 0.f; }
-        if (trl < rl) {
-            const int c0 = (cbase + tcv) * EPV;
-            float sc[EPV], sh[EPV], mu[EPV], is[EPV];
+    for (int e = 0; e < EPV; ++e) { a1[e] = 0.f; a2[e] = 0.f; }
+    if (active) {
+        float sc[EPV], sh[EPV], mu[EPV], is[EPV];
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) { sc[e] = s_sc[c0 + e]; sh[e] = s_sh[c0 + e]; mu[e] = s_mu[c0 + e]; is[e] = s_is[c0 + e]; }
-            // Four rows per trip: eight independent 16-byte loads in flight per thread.  The trips of the blocks are
-            // interleaved (block b takes trips b, b + nblocks, ...), so that at any time the blocks together read one
-            // contiguous, moving window of the two tensors instead of nblocks distant streams.
-            const int rows_trip = 4 * rl;
-            for (int r0 = b * rows_trip; r0 < M; r0 += P.nblocks * rows_trip) {
-                // all eight loads first, as loaded (32 registers); converted one row at a time afterwards.  Rows past
-                // the end read the last row and count as zero.
-                u32x4 graw[4], yraw[4];
+        for (int e = 0; e < EPV; ++e) { sc[e] = s_sc[c0 + e]; sh[e] = s_sh[c0 + e]; mu[e] = s_mu[c0 + e]; is[e] = s_is[c0 + e]; }
+        auto consume = [&](const u32x4 (&graw)[4], const u32x4 (&yraw)[4], int rbase) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int r = min(r0 + trl + u * rl, M - 1);
-                    graw[u] = Vec<T>::load_raw(gp + (size_t)r * C + c0);
-                    yraw[u] = Vec<T>::load_raw(y + (size_t)r * C + c0);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+            for (int u = 0; u < 4; ++u) {
+                float gv[EPV], yv[EPV];
+                Vec<T>::unpack(graw[u], gv);
+                Vec<T>::unpack(yraw[u], yv);
+                const bool in = rbase + trl + u * rl < M;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    float gv[EPV], yv[EPV];
-                    Vec<T>::unpack(graw[u], gv);
-                    Vec<T>::unpack(yraw[u], yv);
-                    const bool in = r0 + trl + u * rl < M;
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) {
-                        float gg = in ? gv[e] : 0.f;
-                        if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
-                        a1[e] += gg;
-                        a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
-                    }
+                for (int e = 0; e < EPV; ++e) {
+                    float gg = in ? gv[e] : 0.f;
+                    if (P.relu && !(fmaf(sc[e], yv[e], sh[e]) > 0.f)) gg = 0.f;
+                    a1[e] += gg;
+                    a2[e] += gg * ((yv[e] - mu[e]) * is[e]);
                 }
             }
+        };
+        while (r0 < M) {
+            int rn = r0 + stride;
+            if (rn < M) request(gb, yb, rn);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(ga, ya, r0);
+            if (rn >= M) break;
+            r0 = rn; rn = r0 + stride;
+            if (rn < M) request(ga, ya, rn);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(gb, yb, r0);
+            r0 = rn;
         }
-        __syncthreads();
-        if (trl < rl) {
+    }
+    if (active) {
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                s_red[((trl * ncv + tcv) * EPV + e) * 2] = a1[e];
-                s_red[((trl * ncv + tcv) * EPV + e) * 2 + 1] = a2[e];
-            }
+        for (int e = 0; e < EPV; ++e) {
+            s_red[((trl * cv + tcv) * EPV + e) * 2] = a1[e];
+            s_red[((trl * cv + tcv) * EPV + e) * 2 + 1] = a2[e];
         }
-        __syncthreads();
-        for (int i = threadIdx.x; i < ncv * EPV; i += NT) {
-            float s1 = 0.f, s2 = 0.f;
-            for (int l = 0; l < rl; ++l) { s1 += s_red[((l * ncv * EPV) + i) * 2]; s2 += s_red[((l * ncv * EPV) + i) * 2 + 1]; }
-            const int c = cbase * EPV + i;
-            double* red = P.red + (size_t)(blockIdx.x % stat_stripes(C)) * 2 * C;
-            atomicAdd(&red[c], (double)s1);
-            atomicAdd(&red[C + c], (double)s2);
-        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < cv * EPV; i += NT) {
+        float s1 = 0.f, s2 = 0.f;
+        for (int l = 0; l < rl; ++l) { s1 += s_red[((l * cv * EPV) + i) * 2]; s2 += s_red[((l * cv * EPV) + i) * 2 + 1]; }
+        double* red = P.red + (size_t)(blockIdx.x % stat_stripes(C)) * 2 * C;
+        atomicAdd(&red[i], (double)s1);
+        atomicAdd(&red[C + i], (double)s2);
     }
 }
 
