@@ -1516,7 +1516,12 @@ static hipError_t launch_group_impl(lp_net* net, std::vector<const Op*>& ops, si
                     p.dgamma = (float*)resolve(o.r[7], b); p.dbeta = (float*)resolve(o.r[8], b);
                     p.add = resolve(o.r[9], b);
                     p.block_start = tot;
-                    if (type != OP_BN_BWD_APPLY) p.nblocks = net->deterministic ? 1 : std::max(1, std::min(256, (p.M + 63) / 64));
+                    if (type == OP_BN_BWD_REDUCE) {
+                        // at least 64 rows per workgroup, and (one trip of the reduction being four rows per row lane) no more
+                        // workgroups than trips
+                        const int rows_trip = 4 * std::max(1, bn_reduce_threads(g.cmax) / (p.C / epv));
+                        p.nblocks = net->deterministic ? 1 : std::max(1, std::min(std::min(256, (p.M + 63) / 64), (p.M + rows_trip - 1) / rows_trip));
+                    } else if (type != OP_BN_BWD_APPLY) p.nblocks = net->deterministic ? 1 : std::max(1, std::min(256, (p.M + 63) / 64));
                     else p.nblocks = elem_blocks((size_t)p.M * p.C / epv);
                     tot += p.nblocks;
                 }

@@ -865,6 +865,13 @@ hipError_t launch_bn_apply(const BnApplyGroup& g, int dtype, bool fused_loss, hi
 hipError_t launch_bn_bwd_reduce(const BnBwdGroup& g, int dtype, hipStream_t s) {
     if (g.total_blocks <= 0) return hipSuccess;
     const size_t lds = (size_t)4 * g.cmax * sizeof(float);
+    // narrow tensors (at most 64 channels): 256-thread workgroups -- with 512 threads half of the 256 workgroups of a
+    // 32 x 32 x 16 tensor have no trip at all and the others' final sum over the row lanes is twice as long
+    if (bn_reduce_threads(g.cmax) == 256) {
+        if (dtype == 1) hipLaunchKernelGGL((bn_bwd_reduce_kernel<bf16_t, 256>), dim3(g.total_blocks), dim3(256), lds, s, g);
+        else hipLaunchKernelGGL((bn_bwd_reduce_kernel<float, 256>), dim3(g.total_blocks), dim3(256), lds, s, g);
+        return hipGetLastError();
+    }
     if (dtype == 1) hipLaunchKernelGGL((bn_bwd_reduce_kernel<bf16_t, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), lds, s, g);
     else hipLaunchKernelGGL((bn_bwd_reduce_kernel<float, kBnReduceBlock>), dim3(g.total_blocks), dim3(kBnReduceBlock), lds, s, g);
     return hipGetLastError();

@@ -215,6 +215,8 @@ constexpr int kStatStripes = 8;
 __host__ __device__ inline int stat_stripes(int C) { return C <= 64 ? 8 : (C <= 320 ? 4 : 1); }
 __host__ __device__ inline size_t stat_bytes(int C) { return sizeof(double) * 2 * (size_t)C * kStatStripes; }
 constexpr int kBnReduceBlock = 512;      // threads per workgroup of the BN backward reduction (measured: 256 -7 %, 1024 -20 %)
+// ... and 256 for launches whose widest tensor has at most 64 channels (see launch_bn_bwd_reduce)
+inline int bn_reduce_threads(int cmax) { return cmax <= 64 ? 256 : kBnReduceBlock; }
 constexpr int kElemVecsPerBlock = 2048;  // 16-byte vectors handled by one workgroup
 
 }  // namespace lp
