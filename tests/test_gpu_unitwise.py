@@ -35,6 +35,23 @@ def test_units_mini_wide():
     check_units(gpu_mini_wide_strided(batch=5))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_units_edge_cases(dtype):
+    """Degenerate sizes and coefficients: a mini-batch of ONE sample (batch statistics over 36 and 9 pixels, every tile
+    ragged), images of 2 x 2 pixels (every 3x3 window hangs over the border on all sides; the stride-2 block leaves 1 x 1),
+    rho = 0 with multipliers (the loss is the multiplier term alone) and a loss scale other than 1."""
+    from workloads import configs as cfg
+    from workloads.configs import Block
+    check_units(gpu_mini_basic(batch=1, dtype=dtype), note=" [batch 1]")
+    blocks = [Block("basic", 8, 8, 8, 1, False), Block("basic", 8, 16, 16, 2, True), Block("basic", 16, 16, 16, 1, False)]
+    net = cfg._assemble("gpu_edge_2x2", [blocks[:1], blocks[1:]], 5, 2, 2, 3, 1, 8, 4, seed=31)
+    net.dtype = dtype
+    check_units(net, note=" [2 x 2 images]")
+    net = gpu_mini_basic(batch=3, dtype=dtype)
+    net.al, net.rho, net.lam_sigma = True, 0.0, 0.5
+    check_units(net, note=" [rho = 0, multipliers]", scale=0.37)
+
+
 def test_units_separate_calls():
     check_units(gpu_mini_basic(batch=3, dtype="bf16"), fused=False)
 
