@@ -337,6 +337,9 @@ def main():
             # compute unit it occupies (one workgroup per CU) against a CU's share of the peak
             roof["workgroups_per_launch"] = dom["blocks"] / dom["launches"]
             roof["frac_on_occupied_cus"] = dom["flops"] / (dom["cu_ms"] * 1e-3) / 1e12 / peak
+            # ... and what all convolutions of the step reach in the timed region itself, where the lanes' launches fill the
+            # chip together (every other kernel of the step included in the time)
+            roof["frac_all_convs_over_timed_step"] = cfg.conv_flops_step(net) / (ms_per_step * 1e-3) / 1e12 / peak
     else:
         achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS}
