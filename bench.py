@@ -178,6 +178,30 @@ def measure_peak():
     return out
 
 
+def measure_step_clock(ls, net, steps=12):
+    """The shader clock while the local step runs: one workgroup of the synthetic MFMA kernel (it records shader-clock
+    cycles and ticks of the constant 100 MHz counter) on a stream of its own beside the steps, about 1.5 ms long; the
+    compute unit it takes is 1/256 of the chip."""
+    import torch
+    from paper_2112_05387_amd import binding as B
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream()
+    probes = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(steps)]
+    B.lp_debug_mfma_peak(side.cuda_stream, 0, 1, 200, probes[0].data_ptr(), sink.data_ptr())
+    torch.cuda.synchronize()
+    for i in range(steps):
+        one_step(ls, net)
+        B.lp_debug_mfma_peak(side.cuda_stream, 0, 1, 2500, probes[i].data_ptr(), sink.data_ptr())
+    torch.cuda.synchronize()
+    ghz = [float(p[0].item()) / float(p[1].item()) * 0.1 for p in probes[2:]]
+    B.lp_debug_mfma_peak(side.cuda_stream, 0, 1, 2500, probes[0].data_ptr(), sink.data_ptr())     # the same probe on an idle chip
+    torch.cuda.synchronize()
+    idle = float(probes[0][0].item()) / float(probes[0][1].item()) * 0.1
+    return {"shader_clock_GHz_during_steps": sum(ghz) / len(ghz), "min": min(ghz), "max": max(ghz),
+            "shader_clock_GHz_probe_alone": idle, "probes": len(ghz)}
+
+
 def cpu_baseline(net_name, target_seconds=60.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: one local step of the same network, at
     the configuration's own mini-batch when the plain loops finish it within about a minute on the host's cores (the
@@ -419,6 +443,8 @@ def main():
         behind_ms = (time.perf_counter() - t0) * 1e3 / args.steps
         out["step_with_update"] = {"inside_backward_ms": inside_ms, "as_a_pass_behind_the_step_ms": behind_ms,
                                    "note": "not part of `value` (the metric is the local step); same box, same run"}
+    if args.measure_peak:
+        out["step_clock"] = measure_step_clock(ls, net)
     ls.close()
     if args.measure_peak:
         out["measured_mfma_peak"] = measure_peak()
