@@ -700,9 +700,14 @@ hipError_t wgrad_dispatch(const WgradGroup& g, int cfg, hipStream_t s) {
     switch (cfg) {
         // narrow filters: k-tiles of twice the pixels (half as many load -> LDS -> barrier rounds per chunk; measured
         // -4 % on the ResNet-56 step, -3 % on ResNet-20)
-        case CFG_N16: return wgrad_launch_bk<T, 16, 128, 2 * CfgK<T>::BK, 1, 4, 16, VEC>(g, s);
-        case CFG_N32: return wgrad_launch_bk<T, 32, 128, 2 * CfgK<T>::BK, 1, 4, 16, VEC>(g, s);
-        case CFG_N64: return wgrad_launch_bk<T, 64, 128, 2 * CfgK<T>::BK, 2, 2, 32, VEC>(g, s);
+        // ... and 144 columns: the 9 taps x 16 / 32 / 64 channels of a 3x3 filter are 1 / 2 / 4 whole tiles (128 columns left
+        // a second or fifth tile that is one eighth full and reads the whole dY chunk again; measured: ResNet-56 step
+        // 1.06 -> 1.02 ms, ResNet-20 0.925 -> 0.895; the 64-channel bf16 tile is the exception: 0.086 -> 0.094 ms)
+        case CFG_N16: return wgrad_launch_bk<T, 16, 144, 2 * CfgK<T>::BK, 1, 3, 16, VEC>(g, s);
+        case CFG_N32: return wgrad_launch_bk<T, 32, 144, 2 * CfgK<T>::BK, 1, 3, 16, VEC>(g, s);
+        case CFG_N64:
+            if constexpr (sizeof(T) == 4) return wgrad_launch_bk<T, 64, 144, 2 * CfgK<T>::BK, 2, 3, 16, VEC>(g, s);
+            else return wgrad_launch_bk<T, 64, 128, 2 * CfgK<T>::BK, 2, 2, 32, VEC>(g, s);
         case CFG_N128: if constexpr (VEC) return wgrad_launch_bk<T, 128, 128, 2 * CfgK<T>::BK, 2, 2, 32, true>(g, s); else break;
         case CFG_N160: if constexpr (VEC) return wgrad_launch<T, 160, 160, 2, 2, 16, true>(g, s); else break;
         default: break;
@@ -725,9 +730,9 @@ CfgInfo conv_cfg_info(int cfg, int dtype) {
 CfgInfo wgrad_cfg_info(int cfg, int dtype) {
     const int bk = dtype == 1 ? 32 : 16;
     switch (cfg) {
-        case CFG_N16: return {16, 128, 2 * bk};
-        case CFG_N32: return {32, 128, 2 * bk};
-        case CFG_N64: return {64, 128, 2 * bk};
+        case CFG_N16: return {16, 144, 2 * bk};
+        case CFG_N32: return {32, 144, 2 * bk};
+        case CFG_N64: return {64, dtype == 1 ? 128 : 144, 2 * bk};
         case CFG_N128: return {128, 128, 2 * bk};
         default: return {160, 160, bk};      // (doubled k-tiles cost this one its second workgroup per CU: slower)
     }
